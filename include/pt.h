@@ -1,0 +1,184 @@
+/*
+ * pt.h - C ABI of the freeze-boundary training step for MI355X (gfx950).
+ *
+ * One training iteration of a Transformer encoder (ViT pre-LN / BERT post-LN,
+ * paper App. A.1) whose L layers f_0 .. f_{L-1} (Sec. 2.1) are split at a
+ * freeze boundary k = L_frozen (Sec. 3.1, Eq. 1):
+ *
+ *   pt_set_freeze_boundary(k)   F = F_frozen o F_pipe            (Sec. 3.2.1)
+ *   pt_frozen_forward           forward-only through the front end and blocks
+ *                               0..k-1, served from / written to the per-sample
+ *                               activation cache           (Sec. 3.4, App. D.1)
+ *   pt_active_fwd_bwd           forward + backward through blocks k..L-1 + head
+ *   pt_layer_grad_norms         ||g_l|| for every layer               (Eq. 1)
+ *   pt_optimizer_step           update of F_pipe's parameters only
+ *                                                        (Sec. 3.3, App. D.2)
+ *
+ * General rules
+ *  - Every pointer argument is marked HOST or DEVICE below.  The library never
+ *    allocates device memory: the caller owns the four arenas handed to
+ *    pt_create (sizes from pt_query_arena_bytes), the input / label buffers and
+ *    the HIP stream.  pt_ctx owns host bookkeeping only.
+ *  - All device work is enqueued on the stream given to pt_create.  Calls that
+ *    return host scalars (loss, norms, reads) synchronise that stream.
+ *  - Errors: every call returns a pt_status; nothing throws or aborts across
+ *    the ABI.  Arguments are validated before anything is enqueued, so on a
+ *    non-OK return the context is unchanged.  pt_last_error gives a message.
+ *  - Call order per step: pt_frozen_forward -> pt_active_fwd_bwd ->
+ *    [pt_layer_grad_norms] -> pt_optimizer_step.  Out of order: PT_ESTATE.
+ *  - Layouts: activations [B,S,D] row-major; linear maps y = x W + b with W
+ *    stored [in,out] row-major; packed QKV weight columns [Q|K|V], head h owns
+ *    columns h*dh..(h+1)*dh-1 of each third.  In PT_BF16 mode activations are
+ *    bf16, accumulation / LayerNorm / softmax statistics / gradients of
+ *    parameters / optimizer state are fp32, and forward/backward kernels read a
+ *    bf16 shadow (round-to-nearest-even) of the fp32 master parameters.
+ */
+#ifndef PT_H_
+#define PT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pt_ctx pt_ctx;
+
+typedef enum {
+  PT_OK = 0,
+  PT_EINVAL = 1,      /* bad argument (NULL, out of range, decreasing boundary) */
+  PT_ESTATE = 2,      /* call out of order                                      */
+  PT_ENOMEM = 3,      /* host allocation failed or an arena is too small        */
+  PT_EDEVICE = 4,     /* a HIP call or kernel reported an error                 */
+  PT_ECACHE_MISS = 5  /* pt_cache_row: the slot holds nothing                   */
+} pt_status;
+
+enum { PT_VIT_PRELN = 0, PT_BERT_POSTLN = 1 };   /* App. A.1: where LayerNorm sits */
+enum { PT_F32 = 0, PT_BF16 = 1 };
+enum { PT_SGDM = 0, PT_ADAMW = 1 };
+
+typedef struct {
+  int32_t arch;        /* PT_VIT_PRELN | PT_BERT_POSTLN                              */
+  int32_t dtype;       /* PT_F32 | PT_BF16                                           */
+  int32_t L, D, H, F;  /* blocks, hidden, heads, MLP width; D % H == 0, D/H % 4 == 0 */
+  int32_t S;           /* sequence length (ViT: (img/patch)^2 + 1)                   */
+  int32_t B;           /* largest batch any call will pass                           */
+  int32_t n_out;       /* classes (ViT) or 2 (BERT span QA)                          */
+  int32_t img, patch, chans;  /* ViT front end                                       */
+  int32_t vocab, max_pos;     /* BERT front end, max_pos >= S                        */
+  float ln_eps;
+  int32_t optimizer;   /* PT_SGDM | PT_ADAMW                                         */
+  int64_t cache_slots; /* 0 = no cache; slot i belongs to sample id i                */
+} pt_config;
+
+typedef struct {
+  float lr, momentum, beta1, beta2, eps, weight_decay;
+} pt_opt_hparams;
+
+/* Bytes of the four caller-owned DEVICE arenas for this configuration:
+ * params (fp32 masters + bf16 shadows), state (fp32 gradients + optimizer
+ * moments), work (activations, saved tensors, scratch), cache (cache_slots rows
+ * of S*D activations).  Each must be 256-byte aligned.  PT_EINVAL on a bad
+ * configuration. */
+pt_status pt_query_arena_bytes(const pt_config* cfg /*HOST*/, size_t* params, size_t* state,
+                               size_t* work, size_t* cache /*HOST out*/);
+
+/* Creates a context over the arenas (DEVICE pointers, sizes as queried).  The
+ * params and state arenas are cleared (enqueued); parameters are then set with
+ * pt_write_tensor.  hip_stream is a hipStream_t (NULL = default stream).  The
+ * boundary starts at k = 0 and the step counter at 0 (Eq. 1: L_frozen^(0)=0). */
+pt_status pt_create(const pt_config* cfg /*HOST*/, void* d_params, void* d_state, void* d_work,
+                    void* d_cache /*DEVICE, may be NULL iff cache_slots==0*/, void* hip_stream,
+                    pt_ctx** out /*HOST out*/);
+pt_status pt_destroy(pt_ctx* ctx);
+
+/* Moves the freeze boundary: blocks 0..k-1 (and, for k >= 1, the front end)
+ * become F_frozen.  0 <= k <= L and k >= current boundary, otherwise PT_EINVAL
+ * and nothing changes (the argmin of Eq. 1 ranges over layers at or above the
+ * previous boundary, so the boundary never moves down).  Gradients and
+ * optimizer moments of newly frozen tensors are cleared and never used again
+ * (Sec. 3.2.1); cache rows written at a smaller k become stale and are advanced
+ * on their next use (Sec. 3.4). */
+pt_status pt_set_freeze_boundary(pt_ctx* ctx, int32_t k);
+pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
+
+/* F_frozen for one batch of nb <= B samples.
+ *  d_input    DEVICE. ViT: fp32 images [nb,chans,img,img]; BERT: int32 ids [nb,S].
+ *  sample_ids HOST, nb unique ids in [0,cache_slots), or NULL to bypass the
+ *             cache.  Ignored when k == 0 (nothing is frozen, the front end is
+ *             being trained).  Per sample: a row written at the current k is a
+ *             hit (copied, no block runs); a row written at k' < k is advanced
+ *             through blocks k'..k-1 only; otherwise the front end and blocks
+ *             0..k-1 run.  Updated rows are written back (App. D.1 item 2).
+ *  d_hk_out   HOST out: DEVICE pointer to the boundary activation [nb,S,D]
+ *             inside the work arena, valid until the next pt_frozen_forward.
+ * Results per sample do not depend on the sample's position in the batch. */
+pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const int64_t* sample_ids,
+                            void** d_hk_out);
+
+/* F_pipe: forward through blocks k..L-1 and the task head, loss, backward down
+ * to block k (and the front end iff k == 0), for the batch of the preceding
+ * pt_frozen_forward.
+ *  d_hk      DEVICE [nb,S,D] boundary activation (normally *d_hk_out); read only.
+ *  d_labels  DEVICE int32: ViT [nb] class ids; BERT [nb,2] (start,end) positions.
+ *  loss_out  HOST out, mean loss over the batch; the call synchronises.  May be
+ *            NULL: then nothing synchronises and pt_last_loss fetches it later.
+ * Gradients of all active tensors are overwritten (not accumulated). */
+pt_status pt_active_fwd_bwd(pt_ctx* ctx, const void* d_hk, const int32_t* d_labels, float* loss_out);
+pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
+
+/* L2 norm of the gradient of every layer taken as one vector (Eq. 1's ||g_l||,
+ * on the raw gradient of the mean loss of the last pt_active_fwd_bwd).
+ * norms_out HOST, L+2 floats: [front end, block 0 .. block L-1, head]; frozen
+ * layers (and the front end when k >= 1) read exactly 0.  Synchronises. */
+pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
+
+/* One optimizer step over the active tensors only; frozen bytes are untouched.
+ * SGD-momentum: v <- mu v + g (+ wd w on decayed tensors), w <- w - lr v.
+ * AdamW: decoupled decay, bias-corrected moments, one shared step counter.
+ * Decayed tensors: weight matrices and the token table.  Also refreshes the
+ * bf16 shadow in PT_BF16 mode. */
+pt_status pt_optimizer_step(pt_ctx* ctx, const pt_opt_hparams* hp /*HOST*/);
+
+/* Eq. 1 with the readings: argmin over blocks k_prev..L-1, bound truncated to
+ * an integer, ties to the lowest index.  norms HOST, L+2 floats as returned by
+ * pt_layer_grad_norms.  Pure host arithmetic; does not move the boundary. */
+pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, float alpha, int32_t* k_next);
+
+/* ---- tensor table and state access (synchronising host copies) ---------- */
+enum { PT_KIND_PARAM = 0, PT_KIND_GRAD = 1, PT_KIND_MOMENT1 = 2, PT_KIND_MOMENT2 = 3,
+       PT_KIND_SHADOW = 4 /* bf16 shadow widened to fp32; PT_BF16 mode only */ };
+
+pt_status pt_num_tensors(const pt_ctx* ctx, int32_t* n /*HOST out*/);
+/* name: HOST buffer of name_cap bytes (NUL-terminated on return); group is the
+ * grad-norm slot (0 front, 1+l block l, L+1 head). */
+pt_status pt_tensor_info(const pt_ctx* ctx, int32_t id, char* name, size_t name_cap, int64_t* numel,
+                         int32_t* rows, int32_t* cols, int32_t* group, int32_t* decayed);
+/* fp32 HOST buffers of numel elements.  pt_write_tensor(PT_KIND_PARAM) also
+ * refreshes the bf16 shadow.  PT_KIND_SHADOW is read-only. */
+pt_status pt_write_tensor(pt_ctx* ctx, int32_t id, int32_t kind, const float* src);
+pt_status pt_read_tensor(pt_ctx* ctx, int32_t id, int32_t kind, float* dst);
+pt_status pt_get_step_count(const pt_ctx* ctx, int64_t* t);
+pt_status pt_set_step_count(pt_ctx* ctx, int64_t t);
+
+/* Activations of the last step widened to fp32 (parity checks). */
+enum { PT_ACT_HK = 0 /*[nb,S,D]*/, PT_ACT_HL = 1 /*[nb,S,D]*/, PT_ACT_LOGITS = 2 /*ViT [nb,n_out]; BERT [nb,S,2]*/,
+       PT_ACT_DHK = 3 /*[nb,S,D] gradient wrt the boundary activation; valid when k == 0 or arch-internal*/ };
+pt_status pt_read_activation(pt_ctx* ctx, int32_t which, float* dst /*HOST*/, size_t numel);
+
+/* Cache inspection.  pt_cache_row copies the raw row bytes (S*D elements of the
+ * activation type) to HOST and reports the boundary it was written at;
+ * PT_ECACHE_MISS if the slot is empty.  pt_cache_stats: counters since creation
+ * of per-sample decisions and of (sample, block) forward evaluations spent in
+ * pt_frozen_forward. */
+pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k);
+pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, int64_t* misses,
+                         int64_t* block_runs);
+
+const char* pt_last_error(const pt_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PT_H_ */

@@ -1,0 +1,112 @@
+// Host-side launchers of the gfx950 kernels.  `dt` selects the activation /
+// compute-parameter element type: 0 = fp32, 1 = bf16 (fp32 accumulation).
+// Every launcher validates nothing: the orchestrator checks shapes first.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pt {
+
+enum Epi {
+  EPI_STORE = 0,      // C = acc
+  EPI_BIAS = 1,       // C = acc + bias[n]
+  EPI_BIAS_RES = 2,   // C = acc + bias[n] + aux[m,n]
+  EPI_BIAS_GELU = 3,  // h = acc + bias[n]; aux_out[m,n] = h (if non-null); C = GELU(h)
+  EPI_MUL_DGELU = 4,  // C = acc * GELU'(aux[m,n])
+  EPI_RES = 5         // C = acc + aux[m,n]
+};
+
+struct Gemm {
+  const void* A = nullptr;  // ta ? [K,M] : [M,K], leading dimension lda
+  const void* B = nullptr;  // tb ? [N,K] : [K,N], leading dimension ldb
+  void* C = nullptr;        // [M,N], leading dimension ldc; T, or float when c_f32
+  int M = 0, N = 0, K = 0;
+  int64_t lda = 0, ldb = 0, ldc = 0;
+  bool ta = false, tb = false;
+  Epi epi = EPI_STORE;
+  const void* bias = nullptr;  // T [N]
+  const void* aux = nullptr;   // T [M,N] ld_aux
+  void* aux_out = nullptr;     // T [M,N] ld_aux
+  int64_t ld_aux = 0;
+  bool c_f32 = false;
+};
+void gemm(int dt, const Gemm& g, hipStream_t st);
+
+// ---- attention (softmax(q k^T / sqrt(dh)) v, no mask) over packed qkv [nb,S,3D]
+void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or null*/, int nb, int S, int H,
+                   int dh, hipStream_t st);
+void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv,
+                   float* delta_ws /*[nb,H,S]*/, int nb, int S, int H, int dh, hipStream_t st);
+
+// ---- LayerNorm over rows of length D
+// y[r] = LN(x[r]); rows addressed r*ldx / r*ldy (elements).  mean/rstd may be null.
+void layernorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y, int64_t ldy,
+                   float* mean, float* rstd, int rows, int D, float eps, hipStream_t st);
+// dx[r] = LNbwd(dy[r]) (+ dres[r] if non-null); dgamma/dbeta fp32 [D] via `partial` scratch
+// of ln_partial_floats(D) floats.
+size_t ln_partial_floats(int D);
+void layernorm_bwd(int dt, const void* dy, int64_t lddy, const void* x, int64_t ldx, const float* mean,
+                   const float* rstd, const void* gamma, const void* dres, int64_t lddres, void* dx, int64_t lddx,
+                   float* dgamma, float* dbeta, float* partial, int rows, int D, hipStream_t st);
+
+// out[n] = sum_m X[m,n] (fp32), X is T [M,N] with leading dimension ld.
+size_t colsum_partial_floats(int N);
+void colsum(int dt, const void* X, int64_t ld, int M, int N, float* out, float* partial, hipStream_t st);
+
+// ---- ViT front end
+// sample b of the output reads image map[b] (map null = identity)
+void vit_patchify(int dt, const float* images, const int64_t* map, void* patches, int nb, int chans, int img, int patch,
+                  hipStream_t st);
+void vit_assemble(int dt, const void* E, const void* cls, const void* pos, void* X, int nb, int S, int D,
+                  hipStream_t st);
+// dE[b*N+i] = dX[b,1+i]; dpos[s] = sum_b dX[b,s]; dcls = sum_b dX[b,0]
+void vit_front_bwd(int dt, const void* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st);
+
+// ---- BERT front end
+void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, void* emb, int nb, int S,
+                int D, hipStream_t st);
+// dEp[s] = sum_b demb[b,s] for s < S (rows >= S untouched); dEw rows: deterministic
+// segmented sum over equal ids.  `dEw` must be zero on entry.
+// `ws`: 2*nb*S int32 of scratch.
+void bert_embed_bwd(int dt, const int32_t* ids, const void* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S,
+                    int D, hipStream_t st);
+
+// ---- losses
+// ViT: z fp32 [nb,C]; writes per-sample loss, dz (T) = (softmax - onehot)/nb.
+void ce_rows(int dt, const float* z, const int32_t* labels, float* loss_rows, void* dz, int nb, int C, hipStream_t st);
+// BERT QA: x [nb,S,D] (T), W [D,2], b[2] (T).  z fp32 [nb,S,2] -> CE over S per column.
+void qa_logits(int dt, const void* x, const void* W, const void* b, float* z, int rows, int D, hipStream_t st);
+void qa_ce(int dt, const float* z, const int32_t* labels, float* loss_rows /*[nb]*/, float* dz /*fp32 [nb,S,2]*/, int nb,
+           int S, hipStream_t st);
+// dx[t] = dz[t,0] W[:,0] + dz[t,1] W[:,1]; dW[d,c] = sum_t x[t,d] dz[t,c]; db[c] = sum_t dz[t,c]
+size_t qa_partial_floats(int D);
+void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, void* dx, float* dW, float* db, float* partial,
+                 int rows, int D, hipStream_t st);
+// loss = (sum_i rows[i]) / n, fixed order
+void mean_reduce(const float* rows, int n, float* out, hipStream_t st);
+
+// ---- plumbing
+void fill_zero(void* p, size_t bytes, hipStream_t st);
+// dst[dst_idx[i]] = src[src_idx[i]] for rows of row_bytes (multiple of 16); idx null = identity
+void copy_rows(void* dst, const int64_t* dst_idx, const void* src, const int64_t* src_idx, int nrows,
+               size_t row_bytes, hipStream_t st);
+void f32_to_bf16(const float* src, void* dst, size_t n, hipStream_t st);
+void bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st);
+
+// ---- gradient norms and optimizers over the padded, contiguous tensor arenas.
+// Arenas are cut into chunks of kChunk floats; chunk c belongs to group chunk_group[c].
+constexpr int kChunk = 1024;
+void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t n_chunks, hipStream_t st);
+// norms[grp] = sqrt(sum of chunk_sq over the chunk range of grp) for active groups, 0 otherwise
+void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk /*[G+1] device*/, int G, int first_active,
+                    int front_active, float* norms, hipStream_t st);
+struct OptArgs {
+  float lr, momentum, beta1, beta2, eps, weight_decay;
+  float bias_c1, bias_c2;  // 1-beta1^t, 1-beta2^t
+};
+void adamw_chunks(float* w, const float* g, float* m, float* v, void* shadow /*bf16 or null*/,
+                  const uint8_t* chunk_decay, int64_t first_chunk, int64_t n_chunks, OptArgs a, hipStream_t st);
+void sgdm_chunks(float* w, const float* g, float* m, void* shadow, const uint8_t* chunk_decay, int64_t first_chunk,
+                 int64_t n_chunks, OptArgs a, hipStream_t st);
+
+}  // namespace pt

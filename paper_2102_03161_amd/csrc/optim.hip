@@ -1,0 +1,125 @@
+// Per-layer gradient norms (Eq. 1's ||g_l||) and the fused optimizers.
+//
+// All parameter tensors live in one arena, each padded to a multiple of
+// kChunk floats, ordered front end, block 0 .. L-1, head.  A layer is therefore
+// a contiguous chunk range and the active set [block k .. head] a contiguous
+// suffix, so both passes are single launches that stream the arena once with
+// 16-byte accesses.  Padding is zero in every arena and stays zero under both
+// update rules.
+#include "common.h"
+#include "kernels.h"
+
+namespace pt {
+
+__global__ __launch_bounds__(256) void sumsq_kernel(const float* __restrict__ g, float* __restrict__ chunk_sq,
+                                                    int64_t first_chunk) {
+  __shared__ float red[4];
+  const int64_t c = first_chunk + blockIdx.x;
+  const float4 v = reinterpret_cast<const float4*>(g + c * kChunk)[threadIdx.x];
+  float s = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  s = block_sum<4>(s, red);
+  if (threadIdx.x == 0) chunk_sq[c] = s;
+}
+void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t n_chunks, hipStream_t st) {
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(sumsq_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, g, chunk_sq, first_chunk);
+}
+
+// one workgroup per layer: fp64 sum of its chunk partials in a fixed order
+__global__ __launch_bounds__(256) void finalize_norms_kernel(const float* __restrict__ chunk_sq,
+                                                             const int64_t* __restrict__ group_first, int G,
+                                                             int first_active, int front_active,
+                                                             float* __restrict__ norms) {
+  __shared__ double red[256];
+  const int grp = blockIdx.x;
+  const bool active = (grp == 0) ? (front_active != 0) : (grp >= first_active);
+  if (!active) {
+    if (threadIdx.x == 0) norms[grp] = 0.f;
+    return;
+  }
+  const int64_t lo = group_first[grp], hi = group_first[grp + 1];
+  double s = 0.0;
+  for (int64_t c = lo + threadIdx.x; c < hi; c += 256) s += (double)chunk_sq[c];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) norms[grp] = (float)sqrt(red[0]);
+}
+void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk, int G, int first_active, int front_active,
+                    float* norms, hipStream_t st) {
+  hipLaunchKernelGGL(finalize_norms_kernel, dim3(G), dim3(256), 0, st, chunk_sq, group_first_chunk, G, first_active,
+                     front_active, norms);
+}
+
+__device__ __forceinline__ void store_shadow4(bf16* p, float a, float b, float c, float d) {
+  union { bf16 h[4]; uint2 u; } t;
+  t.h[0] = from_f32<bf16>(a); t.h[1] = from_f32<bf16>(b); t.h[2] = from_f32<bf16>(c); t.h[3] = from_f32<bf16>(d);
+  *reinterpret_cast<uint2*>(p) = t.u;
+}
+
+__global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                                    float* __restrict__ m, float* __restrict__ v,
+                                                    bf16* __restrict__ shadow, const uint8_t* __restrict__ chunk_decay,
+                                                    int64_t first_chunk, OptArgs a) {
+  const int64_t c = first_chunk + blockIdx.x;
+  const int64_t i = c * kChunk + 4 * threadIdx.x;
+  const float shrink = chunk_decay[c] ? (1.0f - a.lr * a.weight_decay) : 1.0f;
+  float4 wv = *reinterpret_cast<float4*>(w + i);
+  const float4 gv = *reinterpret_cast<const float4*>(g + i);
+  float4 mv = *reinterpret_cast<float4*>(m + i);
+  float4 vv = *reinterpret_cast<float4*>(v + i);
+  float* wp = &wv.x; const float* gp = &gv.x; float* mp = &mv.x; float* vp = &vv.x;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float gg = gp[e];
+    const float mm = a.beta1 * mp[e] + (1.0f - a.beta1) * gg;
+    const float v2 = a.beta2 * vp[e] + (1.0f - a.beta2) * gg * gg;
+    mp[e] = mm;
+    vp[e] = v2;
+    wp[e] = wp[e] * shrink - a.lr * (mm / a.bias_c1) / (sqrtf(v2 / a.bias_c2) + a.eps);
+  }
+  *reinterpret_cast<float4*>(w + i) = wv;
+  *reinterpret_cast<float4*>(m + i) = mv;
+  *reinterpret_cast<float4*>(v + i) = vv;
+  if (shadow) store_shadow4(shadow + i, wv.x, wv.y, wv.z, wv.w);
+}
+void adamw_chunks(float* w, const float* g, float* m, float* v, void* shadow, const uint8_t* chunk_decay,
+                  int64_t first_chunk, int64_t n_chunks, OptArgs a, hipStream_t st) {
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, v, (bf16*)shadow, chunk_decay,
+                     first_chunk, a);
+}
+
+__global__ __launch_bounds__(256) void sgdm_kernel(float* __restrict__ w, const float* __restrict__ g,
+                                                   float* __restrict__ m, bf16* __restrict__ shadow,
+                                                   const uint8_t* __restrict__ chunk_decay, int64_t first_chunk,
+                                                   OptArgs a) {
+  const int64_t c = first_chunk + blockIdx.x;
+  const int64_t i = c * kChunk + 4 * threadIdx.x;
+  const float wd = chunk_decay[c] ? a.weight_decay : 0.0f;
+  float4 wv = *reinterpret_cast<float4*>(w + i);
+  const float4 gv = *reinterpret_cast<const float4*>(g + i);
+  float4 mv = *reinterpret_cast<float4*>(m + i);
+  float* wp = &wv.x; const float* gp = &gv.x; float* mp = &mv.x;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float gg = gp[e] + wd * wp[e];
+    const float mm = a.momentum * mp[e] + gg;
+    mp[e] = mm;
+    wp[e] = wp[e] - a.lr * mm;
+  }
+  *reinterpret_cast<float4*>(w + i) = wv;
+  *reinterpret_cast<float4*>(m + i) = mv;
+  if (shadow) store_shadow4(shadow + i, wv.x, wv.y, wv.z, wv.w);
+}
+void sgdm_chunks(float* w, const float* g, float* m, void* shadow, const uint8_t* chunk_decay, int64_t first_chunk,
+                 int64_t n_chunks, OptArgs a, hipStream_t st) {
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(sgdm_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, (bf16*)shadow, chunk_decay,
+                     first_chunk, a);
+}
+
+}  // namespace pt

@@ -1,0 +1,840 @@
+// C ABI and step orchestration: tensor table, arena plan, freeze-boundary
+// state machine, activation-cache index, and the sequence of kernel launches
+// for F_frozen (forward only, nothing kept) and F_pipe (forward with saved
+// tensors, loss, backward).  Host code only; kernels live in the other files.
+#include "../../include/pt.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_set>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace pt;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+struct TensorDesc {
+  std::string name;
+  int64_t numel;
+  int rows, cols;
+  int group;
+  bool decayed;
+  int64_t offset;  // floats from the start of each per-parameter arena, multiple of kChunk
+  int64_t padded;
+};
+
+const char* const kBlockNames[12] = {"ln1_g", "ln1_b", "Wqkv", "bqkv", "Wo", "bo",
+                                     "ln2_g", "ln2_b", "W1",   "b1",   "W2", "b2"};
+enum BlockTensor { LN1_G, LN1_B, WQKV, BQKV, WO, BO, LN2_G, LN2_B, W1, B1, W2, B2 };
+
+// byte offsets into the work arena of the tensors one block keeps
+struct Slot {
+  size_t U, QKV, CTX, Y, WN, HP, G, LSE, MU1, RS1, MU2, RS2;
+};
+
+struct Plan {
+  std::vector<TensorDesc> tensors;
+  int64_t arena_floats = 0;
+  std::vector<int64_t> group_first_chunk;  // G+1
+  size_t params_bytes = 0, state_bytes = 0, work_bytes = 0, cache_bytes = 0;
+  // work arena
+  std::vector<size_t> X;   // L+1 block inputs / outputs
+  std::vector<Slot> slot;  // L+1 (slot L: scratch of the forward-only prefix)
+  size_t HKOUT, dA, dB, dF, dT1, dT2, dQKV, DELTA;
+  size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
+  size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
+  size_t LOSS, NORMS, LNPART, CSPART, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
+  size_t idx_capacity = 0, stage_floats = 0;
+};
+
+bool validate(const pt_config& c, std::string* why) {
+  auto bad = [&](const char* m) { if (why) *why = m; return false; };
+  if (c.arch != PT_VIT_PRELN && c.arch != PT_BERT_POSTLN) return bad("arch");
+  if (c.dtype != PT_F32 && c.dtype != PT_BF16) return bad("dtype");
+  if (c.optimizer != PT_SGDM && c.optimizer != PT_ADAMW) return bad("optimizer");
+  if (c.L < 1 || c.L > 512 || c.D < 8 || c.H < 1 || c.F < 4 || c.S < 1 || c.B < 1 || c.n_out < 1) return bad("sizes");
+  if (c.D % c.H) return bad("D % H");
+  const int dh = c.D / c.H;
+  if (dh % 8 || dh > 128) return bad("head size must be a multiple of 8 and at most 128");
+  if (c.D > 2048 || c.F % 4) return bad("D <= 2048, F % 4 == 0");
+  if (c.arch == PT_VIT_PRELN) {
+    if (c.img < 1 || c.patch < 1 || c.chans < 1 || c.img % c.patch) return bad("image / patch");
+    const int g = c.img / c.patch;
+    if (g * g + 1 != c.S) return bad("S must be (img/patch)^2 + 1");
+  } else {
+    if (c.vocab < 1 || c.max_pos < c.S) return bad("vocab / max_pos");
+    if (c.n_out != 2) return bad("BERT span-QA head has n_out = 2");
+  }
+  if (c.cache_slots < 0) return bad("cache_slots");
+  if (!(c.ln_eps >= 0.f)) return bad("ln_eps");
+  if ((int64_t)c.B * c.S > (1 << 24)) return bad("B*S too large");
+  return true;
+}
+
+void make_plan(const pt_config& c, Plan* p) {
+  const int L = c.L, D = c.D, F = c.F, S = c.S, B = c.B;
+  const size_t e = c.dtype == PT_BF16 ? 2 : 4;
+  auto add = [&](const std::string& name, int rows, int cols, int group, bool dec) {
+    TensorDesc t;
+    t.name = name; t.rows = rows; t.cols = cols; t.numel = (int64_t)rows * cols; t.group = group; t.decayed = dec;
+    t.offset = p->arena_floats;
+    t.padded = (t.numel + kChunk - 1) / kChunk * kChunk;
+    p->arena_floats += t.padded;
+    p->tensors.push_back(t);
+  };
+  p->group_first_chunk.push_back(0);
+  if (c.arch == PT_VIT_PRELN) {
+    add("front.W_pe", c.chans * c.patch * c.patch, D, 0, true);
+    add("front.b_pe", 1, D, 0, false);
+    add("front.cls", 1, D, 0, false);
+    add("front.pos", S, D, 0, false);
+  } else {
+    add("front.E_w", c.vocab, D, 0, true);
+    add("front.E_p", c.max_pos, D, 0, false);
+    add("front.ln_g", 1, D, 0, false);
+    add("front.ln_b", 1, D, 0, false);
+  }
+  p->group_first_chunk.push_back(p->arena_floats / kChunk);
+  for (int l = 0; l < L; ++l) {
+    const std::string pre = "blk" + std::to_string(l) + ".";
+    const int rows[12] = {1, 1, D, 1, D, 1, 1, 1, D, 1, F, 1};
+    const int cols[12] = {D, D, 3 * D, 3 * D, D, D, D, D, F, F, D, D};
+    for (int j = 0; j < 12; ++j) add(pre + kBlockNames[j], rows[j], cols[j], 1 + l, j == WQKV || j == WO || j == W1 || j == W2);
+    p->group_first_chunk.push_back(p->arena_floats / kChunk);
+  }
+  if (c.arch == PT_VIT_PRELN) {
+    add("head.ln_g", 1, D, L + 1, false);
+    add("head.ln_b", 1, D, L + 1, false);
+  }
+  add("head.W", D, c.n_out, L + 1, true);
+  add("head.b", 1, c.n_out, L + 1, false);
+  p->group_first_chunk.push_back(p->arena_floats / kChunk);
+
+  const size_t P = (size_t)p->arena_floats;
+  p->params_bytes = align_up(P * 4) + (c.dtype == PT_BF16 ? align_up(P * 2) : 0);
+  p->state_bytes = align_up(P * 4) * (c.optimizer == PT_ADAMW ? 3 : 2);
+  p->cache_bytes = (size_t)c.cache_slots * S * D * e;
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
+  const size_t T = (size_t)B * S;
+  const size_t TD = T * D * e, TF = T * F * e, BHS = (size_t)B * c.H * S * 4;
+  p->X.resize(L + 1);
+  for (int l = 0; l <= L; ++l) p->X[l] = take(TD);
+  p->slot.resize(L + 1);
+  for (int l = 0; l <= L; ++l) {
+    Slot& s = p->slot[l];
+    s.U = take(TD); s.QKV = take(3 * TD); s.CTX = take(TD); s.Y = take(TD); s.WN = take(TD);
+    s.HP = take(TF); s.G = take(TF); s.LSE = take(BHS);
+    s.MU1 = take(T * 4); s.RS1 = take(T * 4); s.MU2 = take(T * 4); s.RS2 = take(T * 4);
+  }
+  p->HKOUT = take(TD);
+  p->dA = take(TD); p->dB = take(TD); p->dF = take(TF); p->dT1 = take(TD); p->dT2 = take(TD);
+  p->dQKV = take(3 * TD); p->DELTA = take(BHS);
+  if (c.arch == PT_VIT_PRELN) {
+    const size_t np = (size_t)B * (S - 1);
+    p->PATCH = take(np * c.chans * c.patch * c.patch * e);
+    p->EMB = take(np * D * e);
+    p->DEMB = take(np * D * e);
+    p->MUE = p->RSE = p->CHAINWS = 0;
+    p->CFEAT = take((size_t)B * D * e); p->MUF = take((size_t)B * 4); p->RSF = take((size_t)B * 4);
+    p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); p->DC = take((size_t)B * D * e);
+  } else {
+    p->PATCH = 0;
+    p->EMB = take(TD); p->DEMB = take(TD); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take(T * 8);
+    p->CFEAT = p->MUF = p->RSF = p->DC = 0;
+    p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4);
+  }
+  p->LOSSROWS = take((size_t)B * 4);
+  p->LOSS = take(4);
+  p->NORMS = take((size_t)(L + 2) * 4);
+  p->LNPART = take(ln_partial_floats(D) * 4);
+  const int maxn = std::max(std::max(3 * D, F), c.n_out);
+  p->CSPART = take(colsum_partial_floats(maxn) * 4);
+  p->QAPART = take(qa_partial_floats(D) * 4);
+  const size_t nchunks = P / kChunk;
+  p->CHUNKDECAY = take(nchunks);
+  p->GROUPFIRST = take((size_t)(L + 3) * 8);
+  p->CHUNKSQ = take(nchunks * 4);
+  p->idx_capacity = (size_t)16 * B;  // two turns of up to 8 index arrays of B entries
+  p->IDX = take(p->idx_capacity * 8);
+  int64_t maxt = 0;
+  for (auto& t : p->tensors) maxt = std::max(maxt, t.numel);
+  p->stage_floats = std::max<size_t>({(size_t)maxt, T * D, T * 2, (size_t)B * c.n_out});
+  p->STAGE = take(p->stage_floats * 4);
+  p->work_bytes = off;
+}
+
+}  // namespace
+
+struct pt_ctx {
+  pt_config cfg;
+  Plan plan;
+  int dt = 0;
+  size_t esz = 4;
+  hipStream_t st = nullptr;
+  float* master = nullptr;
+  char* shadow = nullptr;  // bf16 [P] or null
+  float* grads = nullptr;
+  float* mom1 = nullptr;
+  float* mom2 = nullptr;
+  char* work = nullptr;
+  char* cache = nullptr;
+  int k = 0;
+  int64_t step = 0;
+  int phase = 0;  // 0 idle, 1 frozen forward done, 2 backward done
+  int nb = 0;
+  const void* last_input = nullptr;
+  void* last_hk = nullptr;
+  void* last_dhk = nullptr;
+  std::vector<int32_t> slot_k;  // boundary a cache row was written at, -1 = empty
+  int64_t n_hit = 0, n_adv = 0, n_miss = 0, n_runs = 0;
+  // pinned host staging for index arrays, double-buffered by call parity
+  int64_t* h_idx[2] = {nullptr, nullptr};
+  hipEvent_t idx_ev[2] = {nullptr, nullptr};
+  bool idx_ev_used[2] = {false, false};
+  int idx_turn = 0;
+  mutable std::string err;
+
+  const void* cp(int id) const {  // parameter as the kernels read it
+    const TensorDesc& t = plan.tensors[id];
+    return dt ? (const void*)(shadow + t.offset * 2) : (const void*)(master + t.offset);
+  }
+  float* gp(int id) const { return grads + plan.tensors[id].offset; }
+  void* w(size_t off) const { return work + off; }
+  float* wf(size_t off) const { return reinterpret_cast<float*>(work + off); }
+  int blk(int l, int j) const { return 4 + 12 * l + j; }
+  int head(int j) const { return 4 + 12 * cfg.L + j; }  // ViT: ln_g, ln_b, W, b; BERT: W, b
+};
+
+namespace {
+
+pt_status fail(const pt_ctx* c, pt_status s, const std::string& m) {
+  if (c) c->err = m;
+  return s;
+}
+#define HIP_TRY(ctx, expr)                                                                  \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(ctx, PT_EDEVICE, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// one encoder block, forward.  save == false: forward-only (nothing kept).
+// ---------------------------------------------------------------------------
+void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s, int ns, bool save) {
+  const pt_config& g = c->cfg;
+  const int D = g.D, F = g.F, Tn = ns * g.S, dt = c->dt;
+  hipStream_t st = c->st;
+  float* lse = save ? c->wf(s.LSE) : nullptr;
+  float* mu1 = save ? c->wf(s.MU1) : nullptr; float* rs1 = save ? c->wf(s.RS1) : nullptr;
+  float* mu2 = save ? c->wf(s.MU2) : nullptr; float* rs2 = save ? c->wf(s.RS2) : nullptr;
+  auto lin = [&](const void* A, int K, int wid, int bid, void* C, int N, Epi epi, const void* aux, void* aux_out) {
+    Gemm m;
+    m.A = A; m.lda = K; m.B = c->cp(wid); m.ldb = N; m.C = C; m.ldc = N; m.M = Tn; m.N = N; m.K = K;
+    m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = N;
+    gemm(dt, m, st);
+  };
+  if (g.arch == PT_VIT_PRELN) {
+    layernorm_fwd(dt, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    lin(c->w(s.U), D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
+    attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
+    lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.Y), D, EPI_BIAS_RES, xin, nullptr);
+    layernorm_fwd(dt, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st);
+    lin(c->w(s.WN), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
+    lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), xout, D, EPI_BIAS_RES, c->w(s.Y), nullptr);
+  } else {
+    // post-LN: U holds x + Attn(x), Y = LN1(U), WN holds Y + MLP(Y), out = LN2(WN)
+    lin(xin, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
+    attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
+    lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.U), D, EPI_BIAS_RES, xin, nullptr);
+    layernorm_fwd(dt, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    lin(c->w(s.Y), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
+    lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), c->w(s.WN), D, EPI_BIAS_RES, c->w(s.Y), nullptr);
+    layernorm_fwd(dt, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// one encoder block, backward.  dout: gradient wrt the block output; dxin:
+// gradient wrt its input (written iff need_dx, except that the pre-LN path
+// always produces it on the way to the LN1 parameter gradients).
+// ---------------------------------------------------------------------------
+void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, const void* dout, void* dxin, int ns, bool need_dx) {
+  const pt_config& g = c->cfg;
+  const int D = g.D, F = g.F, Tn = ns * g.S, dt = c->dt;
+  hipStream_t st = c->st;
+  const Plan& p = c->plan;
+  float* lnp = c->wf(p.LNPART);
+  float* csp = c->wf(p.CSPART);
+  void* dF = c->w(p.dF); void* dT1 = c->w(p.dT1); void* dT2 = c->w(p.dT2); void* dQKV = c->w(p.dQKV);
+  // dW[K_in, N_out] = X^T dY ; db = colsum(dY)
+  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid) {
+    Gemm m;
+    m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
+    m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
+    gemm(dt, m, st);
+    colsum(dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st);
+  };
+  // dX[Tn, K_in] = dY W^T (+ epilogue)
+  auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux) {
+    Gemm m;
+    m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
+    m.M = Tn; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin;
+    gemm(dt, m, st);
+  };
+  if (g.arch == PT_VIT_PRELN) {
+    wgrad(c->w(s.G), F, dout, D, c->blk(l, W2), c->blk(l, B2));
+    dgrad(dout, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP));
+    wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1), c->blk(l, B1));
+    dgrad(dF, F, c->blk(l, W1), dT1, D, EPI_STORE, nullptr);
+    layernorm_bwd(dt, dT1, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout, D, dT2, D,
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // dT2 = dL/dY
+    wgrad(c->w(s.CTX), D, dT2, D, c->blk(l, WO), c->blk(l, BO));
+    dgrad(dT2, D, c->blk(l, WO), dT1, D, EPI_STORE, nullptr);                           // dT1 = dL/dCTX
+    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dT1, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
+    dgrad(dQKV, 3 * D, c->blk(l, WQKV), dT1, D, EPI_STORE, nullptr);                    // dT1 = dL/dU
+    layernorm_bwd(dt, dT1, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dT2, D, dxin, D,
+                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);
+  } else {
+    layernorm_bwd(dt, dout, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, dT1, D,
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // dT1 = dL/d(Y+MLP)
+    wgrad(c->w(s.G), F, dT1, D, c->blk(l, W2), c->blk(l, B2));
+    dgrad(dT1, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP));
+    wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
+    dgrad(dF, F, c->blk(l, W1), dT2, D, EPI_RES, dT1);                                  // dT2 = dL/dY
+    layernorm_bwd(dt, dT2, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, dT1, D,
+                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);  // dT1 = dL/d(x+Attn)
+    wgrad(c->w(s.CTX), D, dT1, D, c->blk(l, WO), c->blk(l, BO));
+    dgrad(dT1, D, c->blk(l, WO), dT2, D, EPI_STORE, nullptr);                           // dT2 = dL/dCTX
+    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dT2, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
+    if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dxin, D, EPI_RES, dT1);
+  }
+}
+
+// front end over `ns` samples; sample i reads input map[i] (device, or null = identity)
+void front_forward(pt_ctx* c, const void* d_input, const int64_t* d_map, void* xout, int ns, bool save) {
+  const pt_config& g = c->cfg;
+  const Plan& p = c->plan;
+  const int D = g.D, dt = c->dt;
+  hipStream_t st = c->st;
+  if (g.arch == PT_VIT_PRELN) {
+    const int pd = g.chans * g.patch * g.patch, np = ns * (g.S - 1);
+    vit_patchify(dt, (const float*)d_input, d_map, c->w(p.PATCH), ns, g.chans, g.img, g.patch, st);
+    Gemm m;
+    m.A = c->w(p.PATCH); m.lda = pd; m.B = c->cp(0); m.ldb = D; m.C = c->w(p.EMB); m.ldc = D;
+    m.M = np; m.N = D; m.K = pd; m.epi = EPI_BIAS; m.bias = c->cp(1);
+    gemm(dt, m, st);
+    vit_assemble(dt, c->w(p.EMB), c->cp(2), c->cp(3), xout, ns, g.S, D, st);
+  } else {
+    bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->w(p.EMB), ns, g.S, D, st);
+    layernorm_fwd(dt, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
+                  save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st);
+  }
+}
+
+void front_backward(pt_ctx* c, const void* dx, int ns) {
+  const pt_config& g = c->cfg;
+  const Plan& p = c->plan;
+  const int D = g.D, dt = c->dt;
+  hipStream_t st = c->st;
+  if (g.arch == PT_VIT_PRELN) {
+    const int pd = g.chans * g.patch * g.patch, np = ns * (g.S - 1);
+    vit_front_bwd(dt, dx, c->w(p.DEMB), c->gp(3), c->gp(2), ns, g.S, D, st);
+    Gemm m;
+    m.A = c->w(p.PATCH); m.lda = pd; m.ta = true; m.B = c->w(p.DEMB); m.ldb = D; m.C = c->gp(0); m.ldc = D;
+    m.M = pd; m.N = D; m.K = np; m.c_f32 = true;
+    gemm(dt, m, st);
+    colsum(dt, c->w(p.DEMB), D, np, D, c->gp(1), c->wf(p.CSPART), st);
+  } else {
+    layernorm_bwd(dt, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->w(p.DEMB), D,
+                  c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st);
+    fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
+    fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
+    bert_embed_bwd(dt, (const int32_t*)c->last_input, c->w(p.DEMB), c->gp(0), c->gp(1),
+                   reinterpret_cast<int32_t*>(c->w(p.CHAINWS)), ns, g.S, D, st);
+  }
+}
+
+// stage `n` int64 values for the device; returns the device pointer
+struct IdxStager {
+  pt_ctx* c;
+  int turn;
+  size_t used = 0;
+  explicit IdxStager(pt_ctx* ctx) : c(ctx), turn(ctx->idx_turn) {}
+  hipError_t begin() {
+    if (c->idx_ev_used[turn]) return hipEventSynchronize(c->idx_ev[turn]);
+    return hipSuccess;
+  }
+  const int64_t* put(const std::vector<int64_t>& v, hipError_t* e) {
+    if (v.empty()) return nullptr;
+    int64_t* h = c->h_idx[turn] + used;
+    std::memcpy(h, v.data(), v.size() * 8);
+    int64_t* d = reinterpret_cast<int64_t*>(c->w(c->plan.IDX)) + (size_t)turn * (c->plan.idx_capacity / 2) + used;
+    hipError_t r = hipMemcpyAsync(d, h, v.size() * 8, hipMemcpyHostToDevice, c->st);
+    if (r != hipSuccess) *e = r;
+    used += v.size();
+    return d;
+  }
+  hipError_t end() {
+    hipError_t r = hipEventRecord(c->idx_ev[turn], c->st);
+    c->idx_ev_used[turn] = true;
+    c->idx_turn ^= 1;
+    return r;
+  }
+};
+
+}  // namespace
+
+// ===========================================================================
+// C ABI
+// ===========================================================================
+extern "C" {
+
+pt_status pt_query_arena_bytes(const pt_config* cfg, size_t* params, size_t* state, size_t* work, size_t* cache) {
+  if (!cfg || !params || !state || !work || !cache) return PT_EINVAL;
+  if (!validate(*cfg, nullptr)) return PT_EINVAL;
+  Plan p;
+  make_plan(*cfg, &p);
+  *params = p.params_bytes; *state = p.state_bytes; *work = p.work_bytes; *cache = p.cache_bytes;
+  return PT_OK;
+}
+
+pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d_work, void* d_cache, void* hip_stream,
+                    pt_ctx** out) {
+  if (!cfg || !out || !d_params || !d_state || !d_work) return PT_EINVAL;
+  if (!validate(*cfg, nullptr)) return PT_EINVAL;
+  if (cfg->cache_slots > 0 && !d_cache) return PT_EINVAL;
+  for (const void* q : {d_params, d_state, d_work, (void*)d_cache})
+    if (reinterpret_cast<uintptr_t>(q) % kAlign) return PT_EINVAL;
+  pt_ctx* c = new (std::nothrow) pt_ctx();
+  if (!c) return PT_ENOMEM;
+  c->cfg = *cfg;
+  make_plan(*cfg, &c->plan);
+  c->dt = cfg->dtype == PT_BF16 ? 1 : 0;
+  c->esz = c->dt ? 2 : 4;
+  c->st = reinterpret_cast<hipStream_t>(hip_stream);
+  const size_t P = (size_t)c->plan.arena_floats;
+  c->master = reinterpret_cast<float*>(d_params);
+  c->shadow = c->dt ? reinterpret_cast<char*>(d_params) + align_up(P * 4) : nullptr;
+  c->grads = reinterpret_cast<float*>(d_state);
+  c->mom1 = reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + align_up(P * 4));
+  c->mom2 = cfg->optimizer == PT_ADAMW ? reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + 2 * align_up(P * 4)) : nullptr;
+  c->work = reinterpret_cast<char*>(d_work);
+  c->cache = reinterpret_cast<char*>(d_cache);
+  c->slot_k.assign((size_t)cfg->cache_slots, -1);
+  auto cleanup = [&]() {
+    for (int i = 0; i < 2; ++i) {
+      if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
+      if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
+    }
+    delete c;
+  };
+#define CREATE_TRY(expr)                         \
+  do {                                           \
+    if ((expr) != hipSuccess) { cleanup(); return PT_EDEVICE; } \
+  } while (0)
+  for (int i = 0; i < 2; ++i) {
+    CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_idx[i]), (c->plan.idx_capacity / 2) * 8, hipHostMallocDefault));
+    CREATE_TRY(hipEventCreateWithFlags(&c->idx_ev[i], hipEventDisableTiming));
+  }
+  fill_zero(d_params, c->plan.params_bytes, c->st);
+  fill_zero(d_state, c->plan.state_bytes, c->st);
+  // chunk tables
+  const size_t nchunks = P / kChunk;
+  std::vector<uint8_t> decay(nchunks, 0);
+  for (auto& t : c->plan.tensors)
+    if (t.decayed)
+      for (int64_t ch = t.offset / kChunk; ch < (t.offset + t.padded) / kChunk; ++ch) decay[(size_t)ch] = 1;
+  CREATE_TRY(hipMemcpyAsync(c->w(c->plan.CHUNKDECAY), decay.data(), nchunks, hipMemcpyHostToDevice, c->st));
+  CREATE_TRY(hipMemcpyAsync(c->w(c->plan.GROUPFIRST), c->plan.group_first_chunk.data(),
+                            c->plan.group_first_chunk.size() * 8, hipMemcpyHostToDevice, c->st));
+  CREATE_TRY(hipStreamSynchronize(c->st));
+#undef CREATE_TRY
+  *out = c;
+  return PT_OK;
+}
+
+pt_status pt_destroy(pt_ctx* c) {
+  if (!c) return PT_EINVAL;
+  (void)hipStreamSynchronize(c->st);
+  for (int i = 0; i < 2; ++i) {
+    if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
+    if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
+  }
+  delete c;
+  return PT_OK;
+}
+
+const char* pt_last_error(const pt_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+pt_status pt_get_freeze_boundary(const pt_ctx* c, int32_t* k) {
+  if (!c || !k) return PT_EINVAL;
+  *k = c->k;
+  return PT_OK;
+}
+
+pt_status pt_set_freeze_boundary(pt_ctx* c, int32_t k) {
+  if (!c) return PT_EINVAL;
+  if (k < 0 || k > c->cfg.L) return fail(c, PT_EINVAL, "boundary outside 0..L");
+  if (k < c->k) return fail(c, PT_EINVAL, "the boundary never moves down");
+  if (k == c->k) return PT_OK;
+  // newly frozen: front end (if the old boundary was 0) and blocks k_old..k-1
+  const auto& gf = c->plan.group_first_chunk;
+  const int64_t lo = (c->k == 0 ? gf[0] : gf[c->k + 1]) * kChunk, hi = gf[k + 1] * kChunk;
+  fill_zero(c->grads + lo, (size_t)(hi - lo) * 4, c->st);
+  fill_zero(c->mom1 + lo, (size_t)(hi - lo) * 4, c->st);
+  if (c->mom2) fill_zero(c->mom2 + lo, (size_t)(hi - lo) * 4, c->st);
+  c->k = k;
+  c->phase = 0;
+  return PT_OK;
+}
+
+pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const int64_t* sample_ids, void** d_hk_out) {
+  if (!c || !d_input || !d_hk_out) return PT_EINVAL;
+  const pt_config& g = c->cfg;
+  const Plan& p = c->plan;
+  if (nb < 1 || nb > g.B) return fail(c, PT_EINVAL, "batch outside 1..B");
+  const int k = c->k;
+  const size_t row_bytes = (size_t)g.S * g.D * c->esz;
+  if (k == 0) {
+    front_forward(c, d_input, nullptr, c->w(p.X[0]), nb, true);
+    c->last_hk = c->w(p.X[0]);
+  } else {
+    const bool use_cache = sample_ids && g.cache_slots > 0;
+    std::vector<int> kw(nb, -1);
+    if (use_cache) {
+      std::unordered_set<int64_t> seen;
+      for (int i = 0; i < nb; ++i) {
+        if (sample_ids[i] < 0 || sample_ids[i] >= g.cache_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
+        if (!seen.insert(sample_ids[i]).second) return fail(c, PT_EINVAL, "duplicate sample id in a batch");
+        kw[i] = c->slot_k[(size_t)sample_ids[i]];
+      }
+    }
+    // sorted order: misses first, then by the boundary the row was written at (stable)
+    std::vector<int> order(nb);
+    for (int i = 0; i < nb; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return kw[a] < kw[b]; });
+    bool identity = true;
+    for (int i = 0; i < nb; ++i) identity = identity && order[i] == i;
+    int n_miss = 0, n_hit = 0;
+    for (int i = 0; i < nb; ++i) { n_miss += kw[i] < 0; n_hit += kw[i] == k; }
+    IdxStager stg(c);
+    HIP_TRY(c, stg.begin());
+    hipError_t cerr = hipSuccess;
+    if (n_hit == nb) {
+      // every sample is a hit: one gather from the cache, no block runs
+      std::vector<int64_t> src(nb);
+      for (int i = 0; i < nb; ++i) src[i] = sample_ids[i];
+      const int64_t* dsrc = stg.put(src, &cerr);
+      copy_rows(c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st);
+      c->last_hk = c->w(p.HKOUT);
+    } else {
+      if (n_miss > 0) {
+        const int64_t* dmap = nullptr;
+        if (!(identity && n_miss == nb)) {
+          std::vector<int64_t> map(n_miss);
+          for (int i = 0; i < n_miss; ++i) map[i] = order[i];
+          dmap = stg.put(map, &cerr);
+        }
+        front_forward(c, d_input, dmap, c->w(p.X[0]), n_miss, false);
+      }
+      // level j: rows written at j join at their sorted positions, then block j runs on the prefix
+      for (int j = 0; j <= k; ++j) {
+        std::vector<int64_t> dst, src;
+        int n_le = 0;
+        for (int i = 0; i < nb; ++i) {
+          if (kw[order[i]] == j) { dst.push_back(i); src.push_back(sample_ids[order[i]]); }
+          n_le += kw[order[i]] <= j;
+        }
+        if (!dst.empty()) {
+          const int64_t* ddst = stg.put(dst, &cerr);
+          const int64_t* dsrc = stg.put(src, &cerr);
+          copy_rows(c->w(p.X[j]), ddst, c->cache, dsrc, (int)dst.size(), row_bytes, c->st);
+        }
+        // the sorted prefix of n_le samples (misses and rows written at or below j) runs block j
+        if (j < k && n_le > 0) {
+          block_forward(c, j, c->w(p.X[j]), c->w(p.X[j + 1]), p.slot[g.L], n_le, false);
+          c->n_runs += n_le;
+        }
+      }
+      if (use_cache) {
+        std::vector<int64_t> dst, src;
+        for (int i = 0; i < nb; ++i)
+          if (kw[order[i]] < k) { dst.push_back(sample_ids[order[i]]); src.push_back(i); }
+        const int64_t* ddst = stg.put(dst, &cerr);
+        const int64_t* dsrc = stg.put(src, &cerr);
+        copy_rows(c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st);
+      }
+      if (identity) {
+        c->last_hk = c->w(p.X[k]);
+      } else {
+        std::vector<int64_t> dst(nb);
+        for (int i = 0; i < nb; ++i) dst[i] = order[i];
+        const int64_t* ddst = stg.put(dst, &cerr);
+        copy_rows(c->w(p.HKOUT), ddst, c->w(p.X[k]), nullptr, nb, row_bytes, c->st);
+        c->last_hk = c->w(p.HKOUT);
+      }
+    }
+    HIP_TRY(c, stg.end());
+    if (cerr != hipSuccess) return fail(c, PT_EDEVICE, hipGetErrorString(cerr));
+    if (use_cache)
+      for (int i = 0; i < nb; ++i) {
+        if (kw[i] < 0) c->n_miss++; else if (kw[i] == k) c->n_hit++; else c->n_adv++;
+        c->slot_k[(size_t)sample_ids[i]] = k;
+      }
+  }
+  HIP_TRY(c, hipGetLastError());
+  c->nb = nb;
+  c->last_input = d_input;
+  c->phase = 1;
+  *d_hk_out = c->last_hk;
+  return PT_OK;
+}
+
+pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels, float* loss_out) {
+  if (!c || !d_hk || !d_labels) return PT_EINVAL;
+  if (c->phase < 1) return fail(c, PT_ESTATE, "pt_frozen_forward has not run for this step");
+  if (reinterpret_cast<uintptr_t>(d_hk) % 16) return fail(c, PT_EINVAL, "d_hk must be 16-byte aligned");
+  const pt_config& g = c->cfg;
+  const Plan& p = c->plan;
+  const int L = g.L, D = g.D, S = g.S, k = c->k, nb = c->nb, dt = c->dt;
+  hipStream_t st = c->st;
+  // forward through the active blocks, keeping what the backward pass reads
+  const void* x = d_hk;
+  for (int l = k; l < L; ++l) {
+    block_forward(c, l, x, c->w(p.X[l + 1]), p.slot[l], nb, true);
+    x = c->w(p.X[l + 1]);
+  }
+  void* dcur = c->w(p.dA);
+  void* dnext = c->w(p.dB);
+  // head, loss, head backward -> dcur = dL/dx_L
+  if (g.arch == PT_VIT_PRELN) {
+    const int C = g.n_out;
+    const int hg = c->head(0), hb = c->head(1), hW = c->head(2), hbias = c->head(3);
+    layernorm_fwd(dt, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st);
+    Gemm m;
+    m.A = c->w(p.CFEAT); m.lda = D; m.B = c->cp(hW); m.ldb = C; m.C = c->w(p.LOGITS); m.ldc = C;
+    m.M = nb; m.N = C; m.K = D; m.epi = EPI_BIAS; m.bias = c->cp(hbias); m.c_f32 = true;
+    gemm(dt, m, st);
+    ce_rows(dt, c->wf(p.LOGITS), d_labels, c->wf(p.LOSSROWS), c->w(p.DZ), nb, C, st);
+    mean_reduce(c->wf(p.LOSSROWS), nb, c->wf(p.LOSS), st);
+    Gemm wg;
+    wg.A = c->w(p.CFEAT); wg.lda = D; wg.ta = true; wg.B = c->w(p.DZ); wg.ldb = C; wg.C = c->gp(hW); wg.ldc = C;
+    wg.M = D; wg.N = C; wg.K = nb; wg.c_f32 = true;
+    gemm(dt, wg, st);
+    colsum(dt, c->w(p.DZ), C, nb, C, c->gp(hbias), c->wf(p.CSPART), st);
+    Gemm dg;
+    dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
+    dg.M = nb; dg.N = D; dg.K = C;
+    gemm(dt, dg, st);
+    fill_zero(dcur, (size_t)nb * S * D * c->esz, st);
+    layernorm_bwd(dt, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur,
+                  (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st);
+  } else {
+    const int hW = c->head(0), hbias = c->head(1);
+    qa_logits(dt, x, c->cp(hW), c->cp(hbias), c->wf(p.LOGITS), nb * S, D, st);
+    qa_ce(dt, c->wf(p.LOGITS), d_labels, c->wf(p.LOSSROWS), c->wf(p.DZ), nb, S, st);
+    mean_reduce(c->wf(p.LOSSROWS), nb, c->wf(p.LOSS), st);
+    qa_head_bwd(dt, x, c->cp(hW), c->wf(p.DZ), dcur, c->gp(hW), c->gp(hbias), c->wf(p.QAPART), nb * S, D, st);
+  }
+  // backward through the active blocks; stops at the boundary (Sec. 3.2.1)
+  for (int l = L - 1; l >= k; --l) {
+    const void* xin = (l == k) ? d_hk : c->w(p.X[l]);
+    const bool need_dx = (l > k) || (k == 0);
+    block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx);
+    std::swap(dcur, dnext);
+  }
+  if (k == 0) front_backward(c, dcur, nb);
+  c->last_dhk = dcur;
+  HIP_TRY(c, hipGetLastError());
+  c->phase = 2;
+  if (loss_out) return pt_last_loss(c, loss_out);
+  return PT_OK;
+}
+
+pt_status pt_last_loss(pt_ctx* c, float* loss_out) {
+  if (!c || !loss_out) return PT_EINVAL;
+  if (c->phase < 2) return fail(c, PT_ESTATE, "no loss has been computed");
+  HIP_TRY(c, hipMemcpyAsync(loss_out, c->w(c->plan.LOSS), 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  return PT_OK;
+}
+
+pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
+  if (!c || !norms_out) return PT_EINVAL;
+  if (c->phase != 2) return fail(c, PT_ESTATE, "gradient norms need a completed pt_active_fwd_bwd");
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st);
+  finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
+                 c->wf(c->plan.NORMS), c->st);
+  HIP_TRY(c, hipMemcpyAsync(norms_out, c->w(c->plan.NORMS), (size_t)G * 4, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  return PT_OK;
+}
+
+pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {
+  if (!c || !hp) return PT_EINVAL;
+  if (c->phase != 2) return fail(c, PT_ESTATE, "the optimizer needs a completed pt_active_fwd_bwd");
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  const int64_t t = c->step + 1;
+  OptArgs a;
+  a.lr = hp->lr; a.momentum = hp->momentum; a.beta1 = hp->beta1; a.beta2 = hp->beta2; a.eps = hp->eps;
+  a.weight_decay = hp->weight_decay;
+  a.bias_c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)t));
+  a.bias_c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)t));
+  const uint8_t* decay = reinterpret_cast<const uint8_t*>(c->w(c->plan.CHUNKDECAY));
+  if (c->cfg.optimizer == PT_ADAMW)
+    adamw_chunks(c->master, c->grads, c->mom1, c->mom2, c->shadow, decay, first, total - first, a, c->st);
+  else
+    sgdm_chunks(c->master, c->grads, c->mom1, c->shadow, decay, first, total - first, a, c->st);
+  HIP_TRY(c, hipGetLastError());
+  c->step = t;
+  c->phase = 0;
+  return PT_OK;
+}
+
+pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, float alpha, int32_t* k_next) {
+  if (!norms || !k_next || L < 1 || k_prev < 0 || k_prev > L || !(alpha > 0.f && alpha < 1.f)) return PT_EINVAL;
+  if (k_prev == L) { *k_next = L; return PT_OK; }
+  const int bound = (int)std::floor((double)k_prev + (double)alpha * (double)(L - k_prev));
+  int arg = k_prev;
+  for (int l = k_prev + 1; l < L; ++l)
+    if (norms[1 + l] < norms[1 + arg]) arg = l;
+  *k_next = std::max(k_prev, std::min(bound, arg));
+  return PT_OK;
+}
+
+// ---- tensor table ---------------------------------------------------------
+pt_status pt_num_tensors(const pt_ctx* c, int32_t* n) {
+  if (!c || !n) return PT_EINVAL;
+  *n = (int32_t)c->plan.tensors.size();
+  return PT_OK;
+}
+
+pt_status pt_tensor_info(const pt_ctx* c, int32_t id, char* name, size_t name_cap, int64_t* numel, int32_t* rows,
+                         int32_t* cols, int32_t* group, int32_t* decayed) {
+  if (!c || id < 0 || id >= (int)c->plan.tensors.size()) return PT_EINVAL;
+  const TensorDesc& t = c->plan.tensors[id];
+  if (name && name_cap) { std::strncpy(name, t.name.c_str(), name_cap - 1); name[name_cap - 1] = 0; }
+  if (numel) *numel = t.numel;
+  if (rows) *rows = t.rows;
+  if (cols) *cols = t.cols;
+  if (group) *group = t.group;
+  if (decayed) *decayed = t.decayed;
+  return PT_OK;
+}
+
+static float* kind_base(pt_ctx* c, int kind) {
+  switch (kind) {
+    case PT_KIND_PARAM: return c->master;
+    case PT_KIND_GRAD: return c->grads;
+    case PT_KIND_MOMENT1: return c->mom1;
+    case PT_KIND_MOMENT2: return c->mom2;
+    default: return nullptr;
+  }
+}
+
+pt_status pt_write_tensor(pt_ctx* c, int32_t id, int32_t kind, const float* src) {
+  if (!c || !src || id < 0 || id >= (int)c->plan.tensors.size()) return PT_EINVAL;
+  float* base = kind_base(c, kind);
+  if (!base) return fail(c, PT_EINVAL, "tensor kind not writable in this configuration");
+  const TensorDesc& t = c->plan.tensors[id];
+  HIP_TRY(c, hipMemcpyAsync(base + t.offset, src, (size_t)t.numel * 4, hipMemcpyHostToDevice, c->st));
+  if (kind == PT_KIND_PARAM && c->shadow) f32_to_bf16(c->master + t.offset, c->shadow + t.offset * 2, (size_t)t.numel, c->st);
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  return PT_OK;
+}
+
+pt_status pt_read_tensor(pt_ctx* c, int32_t id, int32_t kind, float* dst) {
+  if (!c || !dst || id < 0 || id >= (int)c->plan.tensors.size()) return PT_EINVAL;
+  const TensorDesc& t = c->plan.tensors[id];
+  if (kind == PT_KIND_SHADOW) {
+    if (!c->shadow) return fail(c, PT_EINVAL, "no bf16 shadow in fp32 mode");
+    bf16_to_f32(c->shadow + t.offset * 2, c->wf(c->plan.STAGE), (size_t)t.numel, c->st);
+    HIP_TRY(c, hipMemcpyAsync(dst, c->w(c->plan.STAGE), (size_t)t.numel * 4, hipMemcpyDeviceToHost, c->st));
+  } else {
+    float* base = kind_base(c, kind);
+    if (!base) return fail(c, PT_EINVAL, "tensor kind not present in this configuration");
+    HIP_TRY(c, hipMemcpyAsync(dst, base + t.offset, (size_t)t.numel * 4, hipMemcpyDeviceToHost, c->st));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  return PT_OK;
+}
+
+pt_status pt_get_step_count(const pt_ctx* c, int64_t* t) {
+  if (!c || !t) return PT_EINVAL;
+  *t = c->step;
+  return PT_OK;
+}
+pt_status pt_set_step_count(pt_ctx* c, int64_t t) {
+  if (!c || t < 0) return PT_EINVAL;
+  c->step = t;
+  return PT_OK;
+}
+
+pt_status pt_read_activation(pt_ctx* c, int32_t which, float* dst, size_t numel) {
+  if (!c || !dst) return PT_EINVAL;
+  const pt_config& g = c->cfg;
+  const size_t act = (size_t)c->nb * g.S * g.D;
+  const void* src = nullptr;
+  size_t n = 0;
+  bool is_f32 = c->dt == 0;
+  switch (which) {
+    case PT_ACT_HK: if (c->phase < 1) return fail(c, PT_ESTATE, "no boundary activation yet"); src = c->last_hk; n = act; break;
+    case PT_ACT_HL: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->k == g.L ? c->last_hk : c->w(c->plan.X[g.L]); n = act; break;
+    case PT_ACT_LOGITS: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->w(c->plan.LOGITS);
+      n = g.arch == PT_VIT_PRELN ? (size_t)c->nb * g.n_out : (size_t)c->nb * g.S * 2; is_f32 = true; break;
+    case PT_ACT_DHK: if (c->phase < 2) return fail(c, PT_ESTATE, "no backward pass yet"); src = c->last_dhk; n = act; break;
+    default: return fail(c, PT_EINVAL, "unknown activation");
+  }
+  if (numel != n) return fail(c, PT_EINVAL, "activation size mismatch");
+  if (is_f32) {
+    HIP_TRY(c, hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToHost, c->st));
+  } else {
+    bf16_to_f32(src, c->wf(c->plan.STAGE), n, c->st);
+    HIP_TRY(c, hipMemcpyAsync(dst, c->w(c->plan.STAGE), n * 4, hipMemcpyDeviceToHost, c->st));
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  return PT_OK;
+}
+
+pt_status pt_cache_row(pt_ctx* c, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k) {
+  if (!c || !dst) return PT_EINVAL;
+  if (sample_id < 0 || sample_id >= c->cfg.cache_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
+  const size_t row_bytes = (size_t)c->cfg.S * c->cfg.D * c->esz;
+  if (dst_bytes != row_bytes) return fail(c, PT_EINVAL, "row size mismatch");
+  if (c->slot_k[(size_t)sample_id] < 0) return PT_ECACHE_MISS;
+  HIP_TRY(c, hipMemcpyAsync(dst, c->cache + (size_t)sample_id * row_bytes, row_bytes, hipMemcpyDeviceToHost, c->st));
+  HIP_TRY(c, hipStreamSynchronize(c->st));
+  if (written_at_k) *written_at_k = c->slot_k[(size_t)sample_id];
+  return PT_OK;
+}
+
+pt_status pt_cache_stats(const pt_ctx* c, int64_t* hits, int64_t* advances, int64_t* misses, int64_t* block_runs) {
+  if (!c) return PT_EINVAL;
+  if (hits) *hits = c->n_hit;
+  if (advances) *advances = c->n_adv;
+  if (misses) *misses = c->n_miss;
+  if (block_runs) *block_runs = c->n_runs;
+  return PT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,584 @@
+// Memory-bound passes of the step: LayerNorm forward/backward, bias-gradient
+// column sums, front ends (ViT patch embedding plumbing, BERT embedding lookup
+// and its scatter-add), losses, and row copies for the activation cache.
+// Row reductions are wavefront shuffles (one 64-lane wave per row); reductions
+// across rows are two-stage with a fixed summation order, so every result is
+// reproducible run to run.
+#include "common.h"
+#include "kernels.h"
+
+namespace pt {
+
+// ---- 4-element vector access ------------------------------------------------
+__device__ __forceinline__ void load4(const float* p, float (&v)[4]) {
+  const float4 t = *reinterpret_cast<const float4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ __forceinline__ void load4(const bf16* p, float (&v)[4]) {
+  const uint2 t = *reinterpret_cast<const uint2*>(p);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+__device__ __forceinline__ void store4(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store4(bf16* p, const float (&v)[4]) {
+  union { bf16 h[4]; uint2 u; } t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t.h[i] = from_f32<bf16>(v[i]);
+  *reinterpret_cast<uint2*>(p) = t.u;
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm forward: one wave per row, row held in registers (D <= 256*VPL)
+// ---------------------------------------------------------------------------
+template <typename T, int VPL>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, int64_t ldx, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y, int64_t ldy,
+                                                     float* __restrict__ mean, float* __restrict__ rstd, int rows, int D,
+                                                     float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nvec = D >> 2;
+  const T* xr = x + (int64_t)row * ldx;
+  float v[VPL][4];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+      load4(xr + 4 * c, v[j]);
+      s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+    } else {
+      v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.f;
+    }
+  }
+  const float mu = wave_sum(s) / (float)D;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mu; q += d * d; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(q) / (float)D + eps);
+  if (lane == 0 && mean) { mean[row] = mu; rstd[row] = rs; }
+  T* yr = y + (int64_t)row * ldy;
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+      float g[4], b[4], o[4];
+      load4(gamma + 4 * c, g);
+      load4(beta + 4 * c, b);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = (v[j][e] - mu) * rs * g[e] + b[e];
+      store4(yr + 4 * c, o);
+    }
+  }
+}
+
+void layernorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y, int64_t ldy,
+                   float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
+  if (rows <= 0) return;
+  dim3 grid(cdiv(rows, 4)), blk(256);
+#define LN_FWD(T, V)                                                                                             \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, V>), grid, blk, 0, st, (const T*)x, ldx, (const T*)gamma, (const T*)beta, \
+                     (T*)y, ldy, mean, rstd, rows, D, eps)
+  if (dt == 0) { if (D <= 1024) LN_FWD(float, 4); else LN_FWD(float, 8); }
+  else { if (D <= 1024) LN_FWD(bf16, 4); else LN_FWD(bf16, 8); }
+#undef LN_FWD
+}
+
+// ---------------------------------------------------------------------------
+// LayerNorm backward
+// ---------------------------------------------------------------------------
+constexpr int kLnBwdBlocks = 512;
+size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 2 * D; }
+
+template <typename T, int VPL>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, int64_t lddy, const T* __restrict__ x,
+                                                     int64_t ldx, const float* __restrict__ mean,
+                                                     const float* __restrict__ rstd, const T* __restrict__ gamma,
+                                                     const T* __restrict__ dres, int64_t lddres, T* __restrict__ dx,
+                                                     int64_t lddx, float* __restrict__ partial, int rows, int D) {
+  extern __shared__ float red[];  // [4][2][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = D >> 2;
+  float g[VPL][4], ag[VPL][4], ab[VPL][4];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { ag[j][e] = 0.f; ab[j][e] = 0.f; g[j][e] = 0.f; }
+    if (c < nvec) load4(gamma + 4 * c, g[j]);
+  }
+  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+    const float mu = mean[row], rs = rstd[row];
+    float xh[VPL][4], dh[VPL][4];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float xv[4], dv[4];
+        load4(x + (int64_t)row * ldx + 4 * c, xv);
+        load4(dy + (int64_t)row * lddy + 4 * c, dv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          xh[j][e] = (xv[e] - mu) * rs;
+          ag[j][e] += dv[e] * xh[j][e];
+          ab[j][e] += dv[e];
+          dh[j][e] = dv[e] * g[j][e];
+          s1 += dh[j][e];
+          s2 += dh[j][e] * xh[j][e];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (dh[j][e] - m1 - xh[j][e] * m2) * rs;
+        if (dres) {
+          float r[4];
+          load4(dres + (int64_t)row * lddres + 4 * c, r);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] += r[e];
+        }
+        store4(dx + (int64_t)row * lddx + 4 * c, o);
+      }
+    }
+  }
+  // combine the four waves of the workgroup in a fixed order
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        red[(wave * 2 + 0) * D + 4 * c + e] = ag[j][e];
+        red[(wave * 2 + 1) * D + 4 * c + e] = ab[j][e];
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256) {
+    const float s = ((red[i] + red[2 * D + i]) + red[4 * D + i]) + red[6 * D + i];
+    partial[(size_t)blockIdx.x * 2 * D + i] = s;
+  }
+}
+
+// out[i] = sum over p of partial[p][i], p in increasing order
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int np, int n, float* __restrict__ out0,
+                                       int n0, float* __restrict__ out1) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int p = 0; p < np; ++p) s += partial[(size_t)p * n + i];
+  if (i < n0) out0[i] = s; else out1[i - n0] = s;
+}
+
+void layernorm_bwd(int dt, const void* dy, int64_t lddy, const void* x, int64_t ldx, const float* mean,
+                   const float* rstd, const void* gamma, const void* dres, int64_t lddres, void* dx, int64_t lddx,
+                   float* dgamma, float* dbeta, float* partial, int rows, int D, hipStream_t st) {
+  if (rows <= 0) return;
+  const int nb = cdiv(rows, 4) < kLnBwdBlocks ? cdiv(rows, 4) : kLnBwdBlocks;
+  const size_t shm = (size_t)8 * D * sizeof(float);
+#define LN_BWD(T, V)                                                                                                  \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, V>), dim3(nb), dim3(256), shm, st, (const T*)dy, lddy, (const T*)x, ldx, mean, \
+                     rstd, (const T*)gamma, (const T*)dres, lddres, (T*)dx, lddx, partial, rows, D)
+  if (dt == 0) { if (D <= 1024) LN_BWD(float, 4); else LN_BWD(float, 8); }
+  else { if (D <= 1024) LN_BWD(bf16, 4); else LN_BWD(bf16, 8); }
+#undef LN_BWD
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D, 256)), dim3(256), 0, st, partial, nb, 2 * D, dgamma, D,
+                     dbeta);
+}
+
+// ---------------------------------------------------------------------------
+// column sums (bias gradients)
+// ---------------------------------------------------------------------------
+constexpr int kColsumRowBlocks = 128;
+size_t colsum_partial_floats(int N) { return (size_t)kColsumRowBlocks * N; }
+
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ X, int64_t ld, int M, int N,
+                                                     float* __restrict__ partial) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= N) return;
+  float s = 0.f;
+  for (int r = blockIdx.y; r < M; r += gridDim.y) s += to_f32(X[(int64_t)r * ld + col]);
+  partial[(size_t)blockIdx.y * N + col] = s;
+}
+
+void colsum(int dt, const void* X, int64_t ld, int M, int N, float* out, float* partial, hipStream_t st) {
+  const int nby = M < kColsumRowBlocks ? M : kColsumRowBlocks;
+  dim3 grid(cdiv(N, 256), nby);
+  if (dt == 0) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, ld, M, N, partial);
+  else hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, ld, M, N, partial);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 256)), dim3(256), 0, st, partial, nby, N, out, N,
+                     (float*)nullptr);
+}
+
+// ---------------------------------------------------------------------------
+// ViT front end plumbing
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void patchify_kernel(const float* __restrict__ img, const int64_t* __restrict__ map, T* __restrict__ out,
+                                int nb, int chans, int side, int p) {
+  const int g = side / p, pd = chans * p * p;
+  const int64_t total = (int64_t)nb * g * g * pd;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int j = (int)(i % pd);
+    const int64_t pi = i / pd;
+    const int gx = (int)(pi % g), gy = (int)((pi / g) % g);
+    const int64_t bo = pi / ((int64_t)g * g);
+    const int64_t b = map ? map[bo] : bo;
+    const int px = j % p, py = (j / p) % p, c = j / (p * p);
+    out[i] = from_f32<T>(img[((b * chans + c) * side + gy * p + py) * side + gx * p + px]);
+  }
+}
+void vit_patchify(int dt, const float* images, const int64_t* map, void* patches, int nb, int chans, int img, int patch,
+                  hipStream_t st) {
+  const int64_t total = (int64_t)nb * chans * img * img;
+  const int blocks = (int)(cdiv64(total, 256) < 65536 ? cdiv64(total, 256) : 65536);
+  if (blocks <= 0) return;
+  if (dt == 0) hipLaunchKernelGGL(patchify_kernel<float>, dim3(blocks), dim3(256), 0, st, images, map, (float*)patches, nb, chans, img, patch);
+  else hipLaunchKernelGGL(patchify_kernel<bf16>, dim3(blocks), dim3(256), 0, st, images, map, (bf16*)patches, nb, chans, img, patch);
+}
+
+template <typename T>
+__global__ void vit_assemble_kernel(const T* __restrict__ E, const T* __restrict__ cls, const T* __restrict__ pos,
+                                    T* __restrict__ X, int nb, int S, int D) {
+  const int nv = D >> 2;
+  const int64_t total = (int64_t)nb * S * nv;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % nv);
+    const int64_t r = i / nv;
+    const int s = (int)(r % S), b = (int)(r / S);
+    float a[4], pz[4], o[4];
+    if (s == 0) load4(cls + 4 * c, a); else load4(E + ((int64_t)b * (S - 1) + (s - 1)) * D + 4 * c, a);
+    load4(pos + (int64_t)s * D + 4 * c, pz);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = a[e] + pz[e];
+    store4(X + r * D + 4 * c, o);
+  }
+}
+void vit_assemble(int dt, const void* E, const void* cls, const void* pos, void* X, int nb, int S, int D,
+                  hipStream_t st) {
+  const int64_t total = (int64_t)nb * S * (D / 4);
+  const int blocks = (int)(cdiv64(total, 256) < 65536 ? cdiv64(total, 256) : 65536);
+  if (blocks <= 0) return;
+  if (dt == 0) hipLaunchKernelGGL(vit_assemble_kernel<float>, dim3(blocks), dim3(256), 0, st, (const float*)E, (const float*)cls, (const float*)pos, (float*)X, nb, S, D);
+  else hipLaunchKernelGGL(vit_assemble_kernel<bf16>, dim3(blocks), dim3(256), 0, st, (const bf16*)E, (const bf16*)cls, (const bf16*)pos, (bf16*)X, nb, S, D);
+}
+
+template <typename T>
+__global__ void vit_front_bwd_kernel(const T* __restrict__ dX, T* __restrict__ dE, float* __restrict__ dpos,
+                                     float* __restrict__ dcls, int nb, int S, int D) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S * D) return;
+  const int s = i / D, d = i % D;
+  float acc = 0.f;
+  for (int b = 0; b < nb; ++b) {
+    const T v = dX[((int64_t)b * S + s) * D + d];
+    acc += to_f32(v);
+    if (s > 0) dE[((int64_t)b * (S - 1) + (s - 1)) * D + d] = v;
+  }
+  dpos[i] = acc;
+  if (s == 0) dcls[d] = acc;
+}
+void vit_front_bwd(int dt, const void* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st) {
+  dim3 grid(cdiv(S * D, 256));
+  if (dt == 0) hipLaunchKernelGGL(vit_front_bwd_kernel<float>, grid, dim3(256), 0, st, (const float*)dX, (float*)dE, dpos, dcls, nb, S, D);
+  else hipLaunchKernelGGL(vit_front_bwd_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)dX, (bf16*)dE, dpos, dcls, nb, S, D);
+}
+
+// ---------------------------------------------------------------------------
+// BERT front end
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void bert_embed_kernel(const int32_t* __restrict__ ids, const int64_t* __restrict__ map,
+                                  const T* __restrict__ Ew, const T* __restrict__ Ep, T* __restrict__ emb, int nb, int S,
+                                  int D) {
+  const int nv = D >> 2;
+  const int64_t total = (int64_t)nb * S * nv;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % nv);
+    const int64_t t = i / nv;
+    const int s = (int)(t % S);
+    const int64_t bo = t / S;
+    const int64_t tin = (map ? map[bo] : bo) * S + s;
+    float a[4], b[4], o[4];
+    load4(Ew + (int64_t)ids[tin] * D + 4 * c, a);
+    load4(Ep + (int64_t)s * D + 4 * c, b);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = a[e] + b[e];
+    store4(emb + t * D + 4 * c, o);
+  }
+}
+void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, void* emb, int nb, int S,
+                int D, hipStream_t st) {
+  const int64_t total = (int64_t)nb * S * (D / 4);
+  const int blocks = (int)(cdiv64(total, 256) < 65536 ? cdiv64(total, 256) : 65536);
+  if (blocks <= 0) return;
+  if (dt == 0) hipLaunchKernelGGL(bert_embed_kernel<float>, dim3(blocks), dim3(256), 0, st, ids, map, (const float*)Ew, (const float*)Ep, (float*)emb, nb, S, D);
+  else hipLaunchKernelGGL(bert_embed_kernel<bf16>, dim3(blocks), dim3(256), 0, st, ids, map, (const bf16*)Ew, (const bf16*)Ep, (bf16*)emb, nb, S, D);
+}
+
+// next[t] = smallest t' > t with the same token id (or -1); has_prev[t'] = 1 for it.
+__global__ void token_chain_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ next,
+                                   int32_t* __restrict__ has_prev, int ntok) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= ntok) return;
+  const int32_t id = ids[t];
+  int32_t nx = -1;
+  for (int u = t + 1; u < ntok; ++u)
+    if (ids[u] == id) { nx = u; break; }
+  next[t] = nx;
+  if (nx >= 0) has_prev[nx] = 1;
+}
+// One workgroup per first occurrence of an id: sums the rows of its chain in token order.
+template <typename T>
+__global__ __launch_bounds__(256) void embed_scatter_kernel(const int32_t* __restrict__ ids,
+                                                            const int32_t* __restrict__ next,
+                                                            const int32_t* __restrict__ has_prev,
+                                                            const T* __restrict__ demb, float* __restrict__ dEw, int D) {
+  const int t0 = blockIdx.x;
+  if (has_prev[t0]) return;
+  const int64_t row = ids[t0];
+  for (int d = threadIdx.x; d < D; d += 256) {
+    float acc = 0.f;
+    for (int t = t0; t >= 0; t = next[t]) acc += to_f32(demb[(int64_t)t * D + d]);
+    dEw[row * D + d] = acc;
+  }
+}
+template <typename T>
+__global__ void pos_sum_kernel(const T* __restrict__ demb, float* __restrict__ dEp, int nb, int S, int D) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S * D) return;
+  float acc = 0.f;
+  for (int b = 0; b < nb; ++b) acc += to_f32(demb[(int64_t)b * S * D + i]);
+  dEp[i] = acc;
+}
+void bert_embed_bwd(int dt, const int32_t* ids, const void* demb, float* dEw, float* dEp, int32_t* ws, int nb,
+                       int S, int D, hipStream_t st) {
+  const int ntok = nb * S;
+  int32_t* next = ws;
+  int32_t* has_prev = ws + ntok;
+  fill_zero(has_prev, (size_t)ntok * 4, st);
+  hipLaunchKernelGGL(token_chain_kernel, dim3(cdiv(ntok, 64)), dim3(64), 0, st, ids, next, has_prev, ntok);
+  if (dt == 0) {
+    hipLaunchKernelGGL(embed_scatter_kernel<float>, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, (const float*)demb, dEw, D);
+    hipLaunchKernelGGL(pos_sum_kernel<float>, dim3(cdiv(S * D, 256)), dim3(256), 0, st, (const float*)demb, dEp, nb, S, D);
+  } else {
+    hipLaunchKernelGGL(embed_scatter_kernel<bf16>, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, (const bf16*)demb, dEw, D);
+    hipLaunchKernelGGL(pos_sum_kernel<bf16>, dim3(cdiv(S * D, 256)), dim3(256), 0, st, (const bf16*)demb, dEp, nb, S, D);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// losses
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ z, const int32_t* __restrict__ labels,
+                                                      float* __restrict__ loss_rows, T* __restrict__ dz, int nb, int C) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  const float* zr = z + (int64_t)b * C;
+  float mx = -INFINITY;
+  for (int c = threadIdx.x; c < C; c += 256) mx = fmaxf(mx, zr[c]);
+  mx = block_max<4>(mx, red);
+  float s = 0.f;
+  for (int c = threadIdx.x; c < C; c += 256) s += expf(zr[c] - mx);
+  s = block_sum<4>(s, red);
+  const float lse = mx + logf(s);
+  const int lab = labels[b];
+  if (threadIdx.x == 0) loss_rows[b] = lse - zr[lab];
+  const float inv = 1.0f / (float)nb;
+  for (int c = threadIdx.x; c < C; c += 256) {
+    const float p = expf(zr[c] - lse);
+    dz[(int64_t)b * C + c] = from_f32<T>((p - (c == lab ? 1.f : 0.f)) * inv);
+  }
+}
+void ce_rows(int dt, const float* z, const int32_t* labels, float* loss_rows, void* dz, int nb, int C, hipStream_t st) {
+  if (dt == 0) hipLaunchKernelGGL(ce_rows_kernel<float>, dim3(nb), dim3(256), 0, st, z, labels, loss_rows, (float*)dz, nb, C);
+  else hipLaunchKernelGGL(ce_rows_kernel<bf16>, dim3(nb), dim3(256), 0, st, z, labels, loss_rows, (bf16*)dz, nb, C);
+}
+
+// z[t,c] = x[t,:] . W[:,c] + b[c], one wave per token
+template <typename T>
+__global__ __launch_bounds__(256) void qa_logits_kernel(const T* __restrict__ x, const T* __restrict__ W,
+                                                        const T* __restrict__ b, float* __restrict__ z, int rows, int D) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= rows) return;
+  float s0 = 0.f, s1 = 0.f;
+  for (int d = lane; d < D; d += 64) {
+    const float xv = to_f32(x[(int64_t)t * D + d]);
+    s0 += xv * to_f32(W[2 * d]);
+    s1 += xv * to_f32(W[2 * d + 1]);
+  }
+  s0 = wave_sum(s0);
+  s1 = wave_sum(s1);
+  if (lane == 0) { z[2 * (int64_t)t] = s0 + to_f32(b[0]); z[2 * (int64_t)t + 1] = s1 + to_f32(b[1]); }
+}
+void qa_logits(int dt, const void* x, const void* W, const void* b, float* z, int rows, int D, hipStream_t st) {
+  dim3 grid(cdiv(rows, 4));
+  if (dt == 0) hipLaunchKernelGGL(qa_logits_kernel<float>, grid, dim3(256), 0, st, (const float*)x, (const float*)W, (const float*)b, z, rows, D);
+  else hipLaunchKernelGGL(qa_logits_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)x, (const bf16*)W, (const bf16*)b, z, rows, D);
+}
+
+// one workgroup per sample; cross-entropy over the sequence axis for each of the two logit columns
+__global__ __launch_bounds__(256) void qa_ce_kernel(const float* __restrict__ z, const int32_t* __restrict__ labels,
+                                                    float* __restrict__ loss_rows, float* __restrict__ dz, int nb, int S) {
+  __shared__ float red[4];
+  const int b = blockIdx.x;
+  float loss = 0.f;
+  for (int c = 0; c < 2; ++c) {
+    const float* zc = z + (int64_t)b * S * 2 + c;
+    float mx = -INFINITY;
+    for (int s = threadIdx.x; s < S; s += 256) mx = fmaxf(mx, zc[2 * s]);
+    mx = block_max<4>(mx, red);
+    float sum = 0.f;
+    for (int s = threadIdx.x; s < S; s += 256) sum += expf(zc[2 * s] - mx);
+    sum = block_sum<4>(sum, red);
+    const float lse = mx + logf(sum);
+    const int lab = labels[2 * b + c];
+    loss += 0.5f * (lse - zc[2 * lab]);
+    const float sc = 0.5f / (float)nb;
+    for (int s = threadIdx.x; s < S; s += 256)
+      dz[((int64_t)b * S + s) * 2 + c] = (expf(zc[2 * s] - lse) - (s == lab ? 1.f : 0.f)) * sc;
+  }
+  if (threadIdx.x == 0) loss_rows[b] = loss;
+}
+void qa_ce(int dt, const float* z, const int32_t* labels, float* loss_rows, float* dz, int nb, int S, hipStream_t st) {
+  (void)dt;
+  hipLaunchKernelGGL(qa_ce_kernel, dim3(nb), dim3(256), 0, st, z, labels, loss_rows, dz, nb, S);
+}
+
+constexpr int kQaBlocks = 256;
+size_t qa_partial_floats(int D) { return (size_t)kQaBlocks * (2 * D + 2); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void qa_head_bwd_kernel(const T* __restrict__ x, const T* __restrict__ W,
+                                                          const float* __restrict__ dz, T* __restrict__ dx,
+                                                          float* __restrict__ partial, int rows, int D) {
+  // each thread owns columns d = tid, tid+256, ... (at most 8: D <= 2048)
+  float w0[8], w1[8], a0[8], a1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int d = threadIdx.x + 256 * j;
+    a0[j] = a1[j] = 0.f;
+    w0[j] = d < D ? to_f32(W[2 * d]) : 0.f;
+    w1[j] = d < D ? to_f32(W[2 * d + 1]) : 0.f;
+  }
+  float b0 = 0.f, b1 = 0.f;
+  for (int t = blockIdx.x; t < rows; t += gridDim.x) {
+    const float g0 = dz[2 * (int64_t)t], g1 = dz[2 * (int64_t)t + 1];
+    b0 += g0; b1 += g1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int d = threadIdx.x + 256 * j;
+      if (d < D) {
+        const float xv = to_f32(x[(int64_t)t * D + d]);
+        a0[j] += xv * g0;
+        a1[j] += xv * g1;
+        dx[(int64_t)t * D + d] = from_f32<T>(g0 * w0[j] + g1 * w1[j]);
+      }
+    }
+  }
+  float* p = partial + (size_t)blockIdx.x * (2 * D + 2);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int d = threadIdx.x + 256 * j;
+    if (d < D) { p[2 * d] = a0[j]; p[2 * d + 1] = a1[j]; }
+  }
+  if (threadIdx.x == 0) { p[2 * D] = b0; p[2 * D + 1] = b1; }
+}
+void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, void* dx, float* dW, float* db, float* partial,
+                 int rows, int D, hipStream_t st) {
+  const int nb = rows < kQaBlocks ? rows : kQaBlocks;
+  if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, (float*)dx, partial, rows, D);
+  else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, (bf16*)dx, partial, rows, D);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 256)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
+                     2 * D, db);
+}
+
+__global__ __launch_bounds__(256) void mean_reduce_kernel(const float* __restrict__ rows, int n, float* __restrict__ out) {
+  __shared__ float red[4];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += rows[i];
+  s = block_sum<4>(s, red);
+  if (threadIdx.x == 0) out[0] = s / (float)n;
+}
+void mean_reduce(const float* rows, int n, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(mean_reduce_kernel, dim3(1), dim3(256), 0, st, rows, n, out);
+}
+
+// ---------------------------------------------------------------------------
+// plumbing
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t n32) {
+  const size_t nv = n32 >> 2;
+  uint4* pv = reinterpret_cast<uint4*>(p);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nv; i += (size_t)gridDim.x * blockDim.x)
+    pv[i] = make_uint4(0, 0, 0, 0);
+  if (blockIdx.x == 0 && threadIdx.x < (n32 & 3)) p[(nv << 2) + threadIdx.x] = 0u;
+}
+// p must be 16-byte aligned, bytes a multiple of 4
+void fill_zero(void* p, size_t bytes, hipStream_t st) {
+  if (bytes == 0) return;
+  const size_t n32 = bytes / 4;
+  size_t blocks = (n32 / 4 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks == 0) blocks = 1;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (uint32_t*)p, n32);
+}
+
+__global__ __launch_bounds__(256) void copy_rows_kernel(uint4* __restrict__ dst, const int64_t* __restrict__ dst_idx,
+                                                        const uint4* __restrict__ src,
+                                                        const int64_t* __restrict__ src_idx, size_t row_vecs) {
+  const int r = blockIdx.y;
+  const int64_t dr = dst_idx ? dst_idx[r] : r, sr = src_idx ? src_idx[r] : r;
+  uint4* d = dst + dr * row_vecs;
+  const uint4* s = src + sr * row_vecs;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < row_vecs; i += (size_t)gridDim.x * 256) d[i] = s[i];
+}
+void copy_rows(void* dst, const int64_t* dst_idx, const void* src, const int64_t* src_idx, int nrows,
+               size_t row_bytes, hipStream_t st) {
+  if (nrows <= 0) return;
+  const size_t rv = row_bytes / 16;
+  size_t bx = (rv + 1023) / 1024;
+  if (bx == 0) bx = 1;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)bx, nrows), dim3(256), 0, st, (uint4*)dst, dst_idx,
+                     (const uint4*)src, src_idx, rv);
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ s, bf16* __restrict__ d, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    d[i] = from_f32<bf16>(s[i]);
+}
+__global__ void bf16_to_f32_kernel(const bf16* __restrict__ s, float* __restrict__ d, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    d[i] = to_f32(s[i]);
+}
+static unsigned grid_for(size_t n) {
+  size_t b = (n + 255) / 256;
+  if (b > 65536) b = 65536;
+  return b ? (unsigned)b : 1u;
+}
+void f32_to_bf16(const float* src, void* dst, size_t n, hipStream_t st) {
+  if (n) hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(n)), dim3(256), 0, st, src, (bf16*)dst, n);
+}
+void bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st) {
+  if (n) hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(grid_for(n)), dim3(256), 0, st, (const bf16*)src, dst, n);
+}
+
+}  // namespace pt

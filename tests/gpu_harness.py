@@ -1,0 +1,106 @@
+"""Drives the HIP library and the oracle from the same seeded inputs (test plumbing)."""
+import numpy as np
+
+from oracle import encoder as orc
+from paper_2102_03161_amd import binding, synth
+from tests.helpers import oracle_cfg, rel_err
+
+HP = dict(lr=1e-3, momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
+
+
+def init_values(w, ctx, seed):
+    """fp32 initial parameter values by tensor name; bf16 workloads start from bf16-representable masters."""
+    vals = {}
+    for tid, name, shape, _, _ in ctx.tensors():
+        a = synth.gen_param(seed, name, shape)
+        vals[name] = synth.round_bf16(a) if w["dtype"] == "bf16" else a
+    return vals
+
+
+def load_params(ctx, vals):
+    for tid, name, shape, _, _ in ctx.tensors():
+        ctx.write_tensor(tid, binding.KIND_PARAM, vals[name])
+
+
+def batch_for(w, seed, nb, tag=""):
+    x, y = synth.gen_inputs(w, seed, nb, tag)
+    if w["arch"] == "vit" and w["dtype"] == "bf16":
+        x = synth.round_bf16(x)
+    return x, y
+
+
+def to_dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def gpu_read_all(ctx, kind):
+    return {name: ctx.read_tensor(tid, kind) for tid, name, _, _, _ in ctx.tensors()}
+
+
+def oracle_step(w, vals, x, y, k, hp=HP, state=None, compute_vals=None):
+    """One oracle step in fp64.  compute_vals: parameter values the forward/backward reads
+    (the bf16-rounded masters in bf16 mode); the update is applied to `vals`."""
+    cfg = oracle_cfg(w)
+    p = {n: a.astype(np.float64) for n, a in vals.items()}
+    pc = p if compute_vals is None else {n: a.astype(np.float64) for n, a in compute_vals.items()}
+    xx = x.astype(np.float64) if w["arch"] == "vit" else x
+    hk, fs = orc.frozen_forward(cfg, pc, xx, k)
+    loss, grads, aux = orc.active_fwd_bwd(cfg, pc, hk, y, k, fs)
+    norms = orc.layer_grad_norms(cfg, grads, k)
+    st = orc.new_opt_state(p) if state is None else state
+    if w["optimizer"] == "adamw":
+        orc.adamw_step(cfg, p, grads, st, k, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"])
+    else:
+        orc.sgdm_step(cfg, p, grads, st, k, hp["lr"], hp["momentum"], hp["weight_decay"])
+    return dict(cfg=cfg, hk=hk, loss=loss, grads=grads, norms=norms, aux=aux, params=p, state=st)
+
+
+def gpu_step(torch, ctx, w, x, y, k, hp=HP, sample_ids=None):
+    ctx.set_freeze_boundary(k)
+    dx = to_dev(torch, x)
+    dy = to_dev(torch, y)
+    nb = x.shape[0]
+    hk_ptr = ctx.frozen_forward(dx, sample_ids)
+    loss = ctx.active_fwd_bwd(hk_ptr, dy)
+    S, D = w["S"], w["D"]
+    out = dict(loss=loss)
+    out["hk"] = ctx.read_activation(binding.ACT_HK, (nb, S, D))
+    out["hL"] = ctx.read_activation(binding.ACT_HL, (nb, S, D))
+    out["logits"] = ctx.read_activation(binding.ACT_LOGITS, (nb, w["n_out"]) if w["arch"] == "vit" else (nb, S, 2))
+    out["norms"] = ctx.layer_grad_norms()
+    out["grads"] = gpu_read_all(ctx, binding.KIND_GRAD)
+    ctx.optimizer_step(**hp)
+    out["params"] = gpu_read_all(ctx, binding.KIND_PARAM)
+    torch.cuda.synchronize()
+    return out
+
+
+def compare_step(w, g, o, k, tol, check_params=True):
+    """Per-tensor max-abs error relative to the tensor's largest magnitude."""
+    cfg = o["cfg"]
+    errs = {}
+    errs["loss"] = abs(g["loss"] - o["loss"]) / abs(o["loss"])
+    errs["hk"] = rel_err(g["hk"], o["hk"])
+    errs["hL"] = rel_err(g["hL"], o["aux"]["h_L"])
+    errs["logits"] = rel_err(g["logits"], o["aux"]["logits"])
+    gmax = max(float(np.max(np.abs(a))) for a in o["grads"].values())
+    for name, a in g["grads"].items():
+        if orc.is_active(name, cfg, k):
+            # a tensor whose true gradient is (numerically) zero is held to the scale of the whole gradient
+            ref = o["grads"][name]
+            scale = max(float(np.max(np.abs(ref))), 1e-6 * gmax)
+            errs["grad:" + name] = float(np.max(np.abs(a.astype(np.float64) - ref))) / scale
+        else:
+            assert not np.any(a), f"frozen tensor {name} has a gradient"
+    on = o["norms"]
+    for i in range(len(on)):
+        if on[i] == 0.0:
+            assert g["norms"][i] == 0.0, f"norm slot {i} must be exactly zero"
+        else:
+            errs[f"norm{i}"] = abs(g["norms"][i] - on[i]) / on[i]
+    if check_params:
+        for name, a in g["params"].items():
+            errs["param:" + name] = rel_err(a, o["params"][name])
+    bad = {n: e for n, e in errs.items() if not (e <= tol)}
+    assert not bad, f"tolerance {tol} exceeded: {bad}"
+    return errs

@@ -1,0 +1,153 @@
+"""GPU tests of the frozen-prefix activation cache (Sec. 3.4, App. D.1 item 2):
+integer decisions match the oracle exactly; cached bytes are bit-identical to a
+recompute; advancing a stale row equals a fresh forward; lookup is by sample id,
+not by batch position."""
+import numpy as np
+import pytest
+
+from oracle import encoder as orc
+from paper_2102_03161_amd import binding, synth
+from tests import gpu_harness as H
+from tests.helpers import oracle_cfg, rel_err
+from tests.test_gpu_parity import MID_BERT, MID_VIT
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+def raw_hk(ctx, w, nb):
+    return ctx.read_activation(binding.ACT_HK, (nb, w["S"], w["D"]))
+
+
+def row_as_f32(w, raw):
+    return synth.bf16_to_f32(raw.view(np.uint16)) if w["dtype"] == "bf16" else raw.view(np.float32)
+
+
+@pytest.mark.parametrize("w", [MID_VIT, MID_BERT, dict(MID_VIT, dtype="f32")], ids=["vit_bf16", "bert_bf16", "vit_f32"])
+def test_cache_contract(torch_mod, w):
+    torch = torch_mod
+    L, S, D = w["L"], w["S"], w["D"]
+    nb = w["B"]
+    ctx = binding.Context(binding.make_config(w, cache_slots=64))
+    vals = H.init_values(w, ctx, 21)
+    H.load_params(ctx, vals)
+    cfg = oracle_cfg(w)
+    p64 = {n: a.astype(np.float64) for n, a in vals.items()}
+    ocache = orc.ActivationCache()
+    xa, _ = H.batch_for(w, 21, nb, "a")
+    xb, _ = H.batch_for(w, 21, nb, "b")
+    ids_a = [40 + 2 * i for i in range(nb)]
+    ids_b = [3 + i for i in range(nb)]
+    dxa, dxb = H.to_dev(torch, xa), H.to_dev(torch, xb)
+    o_in = (lambda x: x.astype(np.float64)) if w["arch"] == "vit" else (lambda x: x)
+
+    def decisions(batch_ids, k):
+        return [ocache.decision(s, k) for s in batch_ids]
+
+    # ---- k = 1: first epoch misses, second epoch hits ------------------------
+    ctx.set_freeze_boundary(1)
+    want = decisions(ids_a, 1)
+    ctx.frozen_forward(dxa, ids_a)
+    h_miss = raw_hk(ctx, w, nb)
+    o_h, o_dec, o_runs = ocache.frozen_forward(cfg, p64, o_in(xa), ids_a, 1)
+    assert o_dec == want and [d[0] for d in want] == ["miss"] * nb
+    st = ctx.cache_stats()
+    assert (st["misses"], st["hits"], st["advances"], st["block_runs"]) == (nb, 0, 0, o_runs)
+    tol = 2e-2 if w["dtype"] == "bf16" else 1e-4
+    assert rel_err(h_miss, o_h) < tol
+    # cached bytes == what the forward produced; bypassing the cache gives the same bytes
+    for i, sid in enumerate(ids_a):
+        raw, kw = ctx.cache_row(sid)
+        assert kw == 1 and np.array_equal(row_as_f32(w, raw).reshape(S, D), h_miss[i])
+    ctx.frozen_forward(dxa, None)
+    assert np.array_equal(raw_hk(ctx, w, nb), h_miss)
+    ctx.frozen_forward(dxa, ids_a)
+    assert np.array_equal(raw_hk(ctx, w, nb), h_miss)
+    st2 = ctx.cache_stats()
+    assert st2["hits"] == nb and st2["block_runs"] == st["block_runs"] + nb  # only the bypass call ran blocks
+    ocache.frozen_forward(cfg, p64, o_in(xa), ids_a, 1)
+
+    # ---- shuffled order: rows follow their sample id -------------------------
+    perm = np.random.default_rng(0).permutation(nb)
+    ctx.frozen_forward(H.to_dev(torch, xa[perm]), [ids_a[i] for i in perm])
+    assert np.array_equal(raw_hk(ctx, w, nb), h_miss[perm])
+    assert ctx.cache_stats()["hits"] == 2 * nb
+
+    # ---- a batch mixing hits and misses, in interleaved positions ------------
+    mix_x = np.concatenate([xa[:2], xb[:2], xa[2:3]])
+    mix_ids = ids_a[:2] + ids_b[:2] + ids_a[2:3]
+    order = [2, 0, 3, 1, 4]
+    mix_x, mix_ids = mix_x[order], [mix_ids[i] for i in order]
+    want = decisions(mix_ids, 1)
+    before = ctx.cache_stats()
+    ctx.frozen_forward(H.to_dev(torch, mix_x), mix_ids)
+    h_mix = raw_hk(ctx, w, len(mix_ids))
+    o_h, o_dec, o_runs = ocache.frozen_forward(cfg, p64, o_in(mix_x), mix_ids, 1)
+    assert o_dec == want
+    after = ctx.cache_stats()
+    assert after["misses"] - before["misses"] == sum(d[0] == "miss" for d in want) == 2
+    assert after["hits"] - before["hits"] == 3 and after["block_runs"] - before["block_runs"] == o_runs == 2
+    ctx.frozen_forward(H.to_dev(torch, mix_x), None)
+    assert np.array_equal(raw_hk(ctx, w, len(mix_ids)), h_mix)   # mixed path == plain recompute, bit for bit
+
+    # ---- boundary moves 1 -> L: stale rows advance through blocks 1..L-1 only --
+    ctx.set_freeze_boundary(L)
+    want = decisions(ids_a, L)
+    assert [d for d in want] == [("advance", 1)] * nb
+    before = ctx.cache_stats()
+    ctx.frozen_forward(dxa, ids_a)
+    h_adv = raw_hk(ctx, w, nb)
+    o_h, o_dec, o_runs = ocache.frozen_forward(cfg, p64, o_in(xa), ids_a, L)
+    after = ctx.cache_stats()
+    assert after["advances"] - before["advances"] == nb and after["block_runs"] - before["block_runs"] == o_runs == nb * (L - 1)
+    ctx.frozen_forward(dxa, None)
+    assert np.array_equal(raw_hk(ctx, w, nb), h_adv)             # advance == fresh forward through 0..L-1
+    assert rel_err(h_adv, o_h) < tol
+    # a batch with a hit (written at L), a stale row (written at 1) and a miss
+    tri_x = np.concatenate([xb[1:2], xa[:1], xb[4:5]])
+    tri_ids = [ids_b[1], ids_a[0], ids_b[4]]
+    want = decisions(tri_ids, L)
+    assert [d[0] for d in want] == ["advance", "hit", "miss"]
+    before = ctx.cache_stats()
+    ctx.frozen_forward(H.to_dev(torch, tri_x), tri_ids)
+    h_tri = raw_hk(ctx, w, 3)
+    o_h, o_dec, o_runs = ocache.frozen_forward(cfg, p64, o_in(tri_x), tri_ids, L)
+    after = ctx.cache_stats()
+    assert o_dec == want and after["block_runs"] - before["block_runs"] == o_runs == (L - 1) + L
+    ctx.frozen_forward(H.to_dev(torch, tri_x), None)
+    assert np.array_equal(raw_hk(ctx, w, 3), h_tri)
+    for sid in tri_ids:
+        assert ctx.cache_row(sid)[1] == L
+    ctx.close()
+
+
+def test_training_from_cache_equals_training_from_recompute(torch_mod):
+    """A step whose boundary activation came from the cache gives the same gradients,
+    bit for bit, as one that recomputed the frozen prefix."""
+    torch = torch_mod
+    w = MID_VIT
+    nb = w["B"]
+    res = []
+    for use_cache in (False, True):
+        ctx = binding.Context(binding.make_config(w, cache_slots=16))
+        vals = H.init_values(w, ctx, 23)
+        H.load_params(ctx, vals)
+        x, y = H.batch_for(w, 23, nb)
+        ids = list(range(nb))
+        ctx.set_freeze_boundary(2)
+        if use_cache:
+            ctx.frozen_forward(H.to_dev(torch, x), ids)     # warm the cache
+        res.append(H.gpu_step(torch, ctx, w, x, y, 2, sample_ids=ids if use_cache else None))
+        if use_cache:
+            assert ctx.cache_stats()["hits"] == nb
+        ctx.close()
+    a, b = res
+    assert a["loss"] == b["loss"]
+    for n in a["grads"]:
+        assert np.array_equal(a["grads"][n], b["grads"][n]), n

@@ -1,0 +1,245 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Tolerances (per-tensor max |a-b| / max |b|):
+fp32 mode 1e-4; bf16 mode (fp32 accumulation) 2e-2 on activations, gradients and
+loss; integer state (boundary, cache decisions) and cache bytes exact."""
+import numpy as np
+import pytest
+
+from oracle import encoder as orc
+from paper_2102_03161_amd import binding, synth
+from tests import gpu_harness as H
+from tests.helpers import oracle_cfg, rel_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+# mid-size shapes: several GEMM tiles in every dimension plus ragged tails (T = 300 / 360 rows,
+# S = 50 / 72 keys), head size 64 as in the real models
+MID_VIT = dict(arch="vit", L=3, D=256, H=4, F=1024, S=50, n_out=37, img=56, patch=8, chans=3, vocab=0, max_pos=0,
+               ln_eps=1e-6, B=6, dtype="bf16", optimizer="adamw")
+MID_BERT = dict(arch="bert", L=3, D=256, H=4, F=1024, S=72, n_out=2, img=0, patch=0, chans=0, vocab=1000,
+                max_pos=96, ln_eps=1e-12, B=5, dtype="bf16", optimizer="adamw")
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch
+
+
+def run_case(torch, w, k, nb, seed, tol, hp=H.HP):
+    print(f"case arch={w['arch']} dtype={w['dtype']} L={w['L']} D={w['D']} S={w['S']} nb={nb} k={k} seed={seed}", flush=True)
+    ctx = binding.Context(binding.make_config(w, B=nb))
+    vals = H.init_values(w, ctx, seed)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, seed, nb)
+    g = H.gpu_step(torch, ctx, w, x, y, k, hp)
+    o = H.oracle_step(w, vals, x, y, k, hp)
+    errs = H.compare_step(w, g, o, k, tol)
+    # frozen parameters: bytes untouched by the step
+    for name, a in g["params"].items():
+        if not orc.is_active(name, o["cfg"], k):
+            assert np.array_equal(a, vals[name]), name
+    assert ctx.get_freeze_boundary() == k and ctx.get_step_count() == 1
+    worst = max(errs.items(), key=lambda kv: kv[1])
+    print(f"  worst {worst[0]} = {worst[1]:.3e}", flush=True)
+    ctx.close()
+    return errs
+
+
+@pytest.mark.parametrize("k", [0, 1])
+def test_tiny_vit_fp32(torch_mod, k):
+    w = synth.workload("vit_tiny")
+    run_case(torch_mod, w, k, w["B"], seed=1, tol=TOL["f32"],
+             hp=dict(H.HP, lr=0.03, momentum=0.9, weight_decay=0.0))
+
+
+@pytest.mark.parametrize("k", [0, 1, 2])
+def test_tiny_bert_fp32(torch_mod, k):
+    w = synth.workload("bert_tiny")
+    run_case(torch_mod, w, k, w["B"], seed=4, tol=TOL["f32"])
+
+
+@pytest.mark.parametrize("w", [MID_VIT, MID_BERT], ids=["vit", "bert"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("k", [0, 2, 3])
+def test_mid_shapes(torch_mod, w, dtype, k):
+    w = dict(w, dtype=dtype)
+    run_case(torch_mod, w, k, w["B"], seed=7, tol=TOL[dtype])
+
+
+@pytest.mark.parametrize("k", [0, 6])
+def test_vit_b16_reduced_batch(torch_mod, k):
+    # full ViT-B/16 shapes, parity micro-batch of 4 samples
+    w = synth.workload("vit_b16")
+    run_case(torch_mod, w, k, 4, seed=2, tol=TOL["bf16"])
+
+
+@pytest.mark.parametrize("k", [0, 8])
+def test_bert_base_reduced_batch(torch_mod, k):
+    w = synth.workload("bert_base_qa")
+    run_case(torch_mod, w, k, 2, seed=4, tol=TOL["bf16"])
+
+
+def test_single_sample_and_boundary_at_L(torch_mod):
+    # degenerate cases: one sample; everything frozen but the head (softmax regression)
+    w = dict(MID_VIT, dtype="f32")
+    run_case(torch_mod, w, 1, 1, seed=9, tol=TOL["f32"])
+    run_case(torch_mod, w, w["L"], 3, seed=9, tol=TOL["f32"])
+    wb = dict(MID_BERT, dtype="f32")
+    run_case(torch_mod, wb, wb["L"], 2, seed=9, tol=TOL["f32"])
+
+
+def test_optimizer_arithmetic_on_given_gradients(torch_mod):
+    """Both update rules on identical gradients, several steps, moments included."""
+    torch = torch_mod
+    for opt in ("adamw", "sgdm"):
+        w = dict(MID_VIT, dtype="f32", optimizer=opt)
+        ctx = binding.Context(binding.make_config(w))
+        vals = H.init_values(w, ctx, 3)
+        H.load_params(ctx, vals)
+        cfg = oracle_cfg(w)
+        p = {n: a.astype(np.float64) for n, a in vals.items()}
+        st = orc.new_opt_state(p)
+        x, y = H.batch_for(w, 3, w["B"])
+        rng = np.random.default_rng(5)
+        hp = dict(H.HP, weight_decay=0.05)
+        k = 1
+        ctx.set_freeze_boundary(k)
+        for step in range(3):
+            hk = ctx.frozen_forward(H.to_dev(torch, x))
+            ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+            grads = {}
+            for tid, name, shape, _, _ in ctx.tensors():
+                if orc.is_active(name, cfg, k):
+                    grads[name] = (rng.standard_normal(shape) * 10.0 ** rng.uniform(-6, 0)).astype(np.float32)
+                    ctx.write_tensor(tid, binding.KIND_GRAD, grads[name])
+            ctx.optimizer_step(**hp)
+            g64 = {n: a.astype(np.float64) for n, a in grads.items()}
+            if opt == "adamw":
+                orc.adamw_step(cfg, p, g64, st, k, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"])
+            else:
+                orc.sgdm_step(cfg, p, g64, st, k, hp["lr"], hp["momentum"], hp["weight_decay"])
+            got = H.gpu_read_all(ctx, binding.KIND_PARAM)
+            m1 = H.gpu_read_all(ctx, binding.KIND_MOMENT1)
+            for name in vals:
+                if orc.is_active(name, cfg, k):
+                    d_ref = p[name] - vals[name].astype(np.float64)
+                    d_got = got[name].astype(np.float64) - vals[name].astype(np.float64)
+                    # the update itself, not just the updated weight; fp32 storage of w limits it
+                    assert np.max(np.abs(d_got - d_ref)) <= 2e-5 * np.max(np.abs(d_ref)) + 1e-7 * np.max(np.abs(p[name])), (opt, step, name)
+                    assert rel_err(m1[name], st["m"][name]) < 1e-5, (opt, step, name)
+                else:
+                    assert np.array_equal(got[name], vals[name])
+                    assert not np.any(m1[name])
+            if opt == "adamw":
+                m2 = H.gpu_read_all(ctx, binding.KIND_MOMENT2)
+                for name in vals:
+                    if orc.is_active(name, cfg, k):
+                        assert rel_err(m2[name], st["v"][name]) < 1e-5
+        assert ctx.get_step_count() == 3 == st["t"]
+        ctx.close()
+
+
+def test_bf16_shadow_is_rne_of_master(torch_mod):
+    w = dict(MID_VIT)
+    ctx = binding.Context(binding.make_config(w))
+    rng = np.random.default_rng(0)
+    for tid, name, shape, _, _ in ctx.tensors()[:8]:
+        a = rng.standard_normal(shape).astype(np.float32)
+        a.flat[0] = np.float32(1.00390625)     # tie -> even
+        a.flat[1] = np.float32(1.01171875)     # tie -> up to even
+        ctx.write_tensor(tid, binding.KIND_PARAM, a)
+        assert np.array_equal(ctx.read_tensor(tid, binding.KIND_SHADOW), synth.round_bf16(a)), name
+    ctx.close()
+
+
+def test_two_steps_with_boundary_switch_bf16(torch_mod):
+    """Two consecutive steps with the boundary moving 0 -> 2 in between; the oracle follows
+    from the exported state (bf16-rounded masters for compute, fp32 masters for the update)."""
+    torch = torch_mod
+    w = dict(MID_BERT)
+    nb = w["B"]
+    ctx = binding.Context(binding.make_config(w))
+    vals = H.init_values(w, ctx, 11)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 11, nb)
+    g0 = H.gpu_step(torch, ctx, w, x, y, 0)
+    o0 = H.oracle_step(w, vals, x, y, 0)
+    H.compare_step(w, g0, o0, 0, TOL["bf16"])
+    # continue from the GPU's own state
+    master = g0["params"]
+    shadow = H.gpu_read_all(ctx, binding.KIND_SHADOW)
+    for n in master:
+        assert np.array_equal(shadow[n], synth.round_bf16(master[n])), n
+    st = orc.new_opt_state({n: a.astype(np.float64) for n, a in master.items()})
+    st["t"] = 1
+    for n in master:
+        st["m"][n] = ctx.read_tensor(dict((nm, t) for t, nm, *_ in ctx.tensors())[n], binding.KIND_MOMENT1).astype(np.float64)
+        st["v"][n] = ctx.read_tensor(dict((nm, t) for t, nm, *_ in ctx.tensors())[n], binding.KIND_MOMENT2).astype(np.float64)
+    x2, y2 = H.batch_for(w, 12, nb, tag="second")
+    g1 = H.gpu_step(torch, ctx, w, x2, y2, 2)
+    orc.drop_frozen_state(oracle_cfg(w), st, 2)
+    o1 = H.oracle_step(w, master, x2, y2, 2, state=st, compute_vals=shadow)
+    H.compare_step(w, g1, o1, 2, TOL["bf16"])
+    # moments of the newly frozen tensors are gone
+    m1 = H.gpu_read_all(ctx, binding.KIND_MOMENT1)
+    for n in master:
+        if not orc.is_active(n, oracle_cfg(w), 2):
+            assert not np.any(m1[n]) and np.array_equal(g1["params"][n], master[n])
+    assert ctx.get_step_count() == 2
+    ctx.close()
+
+
+def test_state_machine_and_argument_errors(torch_mod):
+    torch = torch_mod
+    w = synth.workload("vit_tiny")
+    ctx = binding.Context(binding.make_config(w, cache_slots=8))
+    vals = H.init_values(w, ctx, 1)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 1, w["B"])
+    dx, dy = H.to_dev(torch, x), H.to_dev(torch, y)
+
+    def status(fn):
+        with pytest.raises(binding.PtError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: ctx.active_fwd_bwd(dx.data_ptr(), dy)) == binding.PT_ESTATE
+    assert status(lambda: ctx.layer_grad_norms()) == binding.PT_ESTATE
+    assert status(lambda: ctx.optimizer_step(lr=0.1)) == binding.PT_ESTATE
+    assert status(lambda: ctx.set_freeze_boundary(-1)) == binding.PT_EINVAL
+    assert status(lambda: ctx.set_freeze_boundary(w["L"] + 1)) == binding.PT_EINVAL
+    ctx.set_freeze_boundary(1)
+    assert status(lambda: ctx.set_freeze_boundary(0)) == binding.PT_EINVAL
+    assert ctx.get_freeze_boundary() == 1
+    assert status(lambda: ctx.frozen_forward(dx, [0, 1, 2, 99])) == binding.PT_EINVAL
+    assert status(lambda: ctx.frozen_forward(dx, [0, 1, 1, 2])) == binding.PT_EINVAL
+    assert ctx.cache_row(3) is None and ctx.cache_stats()["misses"] == 0
+    big = torch.zeros((w["B"] + 1, 3, 32, 32), device="cuda:0")
+    assert status(lambda: ctx.frozen_forward(big)) == binding.PT_EINVAL
+    hk = ctx.frozen_forward(dx, [0, 1, 2, 3])
+    ctx.active_fwd_bwd(hk, dy)
+    ctx.optimizer_step(lr=0.1)
+    assert status(lambda: ctx.optimizer_step(lr=0.1)) == binding.PT_ESTATE
+    ctx.close()
+
+
+def test_runs_are_bit_reproducible(torch_mod):
+    torch = torch_mod
+    for w in (MID_VIT, MID_BERT):
+        outs = []
+        for _ in range(2):
+            ctx = binding.Context(binding.make_config(w))
+            vals = H.init_values(w, ctx, 5)
+            H.load_params(ctx, vals)
+            x, y = H.batch_for(w, 5, w["B"])
+            outs.append(H.gpu_step(torch, ctx, w, x, y, 1))
+            ctx.close()
+        a, b = outs
+        assert a["loss"] == b["loss"] and np.array_equal(a["hL"], b["hL"]) and np.array_equal(a["norms"], b["norms"])
+        for n in a["grads"]:
+            assert np.array_equal(a["grads"][n], b["grads"][n]), n
+            assert np.array_equal(a["params"][n], b["params"][n]), n
