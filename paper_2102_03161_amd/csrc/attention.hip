@@ -272,7 +272,7 @@ static void attention_fwd_t(const void* qkv, void* ctx, float* lse, int nb, int 
   const size_t shm = sizeof(float) * ((size_t)TQ * dh + (size_t)TK * (dh + 1) + (size_t)TQ * Spad + TQ);
   static size_t configured = 0;
   if (shm > 65536 && shm > configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
                         (int)shm);
     configured = shm;
   }
@@ -292,7 +292,7 @@ static void attention_bwd_t(const void* qkv, const void* ctx, const void* dctx, 
   const size_t shm2 = sizeof(float) * ((size_t)4 * TQ * (dh + 1) + (size_t)2 * TQ * TQ + 2 * TQ);
   static size_t configured = 0;
   if (shm1 > 65536 && shm1 > configured) {
-    hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<T>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<T>),
                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm1);
     configured = shm1;
   }

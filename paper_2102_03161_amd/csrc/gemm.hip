@@ -35,17 +35,13 @@ template <typename T, typename TC, int EPI>
 __device__ __forceinline__ void epilogue_store(const GemmDev<T>& g, int row, int col, float acc) {
   float v = acc;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) v += to_f32(g.bias[col]);
-  if (EPI == EPI_BIAS_RES || EPI == EPI_RES) v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
+  if (EPI == EPI_BIAS_RES) v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
+  if (EPI == EPI_RES) {  // an fp32 output adds the fp32 gradient stream
+    if (sizeof(TC) == 4) v += reinterpret_cast<const float*>(g.aux)[(int64_t)row * g.ld_aux + col];
+    else v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
+  }
   if (EPI == EPI_BIAS_GELU) {
-    if (g.aux_out) {
-      // the saved pre-activation is what the backward pass will read, so GELU is
-      // taken from the stored (rounded) value to keep forward and backward consistent
-      const T hs = from_f32<T>(v);
-      g.aux_out[(int64_t)row * g.ld_aux + col] = hs;
-      v = to_f32(hs);
-    } else {
-      v = to_f32(from_f32<T>(v));
-    }
+    if (g.aux_out) g.aux_out[(int64_t)row * g.ld_aux + col] = from_f32<T>(v);  // pre-activation for the backward pass
     v = gelu_f(v);
   }
   if (EPI == EPI_MUL_DGELU) v *= dgelu_f(to_f32(g.aux[(int64_t)row * g.ld_aux + col]));
@@ -252,9 +248,11 @@ static void launch_mfma_epi(const Gemm& a, hipStream_t st) {
                   (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
   dim3 grid(cdiv(a.N, BN), cdiv(a.M, BM));
   dim3 blk(256);
-  if constexpr (sizeof(TC) == 4) {  // fp32 outputs (weight gradients, logits) only come plain or with a bias
+  if constexpr (sizeof(TC) == 4) {  // fp32 outputs: weight gradients, logits (+bias), gradient stream (+residual)
     if (a.epi == EPI_STORE) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_STORE, TC>), grid, blk, 0, st, g);
-    else hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS, TC>), grid, blk, 0, st, g);
+    else if (a.epi == EPI_BIAS) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS, TC>), grid, blk, 0, st, g);
+    else if (a.epi == EPI_BIAS_RES) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS_RES, TC>), grid, blk, 0, st, g);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_RES, TC>), grid, blk, 0, st, g);
     return;
   }
   switch (a.epi) {
@@ -281,7 +279,7 @@ static bool mfma_ok(const Gemm& a) {
 
 void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return;
-  if (a.c_f32 && a.epi != EPI_STORE && a.epi != EPI_BIAS) return;  // not a combination the step uses
+  if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step
   if (dt == 0) {
     launch_generic_epi<float, float>(a, st);
     return;

@@ -25,7 +25,7 @@ struct Gemm {
   bool ta = false, tb = false;
   Epi epi = EPI_STORE;
   const void* bias = nullptr;  // T [N]
-  const void* aux = nullptr;   // T [M,N] ld_aux
+  const void* aux = nullptr;   // T [M,N] ld_aux (fp32 when c_f32: the gradient stream)
   void* aux_out = nullptr;     // T [M,N] ld_aux
   int64_t ld_aux = 0;
   bool c_f32 = false;
@@ -39,15 +39,18 @@ void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, c
                    float* delta_ws /*[nb,H,S]*/, int nb, int S, int H, int dh, hipStream_t st);
 
 // ---- LayerNorm over rows of length D
-// y[r] = LN(x[r]); rows addressed r*ldx / r*ldy (elements).  mean/rstd may be null.
-void layernorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y, int64_t ldy,
-                   float* mean, float* rstd, int rows, int D, float eps, hipStream_t st);
-// dx[r] = LNbwd(dy[r]) (+ dres[r] if non-null); dgamma/dbeta fp32 [D] via `partial` scratch
-// of ln_partial_floats(D) floats.
+// y[r] = LN(x[r]); rows addressed r*ldx / r*ldy (elements).  x is fp32 when x_f32, else T.
+// mean/rstd may be null.
+void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
+                   int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st);
+// dx[r] = LNbwd(dy[r]) (+ dres[r] if non-null).  dy is the fp32 gradient stream when dy_f32, else T.
+// The result is written to dx_s (fp32) and / or dx_o (T), either may be null; both null computes the
+// parameter gradients only.  dgamma/dbeta fp32 [D] via `partial` scratch of ln_partial_floats(D) floats.
 size_t ln_partial_floats(int D);
-void layernorm_bwd(int dt, const void* dy, int64_t lddy, const void* x, int64_t ldx, const float* mean,
-                   const float* rstd, const void* gamma, const void* dres, int64_t lddres, void* dx, int64_t lddx,
-                   float* dgamma, float* dbeta, float* partial, int rows, int D, hipStream_t st);
+void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                   const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
+                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* partial, int rows, int D,
+                   hipStream_t st);
 
 // out[n] = sum_m X[m,n] (fp32), X is T [M,N] with leading dimension ld.
 size_t colsum_partial_floats(int N);
@@ -60,16 +63,17 @@ void vit_patchify(int dt, const float* images, const int64_t* map, void* patches
 void vit_assemble(int dt, const void* E, const void* cls, const void* pos, void* X, int nb, int S, int D,
                   hipStream_t st);
 // dE[b*N+i] = dX[b,1+i]; dpos[s] = sum_b dX[b,s]; dcls = sum_b dX[b,0]
-void vit_front_bwd(int dt, const void* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st);
+void vit_front_bwd(int dt, const float* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st);
 
 // ---- BERT front end
-void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, void* emb, int nb, int S,
-                int D, hipStream_t st);
+// ids outside [0, vocab) are clamped into the table
+void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, float* emb, int nb, int S,
+                int D, int vocab, hipStream_t st);
 // dEp[s] = sum_b demb[b,s] for s < S (rows >= S untouched); dEw rows: deterministic
 // segmented sum over equal ids.  `dEw` must be zero on entry.
-// `ws`: 2*nb*S int32 of scratch.
-void bert_embed_bwd(int dt, const int32_t* ids, const void* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S,
-                    int D, hipStream_t st);
+// `ws`: 2*nb*S + 4 int32 of scratch.
+void bert_embed_bwd(const int32_t* ids, const float* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S, int D,
+                    int vocab, hipStream_t st);
 
 // ---- losses
 // ViT: z fp32 [nb,C]; writes per-sample loss, dz (T) = (softmax - onehot)/nb.
@@ -80,7 +84,7 @@ void qa_ce(int dt, const float* z, const int32_t* labels, float* loss_rows /*[nb
            int S, hipStream_t st);
 // dx[t] = dz[t,0] W[:,0] + dz[t,1] W[:,1]; dW[d,c] = sum_t x[t,d] dz[t,c]; db[c] = sum_t dz[t,c]
 size_t qa_partial_floats(int D);
-void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, void* dx, float* dW, float* db, float* partial,
+void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* dx, float* dW, float* db, float* partial,
                  int rows, int D, hipStream_t st);
 // loss = (sum_i rows[i]) / n, fixed order
 void mean_reduce(const float* rows, int n, float* out, hipStream_t st);

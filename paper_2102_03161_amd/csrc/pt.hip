@@ -51,7 +51,7 @@ struct Plan {
   // work arena
   std::vector<size_t> X;   // L+1 block inputs / outputs
   std::vector<Slot> slot;  // L+1 (slot L: scratch of the forward-only prefix)
-  size_t HKOUT, dA, dB, dF, dT1, dT2, dQKV, DELTA;
+  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
   size_t LOSS, NORMS, LNPART, CSPART, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
@@ -135,12 +135,16 @@ void make_plan(const pt_config& c, Plan* p) {
   p->slot.resize(L + 1);
   for (int l = 0; l <= L; ++l) {
     Slot& s = p->slot[l];
-    s.U = take(TD); s.QKV = take(3 * TD); s.CTX = take(TD); s.Y = take(TD); s.WN = take(TD);
+    // post-LN keeps the two pre-LayerNorm sums (U, WN) in fp32
+    const size_t TDsum = c.arch == PT_BERT_POSTLN ? T * D * 4 : TD;
+    s.U = take(TDsum); s.QKV = take(3 * TD); s.CTX = take(TD); s.Y = take(TD); s.WN = take(TDsum);
     s.HP = take(TF); s.G = take(TF); s.LSE = take(BHS);
     s.MU1 = take(T * 4); s.RS1 = take(T * 4); s.MU2 = take(T * 4); s.RS2 = take(T * 4);
   }
   p->HKOUT = take(TD);
-  p->dA = take(TD); p->dB = take(TD); p->dF = take(TF); p->dT1 = take(TD); p->dT2 = take(TD);
+  const size_t TD4 = T * D * 4;
+  p->sA = take(TD4); p->sB = take(TD4); p->sC = take(TD4); p->sD = take(TD4);
+  p->oA = take(TD); p->oB = take(TD); p->oC = take(TD); p->oD = take(TD); p->dF = take(TF);
   p->dQKV = take(3 * TD); p->DELTA = take(BHS);
   if (c.arch == PT_VIT_PRELN) {
     const size_t np = (size_t)B * (S - 1);
@@ -152,7 +156,7 @@ void make_plan(const pt_config& c, Plan* p) {
     p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); p->DC = take((size_t)B * D * e);
   } else {
     p->PATCH = 0;
-    p->EMB = take(TD); p->DEMB = take(TD); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take(T * 8);
+    p->EMB = take(TD4); p->DEMB = take(TD4); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take((T + 4) * 8);
     p->CFEAT = p->MUF = p->RSF = p->DC = 0;
     p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4);
   }
@@ -240,88 +244,106 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
   float* lse = save ? c->wf(s.LSE) : nullptr;
   float* mu1 = save ? c->wf(s.MU1) : nullptr; float* rs1 = save ? c->wf(s.RS1) : nullptr;
   float* mu2 = save ? c->wf(s.MU2) : nullptr; float* rs2 = save ? c->wf(s.RS2) : nullptr;
-  auto lin = [&](const void* A, int K, int wid, int bid, void* C, int N, Epi epi, const void* aux, void* aux_out) {
+  auto lin = [&](const void* A, int K, int wid, int bid, void* C, int N, Epi epi, const void* aux, void* aux_out,
+                 bool out_f32 = false) {
     Gemm m;
     m.A = A; m.lda = K; m.B = c->cp(wid); m.ldb = N; m.C = C; m.ldc = N; m.M = Tn; m.N = N; m.K = K;
-    m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = N;
+    m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = N; m.c_f32 = out_f32;
     gemm(dt, m, st);
   };
   if (g.arch == PT_VIT_PRELN) {
-    layernorm_fwd(dt, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    layernorm_fwd(dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st);
     lin(c->w(s.U), D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
     attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
     lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.Y), D, EPI_BIAS_RES, xin, nullptr);
-    layernorm_fwd(dt, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st);
+    layernorm_fwd(dt, false, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st);
     lin(c->w(s.WN), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
     lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), xout, D, EPI_BIAS_RES, c->w(s.Y), nullptr);
   } else {
-    // post-LN: U holds x + Attn(x), Y = LN1(U), WN holds Y + MLP(Y), out = LN2(WN)
+    // post-LN: U holds x + Attn(x) in fp32, Y = LN1(U), WN holds Y + MLP(Y) in fp32, out = LN2(WN)
     lin(xin, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
     attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
-    lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.U), D, EPI_BIAS_RES, xin, nullptr);
-    layernorm_fwd(dt, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.U), D, EPI_BIAS_RES, xin, nullptr, true);
+    layernorm_fwd(dt, true, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st);
     lin(c->w(s.Y), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
-    lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), c->w(s.WN), D, EPI_BIAS_RES, c->w(s.Y), nullptr);
-    layernorm_fwd(dt, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st);
+    lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), c->w(s.WN), D, EPI_BIAS_RES, c->w(s.Y), nullptr, true);
+    layernorm_fwd(dt, true, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st);
   }
 }
 
 // ---------------------------------------------------------------------------
-// one encoder block, backward.  dout: gradient wrt the block output; dxin:
-// gradient wrt its input (written iff need_dx, except that the pre-LN path
-// always produces it on the way to the LN1 parameter gradients).
+// one encoder block, backward.  The gradient of the residual stream is carried
+// in fp32 between blocks (its per-token sums cancel heavily, so bf16 rounding
+// along that path would dominate the bias / LayerNorm-shift gradients); tensors
+// that feed the matrix cores get a T copy written by the kernel that makes them.
+// In: dout_s (fp32) and, for pre-LN, its T copy dout_o.  Out: dx_s / dx_o.
 // ---------------------------------------------------------------------------
-void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, const void* dout, void* dxin, int ns, bool need_dx) {
+struct GradBufs {
+  float* s;  // fp32 stream
+  void* o;   // T copy (pre-LN only)
+};
+
+void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns, bool need_dx) {
   const pt_config& g = c->cfg;
   const int D = g.D, F = g.F, Tn = ns * g.S, dt = c->dt;
   hipStream_t st = c->st;
   const Plan& p = c->plan;
   float* lnp = c->wf(p.LNPART);
   float* csp = c->wf(p.CSPART);
-  void* dF = c->w(p.dF); void* dT1 = c->w(p.dT1); void* dT2 = c->w(p.dT2); void* dQKV = c->w(p.dQKV);
-  // dW[K_in, N_out] = X^T dY ; db = colsum(dY)
-  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid) {
+  float* sC = c->wf(p.sC); float* sD = c->wf(p.sD);
+  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
+  // dW[K_in, N_out] = X^T dY ; db = colsum over tokens of dY (bias_dt 0: fp32 source, else T)
+  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid) {
     Gemm m;
     m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
     gemm(dt, m, st);
-    colsum(dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st);
   };
+  auto bgrad = [&](int src_dt, const void* dY, int Nout, int bid) { colsum(src_dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st); };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
-  auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux) {
+  auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
     Gemm m;
     m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
-    m.M = Tn; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin;
+    m.M = Tn; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin; m.c_f32 = out_f32;
     gemm(dt, m, st);
   };
   if (g.arch == PT_VIT_PRELN) {
-    wgrad(c->w(s.G), F, dout, D, c->blk(l, W2), c->blk(l, B2));
-    dgrad(dout, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP));
-    wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1), c->blk(l, B1));
-    dgrad(dF, F, c->blk(l, W1), dT1, D, EPI_STORE, nullptr);
-    layernorm_bwd(dt, dT1, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout, D, dT2, D,
-                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // dT2 = dL/dY
-    wgrad(c->w(s.CTX), D, dT2, D, c->blk(l, WO), c->blk(l, BO));
-    dgrad(dT2, D, c->blk(l, WO), dT1, D, EPI_STORE, nullptr);                           // dT1 = dL/dCTX
-    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dT1, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
-    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
-    dgrad(dQKV, 3 * D, c->blk(l, WQKV), dT1, D, EPI_STORE, nullptr);                    // dT1 = dL/dU
-    layernorm_bwd(dt, dT1, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dT2, D, dxin, D,
-                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);
+    wgrad(c->w(s.G), F, dout.o, D, c->blk(l, W2));
+    bgrad(0, dout.s, D, c->blk(l, B2));
+    dgrad(dout.o, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
+    wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1));
+    bgrad(dt, dF, F, c->blk(l, B1));
+    dgrad(dF, F, c->blk(l, W1), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dLN2out
+    layernorm_bwd(dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
+                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // sC / oD = dL/dY
+    wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO));
+    bgrad(0, sC, D, c->blk(l, BO));
+    dgrad(oD, D, c->blk(l, WO), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dCTX
+    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV));
+    bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
+    dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
+    layernorm_bwd(dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
+                  need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
+                  c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);
   } else {
-    layernorm_bwd(dt, dout, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, dT1, D,
-                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // dT1 = dL/d(Y+MLP)
-    wgrad(c->w(s.G), F, dT1, D, c->blk(l, W2), c->blk(l, B2));
-    dgrad(dT1, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP));
-    wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
-    dgrad(dF, F, c->blk(l, W1), dT2, D, EPI_RES, dT1);                                  // dT2 = dL/dY
-    layernorm_bwd(dt, dT2, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, dT1, D,
-                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);  // dT1 = dL/d(x+Attn)
-    wgrad(c->w(s.CTX), D, dT1, D, c->blk(l, WO), c->blk(l, BO));
-    dgrad(dT1, D, c->blk(l, WO), dT2, D, EPI_STORE, nullptr);                           // dT2 = dL/dCTX
-    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dT2, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
-    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
-    if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dxin, D, EPI_RES, dT1);
+    layernorm_bwd(dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
+                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // sC / oC = dL/d(Y+MLP)
+    wgrad(c->w(s.G), F, oC, D, c->blk(l, W2));
+    bgrad(0, sC, D, c->blk(l, B2));
+    dgrad(oC, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
+    wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1));
+    bgrad(dt, dF, F, c->blk(l, B1));
+    dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
+    layernorm_bwd(dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
+                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);  // sC / oC = dL/d(x+Attn)
+    wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO));
+    bgrad(0, sC, D, c->blk(l, BO));
+    dgrad(oC, D, c->blk(l, WO), oD, D, EPI_STORE, nullptr, false);                      // oD = dL/dCTX
+    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV));
+    bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
+    if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
   }
 }
 
@@ -340,13 +362,13 @@ void front_forward(pt_ctx* c, const void* d_input, const int64_t* d_map, void* x
     gemm(dt, m, st);
     vit_assemble(dt, c->w(p.EMB), c->cp(2), c->cp(3), xout, ns, g.S, D, st);
   } else {
-    bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->w(p.EMB), ns, g.S, D, st);
-    layernorm_fwd(dt, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
+    bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->wf(p.EMB), ns, g.S, D, g.vocab, st);
+    layernorm_fwd(dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
                   save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st);
   }
 }
 
-void front_backward(pt_ctx* c, const void* dx, int ns) {
+void front_backward(pt_ctx* c, const float* dx, int ns) {
   const pt_config& g = c->cfg;
   const Plan& p = c->plan;
   const int D = g.D, dt = c->dt;
@@ -360,12 +382,12 @@ void front_backward(pt_ctx* c, const void* dx, int ns) {
     gemm(dt, m, st);
     colsum(dt, c->w(p.DEMB), D, np, D, c->gp(1), c->wf(p.CSPART), st);
   } else {
-    layernorm_bwd(dt, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->w(p.DEMB), D,
-                  c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st);
+    layernorm_bwd(dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
+                  nullptr, D, c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st);
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
-    bert_embed_bwd(dt, (const int32_t*)c->last_input, c->w(p.DEMB), c->gp(0), c->gp(1),
-                   reinterpret_cast<int32_t*>(c->w(p.CHAINWS)), ns, g.S, D, st);
+    bert_embed_bwd((const int32_t*)c->last_input, c->wf(p.DEMB), c->gp(0), c->gp(1),
+                   reinterpret_cast<int32_t*>(c->w(p.CHAINWS)), ns, g.S, D, g.vocab, st);
   }
 }
 
@@ -619,13 +641,13 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     block_forward(c, l, x, c->w(p.X[l + 1]), p.slot[l], nb, true);
     x = c->w(p.X[l + 1]);
   }
-  void* dcur = c->w(p.dA);
-  void* dnext = c->w(p.dB);
+  GradBufs dcur{c->wf(p.sA), c->w(p.oA)};
+  GradBufs dnext{c->wf(p.sB), c->w(p.oB)};
   // head, loss, head backward -> dcur = dL/dx_L
   if (g.arch == PT_VIT_PRELN) {
     const int C = g.n_out;
     const int hg = c->head(0), hb = c->head(1), hW = c->head(2), hbias = c->head(3);
-    layernorm_fwd(dt, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st);
+    layernorm_fwd(dt, false, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st);
     Gemm m;
     m.A = c->w(p.CFEAT); m.lda = D; m.B = c->cp(hW); m.ldb = C; m.C = c->w(p.LOGITS); m.ldc = C;
     m.M = nb; m.N = C; m.K = D; m.epi = EPI_BIAS; m.bias = c->cp(hbias); m.c_f32 = true;
@@ -641,15 +663,17 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
     dg.M = nb; dg.N = D; dg.K = C;
     gemm(dt, dg, st);
-    fill_zero(dcur, (size_t)nb * S * D * c->esz, st);
-    layernorm_bwd(dt, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur,
-                  (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st);
+    // only the CLS rows of dL/dx_L are non-zero
+    fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
+    fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
+    layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
+                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st);
   } else {
     const int hW = c->head(0), hbias = c->head(1);
     qa_logits(dt, x, c->cp(hW), c->cp(hbias), c->wf(p.LOGITS), nb * S, D, st);
     qa_ce(dt, c->wf(p.LOGITS), d_labels, c->wf(p.LOSSROWS), c->wf(p.DZ), nb, S, st);
     mean_reduce(c->wf(p.LOSSROWS), nb, c->wf(p.LOSS), st);
-    qa_head_bwd(dt, x, c->cp(hW), c->wf(p.DZ), dcur, c->gp(hW), c->gp(hbias), c->wf(p.QAPART), nb * S, D, st);
+    qa_head_bwd(dt, x, c->cp(hW), c->wf(p.DZ), dcur.s, c->gp(hW), c->gp(hbias), c->wf(p.QAPART), nb * S, D, st);
   }
   // backward through the active blocks; stops at the boundary (Sec. 3.2.1)
   for (int l = L - 1; l >= k; --l) {
@@ -658,8 +682,8 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx);
     std::swap(dcur, dnext);
   }
-  if (k == 0) front_backward(c, dcur, nb);
-  c->last_dhk = dcur;
+  if (k == 0) front_backward(c, dcur.s, nb);
+  c->last_dhk = dcur.s;
   HIP_TRY(c, hipGetLastError());
   c->phase = 2;
   if (loss_out) return pt_last_loss(c, loss_out);
@@ -802,7 +826,7 @@ pt_status pt_read_activation(pt_ctx* c, int32_t which, float* dst, size_t numel)
     case PT_ACT_HL: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->k == g.L ? c->last_hk : c->w(c->plan.X[g.L]); n = act; break;
     case PT_ACT_LOGITS: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->w(c->plan.LOGITS);
       n = g.arch == PT_VIT_PRELN ? (size_t)c->nb * g.n_out : (size_t)c->nb * g.S * 2; is_f32 = true; break;
-    case PT_ACT_DHK: if (c->phase < 2) return fail(c, PT_ESTATE, "no backward pass yet"); src = c->last_dhk; n = act; break;
+    case PT_ACT_DHK: if (c->phase < 2) return fail(c, PT_ESTATE, "no backward pass yet"); src = c->last_dhk; n = act; is_f32 = true; break;
     default: return fail(c, PT_EINVAL, "unknown activation");
   }
   if (numel != n) return fail(c, PT_EINVAL, "activation size mismatch");

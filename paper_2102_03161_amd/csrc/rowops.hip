@@ -32,8 +32,8 @@ __device__ __forceinline__ void store4(bf16* p, const float (&v)[4]) {
 // ---------------------------------------------------------------------------
 // LayerNorm forward: one wave per row, row held in registers (D <= 256*VPL)
 // ---------------------------------------------------------------------------
-template <typename T, int VPL>
-__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, int64_t ldx, const T* __restrict__ gamma,
+template <typename T, typename TX, int VPL>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const TX* __restrict__ x, int64_t ldx, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y, int64_t ldy,
                                                      float* __restrict__ mean, float* __restrict__ rstd, int rows, int D,
                                                      float eps) {
@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, in
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const int nvec = D >> 2;
-  const T* xr = x + (int64_t)row * ldx;
+  const TX* xr = x + (int64_t)row * ldx;
   float v[VPL][4];
   float s = 0.f;
 #pragma unroll
@@ -81,15 +81,16 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, in
   }
 }
 
-void layernorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y, int64_t ldy,
-                   float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
+void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
+                   int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
   if (rows <= 0) return;
   dim3 grid(cdiv(rows, 4)), blk(256);
-#define LN_FWD(T, V)                                                                                             \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, V>), grid, blk, 0, st, (const T*)x, ldx, (const T*)gamma, (const T*)beta, \
-                     (T*)y, ldy, mean, rstd, rows, D, eps)
-  if (dt == 0) { if (D <= 1024) LN_FWD(float, 4); else LN_FWD(float, 8); }
-  else { if (D <= 1024) LN_FWD(bf16, 4); else LN_FWD(bf16, 8); }
+#define LN_FWD(T, TX, V)                                                                                  \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, TX, V>), grid, blk, 0, st, (const TX*)x, ldx, (const T*)gamma, \
+                     (const T*)beta, (T*)y, ldy, mean, rstd, rows, D, eps)
+  if (dt == 0) { if (D <= 1024) LN_FWD(float, float, 4); else LN_FWD(float, float, 8); }
+  else if (x_f32) { if (D <= 1024) LN_FWD(bf16, float, 4); else LN_FWD(bf16, float, 8); }
+  else { if (D <= 1024) LN_FWD(bf16, bf16, 4); else LN_FWD(bf16, bf16, 8); }
 #undef LN_FWD
 }
 
@@ -99,12 +100,15 @@ void layernorm_fwd(int dt, const void* x, int64_t ldx, const void* gamma, const 
 constexpr int kLnBwdBlocks = 512;
 size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 2 * D; }
 
-template <typename T, int VPL>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, int64_t lddy, const T* __restrict__ x,
+// dy may be the fp32 gradient stream or a T tensor; the result goes to an fp32 stream
+// buffer (dx_s), a T copy for the matrix-core operands (dx_o), or both (either may be null).
+template <typename T, typename TDY, typename TX, int VPL>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy, int64_t lddy, const TX* __restrict__ x,
                                                      int64_t ldx, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, const T* __restrict__ gamma,
-                                                     const T* __restrict__ dres, int64_t lddres, T* __restrict__ dx,
-                                                     int64_t lddx, float* __restrict__ partial, int rows, int D) {
+                                                     const float* __restrict__ dres, int64_t lddres,
+                                                     float* __restrict__ dx_s, T* __restrict__ dx_o, int64_t lddx,
+                                                     float* __restrict__ partial, int rows, int D) {
   extern __shared__ float red[];  // [4][2][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nvec = D >> 2;
@@ -138,6 +142,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, i
         }
       }
     }
+    if (!dx_s && !dx_o) continue;  // only the parameter gradients are wanted
     const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
 #pragma unroll
     for (int j = 0; j < VPL; ++j) {
@@ -152,7 +157,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dy, i
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] += r[e];
         }
-        store4(dx + (int64_t)row * lddx + 4 * c, o);
+        if (dx_s) store4(dx_s + (int64_t)row * lddx + 4 * c, o);
+        if (dx_o) store4(dx_o + (int64_t)row * lddx + 4 * c, o);
       }
     }
   }
@@ -185,17 +191,25 @@ __global__ void reduce_partials_kernel(const float* __restrict__ partial, int np
   if (i < n0) out0[i] = s; else out1[i - n0] = s;
 }
 
-void layernorm_bwd(int dt, const void* dy, int64_t lddy, const void* x, int64_t ldx, const float* mean,
-                   const float* rstd, const void* gamma, const void* dres, int64_t lddres, void* dx, int64_t lddx,
-                   float* dgamma, float* dbeta, float* partial, int rows, int D, hipStream_t st) {
+void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                   const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
+                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* partial, int rows, int D,
+                   hipStream_t st) {
   if (rows <= 0) return;
   const int nb = cdiv(rows, 4) < kLnBwdBlocks ? cdiv(rows, 4) : kLnBwdBlocks;
   const size_t shm = (size_t)8 * D * sizeof(float);
-#define LN_BWD(T, V)                                                                                                  \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, V>), dim3(nb), dim3(256), shm, st, (const T*)dy, lddy, (const T*)x, ldx, mean, \
-                     rstd, (const T*)gamma, (const T*)dres, lddres, (T*)dx, lddx, partial, rows, D)
-  if (dt == 0) { if (D <= 1024) LN_BWD(float, 4); else LN_BWD(float, 8); }
-  else { if (D <= 1024) LN_BWD(bf16, 4); else LN_BWD(bf16, 8); }
+#define LN_BWD(T, TDY, TX, V)                                                                                      \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, TDY, TX, V>), dim3(nb), dim3(256), shm, st, (const TDY*)dy, lddy,           \
+                     (const TX*)x, ldx, mean, rstd, (const T*)gamma, dres, lddres, dx_s, (T*)dx_o, lddx, partial, \
+                     rows, D)
+#define LN_BWD_V(T, TDY, TX) \
+  do { if (D <= 1024) LN_BWD(T, TDY, TX, 4); else LN_BWD(T, TDY, TX, 8); } while (0)
+  if (dt == 0) LN_BWD_V(float, float, float);
+  else if (dy_f32 && x_f32) LN_BWD_V(bf16, float, float);
+  else if (dy_f32) LN_BWD_V(bf16, float, bf16);
+  else if (x_f32) LN_BWD_V(bf16, bf16, float);
+  else LN_BWD_V(bf16, bf16, bf16);
+#undef LN_BWD_V
 #undef LN_BWD
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D, 256)), dim3(256), 0, st, partial, nb, 2 * D, dgamma, D,
                      dbeta);
@@ -280,33 +294,37 @@ void vit_assemble(int dt, const void* E, const void* cls, const void* pos, void*
 }
 
 template <typename T>
-__global__ void vit_front_bwd_kernel(const T* __restrict__ dX, T* __restrict__ dE, float* __restrict__ dpos,
+__global__ void vit_front_bwd_kernel(const float* __restrict__ dX, T* __restrict__ dE, float* __restrict__ dpos,
                                      float* __restrict__ dcls, int nb, int S, int D) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= S * D) return;
   const int s = i / D, d = i % D;
   float acc = 0.f;
   for (int b = 0; b < nb; ++b) {
-    const T v = dX[((int64_t)b * S + s) * D + d];
-    acc += to_f32(v);
-    if (s > 0) dE[((int64_t)b * (S - 1) + (s - 1)) * D + d] = v;
+    const float v = dX[((int64_t)b * S + s) * D + d];
+    acc += v;
+    if (s > 0) dE[((int64_t)b * (S - 1) + (s - 1)) * D + d] = from_f32<T>(v);
   }
   dpos[i] = acc;
   if (s == 0) dcls[d] = acc;
 }
-void vit_front_bwd(int dt, const void* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st) {
+void vit_front_bwd(int dt, const float* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st) {
   dim3 grid(cdiv(S * D, 256));
-  if (dt == 0) hipLaunchKernelGGL(vit_front_bwd_kernel<float>, grid, dim3(256), 0, st, (const float*)dX, (float*)dE, dpos, dcls, nb, S, D);
-  else hipLaunchKernelGGL(vit_front_bwd_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)dX, (bf16*)dE, dpos, dcls, nb, S, D);
+  if (dt == 0) hipLaunchKernelGGL(vit_front_bwd_kernel<float>, grid, dim3(256), 0, st, dX, (float*)dE, dpos, dcls, nb, S, D);
+  else hipLaunchKernelGGL(vit_front_bwd_kernel<bf16>, grid, dim3(256), 0, st, dX, (bf16*)dE, dpos, dcls, nb, S, D);
 }
 
 // ---------------------------------------------------------------------------
 // BERT front end
 // ---------------------------------------------------------------------------
+// ids and labels come from the caller; an out-of-range value is clamped so that no
+// access leaves its table
+__device__ __forceinline__ int clamp_id(int v, int n) { return v < 0 ? 0 : (v >= n ? n - 1 : v); }
+
 template <typename T>
 __global__ void bert_embed_kernel(const int32_t* __restrict__ ids, const int64_t* __restrict__ map,
-                                  const T* __restrict__ Ew, const T* __restrict__ Ep, T* __restrict__ emb, int nb, int S,
-                                  int D) {
+                                  const T* __restrict__ Ew, const T* __restrict__ Ep, float* __restrict__ emb, int nb,
+                                  int S, int D, int vocab) {
   const int nv = D >> 2;
   const int64_t total = (int64_t)nb * S * nv;
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
@@ -316,20 +334,20 @@ __global__ void bert_embed_kernel(const int32_t* __restrict__ ids, const int64_t
     const int64_t bo = t / S;
     const int64_t tin = (map ? map[bo] : bo) * S + s;
     float a[4], b[4], o[4];
-    load4(Ew + (int64_t)ids[tin] * D + 4 * c, a);
+    load4(Ew + (int64_t)clamp_id(ids[tin], vocab) * D + 4 * c, a);
     load4(Ep + (int64_t)s * D + 4 * c, b);
 #pragma unroll
     for (int e = 0; e < 4; ++e) o[e] = a[e] + b[e];
     store4(emb + t * D + 4 * c, o);
   }
 }
-void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, void* emb, int nb, int S,
-                int D, hipStream_t st) {
+void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, const void* Ep, float* emb, int nb, int S,
+                int D, int vocab, hipStream_t st) {
   const int64_t total = (int64_t)nb * S * (D / 4);
   const int blocks = (int)(cdiv64(total, 256) < 65536 ? cdiv64(total, 256) : 65536);
   if (blocks <= 0) return;
-  if (dt == 0) hipLaunchKernelGGL(bert_embed_kernel<float>, dim3(blocks), dim3(256), 0, st, ids, map, (const float*)Ew, (const float*)Ep, (float*)emb, nb, S, D);
-  else hipLaunchKernelGGL(bert_embed_kernel<bf16>, dim3(blocks), dim3(256), 0, st, ids, map, (const bf16*)Ew, (const bf16*)Ep, (bf16*)emb, nb, S, D);
+  if (dt == 0) hipLaunchKernelGGL(bert_embed_kernel<float>, dim3(blocks), dim3(256), 0, st, ids, map, (const float*)Ew, (const float*)Ep, emb, nb, S, D, vocab);
+  else hipLaunchKernelGGL(bert_embed_kernel<bf16>, dim3(blocks), dim3(256), 0, st, ids, map, (const bf16*)Ew, (const bf16*)Ep, emb, nb, S, D, vocab);
 }
 
 // next[t] = smallest t' > t with the same token id (or -1); has_prev[t'] = 1 for it.
@@ -345,42 +363,36 @@ __global__ void token_chain_kernel(const int32_t* __restrict__ ids, int32_t* __r
   if (nx >= 0) has_prev[nx] = 1;
 }
 // One workgroup per first occurrence of an id: sums the rows of its chain in token order.
-template <typename T>
 __global__ __launch_bounds__(256) void embed_scatter_kernel(const int32_t* __restrict__ ids,
                                                             const int32_t* __restrict__ next,
                                                             const int32_t* __restrict__ has_prev,
-                                                            const T* __restrict__ demb, float* __restrict__ dEw, int D) {
+                                                            const float* __restrict__ demb, float* __restrict__ dEw,
+                                                            int D, int vocab) {
   const int t0 = blockIdx.x;
   if (has_prev[t0]) return;
-  const int64_t row = ids[t0];
+  const int64_t row = clamp_id(ids[t0], vocab);
   for (int d = threadIdx.x; d < D; d += 256) {
     float acc = 0.f;
-    for (int t = t0; t >= 0; t = next[t]) acc += to_f32(demb[(int64_t)t * D + d]);
+    for (int t = t0; t >= 0; t = next[t]) acc += demb[(int64_t)t * D + d];
     dEw[row * D + d] = acc;
   }
 }
-template <typename T>
-__global__ void pos_sum_kernel(const T* __restrict__ demb, float* __restrict__ dEp, int nb, int S, int D) {
+__global__ void pos_sum_kernel(const float* __restrict__ demb, float* __restrict__ dEp, int nb, int S, int D) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= S * D) return;
   float acc = 0.f;
-  for (int b = 0; b < nb; ++b) acc += to_f32(demb[(int64_t)b * S * D + i]);
+  for (int b = 0; b < nb; ++b) acc += demb[(int64_t)b * S * D + i];
   dEp[i] = acc;
 }
-void bert_embed_bwd(int dt, const int32_t* ids, const void* demb, float* dEw, float* dEp, int32_t* ws, int nb,
-                       int S, int D, hipStream_t st) {
+void bert_embed_bwd(const int32_t* ids, const float* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S, int D,
+                    int vocab, hipStream_t st) {
   const int ntok = nb * S;
   int32_t* next = ws;
-  int32_t* has_prev = ws + ntok;
+  int32_t* has_prev = ws + ((ntok + 3) & ~3);  // keeps the second array 16-byte aligned
   fill_zero(has_prev, (size_t)ntok * 4, st);
   hipLaunchKernelGGL(token_chain_kernel, dim3(cdiv(ntok, 64)), dim3(64), 0, st, ids, next, has_prev, ntok);
-  if (dt == 0) {
-    hipLaunchKernelGGL(embed_scatter_kernel<float>, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, (const float*)demb, dEw, D);
-    hipLaunchKernelGGL(pos_sum_kernel<float>, dim3(cdiv(S * D, 256)), dim3(256), 0, st, (const float*)demb, dEp, nb, S, D);
-  } else {
-    hipLaunchKernelGGL(embed_scatter_kernel<bf16>, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, (const bf16*)demb, dEw, D);
-    hipLaunchKernelGGL(pos_sum_kernel<bf16>, dim3(cdiv(S * D, 256)), dim3(256), 0, st, (const bf16*)demb, dEp, nb, S, D);
-  }
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, demb, dEw, D, vocab);
+  hipLaunchKernelGGL(pos_sum_kernel, dim3(cdiv(S * D, 256)), dim3(256), 0, st, demb, dEp, nb, S, D);
 }
 
 // ---------------------------------------------------------------------------
@@ -399,7 +411,7 @@ __global__ __launch_bounds__(256) void ce_rows_kernel(const float* __restrict__ 
   for (int c = threadIdx.x; c < C; c += 256) s += expf(zr[c] - mx);
   s = block_sum<4>(s, red);
   const float lse = mx + logf(s);
-  const int lab = labels[b];
+  const int lab = clamp_id(labels[b], C);
   if (threadIdx.x == 0) loss_rows[b] = lse - zr[lab];
   const float inv = 1.0f / (float)nb;
   for (int c = threadIdx.x; c < C; c += 256) {
@@ -450,7 +462,7 @@ __global__ __launch_bounds__(256) void qa_ce_kernel(const float* __restrict__ z,
     for (int s = threadIdx.x; s < S; s += 256) sum += expf(zc[2 * s] - mx);
     sum = block_sum<4>(sum, red);
     const float lse = mx + logf(sum);
-    const int lab = labels[2 * b + c];
+    const int lab = clamp_id(labels[2 * b + c], S);
     loss += 0.5f * (lse - zc[2 * lab]);
     const float sc = 0.5f / (float)nb;
     for (int s = threadIdx.x; s < S; s += 256)
@@ -468,7 +480,7 @@ size_t qa_partial_floats(int D) { return (size_t)kQaBlocks * (2 * D + 2); }
 
 template <typename T>
 __global__ __launch_bounds__(256) void qa_head_bwd_kernel(const T* __restrict__ x, const T* __restrict__ W,
-                                                          const float* __restrict__ dz, T* __restrict__ dx,
+                                                          const float* __restrict__ dz, float* __restrict__ dx,
                                                           float* __restrict__ partial, int rows, int D) {
   // each thread owns columns d = tid, tid+256, ... (at most 8: D <= 2048)
   float w0[8], w1[8], a0[8], a1[8];
@@ -490,7 +502,7 @@ __global__ __launch_bounds__(256) void qa_head_bwd_kernel(const T* __restrict__ 
         const float xv = to_f32(x[(int64_t)t * D + d]);
         a0[j] += xv * g0;
         a1[j] += xv * g1;
-        dx[(int64_t)t * D + d] = from_f32<T>(g0 * w0[j] + g1 * w1[j]);
+        dx[(int64_t)t * D + d] = g0 * w0[j] + g1 * w1[j];
       }
     }
   }
@@ -502,11 +514,11 @@ __global__ __launch_bounds__(256) void qa_head_bwd_kernel(const T* __restrict__ 
   }
   if (threadIdx.x == 0) { p[2 * D] = b0; p[2 * D + 1] = b1; }
 }
-void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, void* dx, float* dW, float* db, float* partial,
+void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* dx, float* dW, float* db, float* partial,
                  int rows, int D, hipStream_t st) {
   const int nb = rows < kQaBlocks ? rows : kQaBlocks;
-  if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, (float*)dx, partial, rows, D);
-  else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, (bf16*)dx, partial, rows, D);
+  if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, dx, partial, rows, D);
+  else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, dx, partial, rows, D);
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 256)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
                      2 * D, db);
 }
