@@ -176,6 +176,20 @@ pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_byt
 pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, int64_t* misses,
                          int64_t* block_runs);
 
+/* Optional kernel timing.  While enabled, every launcher call of the listed
+ * categories is bracketed by two HIP events on the context's stream; totals are
+ * folded in when the optimizer step ends or when they are read (synchronises).
+ * `work` sums the algorithmic FLOPs (GEMM and attention categories) or bytes
+ * (optimizer, norms) of the timed launches, 0 for the others.  Timing costs a few
+ * microseconds per launch, so throughput is measured with it off. */
+enum { PT_PROF_GEMM_GENERIC = 0, PT_PROF_GEMM_NN = 1 /* y = x W */, PT_PROF_GEMM_NT = 2 /* dx = dy W^T */,
+       PT_PROF_GEMM_TN = 3 /* dW = x^T dy */, PT_PROF_ATTN_FWD = 4, PT_PROF_ATTN_BWD = 5, PT_PROF_LN_FWD = 6,
+       PT_PROF_LN_BWD = 7, PT_PROF_COLSUM = 8, PT_PROF_OPT = 9, PT_PROF_NORMS = 10, PT_PROF_CACHE = 11,
+       PT_PROF_COUNT = 12 };
+pt_status pt_profile_enable(pt_ctx* ctx, int32_t on);
+pt_status pt_profile_reset(pt_ctx* ctx);
+pt_status pt_profile_read(pt_ctx* ctx, int32_t category, double* total_ms, int64_t* launches, double* work /*HOST out*/);
+
 const char* pt_last_error(const pt_ctx* ctx);
 
 #ifdef __cplusplus

@@ -20,6 +20,8 @@ PT_F32, PT_BF16 = 0, 1
 PT_SGDM, PT_ADAMW = 0, 1
 KIND_PARAM, KIND_GRAD, KIND_MOMENT1, KIND_MOMENT2, KIND_SHADOW = range(5)
 ACT_HK, ACT_HL, ACT_LOGITS, ACT_DHK = range(4)
+PROF_CATEGORIES = ("gemm_generic", "gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd",
+                   "colsum", "opt", "norms", "cache")
 _STATUS = {0: "PT_OK", 1: "PT_EINVAL", 2: "PT_ESTATE", 3: "PT_ENOMEM", 4: "PT_EDEVICE", 5: "PT_ECACHE_MISS"}
 
 
@@ -75,6 +77,9 @@ def load_library():
         "pt_read_activation": [vp, i32, P(C.c_float), sz],
         "pt_cache_row": [vp, i64, vp, sz, P(i32)],
         "pt_cache_stats": [vp, P(i64), P(i64), P(i64), P(i64)],
+        "pt_profile_enable": [vp, i32],
+        "pt_profile_reset": [vp],
+        "pt_profile_read": [vp, i32, P(C.c_double), P(i64), P(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -249,3 +254,19 @@ class Context:
         a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
         self._chk(self.lib.pt_cache_stats(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
         return {"hits": a.value, "advances": b.value, "misses": c.value, "block_runs": d.value}
+
+    # ---- kernel timing ---------------------------------------------------------
+    def profile_enable(self, on: bool):
+        self._chk(self.lib.pt_profile_enable(self.h, 1 if on else 0))
+
+    def profile_reset(self):
+        self._chk(self.lib.pt_profile_reset(self.h))
+
+    def profile_read(self) -> dict:
+        """{category: (total_ms, launches, work)}"""
+        out = {}
+        for i, name in enumerate(PROF_CATEGORIES):
+            ms, n, wk = C.c_double(), C.c_int64(), C.c_double()
+            self._chk(self.lib.pt_profile_read(self.h, i, C.byref(ms), C.byref(n), C.byref(wk)))
+            out[name] = (ms.value, n.value, wk.value)
+        return out

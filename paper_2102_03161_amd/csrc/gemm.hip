@@ -277,6 +277,8 @@ static bool mfma_ok(const Gemm& a) {
   return a_ok && b_ok && a.M >= 32 && a.N >= 32;
 }
 
+bool gemm_uses_mfma(int dt, const Gemm& a) { return dt != 0 && mfma_ok(a); }
+
 void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return;
   if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step

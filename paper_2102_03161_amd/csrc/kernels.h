@@ -31,6 +31,8 @@ struct Gemm {
   bool c_f32 = false;
 };
 void gemm(int dt, const Gemm& g, hipStream_t st);
+// true when gemm() will run the matrix-core kernel for this problem
+bool gemm_uses_mfma(int dt, const Gemm& g);
 
 // ---- attention (softmax(q k^T / sqrt(dh)) v, no mask) over packed qkv [nb,S,3D]
 void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or null*/, int nb, int S, int H,

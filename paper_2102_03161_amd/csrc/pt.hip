@@ -210,6 +210,14 @@ struct pt_ctx {
   bool idx_ev_used[2] = {false, false};
   int idx_turn = 0;
   mutable std::string err;
+  // optional per-category kernel timing with HIP events on the context's stream
+  struct ProfRec { hipEvent_t a, b; int cat; double work; };
+  bool prof_on = false;
+  std::vector<ProfRec> prof_pool;
+  size_t prof_used = 0;
+  double prof_ms[PT_PROF_COUNT] = {};
+  double prof_work[PT_PROF_COUNT] = {};
+  int64_t prof_n[PT_PROF_COUNT] = {};
 
   const void* cp(int id) const {  // parameter as the kernels read it
     const TensorDesc& t = plan.tensors[id];
@@ -223,6 +231,49 @@ struct pt_ctx {
 };
 
 namespace {
+
+// Brackets one launcher call with two events when profiling is on.
+struct ProfScope {
+  pt_ctx* c;
+  pt_ctx::ProfRec* r = nullptr;
+  ProfScope(pt_ctx* ctx, int cat, double work) : c(ctx) {
+    if (!c->prof_on) return;
+    if (c->prof_used == c->prof_pool.size()) {
+      pt_ctx::ProfRec n{};
+      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+      c->prof_pool.push_back(n);
+    }
+    r = &c->prof_pool[c->prof_used++];
+    r->cat = cat;
+    r->work = work;
+    (void)hipEventRecord(r->a, c->st);
+  }
+  ~ProfScope() {
+    if (r) (void)hipEventRecord(r->b, c->st);
+  }
+};
+
+// folds finished event pairs into the per-category totals (synchronises)
+void prof_collect(pt_ctx* c) {
+  if (c->prof_used == 0) return;
+  (void)hipStreamSynchronize(c->st);
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    const auto& r = c->prof_pool[i];
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+      c->prof_ms[r.cat] += ms;
+      c->prof_work[r.cat] += r.work;
+      c->prof_n[r.cat] += 1;
+    }
+  }
+  c->prof_used = 0;
+}
+
+int gemm_cat(int dt, const Gemm& m) {
+  if (!gemm_uses_mfma(dt, m)) return PT_PROF_GEMM_GENERIC;
+  if (m.ta) return PT_PROF_GEMM_TN;
+  return m.tb ? PT_PROF_GEMM_NT : PT_PROF_GEMM_NN;
+}
 
 pt_status fail(const pt_ctx* c, pt_status s, const std::string& m) {
   if (c) c->err = m;
@@ -249,25 +300,25 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
     Gemm m;
     m.A = A; m.lda = K; m.B = c->cp(wid); m.ldb = N; m.C = C; m.ldc = N; m.M = Tn; m.N = N; m.K = K;
     m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = N; m.c_f32 = out_f32;
-    gemm(dt, m, st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
   if (g.arch == PT_VIT_PRELN) {
-    layernorm_fwd(dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st); }
     lin(c->w(s.U), D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
-    attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_FWD, 4.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st); }
     lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.Y), D, EPI_BIAS_RES, xin, nullptr);
-    layernorm_fwd(dt, false, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st); }
     lin(c->w(s.WN), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
     lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), xout, D, EPI_BIAS_RES, c->w(s.Y), nullptr);
   } else {
     // post-LN: U holds x + Attn(x) in fp32, Y = LN1(U), WN holds Y + MLP(Y) in fp32, out = LN2(WN)
     lin(xin, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
-    attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_FWD, 4.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st); }
     lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.U), D, EPI_BIAS_RES, xin, nullptr, true);
-    layernorm_fwd(dt, true, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st); }
     lin(c->w(s.Y), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
     lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), c->w(s.WN), D, EPI_BIAS_RES, c->w(s.Y), nullptr, true);
-    layernorm_fwd(dt, true, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st); }
   }
 }
 
@@ -297,15 +348,15 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     Gemm m;
     m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
-    gemm(dt, m, st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
-  auto bgrad = [&](int src_dt, const void* dY, int Nout, int bid) { colsum(src_dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st); };
+  auto bgrad = [&](int src_dt, const void* dY, int Nout, int bid) { { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(src_dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st); } };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
     Gemm m;
     m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
     m.M = Tn; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin; m.c_f32 = out_f32;
-    gemm(dt, m, st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
   if (g.arch == PT_VIT_PRELN) {
     wgrad(c->w(s.G), F, dout.o, D, c->blk(l, W2));
@@ -314,33 +365,33 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1));
     bgrad(dt, dF, F, c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dLN2out
-    layernorm_bwd(dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
-                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // sC / oD = dL/dY
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
+                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st); }  // sC / oD = dL/dY
     wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO));
     bgrad(0, sC, D, c->blk(l, BO));
     dgrad(oD, D, c->blk(l, WO), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dCTX
-    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV));
     bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
-    layernorm_bwd(dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
-                  c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);
+                  c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st); }
   } else {
-    layernorm_bwd(dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
-                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st);  // sC / oC = dL/d(Y+MLP)
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
+                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st); }  // sC / oC = dL/d(Y+MLP)
     wgrad(c->w(s.G), F, oC, D, c->blk(l, W2));
     bgrad(0, sC, D, c->blk(l, B2));
     dgrad(oC, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
     wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1));
     bgrad(dt, dF, F, c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
-    layernorm_bwd(dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
-                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st);  // sC / oC = dL/d(x+Attn)
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
+                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st); }  // sC / oC = dL/d(x+Attn)
     wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO));
     bgrad(0, sC, D, c->blk(l, BO));
     dgrad(oC, D, c->blk(l, WO), oD, D, EPI_STORE, nullptr, false);                      // oD = dL/dCTX
-    attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
     wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV));
     bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
@@ -359,12 +410,12 @@ void front_forward(pt_ctx* c, const void* d_input, const int64_t* d_map, void* x
     Gemm m;
     m.A = c->w(p.PATCH); m.lda = pd; m.B = c->cp(0); m.ldb = D; m.C = c->w(p.EMB); m.ldc = D;
     m.M = np; m.N = D; m.K = pd; m.epi = EPI_BIAS; m.bias = c->cp(1);
-    gemm(dt, m, st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
     vit_assemble(dt, c->w(p.EMB), c->cp(2), c->cp(3), xout, ns, g.S, D, st);
   } else {
     bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->wf(p.EMB), ns, g.S, D, g.vocab, st);
-    layernorm_fwd(dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
-                  save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
+                  save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st); }
   }
 }
 
@@ -379,11 +430,11 @@ void front_backward(pt_ctx* c, const float* dx, int ns) {
     Gemm m;
     m.A = c->w(p.PATCH); m.lda = pd; m.ta = true; m.B = c->w(p.DEMB); m.ldb = D; m.C = c->gp(0); m.ldc = D;
     m.M = pd; m.N = D; m.K = np; m.c_f32 = true;
-    gemm(dt, m, st);
-    colsum(dt, c->w(p.DEMB), D, np, D, c->gp(1), c->wf(p.CSPART), st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
+    { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(dt, c->w(p.DEMB), D, np, D, c->gp(1), c->wf(p.CSPART), st); }
   } else {
-    layernorm_bwd(dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
-                  nullptr, D, c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st);
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
+                  nullptr, D, c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st); }
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
     bert_embed_bwd((const int32_t*)c->last_input, c->wf(p.DEMB), c->gp(0), c->gp(1),
@@ -497,6 +548,7 @@ pt_status pt_destroy(pt_ctx* c) {
     if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
     if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
   }
+  for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   delete c;
   return PT_OK;
 }
@@ -562,7 +614,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
       std::vector<int64_t> src(nb);
       for (int i = 0; i < nb; ++i) src[i] = sample_ids[i];
       const int64_t* dsrc = stg.put(src, &cerr);
-      copy_rows(c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st);
+      { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st); }
       c->last_hk = c->w(p.HKOUT);
     } else {
       if (n_miss > 0) {
@@ -585,7 +637,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
         if (!dst.empty()) {
           const int64_t* ddst = stg.put(dst, &cerr);
           const int64_t* dsrc = stg.put(src, &cerr);
-          copy_rows(c->w(p.X[j]), ddst, c->cache, dsrc, (int)dst.size(), row_bytes, c->st);
+          { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.X[j]), ddst, c->cache, dsrc, (int)dst.size(), row_bytes, c->st); }
         }
         // the sorted prefix of n_le samples (misses and rows written at or below j) runs block j
         if (j < k && n_le > 0) {
@@ -599,7 +651,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
           if (kw[order[i]] < k) { dst.push_back(sample_ids[order[i]]); src.push_back(i); }
         const int64_t* ddst = stg.put(dst, &cerr);
         const int64_t* dsrc = stg.put(src, &cerr);
-        copy_rows(c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st);
+        { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st); }
       }
       if (identity) {
         c->last_hk = c->w(p.X[k]);
@@ -607,7 +659,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
         std::vector<int64_t> dst(nb);
         for (int i = 0; i < nb; ++i) dst[i] = order[i];
         const int64_t* ddst = stg.put(dst, &cerr);
-        copy_rows(c->w(p.HKOUT), ddst, c->w(p.X[k]), nullptr, nb, row_bytes, c->st);
+        { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.HKOUT), ddst, c->w(p.X[k]), nullptr, nb, row_bytes, c->st); }
         c->last_hk = c->w(p.HKOUT);
       }
     }
@@ -647,27 +699,27 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   if (g.arch == PT_VIT_PRELN) {
     const int C = g.n_out;
     const int hg = c->head(0), hb = c->head(1), hW = c->head(2), hbias = c->head(3);
-    layernorm_fwd(dt, false, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st);
+    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st); }
     Gemm m;
     m.A = c->w(p.CFEAT); m.lda = D; m.B = c->cp(hW); m.ldb = C; m.C = c->w(p.LOGITS); m.ldc = C;
     m.M = nb; m.N = C; m.K = D; m.epi = EPI_BIAS; m.bias = c->cp(hbias); m.c_f32 = true;
-    gemm(dt, m, st);
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
     ce_rows(dt, c->wf(p.LOGITS), d_labels, c->wf(p.LOSSROWS), c->w(p.DZ), nb, C, st);
     mean_reduce(c->wf(p.LOSSROWS), nb, c->wf(p.LOSS), st);
     Gemm wg;
     wg.A = c->w(p.CFEAT); wg.lda = D; wg.ta = true; wg.B = c->w(p.DZ); wg.ldb = C; wg.C = c->gp(hW); wg.ldc = C;
     wg.M = D; wg.N = C; wg.K = nb; wg.c_f32 = true;
-    gemm(dt, wg, st);
-    colsum(dt, c->w(p.DZ), C, nb, C, c->gp(hbias), c->wf(p.CSPART), st);
+    { ProfScope ps_(c, gemm_cat(dt, wg), 2.0 * wg.M * wg.N * wg.K); gemm(dt, wg, st); }
+    { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(dt, c->w(p.DZ), C, nb, C, c->gp(hbias), c->wf(p.CSPART), st); }
     Gemm dg;
     dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
     dg.M = nb; dg.N = D; dg.K = C;
-    gemm(dt, dg, st);
+    { ProfScope ps_(c, gemm_cat(dt, dg), 2.0 * dg.M * dg.N * dg.K); gemm(dt, dg, st); }
     // only the CLS rows of dL/dx_L are non-zero
     fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
     fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
-    layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
-                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st);
+    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
+                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st); }
   } else {
     const int hW = c->head(0), hbias = c->head(1);
     qa_logits(dt, x, c->cp(hW), c->cp(hbias), c->wf(p.LOGITS), nb * S, D, st);
@@ -704,7 +756,7 @@ pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
   const auto& gf = c->plan.group_first_chunk;
   const int G = c->cfg.L + 2, k = c->k;
   const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
-  sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st);
+  { ProfScope ps_(c, PT_PROF_NORMS, 4.0 * (total - first) * kChunk); sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st); }
   finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
                  c->wf(c->plan.NORMS), c->st);
   HIP_TRY(c, hipMemcpyAsync(norms_out, c->w(c->plan.NORMS), (size_t)G * 4, hipMemcpyDeviceToHost, c->st));
@@ -726,12 +778,13 @@ pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {
   a.bias_c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)t));
   const uint8_t* decay = reinterpret_cast<const uint8_t*>(c->w(c->plan.CHUNKDECAY));
   if (c->cfg.optimizer == PT_ADAMW)
-    adamw_chunks(c->master, c->grads, c->mom1, c->mom2, c->shadow, decay, first, total - first, a, c->st);
+    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 30.0 : 28.0) * (total - first) * kChunk); adamw_chunks(c->master, c->grads, c->mom1, c->mom2, c->shadow, decay, first, total - first, a, c->st); }
   else
-    sgdm_chunks(c->master, c->grads, c->mom1, c->shadow, decay, first, total - first, a, c->st);
+    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 22.0 : 20.0) * (total - first) * kChunk); sgdm_chunks(c->master, c->grads, c->mom1, c->shadow, decay, first, total - first, a, c->st); }
   HIP_TRY(c, hipGetLastError());
   c->step = t;
   c->phase = 0;
+  if (c->prof_on) prof_collect(c);
   return PT_OK;
 }
 
@@ -858,6 +911,29 @@ pt_status pt_cache_stats(const pt_ctx* c, int64_t* hits, int64_t* advances, int6
   if (advances) *advances = c->n_adv;
   if (misses) *misses = c->n_miss;
   if (block_runs) *block_runs = c->n_runs;
+  return PT_OK;
+}
+
+pt_status pt_profile_enable(pt_ctx* c, int32_t on) {
+  if (!c) return PT_EINVAL;
+  if (!on) prof_collect(c);
+  c->prof_on = on != 0;
+  return PT_OK;
+}
+
+pt_status pt_profile_reset(pt_ctx* c) {
+  if (!c) return PT_EINVAL;
+  prof_collect(c);
+  for (int i = 0; i < PT_PROF_COUNT; ++i) { c->prof_ms[i] = 0; c->prof_work[i] = 0; c->prof_n[i] = 0; }
+  return PT_OK;
+}
+
+pt_status pt_profile_read(pt_ctx* c, int32_t category, double* total_ms, int64_t* launches, double* work) {
+  if (!c || category < 0 || category >= PT_PROF_COUNT) return PT_EINVAL;
+  prof_collect(c);
+  if (total_ms) *total_ms = c->prof_ms[category];
+  if (launches) *launches = c->prof_n[category];
+  if (work) *work = c->prof_work[category];
   return PT_OK;
 }
 
