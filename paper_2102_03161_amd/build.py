@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpt.so")
-SOURCES = ["gemm.hip", "attention.hip", "rowops.hip", "optim.hip", "pt.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "attention_mfma.hip", "rowops.hip", "optim.hip", "pt.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep fp32 vector math scalar per lane: no packed-fp32 instruction selection
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

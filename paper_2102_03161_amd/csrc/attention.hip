@@ -279,8 +279,14 @@ static void attention_fwd_t(const void* qkv, void* ctx, float* lse, int nb, int 
   hipLaunchKernelGGL(attn_fwd_kernel<T>, dim3(cdiv(S, TQ), H, nb), dim3(256), shm, st, (const T*)qkv, (T*)ctx, lse, S, H,
                      dh, Spad);
 }
+// matrix-core kernels for bf16, head size 64 (attention_mfma.hip)
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, int H, hipStream_t st);
+void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
+                        int nb, int S, int H, hipStream_t st);
+
 void attention_fwd(int dt, const void* qkv, void* ctx, float* lse, int nb, int S, int H, int dh, hipStream_t st) {
   if (nb <= 0) return;
+  if (dt == 1 && dh == 64) { attention_fwd_mfma(qkv, ctx, lse, nb, S, H, st); return; }
   if (dt == 0) attention_fwd_t<float>(qkv, ctx, lse, nb, S, H, dh, st);
   else attention_fwd_t<bf16>(qkv, ctx, lse, nb, S, H, dh, st);
 }
@@ -305,6 +311,7 @@ static void attention_bwd_t(const void* qkv, const void* ctx, const void* dctx, 
 void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv,
                    float* delta_ws, int nb, int S, int H, int dh, hipStream_t st) {
   if (nb <= 0) return;
+  if (dt == 1 && dh == 64) { attention_bwd_mfma(qkv, ctx, dctx, lse, dqkv, delta_ws, nb, S, H, st); return; }
   if (dt == 0) attention_bwd_t<float>(qkv, ctx, dctx, lse, dqkv, delta_ws, nb, S, H, dh, st);
   else attention_bwd_t<bf16>(qkv, ctx, dctx, lse, dqkv, delta_ws, nb, S, H, dh, st);
 }

@@ -1,0 +1,327 @@
+// bf16 softmax attention on the gfx950 matrix cores, head size 64, no mask.
+//
+// Layout trick shared by the three kernels: the score tile is always computed
+// with the dimension a wave OWNS (32 queries in forward / dQ, 32 keys in dK/dV)
+// as the MFMA output column, i.e. one lane = one owned row.  Then
+//   * every per-row quantity (running max, sum, log-sum-exp, delta, the O
+//     rescale factor) is a per-lane scalar: the only cross-lane traffic is one
+//     xor-32 shuffle between the two half-waves;
+//   * the fp32 score/probability accumulator, converted to bf16, already IS the
+//     B operand of the next MFMA (contraction over the streamed dimension), so
+//     probabilities never leave registers;
+//   * the other operand of that MFMA must be read "transposed" (8 streamed rows
+//     for one feature), which the cooperative tile loader provides by writing a
+//     transposed copy of each streamed 32x64 tile into LDS (2x2 16-bit
+//     transposes in registers, 4-byte LDS writes).
+// The streamed dimension goes through LDS in 32-row tiles shared by the four
+// waves of a workgroup.  No atomics: dQ and dK/dV are separate kernels, each
+// recomputing the probabilities from the saved row log-sum-exp, so results are
+// reproducible.
+#include "common.h"
+#include "kernels.h"
+
+namespace pt {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+namespace {
+
+constexpr int DH = 64;
+constexpr int LDR = DH + 8;   // row-major tile: 144-byte rows, conflict-free 16-byte operand reads
+constexpr int LDT = 32 + 4;   // transposed tile [64][32]: 72-byte rows, conflict-free 8-byte operand reads
+
+// Cooperative load (256 threads) of rows r0..r0+31 of a [*, 64] bf16 matrix with row stride ld
+// into a row-major tile Xs[32][LDR] and / or a transposed tile Xt[64][LDT].  Rows >= nrows read as 0.
+__device__ __forceinline__ void load_tile(const bf16* __restrict__ src, int64_t ld, int r0, int nrows, bf16* Xs,
+                                          bf16* Xt, int tid) {
+  const int rp = tid >> 4, dc = tid & 15;
+  const int r = r0 + 2 * rp;
+  uint2 a = make_uint2(0, 0), b = make_uint2(0, 0);
+  if (r < nrows) a = *reinterpret_cast<const uint2*>(src + (int64_t)r * ld + 4 * dc);
+  if (r + 1 < nrows) b = *reinterpret_cast<const uint2*>(src + (int64_t)(r + 1) * ld + 4 * dc);
+  if (Xs) {
+    *reinterpret_cast<uint2*>(Xs + (2 * rp) * LDR + 4 * dc) = a;
+    *reinterpret_cast<uint2*>(Xs + (2 * rp + 1) * LDR + 4 * dc) = b;
+  }
+  if (Xt) {
+    uint32_t* t = reinterpret_cast<uint32_t*>(Xt);
+    const int o = (4 * dc) * (LDT / 2) + rp;  // dword index of Xt[4dc][2rp]
+    t[o] = (a.x & 0xffffu) | (b.x << 16);
+    t[o + (LDT / 2)] = (a.x >> 16) | (b.x & 0xffff0000u);
+    t[o + 2 * (LDT / 2)] = (a.y & 0xffffu) | (b.y << 16);
+    t[o + 3 * (LDT / 2)] = (a.y >> 16) | (b.y & 0xffff0000u);
+  }
+}
+
+// A operand from a row-major tile: row lane%32, features 16*ks + 8*half .. +7
+__device__ __forceinline__ bf16x8 frag_rows(const bf16* Xs, int lane, int ks) {
+  return *reinterpret_cast<const bf16x8*>(Xs + (lane & 31) * LDR + ks * 16 + (lane >> 5) * 8);
+}
+// A operand from a transposed tile: feature 32*dt + lane%32, streamed rows in accumulator order:
+// slot i of k-step ks2 is row 16*ks2 + 8*(i/4) + 4*half + i%4
+__device__ __forceinline__ bf16x8 frag_cols(const bf16* Xt, int lane, int dt, int ks2) {
+  const bf16* p = Xt + (dt * 32 + (lane & 31)) * LDT + 16 * ks2 + 4 * (lane >> 5);
+  union { uint2 u[2]; bf16x8 v; } t;
+  t.u[0] = *reinterpret_cast<const uint2*>(p);
+  t.u[1] = *reinterpret_cast<const uint2*>(p + 8);
+  return t.v;
+}
+// B operand straight from global memory: the lane's own row, features 16*ks + 8*half .. +7
+__device__ __forceinline__ bf16x8 own_row_frag(const bf16* row, bool ok, int lane, int ks) {
+  union { uint4 u; bf16x8 v; } t;
+  t.u = make_uint4(0, 0, 0, 0);
+  if (ok) t.u = *reinterpret_cast<const uint4*>(row + ks * 16 + (lane >> 5) * 8);
+  return t.v;
+}
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int first) {
+  bf16x8 r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r[i] = from_f32<bf16>(a[first + i]);
+  return r;
+}
+// accumulator register v of a 32x32 tile holds tile row 8*(v/4) + 4*half + v%4 (column = lane%32)
+__device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+// store one accumulator pair [feature rows][owned column] as 8-byte pieces of the owner's row
+__device__ __forceinline__ void store_owned_row(bf16* row, const f32x16 (&acc)[2], float mul, int half) {
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      union { bf16 h[4]; uint2 u; } t;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t.h[e] = from_f32<bf16>(acc[dt][4 * g4 + e] * mul);
+      *reinterpret_cast<uint2*>(row + dt * 32 + 8 * g4 + 4 * half) = t.u;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// forward: a wave owns 32 queries, K/V stream through LDS
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+                                                            float* __restrict__ lse, int S, int H) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[32 * LDR];
+  __shared__ __attribute__((aligned(16))) bf16 Vt[64 * LDT];
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);
+  const bool qok = q < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const float scale = 0.125f;  // 1/sqrt(64)
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = own_row_frag(base + (int64_t)q * 3 * D, qok, lane, ks);
+  f32x16 o[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  const int ntile = (S + 31) / 32;
+  for (int kt = 0; kt < ntile; ++kt) {
+    __syncthreads();
+    load_tile(base + D, 3 * D, kt * 32, S, Ks, nullptr, tid);
+    load_tile(base + 2 * D, 3 * D, kt * 32, S, nullptr, Vt, tid);
+    __syncthreads();
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, lane, ks), qf[ks], s, 0, 0, 0);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] * scale : -INFINITY;
+      mx = fmaxf(mx, s[v]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = __expf(m - m_new);
+    float rs = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = __expf(s[v] - m_new);
+      rs += s[v];
+    }
+    rs += __shfl_xor(rs, 32, 64);
+    lsum = lsum * alpha + rs;
+    m = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 pb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(Vt, lane, dt, ks2), pb, o[dt], 0, 0, 0);
+    }
+  }
+  if (qok) {
+    store_owned_row(ctx + ((int64_t)b * S + q) * D + h * DH, o, 1.0f / lsum, half);
+    if (lse && half == 0) lse[((int64_t)b * H + h) * S + q] = m + __logf(lsum);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// backward part 1: delta = rowsum(dO * O) and dQ; a wave owns 32 queries
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                               const bf16* __restrict__ dctx,
+                                                               const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                               float* __restrict__ delta, int S, int H) {
+  __shared__ __attribute__((aligned(16))) bf16 Ks[32 * LDR];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[32 * LDR];
+  __shared__ __attribute__((aligned(16))) bf16 Kt[64 * LDT];
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);
+  const bool qok = q < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const float scale = 0.125f;
+  bf16x8 qf[4], dof[4];
+  float part = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = own_row_frag(base + (int64_t)q * 3 * D, qok, lane, ks);
+    dof[ks] = own_row_frag(dctx + ((int64_t)b * S + q) * D + h * DH, qok, lane, ks);
+    const bf16x8 of = own_row_frag(ctx + ((int64_t)b * S + q) * D + h * DH, qok, lane, ks);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
+  }
+  const float dl = part + __shfl_xor(part, 32, 64);
+  const float lq = qok ? lse[((int64_t)b * H + h) * S + q] : 0.f;
+  if (qok && half == 0) delta[((int64_t)b * H + h) * S + q] = dl;
+  f32x16 dq[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dq[dt][v] = 0.f;
+  const int ntile = (S + 31) / 32;
+  for (int kt = 0; kt < ntile; ++kt) {
+    __syncthreads();
+    load_tile(base + D, 3 * D, kt * 32, S, Ks, Kt, tid);
+    load_tile(base + 2 * D, 3 * D, kt * 32, S, Vs, nullptr, tid);
+    __syncthreads();
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, lane, ks), qf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, lane, ks), dof[ks], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const bool ok = qok && (kt * 32 + acc_row(v, half) < S);
+      const float p = ok ? __expf(s[v] * scale - lq) : 0.f;
+      s[v] = p * (dp[v] - dl);  // dS^T
+    }
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 dsb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(Kt, lane, dt, ks2), dsb, dq[dt], 0, 0, 0);
+    }
+  }
+  if (qok) store_owned_row(dqkv + ((int64_t)b * S + q) * 3 * D + h * DH, dq, scale, half);
+}
+
+// ---------------------------------------------------------------------------
+// backward part 2: dK, dV; a wave owns 32 keys, Q / dO stream through LDS
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __restrict__ qkv,
+                                                                const bf16* __restrict__ dctx,
+                                                                const float* __restrict__ lse,
+                                                                const float* __restrict__ delta,
+                                                                bf16* __restrict__ dqkv, int S, int H) {
+  __shared__ __attribute__((aligned(16))) bf16 Qs[32 * LDR];
+  __shared__ __attribute__((aligned(16))) bf16 dOs[32 * LDR];
+  __shared__ __attribute__((aligned(16))) bf16 Qt[64 * LDT];
+  __shared__ __attribute__((aligned(16))) bf16 dOt[64 * LDT];
+  __shared__ float ls[32], dls[32];
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int key = blockIdx.x * 128 + wave * 32 + (lane & 31);
+  const bool kok = key < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const bf16* dobase = dctx + (int64_t)b * S * D + h * DH;
+  const float scale = 0.125f;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks] = own_row_frag(base + (int64_t)key * 3 * D + D, kok, lane, ks);
+    vf[ks] = own_row_frag(base + (int64_t)key * 3 * D + 2 * D, kok, lane, ks);
+  }
+  f32x16 dk[2], dv[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+  const int ntile = (S + 31) / 32;
+  for (int qt = 0; qt < ntile; ++qt) {
+    __syncthreads();
+    load_tile(base, 3 * D, qt * 32, S, Qs, Qt, tid);
+    load_tile(dobase, D, qt * 32, S, dOs, dOt, tid);
+    if (tid < 32) {
+      const int qq = qt * 32 + tid;
+      ls[tid] = qq < S ? lse[((int64_t)b * H + h) * S + qq] : 0.f;
+      dls[tid] = qq < S ? delta[((int64_t)b * H + h) * S + qq] : 0.f;
+    }
+    __syncthreads();
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Qs, lane, ks), kf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dOs, lane, ks), vf[ks], dp, 0, 0, 0);
+    }
+    f32x16 pr;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int qi = acc_row(v, half);
+      const bool ok = kok && (qt * 32 + qi < S);
+      const float p = ok ? __expf(s[v] * scale - ls[qi]) : 0.f;
+      pr[v] = p;
+      s[v] = p * (dp[v] - dls[qi]);  // dS
+    }
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 pb = pack8(pr, 8 * ks2), dsb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dOt, lane, dt, ks2), pb, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(Qt, lane, dt, ks2), dsb, dk[dt], 0, 0, 0);
+      }
+    }
+  }
+  if (kok) {
+    bf16* row = dqkv + ((int64_t)b * S + key) * 3 * D + h * DH;
+    store_owned_row(row + D, dk, scale, half);
+    store_owned_row(row + 2 * D, dv, 1.0f, half);
+  }
+}
+
+}  // namespace
+
+void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, int H, hipStream_t st) {
+  hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(cdiv(S, 128), H, nb), dim3(256), 0, st, (const bf16*)qkv, (bf16*)ctx, lse,
+                     S, H);
+}
+void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
+                        int nb, int S, int H, hipStream_t st) {
+  dim3 grid(cdiv(S, 128), H, nb);
+  hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, grid, dim3(256), 0, st, (const bf16*)qkv, (const bf16*)ctx,
+                     (const bf16*)dctx, lse, (bf16*)dqkv, delta, S, H);
+  hipLaunchKernelGGL(attn_bwd_dkv_mfma_kernel, grid, dim3(256), 0, st, (const bf16*)qkv, (const bf16*)dctx, lse, delta,
+                     (bf16*)dqkv, S, H);
+}
+
+}  // namespace pt
