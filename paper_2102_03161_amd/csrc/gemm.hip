@@ -101,120 +101,306 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmDev<T> g, int64_t
 }
 
 // ---------------------------------------------------------------------------
-// bf16 MFMA kernel: 128x128x32 tile, 4 waves (2x2), 64x64 per wave
+// bf16 MFMA kernel, tile shape given by Cfg
 // ---------------------------------------------------------------------------
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int LDSK = BK + 8;  // 80-byte rows: 16-byte operand reads of 8 consecutive rows hit distinct banks
+template <int BM_, int BN_, int BK_, int WGM_, int WGN_>
+struct Cfg {
+  static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
+  static constexpr int NT = 64 * WGM * WGN;          // threads
+  static constexpr int WTM = BM / WGM, WTN = BN / WGN;  // per-wave tile
+  static constexpr int TM = WTM / 32, TN = WTN / 32;    // 32x32 MFMA tiles per wave
+  static constexpr int LDSK = BK + 8;  // padded rows: 16-byte operand reads of 8 consecutive rows hit distinct banks
+  static constexpr int KC = BK / 8;    // 16-byte chunks per row
+};
 
-// Stage one 128 x 32 operand tile into 8 dwords per thread.
-// k-major operand (element (r,k) at p[r*ld + k]): two 16-byte loads per thread.
-__device__ __forceinline__ void load_kmajor(const bf16* p, int64_t ld, int R, int K, int r0, int k0, int tid,
-                                            uint32_t (&reg)[8]) {
+// Staging of one ROWS x BK operand tile in registers: NR dwords per thread.
+// k-major operand (element (r,k) at p[r*ld + k]): 16-byte loads.
+template <int ROWS, int BK, int NT>
+struct KMajor {
+  static constexpr int KC = BK / 8, CH = ROWS * KC / NT, NR = 4 * CH, LDSK = BK + 8;
+  static_assert(ROWS * KC % NT == 0, "tile does not divide over the threads");
+  static __device__ __forceinline__ void load(const bf16* p, int64_t ld, int R, int K, int r0, int k0, int tid,
+                                              uint32_t (&reg)[NR]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = tid + i * 256;
-    const int row = c >> 2, kc = (c & 3) * 8;
-    const int gr = r0 + row, gk = k0 + kc;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (gr < R && gk < K) v = *reinterpret_cast<const uint4*>(p + (int64_t)gr * ld + gk);
-    reg[4 * i + 0] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / KC, kc = (c % KC) * 8;
+      const int gr = r0 + row, gk = k0 + kc;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (gr < R && gk < K) v = *reinterpret_cast<const uint4*>(p + (int64_t)gr * ld + gk);
+      reg[4 * i + 0] = v.x; reg[4 * i + 1] = v.y; reg[4 * i + 2] = v.z; reg[4 * i + 3] = v.w;
+    }
   }
-}
-__device__ __forceinline__ void store_kmajor(bf16* s, int tid, const uint32_t (&reg)[8]) {
+  static __device__ __forceinline__ void store(bf16* s, int tid, const uint32_t (&reg)[NR]) {
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = tid + i * 256;
-    const int row = c >> 2, kc = (c & 3) * 8;
-    *reinterpret_cast<uint4*>(s + row * LDSK + kc) = make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
+    for (int i = 0; i < CH; ++i) {
+      const int c = tid + i * NT;
+      const int row = c / KC, kc = (c % KC) * 8;
+      *reinterpret_cast<uint4*>(s + row * LDSK + kc) = make_uint4(reg[4 * i], reg[4 * i + 1], reg[4 * i + 2], reg[4 * i + 3]);
+    }
   }
-}
-// strided operand (element (r,k) at p[k*ld + r]): each thread owns rows 2q,2q+1
-// and eight consecutive k; eight 4-byte loads, 64 lanes cover 256 contiguous bytes.
-__device__ __forceinline__ void load_strided(const bf16* p, int64_t ld, int R, int K, int r0, int k0, int tid,
-                                             uint32_t (&reg)[8]) {
-  const int q = tid & 63, kg = tid >> 6;
-  const int gr = r0 + 2 * q;
+};
+// strided operand (element (r,k) at p[k*ld + r]): a task owns rows 2q,2q+1 and eight consecutive k;
+// eight 4-byte loads (64 lanes cover 256 contiguous bytes), 2x2 16-bit transposes, two 16-byte LDS writes.
+template <int ROWS, int BK, int NT>
+struct Strided {
+  static constexpr int QN = ROWS / 2, TASKS = QN * (BK / 8), TP = TASKS / NT, NR = 8 * TP, LDSK = BK + 8;
+  static_assert(TASKS % NT == 0, "tile does not divide over the threads");
+  static __device__ __forceinline__ void load(const bf16* p, int64_t ld, int R, int K, int r0, int k0, int tid,
+                                              uint32_t (&reg)[NR]) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int gk = k0 + kg * 8 + j;
-    reg[j] = (gr < R && gk < K) ? *reinterpret_cast<const uint32_t*>(p + (int64_t)gk * ld + gr) : 0u;
+    for (int i = 0; i < TP; ++i) {
+      const int t = tid + i * NT;
+      const int q = t % QN, kg = t / QN;
+      const int gr = r0 + 2 * q;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int gk = k0 + kg * 8 + j;
+        reg[8 * i + j] = (gr < R && gk < K) ? *reinterpret_cast<const uint32_t*>(p + (int64_t)gk * ld + gr) : 0u;
+      }
+    }
   }
-}
-__device__ __forceinline__ void store_strided(bf16* s, int tid, const uint32_t (&reg)[8]) {
-  const int q = tid & 63, kg = tid >> 6;
-  uint4 even, odd;  // 2x2 transposes of 16-bit halves
-  even.x = (reg[0] & 0xffffu) | (reg[1] << 16); odd.x = (reg[0] >> 16) | (reg[1] & 0xffff0000u);
-  even.y = (reg[2] & 0xffffu) | (reg[3] << 16); odd.y = (reg[2] >> 16) | (reg[3] & 0xffff0000u);
-  even.z = (reg[4] & 0xffffu) | (reg[5] << 16); odd.z = (reg[4] >> 16) | (reg[5] & 0xffff0000u);
-  even.w = (reg[6] & 0xffffu) | (reg[7] << 16); odd.w = (reg[6] >> 16) | (reg[7] & 0xffff0000u);
-  *reinterpret_cast<uint4*>(s + (2 * q) * LDSK + kg * 8) = even;
-  *reinterpret_cast<uint4*>(s + (2 * q + 1) * LDSK + kg * 8) = odd;
+  static __device__ __forceinline__ void store(bf16* s, int tid, const uint32_t (&reg)[NR]) {
+#pragma unroll
+    for (int i = 0; i < TP; ++i) {
+      const int t = tid + i * NT;
+      const int q = t % QN, kg = t / QN;
+      const uint32_t* r = reg + 8 * i;
+      uint4 even, odd;
+      even.x = (r[0] & 0xffffu) | (r[1] << 16); odd.x = (r[0] >> 16) | (r[1] & 0xffff0000u);
+      even.y = (r[2] & 0xffffu) | (r[3] << 16); odd.y = (r[2] >> 16) | (r[3] & 0xffff0000u);
+      even.z = (r[4] & 0xffffu) | (r[5] << 16); odd.z = (r[4] >> 16) | (r[5] & 0xffff0000u);
+      even.w = (r[6] & 0xffffu) | (r[7] << 16); odd.w = (r[6] >> 16) | (r[7] & 0xffff0000u);
+      *reinterpret_cast<uint4*>(s + (2 * q) * LDSK + kg * 8) = even;
+      *reinterpret_cast<uint4*>(s + (2 * q + 1) * LDSK + kg * 8) = odd;
+    }
+  }
+  // column sums over k of the staged values: lo[i] += rows 2q, hi[i] += rows 2q+1
+  static __device__ __forceinline__ void colsum(const uint32_t (&reg)[NR], float (&lo)[TP], float (&hi)[TP]) {
+#pragma unroll
+    for (int i = 0; i < TP; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        lo[i] += __uint_as_float(reg[8 * i + j] << 16);
+        hi[i] += __uint_as_float(reg[8 * i + j] & 0xffff0000u);
+      }
+  }
+};
+
+template <bool T, int ROWS, int BK, int NT> struct LoaderSel { typedef KMajor<ROWS, BK, NT> type; };
+template <int ROWS, int BK, int NT> struct LoaderSel<true, ROWS, BK, NT> { typedef Strided<ROWS, BK, NT> type; };
+
+struct SplitArgs {
+  int splits;         // grid.z; each split owns a contiguous range of k tiles and its own output slab
+  int tiles_per_split;
+  int64_t slab;       // elements between the output slabs of consecutive splits
+  float* colsum;      // [splits][N] column sums of B over the split's k range (TB == false only), or null
+};
+
+// 8 consecutive output columns of one row: epilogue math and 16-byte stores
+template <int EPI, typename TC>
+__device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cbase, int row, int col, float (&v)[8]) {
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+    union { uint4 u; bf16 h[8]; } b;
+    b.u = *reinterpret_cast<const uint4*>(g.bias + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += to_f32(b.h[e]);
+  }
+  if (EPI == EPI_BIAS_RES || (EPI == EPI_RES && sizeof(TC) == 2) || EPI == EPI_MUL_DGELU) {
+    union { uint4 u; bf16 h[8]; } a;
+    a.u = *reinterpret_cast<const uint4*>(g.aux + (int64_t)row * g.ld_aux + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (EPI == EPI_MUL_DGELU) v[e] *= dgelu_f(to_f32(a.h[e])); else v[e] += to_f32(a.h[e]);
+    }
+  }
+  if (EPI == EPI_RES && sizeof(TC) == 4) {
+    const float* a = reinterpret_cast<const float*>(g.aux) + (int64_t)row * g.ld_aux + col;
+    const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+    v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w; v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
+  }
+  if (EPI == EPI_BIAS_GELU) {
+    if (g.aux_out) {
+      union { uint4 u; bf16 h[8]; } o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
+      *reinterpret_cast<uint4*>(g.aux_out + (int64_t)row * g.ld_aux + col) = o.u;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+  }
+  if (sizeof(TC) == 4) {
+    float* c = reinterpret_cast<float*>(Cbase) + (int64_t)row * g.ldc + col;
+    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    union { uint4 u; bf16 h[8]; } o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(Cbase) + (int64_t)row * g.ldc + col) = o.u;
+  }
 }
 
-template <bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDev<bf16> g) {
-  __shared__ __attribute__((aligned(16))) bf16 As[2][BM * LDSK];
-  __shared__ __attribute__((aligned(16))) bf16 Bs[2][BN * LDSK];
+template <typename C, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n, int total_tiles,
+                                                          int vec_ok) {
+  typedef typename LoaderSel<TA, C::BM, C::BK, C::NT>::type LA;     // A strided when stored [K,M]
+  typedef typename LoaderSel<!TB, C::BN, C::BK, C::NT>::type LB;    // B strided when stored [K,N]
+  constexpr int LDSK = C::LDSK;
+  constexpr int STAGE_LD = C::WTN + 4;
+  constexpr int OPER_BYTES = 2 * (C::BM + C::BN) * LDSK * 2;
+  constexpr int STAGE_BYTES = C::WGM * C::WGN * 32 * STAGE_LD * 4;
+  constexpr int LDS_BYTES = OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+  bf16* As = reinterpret_cast<bf16*>(lds);                       // [2][BM*LDSK]
+  bf16* Bs = As + 2 * C::BM * LDSK;                              // [2][BN*LDSK]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  f32x16 acc[2][2];
+  const int wm = wave / C::WGN, wn = wave % C::WGN;
+  // Workgroups go round-robin to the 8 XCDs, each with its own L2: give every XCD a contiguous
+  // run of tiles (n fastest) so that tiles sharing an A row panel meet in one L2.
+  const int per = (total_tiles + 7) >> 3;
+  const int lin = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (lin >= total_tiles) return;
+  const int m0 = (lin / tiles_n) * C::BM, n0 = (lin % tiles_n) * C::BN;
+  const int split = blockIdx.z;
+
+  f32x16 acc[C::TM][C::TN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < C::TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  uint32_t ra[8], rb[8];
-  auto gload = [&](int k0) {
-    if (TA) load_strided(g.A, g.lda, g.M, g.K, m0, k0, tid, ra); else load_kmajor(g.A, g.lda, g.M, g.K, m0, k0, tid, ra);
-    // B is "k-major" when stored [N,K] (tb), strided when stored [K,N]
-    if (TB) load_kmajor(g.B, g.ldb, g.N, g.K, n0, k0, tid, rb); else load_strided(g.B, g.ldb, g.N, g.K, n0, k0, tid, rb);
+  uint32_t ra[LA::NR], rb[LB::NR];
+  constexpr int CSN = TB ? 1 : LB::NR / 8;
+  float cs_lo[CSN], cs_hi[CSN];
+#pragma unroll
+  for (int i = 0; i < CSN; ++i) { cs_lo[i] = 0.f; cs_hi[i] = 0.f; }
+  const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
+
+  const int nk_all = (g.K + C::BK - 1) / C::BK;
+  const int kt0 = split * sp.tiles_per_split;
+  const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
+
+  auto gload = [&](int kt) {
+    LA::load(g.A, g.lda, g.M, g.K, m0, kt * C::BK, tid, ra);
+    LB::load(g.B, g.ldb, g.N, g.K, n0, kt * C::BK, tid, rb);
+    if constexpr (!TB) {
+      if (do_colsum) LB::colsum(rb, cs_lo, cs_hi);
+    }
   };
   auto sstore = [&](int buf) {
-    if (TA) store_strided(As[buf], tid, ra); else store_kmajor(As[buf], tid, ra);
-    if (TB) store_kmajor(Bs[buf], tid, rb); else store_strided(Bs[buf], tid, rb);
+    LA::store(As + buf * C::BM * LDSK, tid, ra);
+    LB::store(Bs + buf * C::BN * LDSK, tid, rb);
   };
 
-  const int nk = (g.K + BK - 1) / BK;
-  gload(0);
-  sstore(0);
+  if (kt0 < kt1) {
+    gload(kt0);
+    sstore(0);
+  }
   __syncthreads();
   int cur = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) gload((kt + 1) * BK);
-    const bf16* as = As[cur] + (wm * 64 + (lane & 31)) * LDSK + (lane >> 5) * 8;
-    const bf16* bs = Bs[cur] + (wn * 64 + (lane & 31)) * LDSK + (lane >> 5) * 8;
+  for (int kt = kt0; kt < kt1; ++kt) {
+    if (kt + 1 < kt1) gload(kt + 1);
+    const bf16* as = As + cur * C::BM * LDSK + (wm * C::WTM + (lane & 31)) * LDSK + (lane >> 5) * 8;
+    const bf16* bs = Bs + cur * C::BN * LDSK + (wn * C::WTN + (lane & 31)) * LDSK + (lane >> 5) * 8;
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 a[2], b[2];
+    for (int ks = 0; ks < C::BK / 16; ++ks) {
+      bf16x8 a[C::TM], b[C::TN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDSK + ks * 16);
+      for (int i = 0; i < C::TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDSK + ks * 16);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDSK + ks * 16);
+      for (int j = 0; j < C::TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDSK + ks * 16);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < C::TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) sstore(cur ^ 1);
+    if (kt + 1 < kt1) sstore(cur ^ 1);
     __syncthreads();
     cur ^= 1;
   }
+
+  // ---- column sums of B (bias gradient riding on the weight-gradient product) ----
+  if constexpr (!TB) {
+    if (do_colsum) {  // uniform over the workgroup; the main loop ended with a barrier
+      float* red = reinterpret_cast<float*>(lds);  // [BK/8][BN]
+#pragma unroll
+      for (int i = 0; i < CSN; ++i) {
+        const int t = tid + i * C::NT;
+        const int q = t % (C::BN / 2), kg = t / (C::BN / 2);
+        red[kg * C::BN + 2 * q] = cs_lo[i];
+        red[kg * C::BN + 2 * q + 1] = cs_hi[i];
+      }
+      __syncthreads();
+      for (int n = tid; n < C::BN; n += C::NT) {
+        float s = 0.f;
+#pragma unroll
+        for (int kg = 0; kg < C::BK / 8; ++kg) s += red[kg * C::BN + n];
+        if (n0 + n < g.N) sp.colsum[(int64_t)split * g.N + n0 + n] = s;
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue: accumulators -> LDS (per-wave staging) -> 16-byte row-contiguous stores ----
   // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+  void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
+                                : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
+  float* stage = reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD;
+  constexpr int CPR = C::WTN / 8;       // 8-column chunks per row of the wave tile
+  constexpr int RPP = 64 / CPR;         // rows per pass
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < C::TM; ++i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (col >= g.N) continue;
+    for (int j = 0; j < C::TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < g.M) epilogue_store<bf16, TC, EPI>(g, row, col, acc[i][j][v]);
+      for (int v = 0; v < 16; ++v)
+        stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * STAGE_LD + j * 32 + (lane & 31)] = acc[i][j][v];
+    // a wave reads back only what it wrote itself: no workgroup barrier needed (LDS operations of one
+    // wave complete in order); the wave barrier only stops the compiler from moving accesses across it
+    __builtin_amdgcn_wave_barrier();
+    const int cc = (lane % CPR) * 8;
+#pragma unroll
+    for (int pss = 0; pss < 32 / RPP; ++pss) {
+      const int r = pss * RPP + lane / CPR;
+      const int row = m0 + wm * C::WTM + i * 32 + r, col = n0 + wn * C::WTN + cc;
+      if (row >= g.M || col >= g.N) continue;
+      float v8[8];
+      const float4 x0 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc);
+      const float4 x1 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc + 4);
+      v8[0] = x0.x; v8[1] = x0.y; v8[2] = x0.z; v8[3] = x0.w; v8[4] = x1.x; v8[5] = x1.y; v8[6] = x1.z; v8[7] = x1.w;
+      if (vec_ok && col + 8 <= g.N) {
+        epilogue_store8<EPI, TC>(g, Cbase, row, col, v8);
+      } else {
+        GemmDev<bf16> gs = g;
+        gs.C = Cbase;
+        for (int e = 0; e < 8 && col + e < g.N; ++e) epilogue_store<bf16, TC, EPI>(gs, row, col + e, v8[e]);
       }
     }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread)
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
+                                                            float* __restrict__ out, int vec) {
+  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (vec && i + 3 < n) {
+    float4 s = *reinterpret_cast<const float4*>(part + i);
+    for (int z = 1; z < splits; ++z) {
+      const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)z * n + i);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    *reinterpret_cast<float4*>(out + i) = s;
+  } else {
+    for (int64_t j = i; j < n && j < i + 4; ++j) {
+      float s = part[j];
+      for (int z = 1; z < splits; ++z) s += part[(int64_t)z * n + j];
+      out[j] = s;
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -242,29 +428,6 @@ static void launch_generic_epi(const Gemm& a, hipStream_t st) {
   }
 }
 
-template <bool TA, bool TB, typename TC>
-static void launch_mfma_epi(const Gemm& a, hipStream_t st) {
-  GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
-                  (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
-  dim3 grid(cdiv(a.N, BN), cdiv(a.M, BM));
-  dim3 blk(256);
-  if constexpr (sizeof(TC) == 4) {  // fp32 outputs: weight gradients, logits (+bias), gradient stream (+residual)
-    if (a.epi == EPI_STORE) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_STORE, TC>), grid, blk, 0, st, g);
-    else if (a.epi == EPI_BIAS) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS, TC>), grid, blk, 0, st, g);
-    else if (a.epi == EPI_BIAS_RES) hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS_RES, TC>), grid, blk, 0, st, g);
-    else hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_RES, TC>), grid, blk, 0, st, g);
-    return;
-  }
-  switch (a.epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_STORE, TC>), grid, blk, 0, st, g); break;
-    case EPI_BIAS: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS, TC>), grid, blk, 0, st, g); break;
-    case EPI_BIAS_RES: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS_RES, TC>), grid, blk, 0, st, g); break;
-    case EPI_BIAS_GELU: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_BIAS_GELU, TC>), grid, blk, 0, st, g); break;
-    case EPI_MUL_DGELU: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_MUL_DGELU, TC>), grid, blk, 0, st, g); break;
-    case EPI_RES: hipLaunchKernelGGL((gemm_mfma_kernel<TA, TB, EPI_RES, TC>), grid, blk, 0, st, g); break;
-  }
-}
-
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 // The MFMA path needs 16-byte vectors along k for k-major operands and 4-byte
@@ -276,31 +439,98 @@ static bool mfma_ok(const Gemm& a) {
                          : (a.N % 2 == 0 && a.ldb % 2 == 0 && aligned(a.B, 4));
   return a_ok && b_ok && a.M >= 32 && a.N >= 32;
 }
+// whether (layout, epilogue, output type) is one of the combinations the training step uses
+static bool combo_used(const Gemm& a) {
+  if (a.ta && a.tb) return false;
+  if (a.ta) return a.c_f32 && a.epi == EPI_STORE;                                             // weight gradient
+  if (a.tb) return a.c_f32 ? (a.epi == EPI_RES) : (a.epi == EPI_STORE || a.epi == EPI_MUL_DGELU);  // input gradient
+  return a.c_f32 ? (a.epi == EPI_BIAS || a.epi == EPI_BIAS_RES)                                 // forward
+                 : (a.epi == EPI_BIAS || a.epi == EPI_BIAS_RES || a.epi == EPI_BIAS_GELU);
+}
+// 16-byte epilogue accesses need 8-element alignment of everything the epilogue touches
+static bool epilogue_vec_ok(const Gemm& a) {
+  bool ok = a.N % 8 == 0 && a.ldc % 8 == 0 && aligned(a.C, 16);
+  if (a.bias) ok = ok && aligned(a.bias, 16);
+  if (a.aux) ok = ok && a.ld_aux % 8 == 0 && aligned(a.aux, 16);
+  if (a.aux_out) ok = ok && a.ld_aux % 8 == 0 && aligned(a.aux_out, 16);
+  return ok;
+}
 
-bool gemm_uses_mfma(int dt, const Gemm& a) { return dt != 0 && mfma_ok(a); }
+bool gemm_uses_mfma(int dt, const Gemm& a) { return dt != 0 && mfma_ok(a) && combo_used(a); }
+
+typedef Cfg<128, 128, 32, 2, 2> CfgSquare;
+
+template <typename C, bool TA, bool TB, int EPI, typename TC>
+static void launch_mfma(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
+  GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, cbase ? (void*)cbase : a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
+                  (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
+  const int tiles_m = cdiv(a.M, C::BM), tiles_n = cdiv(a.N, C::BN), total = tiles_m * tiles_n;
+  const int nk = cdiv(a.K, C::BK);
+  SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
+  dim3 grid(8 * cdiv(total, 8), 1, splits);
+  hipLaunchKernelGGL((gemm_mfma_kernel<C, TA, TB, EPI, TC>), grid, dim3(C::NT), 0, st, g, sp, tiles_n, total,
+                     epilogue_vec_ok(a) ? 1 : 0);
+}
+
+template <typename C>
+static void dispatch_mfma(const Gemm& a, hipStream_t st) {
+  if (a.ta) {
+    // weight gradient: few output tiles and a long contraction -> split K over grid.z into fp32
+    // slabs, then add the slabs in a fixed order; the bias gradient rides along as column sums of B.
+    const int tiles = cdiv(a.M, C::BM) * cdiv(a.N, C::BN), nk = cdiv(a.K, C::BK);
+    int splits = 1;
+    const int64_t mn = (int64_t)a.M * a.N;
+    if (a.ws) {
+      splits = 768 / tiles;
+      if (splits > nk / 8) splits = nk / 8;
+      if (splits > 16) splits = 16;
+      while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
+      if (splits < 1) splits = 1;
+    }
+    float* cs_part = nullptr;
+    if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
+    if (splits > 1) {
+      launch_mfma<C, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
+      // ldc == N is required for the slab layout
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(mn, 1024)), dim3(256), 0, st, a.ws, splits, mn,
+                         (float*)a.C, (mn % 4 == 0 && aligned(a.ws, 16) && aligned(a.C, 16)) ? 1 : 0);
+      if (a.colsum_out)
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(a.N, 1024)), dim3(256), 0, st, cs_part, splits,
+                           (int64_t)a.N, a.colsum_out,
+                           (a.N % 4 == 0 && aligned(cs_part, 16) && aligned(a.colsum_out, 16)) ? 1 : 0);
+    } else {
+      launch_mfma<C, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
+    }
+    return;
+  }
+  if (a.tb) {
+    if (a.c_f32) launch_mfma<C, false, true, EPI_RES, float>(a, 1, nullptr, 0, nullptr, st);
+    else if (a.epi == EPI_STORE) launch_mfma<C, false, true, EPI_STORE, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else launch_mfma<C, false, true, EPI_MUL_DGELU, bf16>(a, 1, nullptr, 0, nullptr, st);
+    return;
+  }
+  if (a.c_f32) {
+    if (a.epi == EPI_BIAS) launch_mfma<C, false, false, EPI_BIAS, float>(a, 1, nullptr, 0, nullptr, st);
+    else launch_mfma<C, false, false, EPI_BIAS_RES, float>(a, 1, nullptr, 0, nullptr, st);
+  } else {
+    if (a.epi == EPI_BIAS) launch_mfma<C, false, false, EPI_BIAS, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else if (a.epi == EPI_BIAS_RES) launch_mfma<C, false, false, EPI_BIAS_RES, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else launch_mfma<C, false, false, EPI_BIAS_GELU, bf16>(a, 1, nullptr, 0, nullptr, st);
+  }
+}
 
 void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return;
   if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step
-  if (dt == 0) {
-    launch_generic_epi<float, float>(a, st);
+  if (gemm_uses_mfma(dt, a) && (!a.ta || a.ldc == a.N)) {
+    dispatch_mfma<CfgSquare>(a, st);
     return;
   }
-  if (mfma_ok(a)) {
-    if (a.c_f32) {
-      if (!a.ta && !a.tb) launch_mfma_epi<false, false, float>(a, st);
-      else if (!a.ta && a.tb) launch_mfma_epi<false, true, float>(a, st);
-      else if (a.ta && !a.tb) launch_mfma_epi<true, false, float>(a, st);
-      else launch_mfma_epi<true, true, float>(a, st);
-    } else {
-      if (!a.ta && !a.tb) launch_mfma_epi<false, false, bf16>(a, st);
-      else if (!a.ta && a.tb) launch_mfma_epi<false, true, bf16>(a, st);
-      else if (a.ta && !a.tb) launch_mfma_epi<true, false, bf16>(a, st);
-      else launch_mfma_epi<true, true, bf16>(a, st);
-    }
-    return;
-  }
-  if (a.c_f32) launch_generic_epi<bf16, float>(a, st); else launch_generic_epi<bf16, bf16>(a, st);
+  if (dt == 0) launch_generic_epi<float, float>(a, st);
+  else if (a.c_f32) launch_generic_epi<bf16, float>(a, st);
+  else launch_generic_epi<bf16, bf16>(a, st);
+  // column sums of B requested alongside a weight gradient: separate pass on this path
+  if (a.colsum_out && a.ta && !a.tb && a.ws) colsum(dt, a.B, a.ldb, a.K, a.N, a.colsum_out, a.ws, st);
 }
 
 }  // namespace pt

@@ -29,6 +29,12 @@ struct Gemm {
   void* aux_out = nullptr;     // T [M,N] ld_aux
   int64_t ld_aux = 0;
   bool c_f32 = false;
+  // weight-gradient products (ta && !tb, fp32 C with ldc == N) may split K over several workgroups
+  // through `ws` (ws_floats fp32 of scratch) and can also return the column sums of B over K
+  // (the bias gradient) in colsum_out[N]
+  float* ws = nullptr;
+  size_t ws_floats = 0;
+  float* colsum_out = nullptr;
 };
 void gemm(int dt, const Gemm& g, hipStream_t st);
 // true when gemm() will run the matrix-core kernel for this problem
@@ -48,11 +54,13 @@ void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* g
 // dx[r] = LNbwd(dy[r]) (+ dres[r] if non-null).  dy is the fp32 gradient stream when dy_f32, else T.
 // The result is written to dx_s (fp32) and / or dx_o (T), either may be null; both null computes the
 // parameter gradients only.  dgamma/dbeta fp32 [D] via `partial` scratch of ln_partial_floats(D) floats.
+// dxsum (may be null): fp32 [D] column sums of the result over the rows, i.e. the bias gradient of the
+// linear map that produced this LayerNorm's input side.
 size_t ln_partial_floats(int D);
 void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                    const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
-                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* partial, int rows, int D,
-                   hipStream_t st);
+                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
+                   int rows, int D, hipStream_t st);
 
 // out[n] = sum_m X[m,n] (fp32), X is T [M,N] with leading dimension ld.
 size_t colsum_partial_floats(int N);

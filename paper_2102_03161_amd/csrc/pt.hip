@@ -54,8 +54,8 @@ struct Plan {
   size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
-  size_t LOSS, NORMS, LNPART, CSPART, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
-  size_t idx_capacity = 0, stage_floats = 0;
+  size_t LOSS, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
+  size_t idx_capacity = 0, stage_floats = 0, gemmws_floats = 0;
 };
 
 bool validate(const pt_config& c, std::string* why) {
@@ -164,8 +164,21 @@ void make_plan(const pt_config& c, Plan* p) {
   p->LOSS = take(4);
   p->NORMS = take((size_t)(L + 2) * 4);
   p->LNPART = take(ln_partial_floats(D) * 4);
-  const int maxn = std::max(std::max(3 * D, F), c.n_out);
-  p->CSPART = take(colsum_partial_floats(maxn) * 4);
+  // scratch of the weight-gradient products: split-K slabs (up to 16 splits, about 768 workgroups in
+  // flight) plus their column-sum partials; also serves the separate column-sum pass of the FMA path
+  {
+    const int maxn = std::max(std::max(3 * D, F), c.n_out);
+    size_t need = colsum_partial_floats(maxn);
+    const int64_t shapes[6][2] = {{D, 3 * D}, {D, D}, {D, F}, {F, D}, {c.chans * c.patch * c.patch, D}, {D, c.n_out}};
+    for (auto& sh : shapes) {
+      const int64_t tiles = ((sh[0] + 127) / 128) * ((sh[1] + 127) / 128);
+      if (tiles <= 0) continue;
+      const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 768 / tiles));
+      need = std::max(need, (size_t)(splits * (sh[0] * sh[1] + sh[1])));
+    }
+    p->gemmws_floats = need;
+    p->GEMMWS = take(need * 4);
+  }
   p->QAPART = take(qa_partial_floats(D) * 4);
   const size_t nchunks = P / kChunk;
   p->CHUNKDECAY = take(nchunks);
@@ -328,29 +341,32 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
 // along that path would dominate the bias / LayerNorm-shift gradients); tensors
 // that feed the matrix cores get a T copy written by the kernel that makes them.
 // In: dout_s (fp32) and, for pre-LN, its T copy dout_o.  Out: dx_s / dx_o.
+// lower_b2 (pre-LN, may be null): where the column sums of dx go, i.e. the gradient of the second MLP
+// bias of the block below, whose output gradient dx is.
 // ---------------------------------------------------------------------------
 struct GradBufs {
   float* s;  // fp32 stream
   void* o;   // T copy (pre-LN only)
 };
 
-void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns, bool need_dx) {
+void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns, bool need_dx,
+                    float* lower_b2) {
   const pt_config& g = c->cfg;
   const int D = g.D, F = g.F, Tn = ns * g.S, dt = c->dt;
   hipStream_t st = c->st;
   const Plan& p = c->plan;
   float* lnp = c->wf(p.LNPART);
-  float* csp = c->wf(p.CSPART);
   float* sC = c->wf(p.sC); float* sD = c->wf(p.sD);
   void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
   // dW[K_in, N_out] = X^T dY ; db = colsum over tokens of dY (bias_dt 0: fp32 source, else T)
-  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid) {
+  // bid >= 0: also db = column sums of dY over the tokens, riding on the same product
+  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid) {
     Gemm m;
     m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
+    m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
-  auto bgrad = [&](int src_dt, const void* dY, int Nout, int bid) { { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(src_dt, dY, Nout, Tn, Nout, c->gp(bid), csp, st); } };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
     Gemm m;
@@ -359,41 +375,34 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
   if (g.arch == PT_VIT_PRELN) {
-    wgrad(c->w(s.G), F, dout.o, D, c->blk(l, W2));
-    bgrad(0, dout.s, D, c->blk(l, B2));
+    // the gradient of b2 (column sums of dout) came with the kernel that produced dout
+    wgrad(c->w(s.G), F, dout.o, D, c->blk(l, W2), -1);
     dgrad(dout.o, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
-    wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1));
-    bgrad(dt, dF, F, c->blk(l, B1));
+    wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dLN2out
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
-                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st); }  // sC / oD = dL/dY
-    wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO));
-    bgrad(0, sC, D, c->blk(l, BO));
+                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oD = dL/dY
+    wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO), -1);
     dgrad(oD, D, c->blk(l, WO), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
-    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV));
-    bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
+    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
-                  c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st); }
+                  c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
   } else {
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
-                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), lnp, Tn, D, st); }  // sC / oC = dL/d(Y+MLP)
-    wgrad(c->w(s.G), F, oC, D, c->blk(l, W2));
-    bgrad(0, sC, D, c->blk(l, B2));
+                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, Tn, D, st); }  // sC / oC = dL/d(Y+MLP)
+    wgrad(c->w(s.G), F, oC, D, c->blk(l, W2), -1);
     dgrad(oC, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
-    wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1));
-    bgrad(dt, dF, F, c->blk(l, B1));
+    wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
-                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lnp, Tn, D, st); }  // sC / oC = dL/d(x+Attn)
-    wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO));
-    bgrad(0, sC, D, c->blk(l, BO));
+                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oC = dL/d(x+Attn)
+    wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO), -1);
     dgrad(oC, D, c->blk(l, WO), oD, D, EPI_STORE, nullptr, false);                      // oD = dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
-    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV));
-    bgrad(dt, dQKV, 3 * D, c->blk(l, BQKV));
+    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
   }
 }
@@ -430,11 +439,11 @@ void front_backward(pt_ctx* c, const float* dx, int ns) {
     Gemm m;
     m.A = c->w(p.PATCH); m.lda = pd; m.ta = true; m.B = c->w(p.DEMB); m.ldb = D; m.C = c->gp(0); m.ldc = D;
     m.M = pd; m.N = D; m.K = np; m.c_f32 = true;
+    m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = c->gp(1);
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
-    { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(dt, c->w(p.DEMB), D, np, D, c->gp(1), c->wf(p.CSPART), st); }
   } else {
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
-                  nullptr, D, c->gp(2), c->gp(3), c->wf(p.LNPART), ns * g.S, D, st); }
+                  nullptr, D, c->gp(2), c->gp(3), nullptr, c->wf(p.LNPART), ns * g.S, D, st); }
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
     bert_embed_bwd((const int32_t*)c->last_input, c->wf(p.DEMB), c->gp(0), c->gp(1),
@@ -709,8 +718,8 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     Gemm wg;
     wg.A = c->w(p.CFEAT); wg.lda = D; wg.ta = true; wg.B = c->w(p.DZ); wg.ldb = C; wg.C = c->gp(hW); wg.ldc = C;
     wg.M = D; wg.N = C; wg.K = nb; wg.c_f32 = true;
+    wg.ws = c->wf(p.GEMMWS); wg.ws_floats = p.gemmws_floats; wg.colsum_out = c->gp(hbias);
     { ProfScope ps_(c, gemm_cat(dt, wg), 2.0 * wg.M * wg.N * wg.K); gemm(dt, wg, st); }
-    { ProfScope ps_(c, PT_PROF_COLSUM, 0.0); colsum(dt, c->w(p.DZ), C, nb, C, c->gp(hbias), c->wf(p.CSPART), st); }
     Gemm dg;
     dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
     dg.M = nb; dg.N = D; dg.K = C;
@@ -719,7 +728,8 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
     fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
-                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), c->wf(p.LNPART), nb, D, st); }
+                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
+                  c->wf(p.LNPART), nb, D, st); }
   } else {
     const int hW = c->head(0), hbias = c->head(1);
     qa_logits(dt, x, c->cp(hW), c->cp(hbias), c->wf(p.LOGITS), nb * S, D, st);
@@ -731,7 +741,8 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   for (int l = L - 1; l >= k; --l) {
     const void* xin = (l == k) ? d_hk : c->w(p.X[l]);
     const bool need_dx = (l > k) || (k == 0);
-    block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx);
+    float* lower_b2 = (g.arch == PT_VIT_PRELN && l > k) ? c->gp(c->blk(l - 1, B2)) : nullptr;
+    block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     std::swap(dcur, dnext);
   }
   if (k == 0) front_backward(c, dcur.s, nb);

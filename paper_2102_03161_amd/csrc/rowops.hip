@@ -98,7 +98,7 @@ void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* g
 // LayerNorm backward
 // ---------------------------------------------------------------------------
 constexpr int kLnBwdBlocks = 512;
-size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 2 * D; }
+size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 3 * D; }
 
 // dy may be the fp32 gradient stream or a T tensor; the result goes to an fp32 stream
 // buffer (dx_s), a T copy for the matrix-core operands (dx_o), or both (either may be null).
@@ -109,15 +109,15 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy,
                                                      const float* __restrict__ dres, int64_t lddres,
                                                      float* __restrict__ dx_s, T* __restrict__ dx_o, int64_t lddx,
                                                      float* __restrict__ partial, int rows, int D) {
-  extern __shared__ float red[];  // [4][2][D]
+  extern __shared__ float red[];  // [4][3][D]: d(gamma), d(beta), column sums of the output
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nvec = D >> 2;
-  float g[VPL][4], ag[VPL][4], ab[VPL][4];
+  float g[VPL][4], ag[VPL][4], ab[VPL][4], as[VPL][4];
 #pragma unroll
   for (int j = 0; j < VPL; ++j) {
     const int c = lane + 64 * j;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { ag[j][e] = 0.f; ab[j][e] = 0.f; g[j][e] = 0.f; }
+    for (int e = 0; e < 4; ++e) { ag[j][e] = 0.f; ab[j][e] = 0.f; as[j][e] = 0.f; g[j][e] = 0.f; }
     if (c < nvec) load4(gamma + 4 * c, g[j]);
   }
   for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
@@ -157,6 +157,8 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy,
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] += r[e];
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) as[j][e] += o[e];
         if (dx_s) store4(dx_s + (int64_t)row * lddx + 4 * c, o);
         if (dx_o) store4(dx_o + (int64_t)row * lddx + 4 * c, o);
       }
@@ -169,35 +171,49 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy,
     if (c < nvec) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        red[(wave * 2 + 0) * D + 4 * c + e] = ag[j][e];
-        red[(wave * 2 + 1) * D + 4 * c + e] = ab[j][e];
+        red[(wave * 3 + 0) * D + 4 * c + e] = ag[j][e];
+        red[(wave * 3 + 1) * D + 4 * c + e] = ab[j][e];
+        red[(wave * 3 + 2) * D + 4 * c + e] = as[j][e];
       }
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 2 * D; i += 256) {
-    const float s = ((red[i] + red[2 * D + i]) + red[4 * D + i]) + red[6 * D + i];
-    partial[(size_t)blockIdx.x * 2 * D + i] = s;
+  for (int i = threadIdx.x; i < 3 * D; i += 256) {
+    const float s = ((red[i] + red[3 * D + i]) + red[6 * D + i]) + red[9 * D + i];
+    partial[(size_t)blockIdx.x * 3 * D + i] = s;
   }
 }
 
-// out[i] = sum over p of partial[p][i], p in increasing order
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int np, int n, float* __restrict__ out0,
-                                       int n0, float* __restrict__ out1) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
+// out[i] = sum over p of partial[p][i] in a fixed order: 32 columns per workgroup, eight interleaved
+// row groups summed in parallel and then combined in group order.  Column i goes to out0[i] for
+// i < n0, to out1[i - n0] for i < 2 n0, else to out2[i - 2 n0]; a null destination drops the column.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
+                                                              float* __restrict__ out0, int n0,
+                                                              float* __restrict__ out1, float* __restrict__ out2) {
+  __shared__ float red[8][33];
+  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int i = blockIdx.x * 32 + c;
   float s = 0.f;
-  for (int p = 0; p < np; ++p) s += partial[(size_t)p * n + i];
-  if (i < n0) out0[i] = s; else out1[i - n0] = s;
+  if (i < n)
+    for (int p = rg; p < np; p += 8) s += partial[(size_t)p * n + i];
+  red[rg][c] = s;
+  __syncthreads();
+  if (rg == 0 && i < n) {
+    float t = red[0][c];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) t += red[k][c];
+    float* dst = i < n0 ? out0 : (i < 2 * n0 ? out1 : out2);
+    if (dst) dst[i % n0] = t;
+  }
 }
 
 void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                    const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
-                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* partial, int rows, int D,
-                   hipStream_t st) {
+                   float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
+                   int rows, int D, hipStream_t st) {
   if (rows <= 0) return;
   const int nb = cdiv(rows, 4) < kLnBwdBlocks ? cdiv(rows, 4) : kLnBwdBlocks;
-  const size_t shm = (size_t)8 * D * sizeof(float);
+  const size_t shm = (size_t)12 * D * sizeof(float);
 #define LN_BWD(T, TDY, TX, V)                                                                                      \
   hipLaunchKernelGGL((ln_bwd_kernel<T, TDY, TX, V>), dim3(nb), dim3(256), shm, st, (const TDY*)dy, lddy,           \
                      (const TX*)x, ldx, mean, rstd, (const T*)gamma, dres, lddres, dx_s, (T*)dx_o, lddx, partial, \
@@ -211,8 +227,8 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
   else LN_BWD_V(bf16, bf16, bf16);
 #undef LN_BWD_V
 #undef LN_BWD
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D, 256)), dim3(256), 0, st, partial, nb, 2 * D, dgamma, D,
-                     dbeta);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(256), 0, st, partial, nb, 3 * D, dgamma, D,
+                     dbeta, dxsum);
 }
 
 // ---------------------------------------------------------------------------
@@ -236,8 +252,8 @@ void colsum(int dt, const void* X, int64_t ld, int M, int N, float* out, float* 
   dim3 grid(cdiv(N, 256), nby);
   if (dt == 0) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, ld, M, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, ld, M, N, partial);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 256)), dim3(256), 0, st, partial, nby, N, out, N,
-                     (float*)nullptr);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 32)), dim3(256), 0, st, partial, nby, N, out, N,
+                     (float*)nullptr, (float*)nullptr);
 }
 
 // ---------------------------------------------------------------------------
@@ -519,8 +535,8 @@ void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* d
   const int nb = rows < kQaBlocks ? rows : kQaBlocks;
   if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, dx, partial, rows, D);
   else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, dx, partial, rows, D);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 256)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
-                     2 * D, db);
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 32)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
+                     2 * D, db, (float*)nullptr);
 }
 
 __global__ __launch_bounds__(256) void mean_reduce_kernel(const float* __restrict__ rows, int n, float* __restrict__ out) {
