@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpt.so")
-SOURCES = ["gemm.hip", "attention.hip", "attention_mfma.hip", "rowops.hip", "optim.hip", "pt.hip"]
+SOURCES = ["gemm.hip", "gemm_dma.hip", "attention.hip", "attention_mfma.hip", "rowops.hip", "optim.hip", "pt.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep fp32 vector math scalar per lane: no packed-fp32 instruction selection
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -40,7 +40,7 @@ def build(force: bool = True, jobs: int = 4) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h")] + [os.path.join(HERE, "..", "include", "pt.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h", "gemm_epilogue.h")] + [os.path.join(HERE, "..", "include", "pt.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]

@@ -12,41 +12,9 @@
 // element is a deterministic function of its own row and column only.
 #include "common.h"
 #include "kernels.h"
+#include "gemm_epilogue.h"
 
 namespace pt {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-
-template <typename T>
-struct GemmDev {
-  const T* A;
-  const T* B;
-  void* C;
-  int M, N, K;
-  int64_t lda, ldb, ldc;
-  const T* bias;
-  const T* aux;
-  T* aux_out;
-  int64_t ld_aux;
-};
-
-template <typename T, typename TC, int EPI>
-__device__ __forceinline__ void epilogue_store(const GemmDev<T>& g, int row, int col, float acc) {
-  float v = acc;
-  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) v += to_f32(g.bias[col]);
-  if (EPI == EPI_BIAS_RES) v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
-  if (EPI == EPI_RES) {  // an fp32 output adds the fp32 gradient stream
-    if (sizeof(TC) == 4) v += reinterpret_cast<const float*>(g.aux)[(int64_t)row * g.ld_aux + col];
-    else v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
-  }
-  if (EPI == EPI_BIAS_GELU) {
-    if (g.aux_out) g.aux_out[(int64_t)row * g.ld_aux + col] = from_f32<T>(v);  // pre-activation for the backward pass
-    v = gelu_f(v);
-  }
-  if (EPI == EPI_MUL_DGELU) v *= dgelu_f(to_f32(g.aux[(int64_t)row * g.ld_aux + col]));
-  reinterpret_cast<TC*>(g.C)[(int64_t)row * g.ldc + col] = from_f32<TC>(v);
-}
 
 // ---------------------------------------------------------------------------
 // generic FMA kernel: 64x64 tile, 16-deep, 256 threads, 4x4 outputs per thread
@@ -190,57 +158,6 @@ struct Strided {
 template <bool T, int ROWS, int BK, int NT> struct LoaderSel { typedef KMajor<ROWS, BK, NT> type; };
 template <int ROWS, int BK, int NT> struct LoaderSel<true, ROWS, BK, NT> { typedef Strided<ROWS, BK, NT> type; };
 
-struct SplitArgs {
-  int splits;         // grid.z; each split owns a contiguous range of k tiles and its own output slab
-  int tiles_per_split;
-  int64_t slab;       // elements between the output slabs of consecutive splits
-  float* colsum;      // [splits][N] column sums of B over the split's k range (TB == false only), or null
-};
-
-// 8 consecutive output columns of one row: epilogue math and 16-byte stores
-template <int EPI, typename TC>
-__device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cbase, int row, int col, float (&v)[8]) {
-  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
-    union { uint4 u; bf16 h[8]; } b;
-    b.u = *reinterpret_cast<const uint4*>(g.bias + col);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] += to_f32(b.h[e]);
-  }
-  if (EPI == EPI_BIAS_RES || (EPI == EPI_RES && sizeof(TC) == 2) || EPI == EPI_MUL_DGELU) {
-    union { uint4 u; bf16 h[8]; } a;
-    a.u = *reinterpret_cast<const uint4*>(g.aux + (int64_t)row * g.ld_aux + col);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      if (EPI == EPI_MUL_DGELU) v[e] *= dgelu_f(to_f32(a.h[e])); else v[e] += to_f32(a.h[e]);
-    }
-  }
-  if (EPI == EPI_RES && sizeof(TC) == 4) {
-    const float* a = reinterpret_cast<const float*>(g.aux) + (int64_t)row * g.ld_aux + col;
-    const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
-    v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w; v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
-  }
-  if (EPI == EPI_BIAS_GELU) {
-    if (g.aux_out) {
-      union { uint4 u; bf16 h[8]; } o;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
-      *reinterpret_cast<uint4*>(g.aux_out + (int64_t)row * g.ld_aux + col) = o.u;
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
-  }
-  if (sizeof(TC) == 4) {
-    float* c = reinterpret_cast<float*>(Cbase) + (int64_t)row * g.ldc + col;
-    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
-  } else {
-    union { uint4 u; bf16 h[8]; } o;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
-    *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(Cbase) + (int64_t)row * g.ldc + col) = o.u;
-  }
-}
-
 template <typename C, bool TA, bool TB, int EPI, typename TC>
 __global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n, int total_tiles,
                                                           int vec_ok) {
@@ -344,43 +261,10 @@ __global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, Split
     }
   }
 
-  // ---- epilogue: accumulators -> LDS (per-wave staging) -> 16-byte row-contiguous stores ----
-  // accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
   void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
                                 : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
-  float* stage = reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD;
-  constexpr int CPR = C::WTN / 8;       // 8-column chunks per row of the wave tile
-  constexpr int RPP = 64 / CPR;         // rows per pass
-#pragma unroll
-  for (int i = 0; i < C::TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < C::TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * STAGE_LD + j * 32 + (lane & 31)] = acc[i][j][v];
-    // a wave reads back only what it wrote itself: no workgroup barrier needed (LDS operations of one
-    // wave complete in order); the wave barrier only stops the compiler from moving accesses across it
-    __builtin_amdgcn_wave_barrier();
-    const int cc = (lane % CPR) * 8;
-#pragma unroll
-    for (int pss = 0; pss < 32 / RPP; ++pss) {
-      const int r = pss * RPP + lane / CPR;
-      const int row = m0 + wm * C::WTM + i * 32 + r, col = n0 + wn * C::WTN + cc;
-      if (row >= g.M || col >= g.N) continue;
-      float v8[8];
-      const float4 x0 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc);
-      const float4 x1 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc + 4);
-      v8[0] = x0.x; v8[1] = x0.y; v8[2] = x0.z; v8[3] = x0.w; v8[4] = x1.x; v8[5] = x1.y; v8[6] = x1.z; v8[7] = x1.w;
-      if (vec_ok && col + 8 <= g.N) {
-        epilogue_store8<EPI, TC>(g, Cbase, row, col, v8);
-      } else {
-        GemmDev<bf16> gs = g;
-        gs.C = Cbase;
-        for (int e = 0; e < 8 && col + e < g.N; ++e) epilogue_store<bf16, TC, EPI>(gs, row, col + e, v8[e]);
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-  }
+  staged_epilogue<C::TM, C::TN, C::WTM, C::WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD,
+                                                         m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
 }
 
 // out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread)
@@ -401,6 +285,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
       out[j] = s;
     }
   }
+}
+
+void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, hipStream_t st) {
+  const int vec = (n % 4 == 0 && (reinterpret_cast<uintptr_t>(part) % 16) == 0 && (reinterpret_cast<uintptr_t>(out) % 16) == 0) ? 1 : 0;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(n, 1024)), dim3(256), 0, st, part, splits, n, out, vec);
 }
 
 // ---------------------------------------------------------------------------
@@ -448,7 +337,7 @@ static bool combo_used(const Gemm& a) {
                  : (a.epi == EPI_BIAS || a.epi == EPI_BIAS_RES || a.epi == EPI_BIAS_GELU);
 }
 // 16-byte epilogue accesses need 8-element alignment of everything the epilogue touches
-static bool epilogue_vec_ok(const Gemm& a) {
+bool gemm_epilogue_vec_ok(const Gemm& a) {
   bool ok = a.N % 8 == 0 && a.ldc % 8 == 0 && aligned(a.C, 16);
   if (a.bias) ok = ok && aligned(a.bias, 16);
   if (a.aux) ok = ok && a.ld_aux % 8 == 0 && aligned(a.aux, 16);
@@ -458,7 +347,12 @@ static bool epilogue_vec_ok(const Gemm& a) {
 
 bool gemm_uses_mfma(int dt, const Gemm& a) { return dt != 0 && mfma_ok(a) && combo_used(a); }
 
-typedef Cfg<128, 128, 32, 2, 2> CfgSquare;
+typedef Cfg<128, 128, 32, 2, 2> Cfg0;
+
+// kernel selection; -1 = choose by problem shape.  0: register-staged kernel; 10 + v: variant v of
+// the asynchronous global->LDS kernel (tuning hook for experiments)
+static int g_cfg_override = -1;
+void gemm_set_config(int c) { g_cfg_override = c; }
 
 template <typename C, bool TA, bool TB, int EPI, typename TC>
 static void launch_mfma(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
@@ -469,7 +363,7 @@ static void launch_mfma(const Gemm& a, int splits, float* cbase, int64_t slab, f
   SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
   dim3 grid(8 * cdiv(total, 8), 1, splits);
   hipLaunchKernelGGL((gemm_mfma_kernel<C, TA, TB, EPI, TC>), grid, dim3(C::NT), 0, st, g, sp, tiles_n, total,
-                     epilogue_vec_ok(a) ? 1 : 0);
+                     gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
 template <typename C>
@@ -482,6 +376,7 @@ static void dispatch_mfma(const Gemm& a, hipStream_t st) {
     const int64_t mn = (int64_t)a.M * a.N;
     if (a.ws) {
       splits = 768 / tiles;
+      if (splits < 1) splits = 1;
       if (splits > nk / 8) splits = nk / 8;
       if (splits > 16) splits = 16;
       while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
@@ -492,12 +387,8 @@ static void dispatch_mfma(const Gemm& a, hipStream_t st) {
     if (splits > 1) {
       launch_mfma<C, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
       // ldc == N is required for the slab layout
-      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(mn, 1024)), dim3(256), 0, st, a.ws, splits, mn,
-                         (float*)a.C, (mn % 4 == 0 && aligned(a.ws, 16) && aligned(a.C, 16)) ? 1 : 0);
-      if (a.colsum_out)
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(a.N, 1024)), dim3(256), 0, st, cs_part, splits,
-                           (int64_t)a.N, a.colsum_out,
-                           (a.N % 4 == 0 && aligned(cs_part, 16) && aligned(a.colsum_out, 16)) ? 1 : 0);
+      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, st);
+      if (a.colsum_out) gemm_splitk_reduce(cs_part, splits, a.N, a.colsum_out, st);
     } else {
       launch_mfma<C, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
     }
@@ -523,7 +414,15 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.M <= 0 || a.N <= 0) return;
   if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step
   if (gemm_uses_mfma(dt, a) && (!a.ta || a.ldc == a.N)) {
-    dispatch_mfma<CfgSquare>(a, st);
+    if (g_cfg_override != 0 && gemm_dma_ok(a)) {
+      // default: 128x128 tiles, three per CU; wide outputs and the short-M weight gradients do
+      // better with 256x128 tiles and eight waves
+      int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
+      if (g_cfg_override < 0) v = a.ta ? (a.M <= 1024 ? 2 : 1) : (a.N >= 3072 ? 2 : 1);
+      gemm_dma(a, v, st);
+      return;
+    }
+    dispatch_mfma<Cfg0>(a, st);
     return;
   }
   if (dt == 0) launch_generic_epi<float, float>(a, st);

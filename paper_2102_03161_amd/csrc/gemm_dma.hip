@@ -1,0 +1,336 @@
+// bf16 matrix-core GEMM with an asynchronous HBM -> LDS pipeline (gfx950).
+//
+// Operand tiles travel from global memory straight into LDS with
+// global_load_lds_dwordx4 (no staging registers), NS tiles deep, so that the
+// HBM/L2 latency of a tile is hidden behind the MFMA work of the NS-1 tiles
+// before it.  The only synchronisation per k-tile is one s_waitcnt vmcnt(n)
+// (this wave's own tile has landed) and one s_barrier (everybody's has).
+//
+// LDS layouts follow the operand's memory layout, because a wave-wide DMA load
+// writes 64 consecutive 16-byte slots:
+//   k-major operand  (element (r,k) at p[r*ld + k]) : tile [ROWS][BK], read as
+//       16-byte MFMA fragments;
+//   strided operand  (element (r,k) at p[k*ld + r]) : tile [BK][ROWS], read with
+//       ds_read_b64_tr_b16, the LDS transpose read that hands each lane four
+//       consecutive k of one row.
+// Both use an XOR swizzle of the 16-byte slot index (applied to the global
+// address each lane fetches), which makes the fragment reads bank-conflict free.
+//
+// Requirements checked by the host: K a multiple of BK (no zero fill exists on
+// this path), 16-byte aligned rows.  Rows / columns past the edge are clamped to
+// the last valid one: they only feed outputs that are never stored.
+#include "common.h"
+#include "kernels.h"
+#include "gemm_epilogue.h"
+
+namespace pt {
+
+namespace {
+
+#define PT_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define PT_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+
+constexpr int kBK = 32;
+
+__device__ __forceinline__ void compiler_fence() { asm volatile("" ::: "memory"); }
+
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(size_t)((__attribute__((address_space(3))) const void*)(p));
+}
+
+// ---- k-major tile [ROWS][32]: 64-byte rows, slot (row, c') holds chunk c' ^ ((row >> 2) & 3) ----
+template <int ROWS, int NW, int NFRAG>
+struct TileK {
+  static constexpr int BYTES = ROWS * 64, LOADS = ROWS / 16 / NW;  // wave-wide loads per wave
+  static_assert(ROWS % (16 * NW) == 0, "rows must divide over the waves");
+  const bf16* gp[LOADS];   // this lane's source of each load, advanced by one tile per issue
+  int64_t gstep;
+  unsigned foff[2];        // fragment byte offsets within the tile for k-step 0 / 1 (row block 0)
+
+  __device__ __forceinline__ void setup(const bf16* p, int64_t ld, int R, int r0, int k0, int rbase, int wave,
+                                        int lane) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int row = 16 * (wave * LOADS + i) + (lane >> 2);
+      const int c = (lane & 3) ^ ((row >> 2) & 3);
+      int gr = r0 + row;
+      gr = gr < R ? gr : R - 1;
+      gp[i] = p + (int64_t)gr * ld + k0 + 8 * c;
+    }
+    gstep = kBK;
+    const int row = rbase + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) foff[ks] = row * 64 + (((2 * ks + (lane >> 5)) ^ ((row >> 2) & 3)) << 4);
+  }
+  __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
+      gp[i] += gstep;
+    }
+  }
+  // fragments of all row blocks and both k-steps: f[ks][i]
+  __device__ __forceinline__ void read(const unsigned char* tile, bf16x8 (&f)[2][NFRAG]) const {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < NFRAG; ++i) f[ks][i] = *reinterpret_cast<const bf16x8*>(tile + foff[ks] + i * 2048);
+  }
+  static constexpr bool kAsmReads = false;
+};
+
+// ---- strided tile [32][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ ((k & 3) << 1) ----
+// Fragments come from ds_read_b64_tr_b16 (each lane gets four consecutive k of one row).  The reads are
+// issued as inline assembly: the compiler would otherwise wait for every outstanding global->LDS load
+// before each of them, which serialises the pipeline; the caller waits with s_waitcnt lgkmcnt(0).
+template <int ROWS, int NW, int NFRAG>
+struct TileS {
+  static constexpr int ROWB = ROWS * 2, KPL = 1024 / ROWB;       // k rows per wave-wide load
+  static constexpr int BYTES = kBK * ROWB, LOADS = kBK / KPL / NW;
+  static constexpr int CPR = ROWS / 8;                           // 16-byte chunks per k row
+  static_assert(kBK % (KPL * NW) == 0 && KPL >= 1, "tile must divide over the waves");
+  const bf16* gp[LOADS];
+  int64_t gstep;
+  unsigned foff[NFRAG];    // fragment byte offsets (k-step 0, first half) per 32-row block
+
+  __device__ __forceinline__ void setup(const bf16* p, int64_t ld, int R, int r0, int k0, int rbase, int wave,
+                                        int lane) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      const int k = KPL * (wave * LOADS + i) + lane / CPR;
+      const int c = (lane % CPR) ^ ((k & 3) << 1);
+      int gr = r0 + 8 * c;
+      gr = gr + 8 <= R ? gr : (R - 8);   // R >= 8 and R % 8 == 0 are checked by the host
+      gp[i] = p + (int64_t)(k0 + k) * ld + gr;
+    }
+    gstep = (int64_t)kBK * ld;
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int k = 8 * (grp >> 1) + (l16 >> 2);
+#pragma unroll
+    for (int j = 0; j < NFRAG; ++j) {
+      const int col = rbase + j * 32 + (grp & 1) * 16 + 4 * (l16 & 3);
+      foff[j] = k * ROWB + ((((col >> 3) ^ ((k & 3) << 1))) << 4) + (col & 7) * 2;
+    }
+  }
+  __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) {
+      __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
+      gp[i] += gstep;
+    }
+  }
+  __device__ __forceinline__ void read(const unsigned char* tile, bf16x8 (&f)[2][NFRAG]) const {
+    const unsigned base = lds_addr(tile);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int j = 0; j < NFRAG; ++j) {
+        union { u32x2 h[2]; bf16x8 v; } t;
+        const unsigned addr = base + foff[j];
+        // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 rows is a constant offset (the swizzle only uses k & 3)
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[0]) : "v"(addr), "n"(16 * ks * ROWB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"((16 * ks + 4) * ROWB));
+        f[ks][j] = t.v;
+      }
+  }
+  static constexpr bool kAsmReads = true;
+  // sum over the tile's k rows of column n (for the fused bias gradient)
+  static __device__ __forceinline__ float colsum(const unsigned char* lds, int n) {
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < kBK; ++k) {
+      const int c = (n >> 3) ^ ((k & 3) << 1);
+      s += to_f32(*reinterpret_cast<const bf16*>(lds + k * ROWB + c * 16 + (n & 7) * 2));
+    }
+    return s;
+  }
+};
+
+template <bool STRIDED, int ROWS, int NW, int NFRAG> struct TileSel { typedef TileK<ROWS, NW, NFRAG> type; };
+template <int ROWS, int NW, int NFRAG> struct TileSel<true, ROWS, NW, NFRAG> { typedef TileS<ROWS, NW, NFRAG> type; };
+
+// s_waitcnt lgkmcnt(0) that the fragments depend on, so that no MFMA using them can be scheduled before it
+template <int N>
+__device__ __forceinline__ void wait_lds(bf16x8 (&f)[2][N]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[ks][i]));
+}
+
+template <int BM, int BN, int WGM, int WGN, int kNS, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n,
+                                                                  int total_tiles, int vec_ok) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
+  typedef typename TileSel<TA, BM, NW, TM>::type LA;    // A strided when stored [K,M]
+  typedef typename TileSel<!TB, BN, NW, TN>::type LB;   // B strided when stored [K,N]
+  constexpr int STAGE = LA::BYTES + LB::BYTES;
+  constexpr int STAGE_LD = WTN + 4;
+  constexpr int EPI_BYTES = NW * 32 * STAGE_LD * 4;
+  constexpr int LDS_BYTES = kNS * STAGE > EPI_BYTES ? kNS * STAGE : EPI_BYTES;
+  constexpr int LPT = LA::LOADS + LB::LOADS;  // DMA loads per thread per tile
+  static_assert(LPT * 2 <= 15, "vmcnt immediates below assume few loads per tile");
+  static_assert(kBK == 32, "two k-steps per tile");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int per = (total_tiles + 7) >> 3;
+  const int lin = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (lin >= total_tiles) return;
+  const int m0 = (lin / tiles_n) * BM, n0 = (lin % tiles_n) * BN;
+  const int split = blockIdx.z;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk_all = g.K / kBK;
+  const int kt0 = split * sp.tiles_per_split;
+  const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
+  const int n = kt1 > kt0 ? kt1 - kt0 : 0;
+  const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
+  float cs = 0.f;
+
+  LA ta;
+  LB tb;
+  ta.setup(g.A, g.lda, g.M, m0, kt0 * kBK, wm * WTM, wave, lane);
+  tb.setup(g.B, g.ldb, g.N, n0, kt0 * kBK, wn * WTN, wave, lane);
+
+  int fill = 0;  // stage the next issued tile goes to
+#pragma unroll
+  for (int s = 0; s < kNS - 1; ++s)
+    if (s < n) {
+      ta.issue(lds + s * STAGE, wave);
+      tb.issue(lds + s * STAGE + LA::BYTES, wave);
+    }
+  fill = kNS - 1;
+  int cur = 0;   // stage of the tile being consumed
+
+  for (int it = 0; it < n; ++it) {
+    // this wave's loads of tile `it` have landed when at most the loads of the later tiles are pending
+    if (kNS >= 4 && it + 2 < n) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPT));
+    else if (it + 1 < n) __builtin_amdgcn_s_waitcnt(0x0F70 | LPT);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    compiler_fence();
+    __builtin_amdgcn_s_barrier();   // everybody's loads of tile `it` have landed, and tile it-1 is fully consumed
+    compiler_fence();
+    if (it + kNS - 1 < n) {
+      ta.issue(lds + fill * STAGE, wave);
+      tb.issue(lds + fill * STAGE + LA::BYTES, wave);
+    }
+    fill = fill + 1 == kNS ? 0 : fill + 1;
+    const unsigned char* sa = lds + cur * STAGE;
+    const unsigned char* sb = sa + LA::BYTES;
+    cur = cur + 1 == kNS ? 0 : cur + 1;
+    // all fragment reads of the tile are issued up front (distinct registers)
+    bf16x8 a[2][TM], b[2][TN];
+    ta.read(sa, a);
+    tb.read(sb, b);
+    if (LA::kAsmReads) wait_lds(a);
+    if (LB::kAsmReads) wait_lds(b);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+    if constexpr (!TB) {
+      if (do_colsum && tid < BN) cs += LB::colsum(sb, tid);
+    }
+  }
+  compiler_fence();
+  __builtin_amdgcn_s_barrier();   // all fragment reads done: the LDS can be reused for the epilogue
+  compiler_fence();
+  if constexpr (!TB) {
+    if (do_colsum && tid < BN && n0 + tid < g.N) sp.colsum[(int64_t)split * g.N + n0 + tid] = cs;
+  }
+  void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
+                                : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
+  staged_epilogue<TM, TN, WTM, WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD, m0 + wm * WTM,
+                                             n0 + wn * WTN, lane, vec_ok);
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS, bool TA, bool TB, int EPI, typename TC>
+void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
+  GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, cbase ? (void*)cbase : a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
+                  (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
+  const int tiles_m = cdiv(a.M, BM), tiles_n = cdiv(a.N, BN), total = tiles_m * tiles_n;
+  const int nk = a.K / kBK;
+  SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
+  dim3 grid(8 * cdiv(total, 8), 1, splits);
+  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, TA, TB, EPI, TC>), grid, dim3(64 * WGM * WGN), 0, st, g, sp,
+                     tiles_n, total, gemm_epilogue_vec_ok(a) ? 1 : 0);
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+}  // namespace
+
+bool gemm_dma_ok(const Gemm& a) {
+  if (a.K % kBK != 0 || a.K < kBK) return false;
+  if (!aligned16(a.A) || !aligned16(a.B) || a.lda % 8 || a.ldb % 8) return false;
+  if (a.ta && (a.M % 8 || a.M < 8)) return false;
+  if (!a.tb && (a.N % 8 || a.N < 8)) return false;
+  return a.M >= 32 && a.N >= 32;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+static void dispatch_dma(const Gemm& a, hipStream_t st) {
+  if (a.ta) {
+    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nk = a.K / kBK;
+    int splits = 1;
+    const int64_t mn = (int64_t)a.M * a.N;
+    if (a.ws) {
+      splits = 768 / tiles;
+      if (splits > nk / 8) splits = nk / 8;
+      if (splits > 16) splits = 16;
+      if (splits < 1) splits = 1;
+      while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
+    }
+    float* cs_part = nullptr;
+    if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
+    if (splits > 1) {
+      launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
+      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, st);
+      if (a.colsum_out) gemm_splitk_reduce(cs_part, splits, a.N, a.colsum_out, st);
+    } else {
+      launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
+    }
+    return;
+  }
+  if (a.tb) {
+    if (a.c_f32) launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_RES, float>(a, 1, nullptr, 0, nullptr, st);
+    else if (a.epi == EPI_STORE) launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_STORE, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_MUL_DGELU, bf16>(a, 1, nullptr, 0, nullptr, st);
+    return;
+  }
+  if (a.c_f32) {
+    if (a.epi == EPI_BIAS) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS, float>(a, 1, nullptr, 0, nullptr, st);
+    else launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_RES, float>(a, 1, nullptr, 0, nullptr, st);
+  } else {
+    if (a.epi == EPI_BIAS) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else if (a.epi == EPI_BIAS_RES) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_RES, bf16>(a, 1, nullptr, 0, nullptr, st);
+    else launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_GELU, bf16>(a, 1, nullptr, 0, nullptr, st);
+  }
+}
+
+void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
+  switch (variant) {
+    case 1: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
+    case 2: dispatch_dma<256, 128, 4, 2, 3>(a, st); break;
+    case 3: dispatch_dma<256, 256, 2, 4, 3>(a, st); break;
+    default: dispatch_dma<128, 128, 2, 2, 4>(a, st); break;
+  }
+}
+
+}  // namespace pt

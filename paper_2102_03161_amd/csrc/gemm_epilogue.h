@@ -1,0 +1,141 @@
+// Pieces shared by the matrix-core GEMM kernels: the device-side problem
+// descriptor, the fused epilogues, and the LDS-staged store path.
+#pragma once
+#include "common.h"
+#include "kernels.h"
+
+namespace pt {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+template <typename T>
+struct GemmDev {
+  const T* A;
+  const T* B;
+  void* C;
+  int M, N, K;
+  int64_t lda, ldb, ldc;
+  const T* bias;
+  const T* aux;
+  T* aux_out;
+  int64_t ld_aux;
+};
+
+template <typename T, typename TC, int EPI>
+__device__ __forceinline__ void epilogue_store(const GemmDev<T>& g, int row, int col, float acc) {
+  float v = acc;
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) v += to_f32(g.bias[col]);
+  if (EPI == EPI_BIAS_RES) v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
+  if (EPI == EPI_RES) {  // an fp32 output adds the fp32 gradient stream
+    if (sizeof(TC) == 4) v += reinterpret_cast<const float*>(g.aux)[(int64_t)row * g.ld_aux + col];
+    else v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
+  }
+  if (EPI == EPI_BIAS_GELU) {
+    if (g.aux_out) g.aux_out[(int64_t)row * g.ld_aux + col] = from_f32<T>(v);  // pre-activation for the backward pass
+    v = gelu_f(v);
+  }
+  if (EPI == EPI_MUL_DGELU) v *= dgelu_f(to_f32(g.aux[(int64_t)row * g.ld_aux + col]));
+  reinterpret_cast<TC*>(g.C)[(int64_t)row * g.ldc + col] = from_f32<TC>(v);
+}
+
+struct SplitArgs {
+  int splits;         // grid.z; each split owns a contiguous range of k tiles and its own output slab
+  int tiles_per_split;
+  int64_t slab;       // elements between the output slabs of consecutive splits
+  float* colsum;      // [splits][N] column sums of B over the split's k range (TB == false only), or null
+};
+
+// 8 consecutive output columns of one row: epilogue math and 16-byte stores
+template <int EPI, typename TC>
+__device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cbase, int row, int col, float (&v)[8]) {
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+    union { uint4 u; bf16 h[8]; } b;
+    b.u = *reinterpret_cast<const uint4*>(g.bias + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += to_f32(b.h[e]);
+  }
+  if (EPI == EPI_BIAS_RES || (EPI == EPI_RES && sizeof(TC) == 2) || EPI == EPI_MUL_DGELU) {
+    union { uint4 u; bf16 h[8]; } a;
+    a.u = *reinterpret_cast<const uint4*>(g.aux + (int64_t)row * g.ld_aux + col);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (EPI == EPI_MUL_DGELU) v[e] *= dgelu_f(to_f32(a.h[e])); else v[e] += to_f32(a.h[e]);
+    }
+  }
+  if (EPI == EPI_RES && sizeof(TC) == 4) {
+    const float* a = reinterpret_cast<const float*>(g.aux) + (int64_t)row * g.ld_aux + col;
+    const float4 a0 = *reinterpret_cast<const float4*>(a), a1 = *reinterpret_cast<const float4*>(a + 4);
+    v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w; v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
+  }
+  if (EPI == EPI_BIAS_GELU) {
+    if (g.aux_out) {
+      union { uint4 u; bf16 h[8]; } o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
+      *reinterpret_cast<uint4*>(g.aux_out + (int64_t)row * g.ld_aux + col) = o.u;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+  }
+  if (sizeof(TC) == 4) {
+    float* c = reinterpret_cast<float*>(Cbase) + (int64_t)row * g.ldc + col;
+    *reinterpret_cast<float4*>(c) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(c + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    union { uint4 u; bf16 h[8]; } o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
+    *reinterpret_cast<uint4*>(reinterpret_cast<bf16*>(Cbase) + (int64_t)row * g.ldc + col) = o.u;
+  }
+}
+
+// Accumulators of one wave (TM x TN tiles of 32x32) -> per-wave LDS staging -> 16-byte row-contiguous
+// stores with the epilogue applied.  `stage` is this wave's private 32 x (WTN+4) float area; (row0, col0)
+// is the wave tile's origin in C.  A wave reads back only what it wrote itself, so no workgroup barrier
+// is needed (LDS operations of one wave complete in order); the wave barriers only stop the compiler
+// from moving accesses across them.
+// accumulator layout of the 32x32 MFMA: lane holds column lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+template <int TM, int TN, int WTM, int WTN, int EPI, typename TC>
+__device__ __forceinline__ void staged_epilogue(const GemmDev<bf16>& g, void* Cbase, const f32x16 (&acc)[TM][TN],
+                                                float* stage, int row0, int col0, int lane, int vec_ok) {
+  constexpr int STAGE_LD = WTN + 4;
+  constexpr int CPR = WTN / 8;   // 8-column chunks per row of the wave tile
+  constexpr int RPP = 64 / CPR;  // rows per pass
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        stage[(8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * STAGE_LD + j * 32 + (lane & 31)] = acc[i][j][v];
+    __builtin_amdgcn_wave_barrier();
+    const int cc = (lane % CPR) * 8;
+#pragma unroll
+    for (int pss = 0; pss < 32 / RPP; ++pss) {
+      const int r = pss * RPP + lane / CPR;
+      const int row = row0 + i * 32 + r, col = col0 + cc;
+      if (row >= g.M || col >= g.N) continue;
+      float v8[8];
+      const float4 x0 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc);
+      const float4 x1 = *reinterpret_cast<const float4*>(stage + r * STAGE_LD + cc + 4);
+      v8[0] = x0.x; v8[1] = x0.y; v8[2] = x0.z; v8[3] = x0.w; v8[4] = x1.x; v8[5] = x1.y; v8[6] = x1.z; v8[7] = x1.w;
+      if (vec_ok && col + 8 <= g.N) {
+        epilogue_store8<EPI, TC>(g, Cbase, row, col, v8);
+      } else {
+        GemmDev<bf16> gs = g;
+        gs.C = Cbase;
+        for (int e = 0; e < 8 && col + e < g.N; ++e) epilogue_store<bf16, TC, EPI>(gs, row, col + e, v8[e]);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// host side
+bool gemm_epilogue_vec_ok(const Gemm& a);
+void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, hipStream_t st);
+bool gemm_dma_ok(const Gemm& a);
+void gemm_dma(const Gemm& a, int variant, hipStream_t st);
+
+}  // namespace pt

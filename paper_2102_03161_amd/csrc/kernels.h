@@ -39,6 +39,8 @@ struct Gemm {
 void gemm(int dt, const Gemm& g, hipStream_t st);
 // true when gemm() will run the matrix-core kernel for this problem
 bool gemm_uses_mfma(int dt, const Gemm& g);
+// tile-shape override for experiments: -1 = automatic
+void gemm_set_config(int c);
 
 // ---- attention (softmax(q k^T / sqrt(dh)) v, no mask) over packed qkv [nb,S,3D]
 void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or null*/, int nb, int S, int H,
