@@ -72,20 +72,22 @@ struct TileK {
       gp[i] += gstep;
     }
   }
-  // fragments of all row blocks and both k-steps: f[ks][i]
-  __device__ __forceinline__ void read(const unsigned char* tile, bf16x8 (&f)[2][NFRAG]) const {
+  // fragments of all row blocks for one k-step, issued as inline assembly (see TileS::read)
+  static constexpr int READS = NFRAG;   // LDS instructions per k-step
+  __device__ __forceinline__ void read(const unsigned char* tile, int ks, bf16x8 (&f)[NFRAG]) const {
+    const unsigned addr = lds_addr(tile) + foff[ks];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int i = 0; i < NFRAG; ++i) f[ks][i] = *reinterpret_cast<const bf16x8*>(tile + foff[ks] + i * 2048);
+    for (int i = 0; i < NFRAG; ++i)
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[i]) : "v"(addr), "n"(i * 2048));
   }
-  static constexpr bool kAsmReads = false;
 };
 
 // ---- strided tile [32][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ ((k & 3) << 1) ----
-// Fragments come from ds_read_b64_tr_b16 (each lane gets four consecutive k of one row).  The reads are
-// issued as inline assembly: the compiler would otherwise wait for every outstanding global->LDS load
-// before each of them, which serialises the pipeline; the caller waits with s_waitcnt lgkmcnt(0).
+// Fragments come from ds_read_b64_tr_b16 (each lane gets four consecutive k of one row).  All fragment
+// reads are issued as inline assembly: the compiler would otherwise wait for every outstanding
+// global->LDS load before a transpose read, which serialises the pipeline, and explicit lgkmcnt waits
+// let the reads of the second k-step overlap the MFMAs of the first.  LDS operations return in order,
+// so "at most n outstanding" means everything issued before the last n has arrived.
 template <int ROWS, int NW, int NFRAG>
 struct TileS {
   static constexpr int ROWB = ROWS * 2, KPL = 1024 / ROWB;       // k rows per wave-wide load
@@ -122,21 +124,20 @@ struct TileS {
       gp[i] += gstep;
     }
   }
-  __device__ __forceinline__ void read(const unsigned char* tile, bf16x8 (&f)[2][NFRAG]) const {
+  static constexpr int READS = 2 * NFRAG;
+  // ks is a compile-time constant at every call site (unrolled), so the offsets fold to immediates
+  __device__ __forceinline__ void read(const unsigned char* tile, int ks, bf16x8 (&f)[NFRAG]) const {
     const unsigned base = lds_addr(tile);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int j = 0; j < NFRAG; ++j) {
-        union { u32x2 h[2]; bf16x8 v; } t;
-        const unsigned addr = base + foff[j];
-        // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 rows is a constant offset (the swizzle only uses k & 3)
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[0]) : "v"(addr), "n"(16 * ks * ROWB));
-        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"((16 * ks + 4) * ROWB));
-        f[ks][j] = t.v;
-      }
+    for (int j = 0; j < NFRAG; ++j) {
+      union { u32x2 h[2]; bf16x8 v; } t;
+      const unsigned addr = base + foff[j] + 16 * ks * ROWB;
+      // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 rows is a constant offset (the swizzle only uses k & 3)
+      asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(t.h[0]) : "v"(addr));
+      asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"(4 * ROWB));
+      f[j] = t.v;
+    }
   }
-  static constexpr bool kAsmReads = true;
   // sum over the tile's k rows of column n (for the fused bias gradient)
   static __device__ __forceinline__ float colsum(const unsigned char* lds, int n) {
     float s = 0.f;
@@ -152,14 +153,15 @@ struct TileS {
 template <bool STRIDED, int ROWS, int NW, int NFRAG> struct TileSel { typedef TileK<ROWS, NW, NFRAG> type; };
 template <int ROWS, int NW, int NFRAG> struct TileSel<true, ROWS, NW, NFRAG> { typedef TileS<ROWS, NW, NFRAG> type; };
 
-// s_waitcnt lgkmcnt(0) that the fragments depend on, so that no MFMA using them can be scheduled before it
-template <int N>
-__device__ __forceinline__ void wait_lds(bf16x8 (&f)[2][N]) {
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+// s_waitcnt lgkmcnt(PENDING) that the given fragments depend on, so that no MFMA using them can be
+// scheduled before it
+template <int PENDING, int NA, int NB>
+__device__ __forceinline__ void wait_lds(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks)
+  for (int i = 0; i < NA; ++i) asm volatile("" : "+v"(a[i]));
 #pragma unroll
-    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[ks][i]));
+  for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(b[i]));
 }
 
 template <int BM, int BN, int WGM, int WGN, int kNS, bool TA, bool TB, int EPI, typename TC>
@@ -231,19 +233,24 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
     const unsigned char* sa = lds + cur * STAGE;
     const unsigned char* sb = sa + LA::BYTES;
     cur = cur + 1 == kNS ? 0 : cur + 1;
-    // all fragment reads of the tile are issued up front (distinct registers)
-    bf16x8 a[2][TM], b[2][TN];
-    ta.read(sa, a);
-    tb.read(sb, b);
-    if (LA::kAsmReads) wait_lds(a);
-    if (LB::kAsmReads) wait_lds(b);
+    // all fragment reads of the tile are issued up front; the MFMAs of the first k-step start as soon as
+    // its fragments are in, while the second k-step's reads are still in flight
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    ta.read(sa, 0, a0);
+    tb.read(sb, 0, b0);
+    ta.read(sa, 1, a1);
+    tb.read(sb, 1, b1);
+    static_assert(LA::READS + LB::READS <= 15, "lgkmcnt is a 4-bit counter");
+    wait_lds<LA::READS + LB::READS>(a0, b0);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
+    wait_lds<0>(a1, b1);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[ks][j], acc[i][j], 0, 0, 0);
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
     if constexpr (!TB) {
       if (do_colsum && tid < BN) cs += LB::colsum(sb, tid);
     }
