@@ -31,15 +31,24 @@ constexpr int DH = 64;
 constexpr int LDR = DH + 8;   // row-major tile: 144-byte rows, conflict-free 16-byte operand reads
 constexpr int LDT = 32 + 4;   // transposed tile [64][32]: 72-byte rows, conflict-free 8-byte operand reads
 
-// Cooperative load (256 threads) of rows r0..r0+31 of a [*, 64] bf16 matrix with row stride ld
-// into a row-major tile Xs[32][LDR] and / or a transposed tile Xt[64][LDT].  Rows >= nrows read as 0.
-__device__ __forceinline__ void load_tile(const bf16* __restrict__ src, int64_t ld, int r0, int nrows, bf16* Xs,
-                                          bf16* Xt, int tid) {
+// Cooperative load (256 threads) of rows r0..r0+31 of a [*, 64] bf16 matrix with row stride ld, in two
+// halves so that the global loads of the next tile can be in flight while the current one is consumed:
+// tile_gload fetches this thread's two 8-byte pieces (rows 2rp, 2rp+1; features 4dc..4dc+3; rows >= nrows
+// read as 0), tile_sstore writes them to a row-major tile Xs[32][LDR] and / or a transposed tile Xt[64][LDT].
+struct TileRegs { uint2 a, b; };
+__device__ __forceinline__ TileRegs tile_gload(const bf16* __restrict__ src, int64_t ld, int r0, int nrows, int tid) {
   const int rp = tid >> 4, dc = tid & 15;
   const int r = r0 + 2 * rp;
-  uint2 a = make_uint2(0, 0), b = make_uint2(0, 0);
-  if (r < nrows) a = *reinterpret_cast<const uint2*>(src + (int64_t)r * ld + 4 * dc);
-  if (r + 1 < nrows) b = *reinterpret_cast<const uint2*>(src + (int64_t)(r + 1) * ld + 4 * dc);
+  TileRegs t;
+  t.a = make_uint2(0, 0);
+  t.b = make_uint2(0, 0);
+  if (r < nrows) t.a = *reinterpret_cast<const uint2*>(src + (int64_t)r * ld + 4 * dc);
+  if (r + 1 < nrows) t.b = *reinterpret_cast<const uint2*>(src + (int64_t)(r + 1) * ld + 4 * dc);
+  return t;
+}
+__device__ __forceinline__ void tile_sstore(const TileRegs& r, bf16* Xs, bf16* Xt, int tid) {
+  const int rp = tid >> 4, dc = tid & 15;
+  const uint2 a = r.a, b = r.b;
   if (Xs) {
     *reinterpret_cast<uint2*>(Xs + (2 * rp) * LDR + 4 * dc) = a;
     *reinterpret_cast<uint2*>(Xs + (2 * rp + 1) * LDR + 4 * dc) = b;
@@ -120,11 +129,16 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
     for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
   float m = -INFINITY, lsum = 0.f;
   const int ntile = (S + 31) / 32;
+  TileRegs rk = tile_gload(base + D, 3 * D, 0, S, tid), rv = tile_gload(base + 2 * D, 3 * D, 0, S, tid);
   for (int kt = 0; kt < ntile; ++kt) {
     __syncthreads();
-    load_tile(base + D, 3 * D, kt * 32, S, Ks, nullptr, tid);
-    load_tile(base + 2 * D, 3 * D, kt * 32, S, nullptr, Vt, tid);
+    tile_sstore(rk, Ks, nullptr, tid);
+    tile_sstore(rv, nullptr, Vt, tid);
     __syncthreads();
+    if (kt + 1 < ntile) {
+      rk = tile_gload(base + D, 3 * D, (kt + 1) * 32, S, tid);
+      rv = tile_gload(base + 2 * D, 3 * D, (kt + 1) * 32, S, tid);
+    }
     f32x16 s;
 #pragma unroll
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
@@ -202,11 +216,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
 #pragma unroll
     for (int v = 0; v < 16; ++v) dq[dt][v] = 0.f;
   const int ntile = (S + 31) / 32;
+  TileRegs rk = tile_gload(base + D, 3 * D, 0, S, tid), rv = tile_gload(base + 2 * D, 3 * D, 0, S, tid);
   for (int kt = 0; kt < ntile; ++kt) {
     __syncthreads();
-    load_tile(base + D, 3 * D, kt * 32, S, Ks, Kt, tid);
-    load_tile(base + 2 * D, 3 * D, kt * 32, S, Vs, nullptr, tid);
+    tile_sstore(rk, Ks, Kt, tid);
+    tile_sstore(rv, Vs, nullptr, tid);
     __syncthreads();
+    if (kt + 1 < ntile) {
+      rk = tile_gload(base + D, 3 * D, (kt + 1) * 32, S, tid);
+      rv = tile_gload(base + 2 * D, 3 * D, (kt + 1) * 32, S, tid);
+    }
     f32x16 s, dp;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
@@ -265,16 +284,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
   const int ntile = (S + 31) / 32;
+  TileRegs rq = tile_gload(base, 3 * D, 0, S, tid), rdo = tile_gload(dobase, D, 0, S, tid);
+  float nls = 0.f, ndl = 0.f;
+  if (tid < 32 && tid < S) {
+    nls = lse[((int64_t)b * H + h) * S + tid];
+    ndl = delta[((int64_t)b * H + h) * S + tid];
+  }
   for (int qt = 0; qt < ntile; ++qt) {
     __syncthreads();
-    load_tile(base, 3 * D, qt * 32, S, Qs, Qt, tid);
-    load_tile(dobase, D, qt * 32, S, dOs, dOt, tid);
-    if (tid < 32) {
-      const int qq = qt * 32 + tid;
-      ls[tid] = qq < S ? lse[((int64_t)b * H + h) * S + qq] : 0.f;
-      dls[tid] = qq < S ? delta[((int64_t)b * H + h) * S + qq] : 0.f;
-    }
+    tile_sstore(rq, Qs, Qt, tid);
+    tile_sstore(rdo, dOs, dOt, tid);
+    if (tid < 32) { ls[tid] = nls; dls[tid] = ndl; }
     __syncthreads();
+    if (qt + 1 < ntile) {
+      rq = tile_gload(base, 3 * D, (qt + 1) * 32, S, tid);
+      rdo = tile_gload(dobase, D, (qt + 1) * 32, S, tid);
+      if (tid < 32) {
+        const int qq = (qt + 1) * 32 + tid;
+        nls = qq < S ? lse[((int64_t)b * H + h) * S + qq] : 0.f;
+        ndl = qq < S ? delta[((int64_t)b * H + h) * S + qq] : 0.f;
+      }
+    }
     f32x16 s, dp;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }

@@ -415,10 +415,10 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step
   if (gemm_uses_mfma(dt, a) && (!a.ta || a.ldc == a.N)) {
     if (g_cfg_override != 0 && gemm_dma_ok(a)) {
-      // default: 128x128 tiles, three per CU; wide outputs and the short-M weight gradients do
-      // better with 256x128 tiles and eight waves
+      // default: 128x128 tiles, three per CU; wide outputs and the weight gradients do better with
+      // 256x128 tiles and eight waves
       int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
-      if (g_cfg_override < 0) v = a.ta ? (a.M <= 1024 ? 2 : 1) : (a.N >= 3072 ? 2 : 1);
+      if (g_cfg_override < 0) v = (a.ta || a.N >= 3072) ? 2 : 1;
       gemm_dma(a, v, st);
       return;
     }

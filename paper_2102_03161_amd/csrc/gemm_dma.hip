@@ -291,6 +291,10 @@ bool gemm_dma_ok(const Gemm& a) {
   return a.M >= 32 && a.N >= 32;
 }
 
+// workgroups a split-K weight gradient aims for: two 256x128 workgroups per CU
+int g_split_target = 512;
+void gemm_set_split_target(int t) { g_split_target = t; }
+
 template <int BM, int BN, int WGM, int WGN, int NS>
 static void dispatch_dma(const Gemm& a, hipStream_t st) {
   if (a.ta) {
@@ -298,7 +302,7 @@ static void dispatch_dma(const Gemm& a, hipStream_t st) {
     int splits = 1;
     const int64_t mn = (int64_t)a.M * a.N;
     if (a.ws) {
-      splits = 768 / tiles;
+      splits = g_split_target / tiles;
       if (splits > nk / 8) splits = nk / 8;
       if (splits > 16) splits = 16;
       if (splits < 1) splits = 1;
@@ -336,6 +340,7 @@ void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
     case 1: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
     case 2: dispatch_dma<256, 128, 4, 2, 3>(a, st); break;
     case 3: dispatch_dma<256, 256, 2, 4, 3>(a, st); break;
+    case 4: dispatch_dma<256, 256, 2, 4, 4>(a, st); break;
     default: dispatch_dma<128, 128, 2, 2, 4>(a, st); break;
   }
 }

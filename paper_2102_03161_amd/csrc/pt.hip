@@ -173,7 +173,7 @@ void make_plan(const pt_config& c, Plan* p) {
     for (auto& sh : shapes) {
       const int64_t tiles = ((sh[0] + 127) / 128) * ((sh[1] + 127) / 128);
       if (tiles <= 0) continue;
-      const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 768 / tiles));
+      const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 1024 / tiles));
       need = std::max(need, (size_t)(splits * (sh[0] * sh[1] + sh[1])));
     }
     p->gemmws_floats = need;

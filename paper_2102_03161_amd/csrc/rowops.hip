@@ -97,19 +97,20 @@ void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* g
 // ---------------------------------------------------------------------------
 // LayerNorm backward
 // ---------------------------------------------------------------------------
-constexpr int kLnBwdBlocks = 512;
+constexpr int kLnBwdBlocks = 1024;  // workgroups (partial rows) at most
+constexpr int kLnBwdWaves = 4;      // waves per workgroup, one row per wave at a time
 size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 3 * D; }
 
 // dy may be the fp32 gradient stream or a T tensor; the result goes to an fp32 stream
 // buffer (dx_s), a T copy for the matrix-core operands (dx_o), or both (either may be null).
 template <typename T, typename TDY, typename TX, int VPL>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy, int64_t lddy, const TX* __restrict__ x,
+__global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __restrict__ dy, int64_t lddy, const TX* __restrict__ x,
                                                      int64_t ldx, const float* __restrict__ mean,
                                                      const float* __restrict__ rstd, const T* __restrict__ gamma,
                                                      const float* __restrict__ dres, int64_t lddres,
                                                      float* __restrict__ dx_s, T* __restrict__ dx_o, int64_t lddx,
                                                      float* __restrict__ partial, int rows, int D) {
-  extern __shared__ float red[];  // [4][3][D]: d(gamma), d(beta), column sums of the output
+  extern __shared__ float red[];  // [3][D]: d(gamma), d(beta), column sums of the output
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nvec = D >> 2;
   float g[VPL][4], ag[VPL][4], ab[VPL][4], as[VPL][4];
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy,
     for (int e = 0; e < 4; ++e) { ag[j][e] = 0.f; ab[j][e] = 0.f; as[j][e] = 0.f; g[j][e] = 0.f; }
     if (c < nvec) load4(gamma + 4 * c, g[j]);
   }
-  for (int row = blockIdx.x * 4 + wave; row < rows; row += gridDim.x * 4) {
+  for (int row = blockIdx.x * kLnBwdWaves + wave; row < rows; row += gridDim.x * kLnBwdWaves) {
     const float mu = mean[row], rs = rstd[row];
     float xh[VPL][4], dh[VPL][4];
     float s1 = 0.f, s2 = 0.f;
@@ -164,44 +165,46 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const TDY* __restrict__ dy,
       }
     }
   }
-  // combine the four waves of the workgroup in a fixed order
+  // combine the waves of the workgroup in wave order (fixed, so reproducible)
+  for (int w = 0; w < kLnBwdWaves; ++w) {
+    if (wave == w) {
 #pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = lane + 64 * j;
-    if (c < nvec) {
+      for (int j = 0; j < VPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < nvec) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        red[(wave * 3 + 0) * D + 4 * c + e] = ag[j][e];
-        red[(wave * 3 + 1) * D + 4 * c + e] = ab[j][e];
-        red[(wave * 3 + 2) * D + 4 * c + e] = as[j][e];
+          for (int e = 0; e < 4; ++e) {
+            const int i = 4 * c + e;
+            red[i] = (w ? red[i] : 0.f) + ag[j][e];
+            red[D + i] = (w ? red[D + i] : 0.f) + ab[j][e];
+            red[2 * D + i] = (w ? red[2 * D + i] : 0.f) + as[j][e];
+          }
+        }
       }
     }
+    __syncthreads();
   }
-  __syncthreads();
-  for (int i = threadIdx.x; i < 3 * D; i += 256) {
-    const float s = ((red[i] + red[3 * D + i]) + red[6 * D + i]) + red[9 * D + i];
-    partial[(size_t)blockIdx.x * 3 * D + i] = s;
-  }
+  for (int i = threadIdx.x; i < 3 * D; i += 64 * kLnBwdWaves) partial[(size_t)blockIdx.x * 3 * D + i] = red[i];
 }
 
-// out[i] = sum over p of partial[p][i] in a fixed order: 32 columns per workgroup, eight interleaved
+// out[i] = sum over p of partial[p][i] in a fixed order: 8 columns per workgroup, 32 interleaved
 // row groups summed in parallel and then combined in group order.  Column i goes to out0[i] for
 // i < n0, to out1[i - n0] for i < 2 n0, else to out2[i - 2 n0]; a null destination drops the column.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
                                                               float* __restrict__ out0, int n0,
                                                               float* __restrict__ out1, float* __restrict__ out2) {
-  __shared__ float red[8][33];
-  const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int i = blockIdx.x * 32 + c;
+  __shared__ float red[32][9];
+  const int c = threadIdx.x & 7, rg = threadIdx.x >> 3;
+  const int i = blockIdx.x * 8 + c;
   float s = 0.f;
   if (i < n)
-    for (int p = rg; p < np; p += 8) s += partial[(size_t)p * n + i];
+    for (int p = rg; p < np; p += 32) s += partial[(size_t)p * n + i];
   red[rg][c] = s;
   __syncthreads();
   if (rg == 0 && i < n) {
     float t = red[0][c];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) t += red[k][c];
+    for (int k = 1; k < 32; ++k) t += red[k][c];
     float* dst = i < n0 ? out0 : (i < 2 * n0 ? out1 : out2);
     if (dst) dst[i % n0] = t;
   }
@@ -212,14 +215,19 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
                    float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
                    int rows, int D, hipStream_t st) {
   if (rows <= 0) return;
-  const int nb = cdiv(rows, 4) < kLnBwdBlocks ? cdiv(rows, 4) : kLnBwdBlocks;
-  const size_t shm = (size_t)12 * D * sizeof(float);
+  const int nb = cdiv(rows, kLnBwdWaves) < kLnBwdBlocks ? cdiv(rows, kLnBwdWaves) : kLnBwdBlocks;
+  const size_t shm = (size_t)3 * D * sizeof(float);
 #define LN_BWD(T, TDY, TX, V)                                                                                      \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, TDY, TX, V>), dim3(nb), dim3(256), shm, st, (const TDY*)dy, lddy,           \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, TDY, TX, V>), dim3(nb), dim3(64 * kLnBwdWaves), shm, st, (const TDY*)dy, lddy,           \
                      (const TX*)x, ldx, mean, rstd, (const T*)gamma, dres, lddres, dx_s, (T*)dx_o, lddx, partial, \
                      rows, D)
-#define LN_BWD_V(T, TDY, TX) \
-  do { if (D <= 1024) LN_BWD(T, TDY, TX, 4); else LN_BWD(T, TDY, TX, 8); } while (0)
+#define LN_BWD_V(T, TDY, TX)                                             \
+  do {                                                                   \
+    if (D <= 256) LN_BWD(T, TDY, TX, 1);                                 \
+    else if (D <= 768) LN_BWD(T, TDY, TX, 3);                            \
+    else if (D <= 1024) LN_BWD(T, TDY, TX, 4);                           \
+    else LN_BWD(T, TDY, TX, 8);                                          \
+  } while (0)
   if (dt == 0) LN_BWD_V(float, float, float);
   else if (dy_f32 && x_f32) LN_BWD_V(bf16, float, float);
   else if (dy_f32) LN_BWD_V(bf16, float, bf16);
@@ -227,7 +235,7 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
   else LN_BWD_V(bf16, bf16, bf16);
 #undef LN_BWD_V
 #undef LN_BWD
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(256), 0, st, partial, nb, 3 * D, dgamma, D,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 8)), dim3(256), 0, st, partial, nb, 3 * D, dgamma, D,
                      dbeta, dxsum);
 }
 
@@ -252,7 +260,7 @@ void colsum(int dt, const void* X, int64_t ld, int M, int N, float* out, float* 
   dim3 grid(cdiv(N, 256), nby);
   if (dt == 0) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, ld, M, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, ld, M, N, partial);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 32)), dim3(256), 0, st, partial, nby, N, out, N,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 8)), dim3(256), 0, st, partial, nby, N, out, N,
                      (float*)nullptr, (float*)nullptr);
 }
 
@@ -535,7 +543,7 @@ void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* d
   const int nb = rows < kQaBlocks ? rows : kQaBlocks;
   if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, dx, partial, rows, D);
   else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, dx, partial, rows, D);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 32)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 8)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
                      2 * D, db, (float*)nullptr);
 }
 
