@@ -1,0 +1,109 @@
+"""Full-size checks in the launch configuration bench.py times (ViT-B/16, bf16, micro-batch 64):
+sampled outputs against the oracle (the forward pass is independent per sample, so the oracle can
+compute single samples), and properties that hold at any size for what it cannot afford."""
+import numpy as np
+import pytest
+
+from oracle import encoder as orc
+from paper_2102_03161_amd import binding, synth
+from tests import gpu_harness as H
+from tests.helpers import oracle_cfg, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_mod():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+@pytest.fixture(scope="module")
+def vitb(torch_mod):
+    w = synth.workload("vit_b16")
+    ctx = binding.Context(binding.make_config(w, cache_slots=w["B"]))
+    vals = H.init_values(w, ctx, 2)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 2, w["B"])
+    yield w, ctx, vals, x, y
+    ctx.close()
+
+
+def forward_backward(torch, ctx, w, x, y, ids=None):
+    hk = ctx.frozen_forward(H.to_dev(torch, x), ids)
+    loss = ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+    return loss
+
+
+def test_full_batch_forward_matches_oracle_on_sampled_samples(torch_mod, vitb):
+    torch = torch_mod
+    w, ctx, vals, x, y = vitb
+    B, S, D = w["B"], w["S"], w["D"]
+    print("full-size ViT-B/16 B=64 k=0 forward, sampled against the oracle", flush=True)
+    loss = forward_backward(torch, ctx, w, x, y)
+    logits = ctx.read_activation(binding.ACT_LOGITS, (B, w["n_out"]))
+    h0 = ctx.read_activation(binding.ACT_HK, (B, S, D))
+    hL = ctx.read_activation(binding.ACT_HL, (B, S, D))
+    # the reported loss is the mean cross-entropy of the reported logits
+    z = logits.astype(np.float64)
+    lse = np.log(np.exp(z - z.max(1, keepdims=True)).sum(1)) + z.max(1)
+    assert abs(loss - float((lse - z[np.arange(B), y]).mean())) < 1e-5 * abs(loss)
+    cfg = oracle_cfg(w)
+    p = {n: a.astype(np.float64) for n, a in vals.items()}
+    for i in (3, 41, B - 1):
+        xi = x[i:i + 1].astype(np.float64)
+        o_h0, _ = orc.frozen_forward(cfg, p, xi, 0)
+        o_hL = orc.prefix_forward(cfg, p, o_h0, 0, cfg.L)
+        _, o_z, _ = orc.head_loss_forward(cfg, p, o_hL, y[i:i + 1])
+        assert rel_err(h0[i], o_h0[0]) < 2e-2
+        assert rel_err(hL[i], o_hL[0]) < 2e-2
+        assert rel_err(logits[i], o_z[0]) < 2e-2, i
+
+
+def test_full_batch_gradient_is_the_mean_of_sub_batch_gradients(torch_mod, vitb):
+    """d(mean loss over 64)/dw = mean over eight sub-batches of d(mean loss over 8)/dw: ties the
+    full-size launch configuration to the micro-batch one that is checked against the oracle."""
+    torch = torch_mod
+    w, ctx, vals, x, y = vitb
+    B = w["B"]
+    tid = {name: t for t, name, *_ in ctx.tensors()}
+    probe = ["front.W_pe", "front.pos", "blk0.Wqkv", "blk0.ln1_g", "blk5.W1", "blk5.bo", "blk11.W2", "blk11.b1",
+             "head.ln_b", "head.W"]
+    forward_backward(torch, ctx, w, x, y)
+    norms = ctx.layer_grad_norms()
+    full = {n: ctx.read_tensor(tid[n], binding.KIND_GRAD) for n in probe}
+    # norms are the root of the sum of squares of the gradients that can be read back
+    blk5 = [ctx.read_tensor(tid[f"blk5.{t}"], binding.KIND_GRAD).astype(np.float64) for t in orc.BLOCK_TENSORS]
+    assert abs(norms[6] - np.sqrt(sum((a ** 2).sum() for a in blk5))) < 1e-5 * norms[6]
+    acc = {n: np.zeros_like(full[n], dtype=np.float64) for n in probe}
+    for c in range(8):
+        sl = slice(8 * c, 8 * c + 8)
+        forward_backward(torch, ctx, w, x[sl], y[sl])
+        for n in probe:
+            acc[n] += ctx.read_tensor(tid[n], binding.KIND_GRAD)
+    gmax = max(float(np.max(np.abs(a))) for a in full.values())
+    for n in probe:
+        ref = acc[n] / 8
+        err = float(np.max(np.abs(full[n] - ref))) / max(float(np.max(np.abs(ref))), 1e-2 * gmax)
+        assert err < 2e-2, (n, err)
+
+
+def test_full_batch_cache_hit_equals_recompute_and_trains_the_same(torch_mod, vitb):
+    torch = torch_mod
+    w, ctx, vals, x, y = vitb
+    B, S, D = w["B"], w["S"], w["D"]
+    ids = np.arange(B)[::-1].copy()
+    ctx.set_freeze_boundary(6)
+    l_miss = forward_backward(torch, ctx, w, x, y, ids)
+    h_miss = ctx.read_activation(binding.ACT_HK, (B, S, D))
+    g_miss = ctx.read_tensor(dict((n, t) for t, n, *_ in ctx.tensors())["blk6.Wqkv"], binding.KIND_GRAD)
+    before = ctx.cache_stats()
+    l_hit = forward_backward(torch, ctx, w, x, y, ids)
+    after = ctx.cache_stats()
+    assert after["hits"] - before["hits"] == B and after["block_runs"] == before["block_runs"]
+    assert np.array_equal(ctx.read_activation(binding.ACT_HK, (B, S, D)), h_miss)
+    assert l_hit == l_miss
+    assert np.array_equal(ctx.read_tensor(dict((n, t) for t, n, *_ in ctx.tensors())["blk6.Wqkv"], binding.KIND_GRAD), g_miss)
+    norms = ctx.layer_grad_norms()
+    assert np.all(norms[:7] == 0.0) and np.all(norms[7:] > 0.0)

@@ -252,3 +252,41 @@ def test_runs_are_bit_reproducible(torch_mod):
         for n in a["grads"]:
             assert np.array_equal(a["grads"][n], b["grads"][n]), n
             assert np.array_equal(a["params"][n], b["params"][n]), n
+
+
+def test_vit_b16_boundary_schedule(torch_mod):
+    """ViT-B/16 shapes, parity micro-batch, boundary advancing 0 -> 3 -> 6 -> 9 with one step per phase;
+    at every switch the oracle restarts from the state exported by the library."""
+    torch = torch_mod
+    w = synth.workload("vit_b16")
+    nb = 4
+    cfg = oracle_cfg(w)
+    ctx = binding.Context(binding.make_config(w, B=nb))
+    vals = H.init_values(w, ctx, 5)
+    H.load_params(ctx, vals)
+    tid = {nm: t for t, nm, *_ in ctx.tensors()}
+    for step, k in enumerate((0, 3, 6, 9)):
+        print(f"schedule step {step} k={k}", flush=True)
+        ctx.set_freeze_boundary(k)          # clears the state of newly frozen tensors before it is exported
+        master = H.gpu_read_all(ctx, binding.KIND_PARAM)
+        shadow = H.gpu_read_all(ctx, binding.KIND_SHADOW)
+
+        def exported_state():
+            st = orc.new_opt_state({n: a.astype(np.float64) for n, a in master.items()})
+            st["t"] = ctx.get_step_count()
+            for n in master:
+                st["m"][n] = ctx.read_tensor(tid[n], binding.KIND_MOMENT1).astype(np.float64)
+                st["v"][n] = ctx.read_tensor(tid[n], binding.KIND_MOMENT2).astype(np.float64)
+            orc.drop_frozen_state(cfg, st, k)
+            return st
+        st_a, st_b = exported_state(), exported_state()
+        x, y = H.batch_for(w, 5, nb, tag=f"phase{step}")
+        g = H.gpu_step(torch, ctx, w, x, y, k)
+        o = H.oracle_step(w, master, x, y, k, state=st_a, compute_vals=shadow)
+        H.oracle_update(w, o, master, g["grads"], k, state=st_b)
+        H.compare_step(w, g, o, k, TOL["bf16"])
+        for n, a in g["params"].items():
+            if not orc.is_active(n, cfg, k):
+                assert np.array_equal(a, master[n]), n
+        assert ctx.get_freeze_boundary() == k and ctx.get_step_count() == step + 1
+    ctx.close()
