@@ -25,6 +25,11 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of each GEMM class (mean over the launches of one step), from rocprofv3
+# --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
+# read for the --calibrate-copy kernel; the figures and commands are in profiles/.
+MEASURED_TRAFFIC = {}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -36,6 +41,9 @@ def parse():
     ap.add_argument("--no-sweep", action="store_true", help="skip the extra k = 6 / 9 measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--profile-steps", type=int, default=3)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy four times (a kernel of known HBM traffic, for scaling "
+                         "the memory counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -90,6 +98,13 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / n_steps
 
+    if a.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if a.k:
         ctx.set_freeze_boundary(a.k)
     sec = timed(a.warmup, a.steps)
@@ -128,11 +143,12 @@ def main():
     dom = max(gemm_names, key=lambda n: prof[n][0])
     ms, n, wk = prof[dom]
     ach = wk / (ms * 1e-3) / 1e12
-    result["roofline"] = {"kernel": {"gemm_tn": "gemm_mfma_kernel<TA=true,TB=false> (weight gradient dW = x^T dy)",
-                                     "gemm_nn": "gemm_mfma_kernel<TA=false,TB=false> (forward y = x W)",
-                                     "gemm_nt": "gemm_mfma_kernel<TA=false,TB=true> (input gradient dx = dy W^T)"}[dom],
+    result["roofline"] = {"kernel": {"gemm_tn": "gemm_dma_kernel<TA=true,TB=false> (weight gradient dW = x^T dy)",
+                                     "gemm_nn": "gemm_dma_kernel<TA=false,TB=false> (forward y = x W)",
+                                     "gemm_nt": "gemm_dma_kernel<TA=false,TB=true> (input gradient dx = dy W^T)"}[dom],
                           "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                          "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                          "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                          "traffic": MEASURED_TRAFFIC.get((a.workload, a.k, dom)),
                           "avg_launch_us": round(1e3 * ms / n, 2), "launches_per_step": n // a.profile_steps,
                           "flops_per_launch": wk / n}
 
@@ -153,10 +169,11 @@ def main():
     if not a.no_cpu:
         from oracle import encoder as orc
         from threadpoolctl import threadpool_info
-        Bo = 24
+        Bo = 8
         cfg = orc.Config(**synth.model_fields(w))
-        p = {n: synth.gen_param(seed, n, s).astype(np.float32) for n, s in orc.param_shapes(cfg).items()}
+        p = {n: synth.gen_param(seed, n, s).astype(np.float64) for n, s in orc.param_shapes(cfg).items()}
         x, y = synth.gen_inputs(w, seed, Bo)
+        x = x.astype(np.float64) if x.dtype.kind == 'f' else x
         st = orc.new_opt_state(p)
         t0 = time.perf_counter()
         hk, fs = orc.frozen_forward(cfg, p, x, a.k)
@@ -167,7 +184,7 @@ def main():
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
         result["cpu_baseline"] = {"value": round(Bo / dt, 3), "unit": "samples/s", "cores": threads, "kind": "oracle",
                                   "sample": f"one full step (frozen forward, forward+backward, grad norms, AdamW) of the "
-                                            f"numpy oracle in fp32 at batch {Bo}, same shapes, k={a.k}; {dt:.1f} s"}
+                                            f"numpy oracle in fp64 at batch {Bo}, same shapes, k={a.k}; {dt:.1f} s"}
     print(json.dumps(result))
 
 

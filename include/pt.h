@@ -61,7 +61,7 @@ enum { PT_SGDM = 0, PT_ADAMW = 1 };
 typedef struct {
   int32_t arch;        /* PT_VIT_PRELN | PT_BERT_POSTLN                              */
   int32_t dtype;       /* PT_F32 | PT_BF16                                           */
-  int32_t L, D, H, F;  /* blocks, hidden, heads, MLP width; D % H == 0, D/H % 4 == 0 */
+  int32_t L, D, H, F;  /* blocks, hidden, heads, MLP width; D % H == 0, D/H % 8 == 0 and <= 128, D <= 2048, F % 4 == 0 */
   int32_t S;           /* sequence length (ViT: (img/patch)^2 + 1)                   */
   int32_t B;           /* largest batch any call will pass                           */
   int32_t n_out;       /* classes (ViT) or 2 (BERT span QA)                          */

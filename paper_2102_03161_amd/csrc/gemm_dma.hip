@@ -165,8 +165,8 @@ __device__ __forceinline__ void wait_lds(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int kNS, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n,
-                                                                  int total_tiles, int vec_ok) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
+                                                                  int group_n, int vec_ok) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
   typedef typename TileSel<TA, BM, NW, TM>::type LA;    // A strided when stored [K,M]
@@ -181,11 +181,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
   __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int per = (total_tiles + 7) >> 3;
-  const int lin = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (lin >= total_tiles) return;
-  const int m0 = (lin / tiles_n) * BM, n0 = (lin % tiles_n) * BN;
-  const int split = blockIdx.z;
+  // Workgroups are dealt to the 8 XCDs round-robin by their index, and each XCD has an L2 of its own.  The
+  // index is remapped so that one XCD works through a contiguous range of the sequence
+  //   for split: for column group (group_n tile columns): for tile row: for tile column in the group
+  // which keeps a K slice (split-K) or a band of B panels small enough to stay in that L2 while the A panels
+  // stream past it once.
+  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int t = work - split * total_tiles;
+  const int grp = t / (group_n * tiles_m);
+  const int rem = t - grp * group_n * tiles_m;
+  const int gw = tiles_n - grp * group_n < group_n ? tiles_n - grp * group_n : group_n;
+  const int m0 = (rem / gw) * BM, n0 = (grp * group_n + rem % gw) * BN;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -267,6 +277,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
                                              n0 + wn * WTN, lane, vec_ok);
 }
 
+int g_group_n = 0;                  // forced column-group width (tuning); 0 = derive from g_group_bytes
+int64_t g_group_bytes = 1536 << 10;  // L2 bytes a column group's B panels may take
+
 template <int BM, int BN, int WGM, int WGN, int NS, bool TA, bool TB, int EPI, typename TC>
 void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
   GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, cbase ? (void*)cbase : a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
@@ -274,9 +287,17 @@ void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* co
   const int tiles_m = cdiv(a.M, BM), tiles_n = cdiv(a.N, BN), total = tiles_m * tiles_n;
   const int nk = a.K / kBK;
   SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
-  dim3 grid(8 * cdiv(total, 8), 1, splits);
+  dim3 grid(8 * cdiv(total * splits, 8), 1, 1);
+  // column-group width: the B panels of a group (whole K) should fit beside the streaming A panels in a 4 MB L2
+  int group_n = g_group_n;
+  if (group_n <= 0) {
+    const int64_t panel = (int64_t)BN * (a.K / splits) * 2;
+    group_n = (int)(g_group_bytes / (panel > 0 ? panel : 1));
+    if (group_n < 1) group_n = 1;
+  }
+  if (group_n > tiles_n) group_n = tiles_n;
   hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, TA, TB, EPI, TC>), grid, dim3(64 * WGM * WGN), 0, st, g, sp,
-                     tiles_n, total, gemm_epilogue_vec_ok(a) ? 1 : 0);
+                     tiles_m, tiles_n, group_n, gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -294,6 +315,10 @@ bool gemm_dma_ok(const Gemm& a) {
 // workgroups a split-K weight gradient aims for: two 256x128 workgroups per CU
 int g_split_target = 512;
 void gemm_set_split_target(int t) { g_split_target = t; }
+void gemm_set_group(int tiles, long bytes) {
+  g_group_n = tiles;
+  if (bytes > 0) g_group_bytes = bytes;
+}
 
 template <int BM, int BN, int WGM, int WGN, int NS>
 static void dispatch_dma(const Gemm& a, hipStream_t st) {
