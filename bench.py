@@ -169,7 +169,7 @@ def main():
     if not a.no_cpu:
         from oracle import encoder as orc
         from threadpoolctl import threadpool_info
-        Bo = 8
+        Bo = 32
         cfg = orc.Config(**synth.model_fields(w))
         p = {n: synth.gen_param(seed, n, s).astype(np.float64) for n, s in orc.param_shapes(cfg).items()}
         x, y = synth.gen_inputs(w, seed, Bo)

@@ -16,6 +16,10 @@ SOURCES = ["gemm.hip", "gemm_dma.hip", "attention.hip", "attention_mfma.hip", "r
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # keep fp32 vector math scalar per lane: no packed-fp32 instruction selection
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-file additions.  The attention kernels keep long-lived MFMA accumulators next to short-lived score tiles;
+# with the default AGPR form of the MFMA result the compiler shuttles the long-lived ones between register
+# files every iteration, so these kernels are built with MFMA results in ordinary VGPRs.
+EXTRA_FLAGS = {"attention_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _hipcc() -> str:
@@ -26,7 +30,7 @@ def _hipcc() -> str:
 
 
 def _compile(src: str, obj: str) -> None:
-    cmd = [_hipcc(), *FLAGS, "-c", src, "-o", obj]
+    cmd = [_hipcc(), *FLAGS, *EXTRA_FLAGS.get(os.path.basename(src), []), "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

@@ -83,6 +83,8 @@ __device__ __forceinline__ bf16x8 own_row_frag(const bf16* row, bool ok, int lan
   if (ok) t.u = *reinterpret_cast<const uint4*>(row + ks * 16 + (lane >> 5) * 8);
   return t.v;
 }
+// 2^x by the hardware instruction (results below the normal range flush to zero, which softmax tolerates)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ bf16x8 pack8(const f32x16& a, int first) {
   bf16x8 r;
 #pragma unroll
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
   const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);
   const bool qok = q < S;
   const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
-  const float scale = 0.125f;  // 1/sqrt(64)
+  const float c = 0.125f * 1.44269504088896f;  // 1/sqrt(64) * log2(e): scores are handled in the log2 domain
   bf16x8 qf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) qf[ks] = own_row_frag(base + (int64_t)q * 3 * D, qok, lane, ks);
@@ -144,28 +146,33 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
     for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, lane, ks), qf[ks], s, 0, 0, 0);
-    float mx = -INFINITY;
+    if (kt == ntile - 1 && (S & 31)) {  // keys past the end exist only in the last tile
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] * scale : -INFINITY;
-      mx = fmaxf(mx, s[v]);
+      for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m, mx);
-    const float alpha = __expf(m - m_new);
+    float mx = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
+    // softmax is invariant under the shift m, so the reference maximum only has to keep exp2 in range: it is
+    // moved (and the running sums rescaled) only when a row's maximum has grown by more than 2^8
+    if (__any(mx > m + 8.f)) {
+      const float m_new = mx > m + 8.f ? mx : m;
+      const float alpha = fast_exp2(m - m_new);
+      lsum *= alpha;
+      m = m_new;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+    }
     float rs = 0.f;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      s[v] = __expf(s[v] - m_new);
+      s[v] = fast_exp2(fmaf(s[v], c, -m));
       rs += s[v];
     }
-    rs += __shfl_xor(rs, 32, 64);
-    lsum = lsum * alpha + rs;
-    m = m_new;
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+    lsum += rs + __shfl_xor(rs, 32, 64);
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2) {
       const bf16x8 pb = pack8(s, 8 * ks2);
@@ -176,7 +183,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(const bf16* __restri
   }
   if (qok) {
     store_owned_row(ctx + ((int64_t)b * S + q) * D + h * DH, o, 1.0f / lsum, half);
-    if (lse && half == 0) lse[((int64_t)b * H + h) * S + q] = m + __logf(lsum);
+    if (lse && half == 0) lse[((int64_t)b * H + h) * S + q] = (m + __log2f(lsum)) * 0.693147180559945f;
   }
 }
 
@@ -196,7 +203,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
   const int q = blockIdx.x * 128 + wave * 32 + (lane & 31);
   const bool qok = q < S;
   const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
-  const float scale = 0.125f;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
   bf16x8 qf[4], dof[4];
   float part = 0.f;
 #pragma unroll
@@ -208,7 +215,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
     for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
   }
   const float dl = part + __shfl_xor(part, 32, 64);
-  const float lq = qok ? lse[((int64_t)b * H + h) * S + q] : 0.f;
+  // rows past the end keep finite values (their dQ is never stored)
+  const float lq2 = (qok ? lse[((int64_t)b * H + h) * S + q] : 0.f) * 1.44269504088896f;
   if (qok && half == 0) delta[((int64_t)b * H + h) * S + q] = dl;
   f32x16 dq[2];
 #pragma unroll
@@ -234,10 +242,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(const bf16* __res
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Ks, lane, ks), qf[ks], s, 0, 0, 0);
       dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(Vs, lane, ks), dof[ks], dp, 0, 0, 0);
     }
+    if (kt == ntile - 1 && (S & 31)) {  // keys past the end: probability 0
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
+    }
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const bool ok = qok && (kt * 32 + acc_row(v, half) < S);
-      const float p = ok ? __expf(s[v] * scale - lq) : 0.f;
+      const float p = fast_exp2(fmaf(s[v], c, -lq2));
       s[v] = p * (dp[v] - dl);  // dS^T
     }
 #pragma unroll
@@ -263,7 +274,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   __shared__ __attribute__((aligned(16))) bf16 dOs[32 * LDR];
   __shared__ __attribute__((aligned(16))) bf16 Qt[64 * LDT];
   __shared__ __attribute__((aligned(16))) bf16 dOt[64 * LDT];
-  __shared__ float ls[32], dls[32];
+  __shared__ __attribute__((aligned(16))) float ls[32], dls[32];  // row log-sum-exp (log2 domain) and delta of the tile
   const int D = H * DH;
   const int b = blockIdx.z, h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -271,7 +282,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   const bool kok = key < S;
   const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
   const bf16* dobase = dctx + (int64_t)b * S * D + h * DH;
-  const float scale = 0.125f;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
   bf16x8 kf[4], vf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
@@ -285,9 +296,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
   const int ntile = (S + 31) / 32;
   TileRegs rq = tile_gload(base, 3 * D, 0, S, tid), rdo = tile_gload(dobase, D, 0, S, tid);
-  float nls = 0.f, ndl = 0.f;
+  // a query row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
+  float nls = INFINITY, ndl = 0.f;
   if (tid < 32 && tid < S) {
-    nls = lse[((int64_t)b * H + h) * S + tid];
+    nls = lse[((int64_t)b * H + h) * S + tid] * 1.44269504088896f;
     ndl = delta[((int64_t)b * H + h) * S + tid];
   }
   for (int qt = 0; qt < ntile; ++qt) {
@@ -301,7 +313,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
       rdo = tile_gload(dobase, D, (qt + 1) * 32, S, tid);
       if (tid < 32) {
         const int qq = (qt + 1) * 32 + tid;
-        nls = qq < S ? lse[((int64_t)b * H + h) * S + qq] : 0.f;
+        nls = qq < S ? lse[((int64_t)b * H + h) * S + qq] * 1.44269504088896f : INFINITY;
         ndl = qq < S ? delta[((int64_t)b * H + h) * S + qq] : 0.f;
       }
     }
@@ -315,12 +327,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
     }
     f32x16 pr;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int qi = acc_row(v, half);
-      const bool ok = kok && (qt * 32 + qi < S);
-      const float p = ok ? __expf(s[v] * scale - ls[qi]) : 0.f;
-      pr[v] = p;
-      s[v] = p * (dp[v] - dls[qi]);  // dS
+    for (int g4 = 0; g4 < 4; ++g4) {  // accumulator registers 4g..4g+3 are tile rows 8g + 4*half + 0..3
+      const float4 l4 = *reinterpret_cast<const float4*>(ls + 8 * g4 + 4 * half);
+      const float4 d4 = *reinterpret_cast<const float4*>(dls + 8 * g4 + 4 * half);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int v = 4 * g4 + e;
+        const float p = fast_exp2(fmaf(s[v], c, -lv[e]));
+        pr[v] = p;
+        s[v] = p * (dp[v] - dv4[e]);  // dS
+      }
     }
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2) {
