@@ -57,6 +57,10 @@ typedef enum {
 enum { PT_VIT_PRELN = 0, PT_BERT_POSTLN = 1 };   /* App. A.1: where LayerNorm sits */
 enum { PT_F32 = 0, PT_BF16 = 1 };
 enum { PT_SGDM = 0, PT_ADAMW = 1 };
+/* Task head.  DEFAULT: ViT = final LayerNorm + CLS token + linear classifier (image classification,
+ * Sec. 4.1); BERT = per-token start / end logits (span QA, Sec. 4.1).  CLS (BERT only): the first
+ * token's final activation -> linear classifier over n_out classes (sequence classification). */
+enum { PT_HEAD_DEFAULT = 0, PT_HEAD_CLS = 1 };
 
 typedef struct {
   int32_t arch;        /* PT_VIT_PRELN | PT_BERT_POSTLN                              */
@@ -64,11 +68,13 @@ typedef struct {
   int32_t L, D, H, F;  /* blocks, hidden, heads, MLP width; D % H == 0, D/H % 8 == 0 and <= 128, D <= 2048, F % 4 == 0 */
   int32_t S;           /* sequence length (ViT: (img/patch)^2 + 1)                   */
   int32_t B;           /* largest batch any call will pass                           */
-  int32_t n_out;       /* classes (ViT) or 2 (BERT span QA)                          */
+  int32_t n_out;       /* classes (ViT, BERT with PT_HEAD_CLS) or 2 (BERT span QA)   */
   int32_t img, patch, chans;  /* ViT front end                                       */
   int32_t vocab, max_pos;     /* BERT front end, max_pos >= S                        */
   float ln_eps;
   int32_t optimizer;   /* PT_SGDM | PT_ADAMW                                         */
+  int32_t head;        /* PT_HEAD_DEFAULT | PT_HEAD_CLS                              */
+  int32_t grad_accum;  /* 1: the state arena also holds a gradient accumulator, see pt_accumulate_grads */
   int64_t cache_slots; /* 0 = no cache; slot i belongs to sample id i                */
 } pt_config;
 
@@ -78,7 +84,7 @@ typedef struct {
 
 /* Bytes of the four caller-owned DEVICE arenas for this configuration:
  * params (fp32 masters + bf16 shadows), state (fp32 gradients + optimizer
- * moments), work (activations, saved tensors, scratch), cache (cache_slots rows
+ * moments, + one gradient accumulator when grad_accum is set), work (activations, saved tensors, scratch), cache (cache_slots rows
  * of S*D activations).  Each must be 256-byte aligned.  PT_EINVAL on a bad
  * configuration. */
 pt_status pt_query_arena_bytes(const pt_config* cfg /*HOST*/, size_t* params, size_t* state,
@@ -121,7 +127,8 @@ pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const 
  * to block k (and the front end iff k == 0), for the batch of the preceding
  * pt_frozen_forward.
  *  d_hk      DEVICE [nb,S,D] boundary activation (normally *d_hk_out); read only.
- *  d_labels  DEVICE int32: ViT [nb] class ids; BERT [nb,2] (start,end) positions.
+ *  d_labels  DEVICE int32: ViT and BERT with PT_HEAD_CLS [nb] class ids; BERT span QA [nb,2]
+ *             (start,end) positions.
  *  loss_out  HOST out, mean loss over the batch; the call synchronises.  May be
  *            NULL: then nothing synchronises and pt_last_loss fetches it later.
  * Gradients of all active tensors are overwritten (not accumulated). */
@@ -133,6 +140,21 @@ pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
  * norms_out HOST, L+2 floats: [front end, block 0 .. block L-1, head]; frozen
  * layers (and the front end when k >= 1) read exactly 0.  Synchronises. */
 pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
+
+/* Micro-batch gradient accumulation (Sec. 2.1 pipeline parallelism and Sec. 3.2.3:
+ * a mini-batch is processed as M micro-batches whose gradients are combined
+ * before the single optimizer step).  For configurations with grad_accum = 1:
+ * after each micro-batch's pt_active_fwd_bwd, pt_accumulate_grads adds
+ * nb * gradient (nb = that micro-batch's size; first != 0 starts a new sum) and
+ * nb * loss into the accumulator and readies the context for the next
+ * micro-batch; pt_finish_accumulation then leaves the sample-weighted mean
+ * gradient (= the gradient of the mean loss over all accumulated samples) where
+ * pt_layer_grad_norms and pt_optimizer_step read it, and returns the mean loss
+ * (mean_loss_out HOST, may be NULL; a non-NULL pointer synchronises).  Only the
+ * active tensors are touched.  PT_ESTATE if called out of order, if grad_accum
+ * is 0, or if the boundary is moved while a sum is in progress. */
+pt_status pt_accumulate_grads(pt_ctx* ctx, int32_t first);
+pt_status pt_finish_accumulation(pt_ctx* ctx, float* mean_loss_out);
 
 /* One optimizer step over the active tensors only; frozen bytes are untouched.
  * SGD-momentum: v <- mu v + g (+ wd w on decayed tensors), w <- w - lr v.

@@ -64,6 +64,7 @@ class Config:
     vocab: int = 0       # BERT: vocabulary size
     max_pos: int = 0     # BERT: rows of the learned position table (>= S)
     ln_eps: float = 1e-6
+    head: str = "default"  # "default": ViT classifier / BERT span QA; "cls": BERT sequence classification
 
 
 BLOCK_TENSORS = ("ln1_g", "ln1_b", "Wqkv", "bqkv", "Wo", "bo",
@@ -327,6 +328,7 @@ def front_backward(cfg, p, dx, saved, grads):
 # --------------------------------------------------------------------------
 def head_loss_forward(cfg, p, xL, labels):
     """ViT: final LN, CLS token, linear classifier, mean cross-entropy.
+    BERT sequence classification (head "cls"): first token, linear classifier, mean cross-entropy.
     BERT span QA: per-token two-logit linear map; cross-entropy over the
     sequence axis for the start logit and for the end logit; their mean."""
     B = xL.shape[0]
@@ -338,6 +340,14 @@ def head_loss_forward(cfg, p, xL, labels):
         lse = np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1)) + z.max(-1)
         loss = (lse - z[np.arange(B), labels]).mean()
         return loss, z, (c, s, prob, labels)
+    if cfg.head == "cls":
+        # sequence classification: first token's final activation -> linear classifier -> mean CE
+        c = xL[:, 0, :]
+        z = c @ p["head.W"] + p["head.b"]                       # [B, C]
+        prob = softmax_lastaxis(z)
+        lse = np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1)) + z.max(-1)
+        loss = (lse - z[np.arange(B), labels]).mean()
+        return loss, z, (c, prob, labels)
     z = xL @ p["head.W"] + p["head.b"]                          # [B, S, 2]
     zt = z.transpose(0, 2, 1)                                   # [B, 2, S]
     prob = softmax_lastaxis(zt)
@@ -361,6 +371,16 @@ def head_loss_backward(cfg, p, saved, xL_shape, grads):
         dcls, grads["head.ln_g"], grads["head.ln_b"] = layer_norm_bwd(dc, s, p["head.ln_g"])
         dx = np.zeros(xL_shape, dtype=dcls.dtype)
         dx[:, 0, :] = dcls
+        return dx
+    if cfg.head == "cls":
+        c, prob, labels = saved
+        dz = prob.copy()
+        dz[np.arange(B), labels] -= 1.0
+        dz /= B
+        grads["head.W"] = c.T @ dz
+        grads["head.b"] = dz.sum(axis=0)
+        dx = np.zeros(xL_shape, dtype=dz.dtype)
+        dx[:, 0, :] = dz @ p["head.W"].T
         return dx
     xL, prob, labels = saved
     dzt = prob.copy()                                           # [B, 2, S]
@@ -408,6 +428,28 @@ def active_fwd_bwd(cfg, p, h_k, labels, k, front_saved=None):
         assert front_saved is not None
         front_backward(cfg, p, dh, front_saved, grads)
     return loss, grads, {"logits": z, "h_L": h, "dh_k": dh}
+
+
+def accumulated_fwd_bwd(cfg, p, inputs, labels, k, sizes):
+    """Micro-batch accumulation (Sec. 2.1, Sec. 3.2.3): the mini-batch is cut into micro-batches of
+    the given sizes; each runs frozen forward + active forward/backward on its own, and the step's
+    loss and gradient are the sample-weighted means  sum_i n_i * (.)_i / sum_i n_i.
+    Returns (loss, grads)."""
+    assert sum(sizes) == len(inputs)
+    loss, grads, at = 0.0, None, 0
+    for n in sizes:
+        x, y = inputs[at:at + n], labels[at:at + n]
+        at += n
+        hk, fs = frozen_forward(cfg, p, x, k)
+        li, gi, _ = active_fwd_bwd(cfg, p, hk, y, k, fs)
+        loss += n * li
+        if grads is None:
+            grads = {name: n * g for name, g in gi.items()}
+        else:
+            for name, g in gi.items():
+                grads[name] = grads[name] + n * g
+    tot = float(sum(sizes))
+    return loss / tot, {name: g / tot for name, g in grads.items()}
 
 
 def layer_grad_norms(cfg, grads, k):

@@ -18,6 +18,7 @@ PT_OK, PT_EINVAL, PT_ESTATE, PT_ENOMEM, PT_EDEVICE, PT_ECACHE_MISS = range(6)
 PT_VIT_PRELN, PT_BERT_POSTLN = 0, 1
 PT_F32, PT_BF16 = 0, 1
 PT_SGDM, PT_ADAMW = 0, 1
+PT_HEAD_DEFAULT, PT_HEAD_CLS = 0, 1
 KIND_PARAM, KIND_GRAD, KIND_MOMENT1, KIND_MOMENT2, KIND_SHADOW = range(5)
 ACT_HK, ACT_HL, ACT_LOGITS, ACT_DHK = range(4)
 PROF_CATEGORIES = ("gemm_generic", "gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd",
@@ -29,7 +30,8 @@ class PtConfig(C.Structure):
     _fields_ = [("arch", C.c_int32), ("dtype", C.c_int32), ("L", C.c_int32), ("D", C.c_int32), ("H", C.c_int32),
                 ("F", C.c_int32), ("S", C.c_int32), ("B", C.c_int32), ("n_out", C.c_int32), ("img", C.c_int32),
                 ("patch", C.c_int32), ("chans", C.c_int32), ("vocab", C.c_int32), ("max_pos", C.c_int32),
-                ("ln_eps", C.c_float), ("optimizer", C.c_int32), ("cache_slots", C.c_int64)]
+                ("ln_eps", C.c_float), ("optimizer", C.c_int32), ("head", C.c_int32), ("grad_accum", C.c_int32),
+                ("cache_slots", C.c_int64)]
 
 
 class PtOptHparams(C.Structure):
@@ -67,6 +69,8 @@ def load_library():
         "pt_last_loss": [vp, P(C.c_float)],
         "pt_layer_grad_norms": [vp, P(C.c_float)],
         "pt_optimizer_step": [vp, P(PtOptHparams)],
+        "pt_accumulate_grads": [vp, i32],
+        "pt_finish_accumulation": [vp, P(C.c_float)],
         "pt_next_boundary": [P(C.c_float), i32, i32, C.c_float, P(i32)],
         "pt_num_tensors": [vp, P(i32)],
         "pt_tensor_info": [vp, i32, C.c_char_p, sz, P(i64), P(i32), P(i32), P(i32), P(i32)],
@@ -91,14 +95,16 @@ def load_library():
     return lib
 
 
-def make_config(w: dict, B: int | None = None, cache_slots: int = 0) -> PtConfig:
+def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum: bool = False) -> PtConfig:
     """pt_config from a workload dict (see synth.WORKLOADS)."""
     return PtConfig(
         arch=PT_VIT_PRELN if w["arch"] == "vit" else PT_BERT_POSTLN,
         dtype=PT_BF16 if w["dtype"] == "bf16" else PT_F32,
         L=w["L"], D=w["D"], H=w["H"], F=w["F"], S=w["S"], B=w["B"] if B is None else B, n_out=w["n_out"],
         img=w["img"], patch=w["patch"], chans=w["chans"], vocab=w["vocab"], max_pos=w["max_pos"],
-        ln_eps=w["ln_eps"], optimizer=PT_ADAMW if w["optimizer"] == "adamw" else PT_SGDM, cache_slots=cache_slots)
+        ln_eps=w["ln_eps"], optimizer=PT_ADAMW if w["optimizer"] == "adamw" else PT_SGDM,
+        head=PT_HEAD_CLS if w.get("head", "default") == "cls" else PT_HEAD_DEFAULT, grad_accum=1 if grad_accum else 0,
+        cache_slots=cache_slots)
 
 
 def query_arena_bytes(cfg: PtConfig):
@@ -195,6 +201,14 @@ class Context:
         out = np.zeros(self.cfg.L + 2, dtype=np.float32)
         self._chk(self.lib.pt_layer_grad_norms(self.h, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    def accumulate_grads(self, first: bool):
+        self._chk(self.lib.pt_accumulate_grads(self.h, 1 if first else 0))
+
+    def finish_accumulation(self, want_loss: bool = True):
+        out = C.c_float()
+        self._chk(self.lib.pt_finish_accumulation(self.h, C.byref(out) if want_loss else None))
+        return out.value if want_loss else None
 
     def optimizer_step(self, lr, momentum=0.9, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0):
         hp = PtOptHparams(lr, momentum, beta1, beta2, eps, weight_decay)

@@ -112,6 +112,10 @@ void bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st);
 // ---- gradient norms and optimizers over the padded, contiguous tensor arenas.
 // Arenas are cut into chunks of kChunk floats; chunk c belongs to group chunk_group[c].
 constexpr int kChunk = 1024;
+void grad_accumulate_chunks(float* acc, const float* g, int64_t first_chunk, int64_t n_chunks, float weight, bool first,
+                            const float* loss, float* loss_acc, hipStream_t st);
+void grad_average_chunks(float* g, const float* acc, int64_t first_chunk, int64_t n_chunks, float inv, float* loss,
+                         const float* loss_acc, hipStream_t st);
 void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t n_chunks, hipStream_t st);
 // norms[grp] = sqrt(sum of chunk_sq over the chunk range of grp) for active groups, 0 otherwise
 void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk /*[G+1] device*/, int G, int first_active,

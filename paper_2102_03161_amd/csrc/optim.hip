@@ -122,4 +122,40 @@ void sgdm_chunks(float* w, const float* g, float* m, void* shadow, const uint8_t
                      first_chunk, a);
 }
 
+// acc = (first ? 0 : acc) + weight * g over whole chunks; lane 0 of workgroup 0 folds the loss the same way
+__global__ __launch_bounds__(256) void grad_accumulate_kernel(float* __restrict__ acc, const float* __restrict__ g,
+                                                              int64_t first_chunk, float weight, int first,
+                                                              const float* __restrict__ loss, float* __restrict__ loss_acc) {
+  const int64_t i = (first_chunk + blockIdx.x) * kChunk + 4 * threadIdx.x;
+  const float4 gv = *reinterpret_cast<const float4*>(g + i);
+  float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (!first) av = *reinterpret_cast<const float4*>(acc + i);
+  av.x += weight * gv.x; av.y += weight * gv.y; av.z += weight * gv.z; av.w += weight * gv.w;
+  *reinterpret_cast<float4*>(acc + i) = av;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *loss_acc = (first ? 0.f : *loss_acc) + weight * *loss;
+}
+void grad_accumulate_chunks(float* acc, const float* g, int64_t first_chunk, int64_t n_chunks, float weight, bool first,
+                            const float* loss, float* loss_acc, hipStream_t st) {
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(grad_accumulate_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, acc, g, first_chunk, weight,
+                     first ? 1 : 0, loss, loss_acc);
+}
+
+// g = acc * inv over whole chunks; loss = loss_acc * inv
+__global__ __launch_bounds__(256) void grad_average_kernel(float* __restrict__ g, const float* __restrict__ acc,
+                                                           int64_t first_chunk, float inv, float* __restrict__ loss,
+                                                           const float* __restrict__ loss_acc) {
+  const int64_t i = (first_chunk + blockIdx.x) * kChunk + 4 * threadIdx.x;
+  float4 av = *reinterpret_cast<const float4*>(acc + i);
+  av.x *= inv; av.y *= inv; av.z *= inv; av.w *= inv;
+  *reinterpret_cast<float4*>(g + i) = av;
+  if (blockIdx.x == 0 && threadIdx.x == 0) *loss = *loss_acc * inv;
+}
+void grad_average_chunks(float* g, const float* acc, int64_t first_chunk, int64_t n_chunks, float inv, float* loss,
+                         const float* loss_acc, hipStream_t st) {
+  if (n_chunks <= 0) return;
+  hipLaunchKernelGGL(grad_average_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, g, acc, first_chunk, inv, loss,
+                     loss_acc);
+}
+
 }  // namespace pt

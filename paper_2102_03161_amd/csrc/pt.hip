@@ -54,7 +54,7 @@ struct Plan {
   size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
-  size_t LOSS, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
+  size_t LOSS, LOSSACC, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
   size_t idx_capacity = 0, stage_floats = 0, gemmws_floats = 0;
 };
 
@@ -63,6 +63,7 @@ bool validate(const pt_config& c, std::string* why) {
   if (c.arch != PT_VIT_PRELN && c.arch != PT_BERT_POSTLN) return bad("arch");
   if (c.dtype != PT_F32 && c.dtype != PT_BF16) return bad("dtype");
   if (c.optimizer != PT_SGDM && c.optimizer != PT_ADAMW) return bad("optimizer");
+  if (c.head != PT_HEAD_DEFAULT && c.head != PT_HEAD_CLS) return bad("head");
   if (c.L < 1 || c.L > 512 || c.D < 8 || c.H < 1 || c.F < 4 || c.S < 1 || c.B < 1 || c.n_out < 1) return bad("sizes");
   if (c.D % c.H) return bad("D % H");
   const int dh = c.D / c.H;
@@ -74,7 +75,7 @@ bool validate(const pt_config& c, std::string* why) {
     if (g * g + 1 != c.S) return bad("S must be (img/patch)^2 + 1");
   } else {
     if (c.vocab < 1 || c.max_pos < c.S) return bad("vocab / max_pos");
-    if (c.n_out != 2) return bad("BERT span-QA head has n_out = 2");
+    if (c.head == PT_HEAD_DEFAULT && c.n_out != 2) return bad("BERT span-QA head has n_out = 2");
   }
   if (c.cache_slots < 0) return bad("cache_slots");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps");
@@ -123,7 +124,7 @@ void make_plan(const pt_config& c, Plan* p) {
 
   const size_t P = (size_t)p->arena_floats;
   p->params_bytes = align_up(P * 4) + (c.dtype == PT_BF16 ? align_up(P * 2) : 0);
-  p->state_bytes = align_up(P * 4) * (c.optimizer == PT_ADAMW ? 3 : 2);
+  p->state_bytes = align_up(P * 4) * ((c.optimizer == PT_ADAMW ? 3 : 2) + (c.grad_accum ? 1 : 0));
   p->cache_bytes = (size_t)c.cache_slots * S * D * e;
 
   size_t off = 0;
@@ -158,10 +159,12 @@ void make_plan(const pt_config& c, Plan* p) {
     p->PATCH = 0;
     p->EMB = take(TD4); p->DEMB = take(TD4); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take((T + 4) * 8);
     p->CFEAT = p->MUF = p->RSF = p->DC = 0;
-    p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4);
+    if (c.head == PT_HEAD_CLS) { p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); }
+    else { p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4); }
   }
   p->LOSSROWS = take((size_t)B * 4);
   p->LOSS = take(4);
+  p->LOSSACC = take(4);
   p->NORMS = take((size_t)(L + 2) * 4);
   p->LNPART = take(ln_partial_floats(D) * 4);
   // scratch of the weight-gradient products: split-K slabs (up to 16 splits, about 768 workgroups in
@@ -206,6 +209,8 @@ struct pt_ctx {
   float* grads = nullptr;
   float* mom1 = nullptr;
   float* mom2 = nullptr;
+  float* gacc = nullptr;      // gradient accumulator over micro-batches (grad_accum configurations)
+  int64_t acc_samples = 0;    // samples accumulated so far; 0 = no accumulation in progress
   char* work = nullptr;
   char* cache = nullptr;
   int k = 0;
@@ -515,6 +520,9 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
   c->grads = reinterpret_cast<float*>(d_state);
   c->mom1 = reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + align_up(P * 4));
   c->mom2 = cfg->optimizer == PT_ADAMW ? reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + 2 * align_up(P * 4)) : nullptr;
+  c->gacc = cfg->grad_accum ? reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) +
+                                                       (cfg->optimizer == PT_ADAMW ? 3 : 2) * align_up(P * 4))
+                            : nullptr;
   c->work = reinterpret_cast<char*>(d_work);
   c->cache = reinterpret_cast<char*>(d_cache);
   c->slot_k.assign((size_t)cfg->cache_slots, -1);
@@ -575,6 +583,7 @@ pt_status pt_set_freeze_boundary(pt_ctx* c, int32_t k) {
   if (k < 0 || k > c->cfg.L) return fail(c, PT_EINVAL, "boundary outside 0..L");
   if (k < c->k) return fail(c, PT_EINVAL, "the boundary never moves down");
   if (k == c->k) return PT_OK;
+  if (c->acc_samples) return fail(c, PT_ESTATE, "the boundary cannot move while gradients are being accumulated");
   // newly frozen: front end (if the old boundary was 0) and blocks k_old..k-1
   const auto& gf = c->plan.group_first_chunk;
   const int64_t lo = (c->k == 0 ? gf[0] : gf[c->k + 1]) * kChunk, hi = gf[k + 1] * kChunk;
@@ -730,6 +739,28 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
                   dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
                   c->wf(p.LNPART), nb, D, st); }
+  } else if (g.head == PT_HEAD_CLS) {
+    // sequence classification: the first token's final activation -> linear classifier -> cross-entropy
+    const int C = g.n_out;
+    const int hW = c->head(0), hbias = c->head(1);
+    const int64_t SD = (int64_t)S * D;
+    Gemm m;
+    m.A = x; m.lda = SD; m.B = c->cp(hW); m.ldb = C; m.C = c->w(p.LOGITS); m.ldc = C;
+    m.M = nb; m.N = C; m.K = D; m.epi = EPI_BIAS; m.bias = c->cp(hbias); m.c_f32 = true;
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
+    ce_rows(dt, c->wf(p.LOGITS), d_labels, c->wf(p.LOSSROWS), c->w(p.DZ), nb, C, st);
+    mean_reduce(c->wf(p.LOSSROWS), nb, c->wf(p.LOSS), st);
+    Gemm wg;
+    wg.A = x; wg.lda = SD; wg.ta = true; wg.B = c->w(p.DZ); wg.ldb = C; wg.C = c->gp(hW); wg.ldc = C;
+    wg.M = D; wg.N = C; wg.K = nb; wg.c_f32 = true;
+    wg.ws = c->wf(p.GEMMWS); wg.ws_floats = p.gemmws_floats; wg.colsum_out = c->gp(hbias);
+    { ProfScope ps_(c, gemm_cat(dt, wg), 2.0 * wg.M * wg.N * wg.K); gemm(dt, wg, st); }
+    // dL/dx_L is zero except in the first token's rows, which the input-gradient product writes in place
+    fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
+    Gemm dg;
+    dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = dcur.s; dg.ldc = SD;
+    dg.M = nb; dg.N = D; dg.K = C; dg.c_f32 = true;
+    { ProfScope ps_(c, gemm_cat(dt, dg), 2.0 * dg.M * dg.N * dg.K); gemm(dt, dg, st); }
   } else {
     const int hW = c->head(0), hbias = c->head(1);
     qa_logits(dt, x, c->cp(hW), c->cp(hbias), c->wf(p.LOGITS), nb * S, D, st);
@@ -796,6 +827,40 @@ pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {
   c->step = t;
   c->phase = 0;
   if (c->prof_on) prof_collect(c);
+  return PT_OK;
+}
+
+pt_status pt_accumulate_grads(pt_ctx* c, int32_t first) {
+  if (!c) return PT_EINVAL;
+  if (!c->gacc) return fail(c, PT_ESTATE, "the configuration has grad_accum = 0");
+  if (c->phase != 2) return fail(c, PT_ESTATE, "accumulation needs a completed pt_active_fwd_bwd");
+  if (!first && c->acc_samples == 0) return fail(c, PT_ESTATE, "no accumulation in progress: pass first = 1");
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t lo = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  { ProfScope ps_(c, PT_PROF_OPT, 12.0 * (total - lo) * kChunk);
+    grad_accumulate_chunks(c->gacc, c->grads, lo, total - lo, (float)c->nb, first != 0, c->wf(c->plan.LOSS),
+                           c->wf(c->plan.LOSSACC), c->st); }
+  HIP_TRY(c, hipGetLastError());
+  c->acc_samples = (first ? 0 : c->acc_samples) + c->nb;
+  c->phase = 0;
+  return PT_OK;
+}
+
+pt_status pt_finish_accumulation(pt_ctx* c, float* mean_loss_out) {
+  if (!c) return PT_EINVAL;
+  if (!c->gacc || c->acc_samples == 0) return fail(c, PT_ESTATE, "no accumulation in progress");
+  if (c->phase != 0) return fail(c, PT_ESTATE, "a micro-batch is in flight: accumulate it first");
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t lo = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  { ProfScope ps_(c, PT_PROF_OPT, 8.0 * (total - lo) * kChunk);
+    grad_average_chunks(c->grads, c->gacc, lo, total - lo, 1.0f / (float)c->acc_samples, c->wf(c->plan.LOSS),
+                        c->wf(c->plan.LOSSACC), c->st); }
+  HIP_TRY(c, hipGetLastError());
+  c->acc_samples = 0;
+  c->phase = 2;
+  if (mean_loss_out) return pt_last_loss(c, mean_loss_out);
   return PT_OK;
 }
 
@@ -889,7 +954,7 @@ pt_status pt_read_activation(pt_ctx* c, int32_t which, float* dst, size_t numel)
     case PT_ACT_HK: if (c->phase < 1) return fail(c, PT_ESTATE, "no boundary activation yet"); src = c->last_hk; n = act; break;
     case PT_ACT_HL: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->k == g.L ? c->last_hk : c->w(c->plan.X[g.L]); n = act; break;
     case PT_ACT_LOGITS: if (c->phase < 2) return fail(c, PT_ESTATE, "no forward pass yet"); src = c->w(c->plan.LOGITS);
-      n = g.arch == PT_VIT_PRELN ? (size_t)c->nb * g.n_out : (size_t)c->nb * g.S * 2; is_f32 = true; break;
+      n = (g.arch == PT_VIT_PRELN || g.head == PT_HEAD_CLS) ? (size_t)c->nb * g.n_out : (size_t)c->nb * g.S * 2; is_f32 = true; break;
     case PT_ACT_DHK: if (c->phase < 2) return fail(c, PT_ESTATE, "no backward pass yet"); src = c->last_dhk; n = act; is_f32 = true; break;
     default: return fail(c, PT_EINVAL, "unknown activation");
   }

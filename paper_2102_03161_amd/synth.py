@@ -32,6 +32,14 @@ WORKLOADS = {
     # BERT-base span QA: 12 post-LN blocks, S = 384
     "bert_base_qa": dict(arch="bert", L=12, D=768, H=12, F=3072, S=384, n_out=2, img=0, patch=0, chans=0,
                          vocab=30522, max_pos=512, ln_eps=1e-12, B=32, dtype="bf16", optimizer="adamw"),
+    # BERT-large span QA (the paper's SQuAD model, App. A.1 / Sec. 4.1): 24 post-LN blocks, S = 512
+    "bert_large_qa": dict(arch="bert", L=24, D=1024, H=16, F=4096, S=512, n_out=2, img=0, patch=0, chans=0,
+                          vocab=30522, max_pos=512, ln_eps=1e-12, B=64, dtype="bf16", optimizer="adamw"),
+    # BERT-base sequence classification (SST-2-shaped: 2 classes, S = 128)
+    "bert_base_cls": dict(arch="bert", L=12, D=768, H=12, F=3072, S=128, n_out=2, img=0, patch=0, chans=0,
+                          vocab=30522, max_pos=512, ln_eps=1e-12, B=64, dtype="bf16", optimizer="adamw", head="cls"),
+    "bert_tiny_cls": dict(arch="bert", L=2, D=64, H=4, F=256, S=24, n_out=3, img=0, patch=0, chans=0,
+                          vocab=97, max_pos=32, ln_eps=1e-12, B=4, dtype="f32", optimizer="adamw", head="cls"),
 }
 
 MODEL_KEYS = ("arch", "L", "D", "H", "F", "S", "n_out", "img", "patch", "chans", "vocab", "max_pos", "ln_eps")
@@ -44,7 +52,9 @@ def workload(name: str, **overrides) -> dict:
 
 
 def model_fields(w: dict) -> dict:
-    return {k: w[k] for k in MODEL_KEYS}
+    f = {k: w[k] for k in MODEL_KEYS}
+    f["head"] = w.get("head", "default")
+    return f
 
 
 def _rng(seed: int, name: str) -> np.random.Generator:
@@ -69,7 +79,8 @@ def gen_param(seed: int, name: str, shape) -> np.ndarray:
 def gen_inputs(w: dict, seed: int, B: int | None = None, tag: str = ""):
     """(inputs, labels) for one batch.  ViT: fp32 images [B,C,H,W] ~ N(0,1),
     labels int32 [B] uniform in [0, n_out).  BERT: int32 ids [B,S] uniform in
-    [0, vocab), labels int32 [B,2] (start, end) uniform in [0, S)."""
+    [0, vocab), labels int32 [B,2] (start, end) uniform in [0, S), or for the
+    classification head int32 [B] uniform in [0, n_out)."""
     B = w["B"] if B is None else B
     r = _rng(seed, "batch:" + tag)
     if w["arch"] == "vit":
@@ -77,7 +88,10 @@ def gen_inputs(w: dict, seed: int, B: int | None = None, tag: str = ""):
         y = r.integers(0, w["n_out"], size=(B,), dtype=np.int32)
     else:
         x = r.integers(0, w["vocab"], size=(B, w["S"]), dtype=np.int32)
-        y = r.integers(0, w["S"], size=(B, 2), dtype=np.int32)
+        if w.get("head", "default") == "cls":
+            y = r.integers(0, w["n_out"], size=(B,), dtype=np.int32)
+        else:
+            y = r.integers(0, w["S"], size=(B, 2), dtype=np.int32)
     return x, y
 
 

@@ -85,7 +85,7 @@ def gpu_step(torch, ctx, w, x, y, k, hp=HP, sample_ids=None):
     out = dict(loss=loss)
     out["hk"] = ctx.read_activation(binding.ACT_HK, (nb, S, D))
     out["hL"] = ctx.read_activation(binding.ACT_HL, (nb, S, D))
-    out["logits"] = ctx.read_activation(binding.ACT_LOGITS, (nb, w["n_out"]) if w["arch"] == "vit" else (nb, S, 2))
+    out["logits"] = ctx.read_activation(binding.ACT_LOGITS, (nb, w["n_out"]) if (w["arch"] == "vit" or w.get("head") == "cls") else (nb, S, 2))
     out["norms"] = ctx.layer_grad_norms()
     out["grads"] = gpu_read_all(ctx, binding.KIND_GRAD)
     ctx.optimizer_step(**hp)

@@ -34,3 +34,4 @@ SMALL_VIT = dict(arch="vit", L=3, D=16, H=2, F=40, S=5, n_out=3, img=4, patch=2,
                  vocab=0, max_pos=0, ln_eps=1e-6, B=3, dtype="f32", optimizer="sgdm")
 SMALL_BERT = dict(arch="bert", L=3, D=16, H=2, F=40, S=6, n_out=2, img=0, patch=0, chans=0,
                   vocab=11, max_pos=8, ln_eps=1e-12, B=3, dtype="f32", optimizer="adamw")
+SMALL_BERT_CLS = dict(SMALL_BERT, n_out=4, head="cls")

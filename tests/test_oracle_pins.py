@@ -10,9 +10,10 @@ import torch.nn.functional as tF
 
 from oracle import encoder as orc
 from paper_2102_03161_amd import synth
-from tests.helpers import SMALL_BERT, SMALL_VIT, oracle_cfg, oracle_params, rel_err
+from tests.helpers import SMALL_BERT, SMALL_BERT_CLS, SMALL_VIT, oracle_cfg, oracle_params, rel_err
 
-ARCHS = [SMALL_VIT, SMALL_BERT]
+ARCHS = [SMALL_VIT, SMALL_BERT, SMALL_BERT_CLS]
+ARCH_IDS = ["vit", "bert", "bert_cls"]
 
 
 def full_loss(cfg, p, x, y):
@@ -29,7 +30,7 @@ def batch(w, seed=7):
 
 
 # ---------------------------------------------------------------- finite differences
-@pytest.mark.parametrize("w", ARCHS, ids=["vit", "bert"])
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
 @pytest.mark.parametrize("k", [0, 1, 2])
 def test_backward_matches_central_differences(w, k):
     cfg, p = oracle_params(w, seed=11, scale=0.4)
@@ -110,6 +111,9 @@ def torch_model_loss(w, cfg, p, x, y):
         c = tF.layer_norm(h[:, 0], (D,), tp["head.ln_g"], tp["head.ln_b"], cfg.ln_eps)
         z = c @ tp["head.W"] + tp["head.b"]
         loss = tF.cross_entropy(z, torch.tensor(y, dtype=torch.long))
+    elif cfg.head == "cls":
+        z = h[:, 0] @ tp["head.W"] + tp["head.b"]
+        loss = tF.cross_entropy(z, torch.tensor(y, dtype=torch.long))
     else:
         z = h @ tp["head.W"] + tp["head.b"]
         yy = torch.tensor(y, dtype=torch.long)
@@ -118,8 +122,9 @@ def torch_model_loss(w, cfg, p, x, y):
     return float(loss.detach()), {n: t.grad.numpy() for n, t in tp.items()}, z.detach().numpy()
 
 
-@pytest.mark.parametrize("w", ARCHS + [synth.workload("vit_tiny"), synth.workload("bert_tiny")],
-                         ids=["vit_s", "bert_s", "vit_tiny", "bert_tiny"])
+@pytest.mark.parametrize("w", ARCHS + [synth.workload("vit_tiny"), synth.workload("bert_tiny"),
+                                       synth.workload("bert_tiny_cls")],
+                         ids=["vit_s", "bert_s", "bert_cls_s", "vit_tiny", "bert_tiny", "bert_tiny_cls"])
 def test_whole_step_matches_torch_modules(w):
     cfg, p = oracle_params(w, seed=5, scale=0.3)
     x, y = batch(w)
@@ -224,7 +229,7 @@ def test_sequence_length_one_reduces_to_value_path():
     assert np.allclose(a, ref, atol=1e-14)
 
 
-@pytest.mark.parametrize("w", ARCHS, ids=["vit", "bert"])
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
 def test_block_is_permutation_equivariant_over_tokens(w):
     cfg, p = oracle_params(w, seed=9, scale=0.5)
     rng = np.random.default_rng(6)
@@ -295,7 +300,7 @@ def test_zero_head_gives_log_of_class_count(w, ln_c):
     assert all(np.all(grads[n] == 0) for n in grads if n.startswith("blk"))
 
 
-@pytest.mark.parametrize("w", ARCHS, ids=["vit", "bert"])
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
 def test_boundary_at_L_is_softmax_regression(w):
     cfg, p = oracle_params(w, seed=3, scale=0.5)
     x, y = batch(w)
@@ -311,6 +316,11 @@ def test_boundary_at_L_is_softmax_regression(w):
         prob = sp_softmax(feats @ p["head.W"] + p["head.b"], axis=-1)
         onehot = np.eye(cfg.n_out)[y]
         assert np.allclose(grads["head.W"], feats.T @ (prob - onehot) / B, atol=1e-14)
+    elif cfg.head == "cls":
+        prob = sp_softmax(h[:, 0] @ p["head.W"] + p["head.b"], axis=-1)
+        onehot = np.eye(cfg.n_out)[y]
+        assert np.allclose(grads["head.W"], h[:, 0].T @ (prob - onehot) / B, atol=1e-14)
+        assert np.allclose(grads["head.b"], (prob - onehot).sum(0) / B, atol=1e-14)
     else:
         z = h @ p["head.W"] + p["head.b"]
         prob = sp_softmax(z, axis=1)
@@ -322,7 +332,7 @@ def test_boundary_at_L_is_softmax_regression(w):
 
 
 # ---------------------------------------------------------------- freeze semantics
-@pytest.mark.parametrize("w", ARCHS, ids=["vit", "bert"])
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
 def test_freezing_is_structural(w):
     cfg, p = oracle_params(w, seed=8, scale=0.3)
     x, y = batch(w)
@@ -352,6 +362,31 @@ def test_freezing_is_structural(w):
             else:
                 assert np.array_equal(q[n], p[n])
                 assert n not in st["m"] and n not in st["v"]
+
+
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
+@pytest.mark.parametrize("k", [0, 1])
+def test_micro_batch_accumulation_equals_the_full_batch(w, k):
+    """The loss is a mean over samples, so the sample-weighted mean of micro-batch gradients is the
+    full-batch gradient (pinned above by central differences), whatever the cut, ragged included."""
+    cfg, p = oracle_params(w, seed=5, scale=0.3)
+    x, y = batch(w)
+    B = x.shape[0]
+    hk, fs = orc.frozen_forward(cfg, p, x, k)
+    loss, grads, _ = orc.active_fwd_bwd(cfg, p, hk, y, k, fs)
+    for sizes in ([B], [1] * B, [B - 1, 1], [2, B - 2]):
+        la, ga = orc.accumulated_fwd_bwd(cfg, p, x, y, k, sizes)
+        assert abs(la - loss) < 1e-13 * abs(loss)
+        assert set(ga) == set(grads)
+        for n in grads:
+            assert np.allclose(ga[n], grads[n], rtol=0, atol=1e-13 * max(1.0, np.abs(grads[n]).max())), (n, sizes)
+    # a planted mistake would show: an unweighted mean of unequal micro-batches is a different vector
+    hk1, fs1 = orc.frozen_forward(cfg, p, x[:B - 1], k)
+    _, g1, _ = orc.active_fwd_bwd(cfg, p, hk1, y[:B - 1], k, fs1)
+    hk2, fs2 = orc.frozen_forward(cfg, p, x[B - 1:], k)
+    _, g2, _ = orc.active_fwd_bwd(cfg, p, hk2, y[B - 1:], k, fs2)
+    wrong = 0.5 * (g1["head.W"] + g2["head.W"])
+    assert np.abs(wrong - grads["head.W"]).max() > 1e-6 * np.abs(grads["head.W"]).max()
 
 
 def test_grad_norm_slots_add_up_to_global_norm():
@@ -440,7 +475,7 @@ def test_adamw_closed_forms_and_torch():
 
 
 # ---------------------------------------------------------------- cache
-@pytest.mark.parametrize("w", ARCHS, ids=["vit", "bert"])
+@pytest.mark.parametrize("w", ARCHS, ids=ARCH_IDS)
 def test_cache_hit_advance_and_permutation(w):
     cfg, p = oracle_params(w, seed=8, scale=0.3)
     x, y = batch(w)
