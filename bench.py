@@ -36,7 +36,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="vit_b16", help="vit_b16 | vit_b16_b128 | bert_base_qa")
+    ap.add_argument("--workload", default="vit_b16",
+                    help="vit_b16 | vit_b16_b128 | bert_base_qa | bert_large_qa | bert_base_cls")
+    ap.add_argument("--micro-batches", type=int, default=1,
+                    help="M > 1: a step is M micro-batches of the workload's batch accumulated into one optimizer step")
     ap.add_argument("--k", type=int, default=0, help="freeze boundary of the timed run")
     ap.add_argument("--no-sweep", action="store_true", help="skip the extra k = 6 / 9 measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
@@ -70,7 +73,8 @@ def main():
     w = synth.workload(a.workload)
     B = w["B"]
     n_ids = 4 * B
-    ctx = binding.Context(binding.make_config(w, cache_slots=n_ids))
+    M = a.micro_batches
+    ctx = binding.Context(binding.make_config(w, cache_slots=n_ids, grad_accum=M > 1))
     seed = 2
     for tid, name, shape, _, _ in ctx.tensors():
         ctx.write_tensor(tid, binding.KIND_PARAM, synth.round_bf16(synth.gen_param(seed, name, shape)))
@@ -81,9 +85,14 @@ def main():
     hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01)
 
     def step(i, use_cache=False):
-        x, y, ids = batches[i % len(batches)]
-        hk = ctx.frozen_forward(x, ids if use_cache else None)
-        ctx.active_fwd_bwd(hk, y, want_loss=False)
+        for j in range(M):
+            x, y, ids = batches[(i * M + j) % len(batches)]
+            hk = ctx.frozen_forward(x, ids if use_cache else None)
+            ctx.active_fwd_bwd(hk, y, want_loss=False)
+            if M > 1:
+                ctx.accumulate_grads(first=(j == 0))
+        if M > 1:
+            ctx.finish_accumulation(want_loss=False)
         norms = ctx.layer_grad_norms()        # synchronises: the freeze rule reads these on the host
         ctx.optimizer_step(**hp)
         return norms
@@ -108,16 +117,17 @@ def main():
     if a.k:
         ctx.set_freeze_boundary(a.k)
     sec = timed(a.warmup, a.steps)
-    sps = B / sec
-    fl = flops_per_sample(w, a.k, False) * B
+    sps = M * B / sec
+    fl = flops_per_sample(w, a.k, False) * B * M
     result = {
         "metric": "train samples/sec on 1 GPU vs frozen prefix k; % bf16 MFMA peak",
         "value": round(sps, 2), "unit": "samples/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{a.workload}: {w['arch']} L={w['L']} D={w['D']} H={w['H']} F={w['F']} S={w['S']} "
-                               f"micro-batch {B}, AdamW, freeze boundary k={a.k}, no cache",
-                   "global_batch": B, "seq_len": w["S"], "k": a.k},
+                               f"micro-batch {B}" + (f" x {M} accumulated" if M > 1 else "") +
+                               f", AdamW, freeze boundary k={a.k}, no cache",
+                   "global_batch": B * M, "seq_len": w["S"], "k": a.k},
         "step_tflops": round(fl / sec / 1e12, 2),
         "step_frac_of_bf16_peak": round(fl / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
     }
@@ -155,13 +165,13 @@ def main():
     # ---- samples/s versus k (the boundary only moves up): uncached and cached ----
     if not a.no_sweep and a.k == 0:
         sweep = {"k0": round(sps, 1)}
-        for k in (w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4):
+        for k in (1, w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4):
             ctx.set_freeze_boundary(k)
             s_unc = timed(2, 8, use_cache=False)
             step(0, True); step(1, True); step(2, True); step(3, True)     # fill / advance the cache rows
             s_hit = timed(2, 8, use_cache=True)
-            sweep[f"k{k}"] = round(B / s_unc, 1)
-            sweep[f"k{k}_cached"] = round(B / s_hit, 1)
+            sweep[f"k{k}"] = round(M * B / s_unc, 1)
+            sweep[f"k{k}_cached"] = round(M * B / s_hit, 1)
         result["samples_per_s_vs_k"] = sweep
     ctx.close()
 

@@ -76,6 +76,9 @@ typedef struct {
   int32_t head;        /* PT_HEAD_DEFAULT | PT_HEAD_CLS                              */
   int32_t grad_accum;  /* 1: the state arena also holds a gradient accumulator, see pt_accumulate_grads */
   int64_t cache_slots; /* 0 = no cache; slot i belongs to sample id i                */
+  int64_t host_slots;  /* rows of the host tier: sample ids cache_slots .. cache_slots+host_slots-1 (0 = none) */
+  int64_t window_slots;/* device rows the host tier is staged through, >= 2 B when host_slots > 0; they are
+                          the last rows of the cache arena                            */
 } pt_config;
 
 typedef struct {
@@ -111,7 +114,7 @@ pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
 
 /* F_frozen for one batch of nb <= B samples.
  *  d_input    DEVICE. ViT: fp32 images [nb,chans,img,img]; BERT: int32 ids [nb,S].
- *  sample_ids HOST, nb unique ids in [0,cache_slots), or NULL to bypass the
+ *  sample_ids HOST, nb unique ids in [0,cache_slots+host_slots), or NULL to bypass the
  *             cache.  Ignored when k == 0 (nothing is frozen, the front end is
  *             being trained).  Per sample: a row written at the current k is a
  *             hit (copied, no block runs); a row written at k' < k is advanced
@@ -195,6 +198,26 @@ pt_status pt_read_activation(pt_ctx* ctx, int32_t which, float* dst /*HOST*/, si
  * of per-sample decisions and of (sample, block) forward evaluations spent in
  * pt_frozen_forward. */
 pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k);
+
+/* Host tier of the cache (Sec. 3.4, App. E: when the cached activations do not
+ * fit the fast tier they live one level down and pass through a sliding window
+ * that is filled ahead of use and emptied as rows are consumed).  Here the fast
+ * tier is HBM (sample ids below cache_slots) and the lower tier is pinned HOST
+ * memory of host_slots rows (S*D elements of the activation type each), owned by
+ * the caller and attached once after pt_create.  Host rows travel on a copy
+ * stream of the library's own: pt_cache_prefetch stages the valid host rows of
+ * the given ids (typically the NEXT batch's) into free window slots while the
+ * current step computes (best effort: it stops when the window is full;
+ * staged_out HOST, may be NULL); pt_frozen_forward uses staged rows, stages the
+ * others on demand, writes new or advanced rows back to the host asynchronously
+ * and releases window slots as rows are consumed.  Decisions (hit / advance /
+ * miss) and the bytes of h_k do not depend on the tier.  pt_host_tier_stats:
+ * rows moved each way, rows staged by pt_cache_prefetch, and how many of those
+ * were then used. */
+pt_status pt_attach_host_tier(pt_ctx* ctx, void* h_rows /*pinned HOST*/, size_t bytes);
+pt_status pt_cache_prefetch(pt_ctx* ctx, const int64_t* sample_ids /*HOST*/, int32_t n, int32_t* staged_out);
+pt_status pt_host_tier_stats(const pt_ctx* ctx, int64_t* rows_to_device, int64_t* rows_to_host,
+                             int64_t* prefetched, int64_t* prefetched_used);
 pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, int64_t* misses,
                          int64_t* block_runs);
 

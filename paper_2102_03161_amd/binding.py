@@ -31,7 +31,7 @@ class PtConfig(C.Structure):
                 ("F", C.c_int32), ("S", C.c_int32), ("B", C.c_int32), ("n_out", C.c_int32), ("img", C.c_int32),
                 ("patch", C.c_int32), ("chans", C.c_int32), ("vocab", C.c_int32), ("max_pos", C.c_int32),
                 ("ln_eps", C.c_float), ("optimizer", C.c_int32), ("head", C.c_int32), ("grad_accum", C.c_int32),
-                ("cache_slots", C.c_int64)]
+                ("cache_slots", C.c_int64), ("host_slots", C.c_int64), ("window_slots", C.c_int64)]
 
 
 class PtOptHparams(C.Structure):
@@ -81,6 +81,9 @@ def load_library():
         "pt_read_activation": [vp, i32, P(C.c_float), sz],
         "pt_cache_row": [vp, i64, vp, sz, P(i32)],
         "pt_cache_stats": [vp, P(i64), P(i64), P(i64), P(i64)],
+        "pt_attach_host_tier": [vp, vp, sz],
+        "pt_cache_prefetch": [vp, P(i64), i32, P(i32)],
+        "pt_host_tier_stats": [vp, P(i64), P(i64), P(i64), P(i64)],
         "pt_profile_enable": [vp, i32],
         "pt_profile_reset": [vp],
         "pt_profile_read": [vp, i32, P(C.c_double), P(i64), P(C.c_double)],
@@ -95,7 +98,8 @@ def load_library():
     return lib
 
 
-def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum: bool = False) -> PtConfig:
+def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum: bool = False,
+                host_slots: int = 0, window_slots: int = 0) -> PtConfig:
     """pt_config from a workload dict (see synth.WORKLOADS)."""
     return PtConfig(
         arch=PT_VIT_PRELN if w["arch"] == "vit" else PT_BERT_POSTLN,
@@ -104,7 +108,7 @@ def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum:
         img=w["img"], patch=w["patch"], chans=w["chans"], vocab=w["vocab"], max_pos=w["max_pos"],
         ln_eps=w["ln_eps"], optimizer=PT_ADAMW if w["optimizer"] == "adamw" else PT_SGDM,
         head=PT_HEAD_CLS if w.get("head", "default") == "cls" else PT_HEAD_DEFAULT, grad_accum=1 if grad_accum else 0,
-        cache_slots=cache_slots)
+        cache_slots=cache_slots, host_slots=host_slots, window_slots=window_slots)
 
 
 def query_arena_bytes(cfg: PtConfig):
@@ -141,13 +145,19 @@ class Context:
             self.stream = torch.cuda.current_stream(self.device) if stream is None else stream
             h = C.c_void_p()
             st = self.lib.pt_create(C.byref(cfg), *[C.c_void_p(a.data_ptr()) for a in self.arenas[:3]],
-                                    C.c_void_p(self.arenas[3].data_ptr()) if cfg.cache_slots > 0 else None,
+                                    C.c_void_p(self.arenas[3].data_ptr()) if cfg.cache_slots + cfg.window_slots > 0 else None,
                                     C.c_void_p(self.stream.cuda_stream), C.byref(h))
         if st != PT_OK:
             raise PtError(st, "pt_create")
         self.h = h
         self.esz = 2 if cfg.dtype == PT_BF16 else 4
         self._names = None
+        self.host_tier = None
+        if cfg.host_slots > 0:
+            # the lower cache tier: pinned host memory owned here, attached once
+            nbytes = cfg.host_slots * cfg.S * cfg.D * self.esz
+            self.host_tier = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+            self._chk(self.lib.pt_attach_host_tier(self.h, C.c_void_p(self.host_tier.data_ptr()), nbytes))
 
     def close(self):
         if self.h:
@@ -268,6 +278,17 @@ class Context:
         a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
         self._chk(self.lib.pt_cache_stats(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
         return {"hits": a.value, "advances": b.value, "misses": c.value, "block_runs": d.value}
+
+    def cache_prefetch(self, sample_ids) -> int:
+        ids = np.ascontiguousarray(sample_ids, dtype=np.int64)
+        n = C.c_int32()
+        self._chk(self.lib.pt_cache_prefetch(self.h, ids.ctypes.data_as(C.POINTER(C.c_int64)), len(ids), C.byref(n)))
+        return n.value
+
+    def host_tier_stats(self):
+        a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+        self._chk(self.lib.pt_host_tier_stats(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
+        return {"rows_to_device": a.value, "rows_to_host": b.value, "prefetched": c.value, "prefetched_used": d.value}
 
     # ---- kernel timing ---------------------------------------------------------
     def profile_enable(self, on: bool):

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <unordered_set>
 #include <vector>
 
@@ -77,7 +78,9 @@ bool validate(const pt_config& c, std::string* why) {
     if (c.vocab < 1 || c.max_pos < c.S) return bad("vocab / max_pos");
     if (c.head == PT_HEAD_DEFAULT && c.n_out != 2) return bad("BERT span-QA head has n_out = 2");
   }
-  if (c.cache_slots < 0) return bad("cache_slots");
+  if (c.cache_slots < 0 || c.host_slots < 0 || c.window_slots < 0) return bad("cache_slots / host_slots / window_slots");
+  if (c.host_slots > 0 && c.window_slots < 2 * (int64_t)c.B) return bad("a host tier needs window_slots >= 2 B");
+  if (c.host_slots == 0 && c.window_slots != 0) return bad("window_slots without host_slots");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps");
   if ((int64_t)c.B * c.S > (1 << 24)) return bad("B*S too large");
   return true;
@@ -125,7 +128,7 @@ void make_plan(const pt_config& c, Plan* p) {
   const size_t P = (size_t)p->arena_floats;
   p->params_bytes = align_up(P * 4) + (c.dtype == PT_BF16 ? align_up(P * 2) : 0);
   p->state_bytes = align_up(P * 4) * ((c.optimizer == PT_ADAMW ? 3 : 2) + (c.grad_accum ? 1 : 0));
-  p->cache_bytes = (size_t)c.cache_slots * S * D * e;
+  p->cache_bytes = (size_t)(c.cache_slots + c.window_slots) * S * D * e;
 
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
@@ -220,7 +223,17 @@ struct pt_ctx {
   const void* last_input = nullptr;
   void* last_hk = nullptr;
   void* last_dhk = nullptr;
-  std::vector<int32_t> slot_k;  // boundary a cache row was written at, -1 = empty
+  std::vector<int32_t> slot_k;  // boundary a cache row was written at, -1 = empty (HBM rows, then host rows)
+  // host tier: rows of sample ids >= cache_slots live in pinned host memory and pass through a window of
+  // device rows (the last window_slots rows of the cache arena) on a copy stream of their own
+  struct WinSlot { int64_t id = -1; int state = 0; hipEvent_t ev = nullptr; int64_t stamp = 0; };  // 0 free, 1 staged, 2 write-back
+  char* host_rows = nullptr;
+  hipStream_t copy_st = nullptr;
+  hipEvent_t ev_copy = nullptr, ev_main = nullptr;
+  std::vector<WinSlot> win;
+  std::unordered_map<int64_t, int> win_of;  // staged rows: sample id -> window slot
+  int64_t call_stamp = 0;
+  int64_t n_h2d = 0, n_d2h = 0, n_prefetched = 0, n_prefetch_used = 0;
   int64_t n_hit = 0, n_adv = 0, n_miss = 0, n_runs = 0;
   // pinned host staging for index arrays, double-buffered by call parity
   int64_t* h_idx[2] = {nullptr, nullptr};
@@ -504,7 +517,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
                     pt_ctx** out) {
   if (!cfg || !out || !d_params || !d_state || !d_work) return PT_EINVAL;
   if (!validate(*cfg, nullptr)) return PT_EINVAL;
-  if (cfg->cache_slots > 0 && !d_cache) return PT_EINVAL;
+  if (cfg->cache_slots + cfg->window_slots > 0 && !d_cache) return PT_EINVAL;
   for (const void* q : {d_params, d_state, d_work, (void*)d_cache})
     if (reinterpret_cast<uintptr_t>(q) % kAlign) return PT_EINVAL;
   pt_ctx* c = new (std::nothrow) pt_ctx();
@@ -525,7 +538,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
                             : nullptr;
   c->work = reinterpret_cast<char*>(d_work);
   c->cache = reinterpret_cast<char*>(d_cache);
-  c->slot_k.assign((size_t)cfg->cache_slots, -1);
+  c->slot_k.assign((size_t)(cfg->cache_slots + cfg->host_slots), -1);
   auto cleanup = [&]() {
     for (int i = 0; i < 2; ++i) {
       if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
@@ -566,6 +579,13 @@ pt_status pt_destroy(pt_ctx* c) {
     if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
   }
   for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  if (c->copy_st) {
+    (void)hipStreamSynchronize(c->copy_st);
+    for (auto& w : c->win) if (w.ev) (void)hipEventDestroy(w.ev);
+    if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
+    if (c->ev_main) (void)hipEventDestroy(c->ev_main);
+    (void)hipStreamDestroy(c->copy_st);
+  }
   delete c;
   return PT_OK;
 }
@@ -595,6 +615,98 @@ pt_status pt_set_freeze_boundary(pt_ctx* c, int32_t k) {
   return PT_OK;
 }
 
+// ---- host tier of the activation cache (Sec. 3.4 / App. E: hierarchical cache with a sliding window) ----
+namespace {
+
+size_t cache_row_bytes(const pt_ctx* c) { return (size_t)c->cfg.S * c->cfg.D * c->esz; }
+char* window_row(const pt_ctx* c, int slot) { return c->cache + (size_t)(c->cfg.cache_slots + slot) * cache_row_bytes(c); }
+char* host_row(const pt_ctx* c, int64_t id) { return c->host_rows + (size_t)(id - c->cfg.cache_slots) * cache_row_bytes(c); }
+
+// A free window slot, or -1.  Write-back slots are reclaimed once their copy has completed; `evict` also gives
+// up staged rows that this call does not use; `block` waits for the copy stream as the last resort.
+int window_alloc(pt_ctx* c, bool evict, bool block) {
+  for (int pass = 0; pass < 2; ++pass) {
+    for (size_t i = 0; i < c->win.size(); ++i)
+      if (c->win[i].state == 0) return (int)i;
+    for (size_t i = 0; i < c->win.size(); ++i)
+      if (c->win[i].state == 2) {
+        if (hipEventQuery(c->win[i].ev) == hipSuccess) { c->win[i].state = 0; c->win[i].id = -1; return (int)i; }
+        (void)hipGetLastError();   // "not ready" is an answer, not an error to be reported later
+      }
+    if (evict) {
+      int best = -1;
+      for (size_t i = 0; i < c->win.size(); ++i)
+        if (c->win[i].state == 1 && c->win[i].stamp != c->call_stamp && (best < 0 || c->win[i].stamp < c->win[best].stamp)) best = (int)i;
+      if (best >= 0) { c->win_of.erase(c->win[best].id); c->win[best].state = 0; c->win[best].id = -1; return best; }
+    }
+    if (!block || pass == 1) break;
+    if (hipStreamSynchronize(c->copy_st) != hipSuccess) return -1;
+    for (auto& w : c->win) if (w.state == 2) { w.state = 0; w.id = -1; }
+  }
+  return -1;
+}
+
+// Stages the host row of `id` into a window slot (asynchronously, on the copy stream); returns the slot or -1.
+int window_stage(pt_ctx* c, int64_t id, bool evict, bool block, hipError_t* err) {
+  auto it = c->win_of.find(id);
+  if (it != c->win_of.end()) return it->second;
+  const int slot = window_alloc(c, evict, block);
+  if (slot < 0) return -1;
+  const hipError_t e = hipMemcpyAsync(window_row(c, slot), host_row(c, id), cache_row_bytes(c), hipMemcpyHostToDevice, c->copy_st);
+  if (e != hipSuccess) { if (err) *err = e; return -1; }
+  c->win[slot].id = id; c->win[slot].state = 1; c->win[slot].stamp = c->call_stamp;
+  c->win_of[id] = slot;
+  c->n_h2d++;
+  return slot;
+}
+
+}  // namespace
+
+pt_status pt_attach_host_tier(pt_ctx* c, void* h_rows, size_t bytes) {
+  if (!c || !h_rows) return PT_EINVAL;
+  if (c->cfg.host_slots <= 0) return fail(c, PT_ESTATE, "the configuration has host_slots = 0");
+  if (c->host_rows) return fail(c, PT_ESTATE, "a host tier is already attached");
+  if (bytes < (size_t)c->cfg.host_slots * cache_row_bytes(c)) return fail(c, PT_ENOMEM, "host tier memory too small");
+  HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_st, hipStreamNonBlocking));
+  HIP_TRY(c, hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
+  HIP_TRY(c, hipEventCreateWithFlags(&c->ev_main, hipEventDisableTiming));
+  c->win.resize((size_t)c->cfg.window_slots);
+  for (auto& w : c->win) HIP_TRY(c, hipEventCreateWithFlags(&w.ev, hipEventDisableTiming));
+  c->host_rows = static_cast<char*>(h_rows);
+  return PT_OK;
+}
+
+pt_status pt_cache_prefetch(pt_ctx* c, const int64_t* sample_ids, int32_t n, int32_t* staged_out) {
+  if (!c || (!sample_ids && n > 0) || n < 0) return PT_EINVAL;
+  if (staged_out) *staged_out = 0;
+  if (!c->host_rows) return PT_OK;   // nothing lives on the host: every row is already in HBM
+  const int64_t lo = c->cfg.cache_slots, hi = lo + c->cfg.host_slots;
+  c->call_stamp++;
+  hipError_t err = hipSuccess;
+  int staged = 0;
+  for (int i = 0; i < n; ++i) {
+    const int64_t id = sample_ids[i];
+    if (id < 0 || id >= hi) return fail(c, PT_EINVAL, "sample id outside the cache");
+    if (id < lo || c->slot_k[(size_t)id] < 0 || c->win_of.count(id)) continue;
+    if (window_stage(c, id, false, false, &err) < 0) break;   // best effort: the window is full
+    ++staged;
+  }
+  if (err != hipSuccess) return fail(c, PT_EDEVICE, hipGetErrorString(err));
+  c->n_prefetched += staged;
+  if (staged_out) *staged_out = staged;
+  return PT_OK;
+}
+
+pt_status pt_host_tier_stats(const pt_ctx* c, int64_t* rows_to_device, int64_t* rows_to_host, int64_t* prefetched,
+                             int64_t* prefetched_used) {
+  if (!c) return PT_EINVAL;
+  if (rows_to_device) *rows_to_device = c->n_h2d;
+  if (rows_to_host) *rows_to_host = c->n_d2h;
+  if (prefetched) *prefetched = c->n_prefetched;
+  if (prefetched_used) *prefetched_used = c->n_prefetch_used;
+  return PT_OK;
+}
+
 pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const int64_t* sample_ids, void** d_hk_out) {
   if (!c || !d_input || !d_hk_out) return PT_EINVAL;
   const pt_config& g = c->cfg;
@@ -606,14 +718,53 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
     front_forward(c, d_input, nullptr, c->w(p.X[0]), nb, true);
     c->last_hk = c->w(p.X[0]);
   } else {
-    const bool use_cache = sample_ids && g.cache_slots > 0;
+    const bool use_cache = sample_ids && g.cache_slots + g.host_slots > 0;
     std::vector<int> kw(nb, -1);
+    // device row of each sample in the cache arena: its own slot, or a window slot for the host tier
+    std::vector<int64_t> row_r(nb, -1), row_w(nb, -1);
+    bool host_used = false;
     if (use_cache) {
+      if (g.host_slots > 0 && !c->host_rows) return fail(c, PT_ESTATE, "host_slots > 0 but no host tier is attached");
       std::unordered_set<int64_t> seen;
       for (int i = 0; i < nb; ++i) {
-        if (sample_ids[i] < 0 || sample_ids[i] >= g.cache_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
+        if (sample_ids[i] < 0 || sample_ids[i] >= g.cache_slots + g.host_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
         if (!seen.insert(sample_ids[i]).second) return fail(c, PT_EINVAL, "duplicate sample id in a batch");
         kw[i] = c->slot_k[(size_t)sample_ids[i]];
+        if (sample_ids[i] < g.cache_slots) row_r[i] = row_w[i] = sample_ids[i];
+      }
+      // host tier: rows already staged by pt_cache_prefetch are used as they are, the others are staged now;
+      // a row that will be (re)written gets a window slot to be copied back from.  All window slots are
+      // chosen before the main stream is made to wait for the copy stream, so none of them is in flight
+      // when a kernel below touches it.
+      c->call_stamp++;
+      hipError_t herr = hipSuccess;
+      for (int i = 0; i < nb; ++i) {
+        if (sample_ids[i] < g.cache_slots || kw[i] < 0) continue;
+        auto it = c->win_of.find(sample_ids[i]);
+        if (it != c->win_of.end()) { c->win[it->second].stamp = c->call_stamp; c->n_prefetch_used++; }
+      }
+      for (int i = 0; i < nb; ++i) {
+        if (sample_ids[i] < g.cache_slots) continue;
+        host_used = true;
+        int slot = -1;
+        if (kw[i] >= 0) {
+          slot = window_stage(c, sample_ids[i], true, true, &herr);
+          if (slot < 0) return fail(c, herr != hipSuccess ? PT_EDEVICE : PT_ENOMEM, "no window slot for a host-tier row");
+          c->win[slot].stamp = c->call_stamp;
+          row_r[i] = g.cache_slots + slot;
+        }
+        if (kw[i] < k) {
+          if (slot < 0) {
+            slot = window_alloc(c, true, true);
+            if (slot < 0) return fail(c, PT_ENOMEM, "no window slot for a host-tier row");
+            c->win[slot].id = sample_ids[i]; c->win[slot].state = 1; c->win[slot].stamp = c->call_stamp;
+          }
+          row_w[i] = g.cache_slots + slot;
+        }
+      }
+      if (host_used) {
+        HIP_TRY(c, hipEventRecord(c->ev_copy, c->copy_st));
+        HIP_TRY(c, hipStreamWaitEvent(c->st, c->ev_copy, 0));
       }
     }
     // sorted order: misses first, then by the boundary the row was written at (stable)
@@ -630,7 +781,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
     if (n_hit == nb) {
       // every sample is a hit: one gather from the cache, no block runs
       std::vector<int64_t> src(nb);
-      for (int i = 0; i < nb; ++i) src[i] = sample_ids[i];
+      for (int i = 0; i < nb; ++i) src[i] = row_r[i];
       const int64_t* dsrc = stg.put(src, &cerr);
       { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st); }
       c->last_hk = c->w(p.HKOUT);
@@ -649,7 +800,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
         std::vector<int64_t> dst, src;
         int n_le = 0;
         for (int i = 0; i < nb; ++i) {
-          if (kw[order[i]] == j) { dst.push_back(i); src.push_back(sample_ids[order[i]]); }
+          if (kw[order[i]] == j) { dst.push_back(i); src.push_back(row_r[order[i]]); }
           n_le += kw[order[i]] <= j;
         }
         if (!dst.empty()) {
@@ -666,7 +817,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
       if (use_cache) {
         std::vector<int64_t> dst, src;
         for (int i = 0; i < nb; ++i)
-          if (kw[order[i]] < k) { dst.push_back(sample_ids[order[i]]); src.push_back(i); }
+          if (kw[order[i]] < k) { dst.push_back(row_w[order[i]]); src.push_back(i); }
         const int64_t* ddst = stg.put(dst, &cerr);
         const int64_t* dsrc = stg.put(src, &cerr);
         { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st); }
@@ -683,6 +834,25 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
     }
     HIP_TRY(c, stg.end());
     if (cerr != hipSuccess) return fail(c, PT_EDEVICE, hipGetErrorString(cerr));
+    if (host_used) {
+      // the copy stream continues only after this call's kernels: rewritten rows go back to the host, rows that
+      // were only read give their window slot back
+      HIP_TRY(c, hipEventRecord(c->ev_main, c->st));
+      HIP_TRY(c, hipStreamWaitEvent(c->copy_st, c->ev_main, 0));
+      for (int i = 0; i < nb; ++i) {
+        if (sample_ids[i] < g.cache_slots) continue;
+        const int slot = (int)((row_w[i] >= 0 ? row_w[i] : row_r[i]) - g.cache_slots);
+        c->win_of.erase(sample_ids[i]);
+        if (row_w[i] >= 0) {
+          HIP_TRY(c, hipMemcpyAsync(host_row(c, sample_ids[i]), window_row(c, slot), row_bytes, hipMemcpyDeviceToHost, c->copy_st));
+          HIP_TRY(c, hipEventRecord(c->win[slot].ev, c->copy_st));
+          c->win[slot].state = 2;
+          c->n_d2h++;
+        } else {
+          c->win[slot].state = 0; c->win[slot].id = -1;
+        }
+      }
+    }
     if (use_cache)
       for (int i = 0; i < nb; ++i) {
         if (kw[i] < 0) c->n_miss++; else if (kw[i] == k) c->n_hit++; else c->n_adv++;
@@ -971,10 +1141,18 @@ pt_status pt_read_activation(pt_ctx* c, int32_t which, float* dst, size_t numel)
 
 pt_status pt_cache_row(pt_ctx* c, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k) {
   if (!c || !dst) return PT_EINVAL;
-  if (sample_id < 0 || sample_id >= c->cfg.cache_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
+  if (sample_id < 0 || sample_id >= c->cfg.cache_slots + c->cfg.host_slots) return fail(c, PT_EINVAL, "sample id outside the cache");
   const size_t row_bytes = (size_t)c->cfg.S * c->cfg.D * c->esz;
   if (dst_bytes != row_bytes) return fail(c, PT_EINVAL, "row size mismatch");
   if (c->slot_k[(size_t)sample_id] < 0) return PT_ECACHE_MISS;
+  if (sample_id >= c->cfg.cache_slots) {
+    if (!c->host_rows) return fail(c, PT_ESTATE, "no host tier is attached");
+    HIP_TRY(c, hipStreamSynchronize(c->st));
+    HIP_TRY(c, hipStreamSynchronize(c->copy_st));
+    std::memcpy(dst, host_row(c, sample_id), row_bytes);
+    if (written_at_k) *written_at_k = c->slot_k[(size_t)sample_id];
+    return PT_OK;
+  }
   HIP_TRY(c, hipMemcpyAsync(dst, c->cache + (size_t)sample_id * row_bytes, row_bytes, hipMemcpyDeviceToHost, c->st));
   HIP_TRY(c, hipStreamSynchronize(c->st));
   if (written_at_k) *written_at_k = c->slot_k[(size_t)sample_id];

@@ -151,3 +151,81 @@ def test_training_from_cache_equals_training_from_recompute(torch_mod):
     assert a["loss"] == b["loss"]
     for n in a["grads"]:
         assert np.array_equal(a["grads"][n], b["grads"][n]), n
+
+
+@pytest.mark.parametrize("w", [MID_VIT, MID_BERT], ids=["vit_bf16", "bert_bf16"])
+def test_host_tier_is_invisible_to_the_result(torch_mod, w):
+    """A context whose cache is mostly in pinned host memory (ids >= cache_slots pass through a window of
+    2 B device rows) against an all-HBM context and the oracle's cache on the same call sequence: the same
+    decisions, bit-identical h_k and cached rows, with and without prefetching, across boundary moves."""
+    torch = torch_mod
+    S, D = w["S"], w["D"]
+    nb = 4
+    n_ids = 16
+    tiered = binding.Context(binding.make_config(w, B=nb, cache_slots=3, host_slots=n_ids - 3, window_slots=2 * nb))
+    plain = binding.Context(binding.make_config(w, B=nb, cache_slots=n_ids))
+    vals = H.init_values(w, plain, 23)
+    H.load_params(plain, vals)
+    H.load_params(tiered, vals)
+    cfg = oracle_cfg(w)
+    p64 = {n: a.astype(np.float64) for n, a in vals.items()}
+    ocache = orc.ActivationCache()
+    xs, _ = H.batch_for(w, 23, n_ids, "pool")
+    o_in = (lambda x: x.astype(np.float64)) if w["arch"] == "vit" else (lambda x: x)
+    rng = np.random.default_rng(5)
+    tally = {"hit": 0, "advance": 0, "miss": 0}
+
+    def call(ids, k, prefetch_next=None):
+        ids = [int(i) for i in ids]
+        print(f"host tier call k={k} ids={ids}", flush=True)
+        want = [ocache.decision(s, k) for s in ids]
+        for d in want:
+            tally[d[0]] += 1
+        dx = H.to_dev(torch, xs[ids])
+        tiered.frozen_forward(dx, ids)
+        if prefetch_next is not None:
+            tiered.cache_prefetch(prefetch_next)
+        a = raw_hk(tiered, w, len(ids))
+        plain.frozen_forward(dx, ids)
+        b = raw_hk(plain, w, len(ids))
+        assert np.array_equal(a, b)
+        ocache.frozen_forward(cfg, p64, o_in(xs[ids]), ids, k)
+        return want
+
+    for c in (tiered, plain):
+        c.set_freeze_boundary(1)
+    order = rng.permutation(n_ids)
+    batches = [order[i:i + nb] for i in range(0, n_ids, nb)]
+    for i, ids in enumerate(batches):                       # epoch 1: misses, written through the window
+        assert [d[0] for d in call(ids, 1)] == ["miss"] * nb
+    assert tiered.cache_stats() == plain.cache_stats()
+    for i, ids in enumerate(batches):                       # epoch 2: hits; the next batch is prefetched
+        nxt = batches[i + 1] if i + 1 < len(batches) else None
+        assert [d[0] for d in call(ids, 1, prefetch_next=nxt)] == ["hit"] * nb
+    hs = tiered.host_tier_stats()
+    assert hs["rows_to_host"] == n_ids - 3 and hs["prefetched"] > 0 and hs["prefetched_used"] == hs["prefetched"]
+    for c in (tiered, plain):
+        c.set_freeze_boundary(2)
+    order2 = rng.permutation(n_ids)
+    for i in range(0, n_ids - nb, nb):                      # epoch 3: advances (stale rows), no prefetch
+        assert [d[0] for d in call(order2[i:i + nb], 2)] == ["advance"] * nb
+    mixed = list(order2[n_ids - nb:n_ids - 2]) + list(order2[:2])   # two stale rows, two current ones
+    got = call(mixed, 2, prefetch_next=order2[:nb])
+    assert [d[0] for d in got] == ["advance", "advance", "hit", "hit"]
+    call(order2[:nb], 2)                                    # prefetched hits again
+    got = call(list(order2[n_ids - 2:]) + list(order2[4:6]), 2)
+    assert [d[0] for d in got] == ["advance", "advance", "hit", "hit"]
+    assert tiered.cache_stats() == plain.cache_stats()
+    st = tiered.cache_stats()
+    assert (st["hits"], st["advances"], st["misses"]) == (tally["hit"], tally["advance"], tally["miss"])
+    for sid in range(n_ids):                                # every row, whichever tier holds it
+        ra, ka = tiered.cache_row(sid)
+        rb, kb = plain.cache_row(sid)
+        assert ka == kb == 2 and np.array_equal(ra, rb), sid
+    # the host tier moved rows both ways and the ids outside both tiers are refused
+    hs = tiered.host_tier_stats()
+    assert hs["rows_to_device"] > 0 and hs["rows_to_host"] >= 2 * (n_ids - 3)
+    with pytest.raises(binding.PtError):
+        tiered.frozen_forward(H.to_dev(torch, xs[:nb]), [0, 1, 2, n_ids])
+    tiered.close()
+    plain.close()
