@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--k", type=int, default=0, help="freeze boundary of the timed run")
     ap.add_argument("--no-sweep", action="store_true", help="skip the extra k = 6 / 9 measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
+    ap.add_argument("--host-tier", action="store_true",
+                    help="keep every cached row in pinned host memory (window of 4 batches in HBM, next batch prefetched)")
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy four times (a kernel of known HBM traffic, for scaling "
@@ -74,7 +76,10 @@ def main():
     B = w["B"]
     n_ids = 4 * B
     M = a.micro_batches
-    ctx = binding.Context(binding.make_config(w, cache_slots=n_ids, grad_accum=M > 1))
+    if a.host_tier:
+        ctx = binding.Context(binding.make_config(w, cache_slots=0, host_slots=n_ids, window_slots=4 * B, grad_accum=M > 1))
+    else:
+        ctx = binding.Context(binding.make_config(w, cache_slots=n_ids, grad_accum=M > 1))
     seed = 2
     for tid, name, shape, _, _ in ctx.tensors():
         ctx.write_tensor(tid, binding.KIND_PARAM, synth.round_bf16(synth.gen_param(seed, name, shape)))
@@ -88,6 +93,8 @@ def main():
         for j in range(M):
             x, y, ids = batches[(i * M + j) % len(batches)]
             hk = ctx.frozen_forward(x, ids if use_cache else None)
+            if use_cache and a.host_tier:   # stage the next batch's rows while this one trains
+                ctx.cache_prefetch(batches[(i * M + j + 1) % len(batches)][2])
             ctx.active_fwd_bwd(hk, y, want_loss=False)
             if M > 1:
                 ctx.accumulate_grads(first=(j == 0))
@@ -173,6 +180,9 @@ def main():
             sweep[f"k{k}"] = round(M * B / s_unc, 1)
             sweep[f"k{k}_cached"] = round(M * B / s_hit, 1)
         result["samples_per_s_vs_k"] = sweep
+        if a.host_tier:
+            result["cache_tier"] = "host-pinned rows, 4-batch HBM window, next batch prefetched"
+            result["host_tier_stats"] = ctx.host_tier_stats()
     ctx.close()
 
     # ---- the CPU checker timed on a small batch of the same shapes ----

@@ -416,9 +416,14 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (gemm_uses_mfma(dt, a) && (!a.ta || a.ldc == a.N)) {
     if (g_cfg_override != 0 && gemm_dma_ok(a)) {
       // default: 128x128 tiles, three per CU; wide outputs and the weight gradients do better with
-      // 256x128 tiles and eight waves
+      // 256x128 tiles and eight waves; input gradients with a narrow output and a long K with 256x256
+      // tiles, one workgroup per CU (measured: fewer, larger workgroups win there although a third of
+      // the CUs stays idle)
       int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
-      if (g_cfg_override < 0) v = (a.ta || a.N >= 3072) ? 2 : 1;
+      if (g_cfg_override < 0) {
+        v = (a.ta || a.N >= 3072) ? 2 : 1;
+        if (a.tb && a.N <= 1024 && a.K >= 2048 && a.M >= 4096) v = 3;
+      }
       gemm_dma(a, v, st);
       return;
     }

@@ -365,8 +365,7 @@ void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
     case 1: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
     case 2: dispatch_dma<256, 128, 4, 2, 3>(a, st); break;
     case 3: dispatch_dma<256, 256, 2, 4, 3>(a, st); break;
-    case 4: dispatch_dma<256, 256, 2, 4, 4>(a, st); break;
-    default: dispatch_dma<128, 128, 2, 2, 4>(a, st); break;
+    default: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
   }
 }
 
