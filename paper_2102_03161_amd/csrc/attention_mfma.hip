@@ -356,14 +356,380 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(const bf16* __re
   }
 }
 
+
+// ===========================================================================
+// Resident variants: when the whole streamed side of one (sample, head) fits in LDS, it is loaded once with
+// every global load in flight at the same time, and the tile loop then runs without barriers or further
+// global loads (the streaming kernels above pay one global-load latency per 32-row tile).  Tiles stay
+// row-major; the operand that must be read "transposed" comes from the LDS transpose read
+// ds_read_b64_tr_b16, which hands a lane four consecutive rows of one feature.  A workgroup has one wave per
+// 32 owned rows (at most 8 waves; longer sequences split the owned rows over blockIdx.x).
+// ===========================================================================
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(size_t)((__attribute__((address_space(3))) const void*)(p));
+}
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+// rows [0, rows_pad) of two [*, 64] matrices into row-major LDS images (rows >= nrows read as 0).  Eight
+// 16-byte global loads per thread are issued before the first LDS store, so a workgroup pays the global
+// latency once per round instead of once per piece.
+__device__ __forceinline__ void load_resident2(bf16* dst_a, const bf16* __restrict__ src_a, int64_t ld_a, bf16* dst_b,
+                                               const bf16* __restrict__ src_b, int64_t ld_b, int nrows, int rows_pad,
+                                               int tid, int nthreads) {
+  const int total = rows_pad * 8;
+  for (int c0 = tid; c0 < total; c0 += 4 * nthreads) {
+    uint4 va[4], vb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
+      va[u] = make_uint4(0, 0, 0, 0);
+      vb[u] = make_uint4(0, 0, 0, 0);
+      if (c < total && row < nrows) {
+        va[u] = *reinterpret_cast<const uint4*>(src_a + (int64_t)row * ld_a + ch * 8);
+        vb[u] = *reinterpret_cast<const uint4*>(src_b + (int64_t)row * ld_b + ch * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
+      if (c < total) {
+        *reinterpret_cast<uint4*>(dst_a + row * LDR + ch * 8) = va[u];
+        *reinterpret_cast<uint4*>(dst_b + row * LDR + ch * 8) = vb[u];
+      }
+    }
+  }
+}
+// A operand "feature dt*32 + lane%32 over 8 streamed rows in accumulator order" from a row-major tile:
+// two transpose reads of rows 16*ks2 + 4*half + {0..3} and the same + 8.  The 16 lanes of a group address a
+// 4 x 16 block (lane l: row l/4, features 4*(l%4)..+3) and lane i receives the four rows of feature i.
+// The caller waits for the reads (lds_wait) before the fragment is used.
+__device__ __forceinline__ void frag_cols_tr(const bf16* X, int lane, int dt, int ks2, bf16x8& f) {
+  const int l16 = lane & 15, grp = lane >> 4;
+  const int row = 16 * ks2 + 4 * (grp >> 1) + (l16 >> 2);
+  const int col = dt * 32 + 16 * (grp & 1) + 4 * (l16 & 3);
+  const unsigned addr = lds_addr(X + row * LDR + col);
+  union { u32x2 h[2]; bf16x8 v; } t;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(t.h[0]) : "v"(addr));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"(8 * LDR * 2));
+  f = t.v;
+}
+// A operand "row lane%32, features 16*ks + 8*half .. +7" of a row-major tile, issued without a wait so that
+// the reads of a whole tile are in flight together (the compiler would otherwise wait for each fragment right
+// before the MFMA that uses it).  base = address of the lane's row start + 16*half bytes.
+__device__ __forceinline__ void frag_rows_issue(unsigned base, bf16x8 (&f)[4]) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f[0]) : "v"(base));
+  asm volatile("ds_read_b128 %0, %1 offset:32" : "=v"(f[1]) : "v"(base));
+  asm volatile("ds_read_b128 %0, %1 offset:64" : "=v"(f[2]) : "v"(base));
+  asm volatile("ds_read_b128 %0, %1 offset:96" : "=v"(f[3]) : "v"(base));
+}
+// waits until at most PENDING LDS operations are outstanding (they return in order) and makes the given
+// fragments depend on the wait, so that no MFMA reading them is scheduled before it
+template <int PENDING, int N>
+__device__ __forceinline__ void lds_wait(bf16x8 (&f)[N]) {
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(PENDING) : "memory");
+#pragma unroll
+  for (int i = 0; i < N; ++i) asm volatile("" : "+v"(f[i]));
+}
+
+__global__ __launch_bounds__(512) void attn_fwd_res_kernel(const bf16* __restrict__ qkv, bf16* __restrict__ ctx,
+                                                           float* __restrict__ lse, int S, int H, int ntile) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Ks = reinterpret_cast<bf16*>(smem);
+  bf16* Vs = Ks + ntile * 32 * LDR;
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int nw = blockDim.x >> 6;
+  const int q = (blockIdx.x * nw + wave) * 32 + (lane & 31);
+  const bool qok = q < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const float c = 0.125f * 1.44269504088896f;
+  bf16x8 qf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) qf[ks] = own_row_frag(base + (int64_t)q * 3 * D, qok, lane, ks);
+  load_resident2(Ks, base + D, 3 * D, Vs, base + 2 * D, 3 * D, S, ntile * 32, tid, blockDim.x);
+  __syncthreads();
+  if ((blockIdx.x * nw + wave) * 32 >= S) return;   // a wave without queries (no barrier follows)
+  f32x16 o[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+  const unsigned rows_base = lds_addr(Ks + (lane & 31) * LDR + half * 8);
+  for (int kt = 0; kt < ntile; ++kt) {
+    const bf16* Vt = Vs + kt * 32 * LDR;
+    bf16x8 kr[4], vf[4];   // K rows [ks]; V columns [ks2][dt]
+    frag_rows_issue(rows_base + kt * (32 * LDR * 2), kr);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Vt, lane, dt, ks2, vf[2 * ks2 + dt]);
+    f32x16 s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+    lds_wait<8>(kr);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
+    if (kt == ntile - 1 && (S & 31)) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
+    }
+    float mx = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[v]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c;
+    if (__any(mx > m + 8.f)) {
+      const float m_new = mx > m + 8.f ? mx : m;
+      const float alpha = fast_exp2(m - m_new);
+      lsum *= alpha;
+      m = m_new;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+    }
+    float rs = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      s[v] = fast_exp2(fmaf(s[v], c, -m));
+      rs += s[v];
+    }
+    lsum += rs + __shfl_xor(rs, 32, 64);
+    lds_wait<0>(vf);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 pb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[2 * ks2 + dt], pb, o[dt], 0, 0, 0);
+    }
+  }
+  if (qok) {
+    store_owned_row(ctx + ((int64_t)b * S + q) * D + h * DH, o, 1.0f / lsum, half);
+    if (lse && half == 0) lse[((int64_t)b * H + h) * S + q] = (m + __log2f(lsum)) * 0.693147180559945f;
+  }
+}
+
+__global__ __launch_bounds__(512) void attn_bwd_dq_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                              const bf16* __restrict__ dctx,
+                                                              const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                              float* __restrict__ delta, int S, int H, int ntile) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Ks = reinterpret_cast<bf16*>(smem);
+  bf16* Vs = Ks + ntile * 32 * LDR;
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int nw = blockDim.x >> 6;
+  const int q = (blockIdx.x * nw + wave) * 32 + (lane & 31);
+  const bool qok = q < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+  bf16x8 qf[4], dof[4];
+  float part = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = own_row_frag(base + (int64_t)q * 3 * D, qok, lane, ks);
+    dof[ks] = own_row_frag(dctx + ((int64_t)b * S + q) * D + h * DH, qok, lane, ks);
+    const bf16x8 of = own_row_frag(ctx + ((int64_t)b * S + q) * D + h * DH, qok, lane, ks);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
+  }
+  load_resident2(Ks, base + D, 3 * D, Vs, base + 2 * D, 3 * D, S, ntile * 32, tid, blockDim.x);
+  __syncthreads();
+  if ((blockIdx.x * nw + wave) * 32 >= S) return;
+  const float dl = part + __shfl_xor(part, 32, 64);
+  const float lq2 = (qok ? lse[((int64_t)b * H + h) * S + q] : 0.f) * 1.44269504088896f;
+  if (qok && half == 0) delta[((int64_t)b * H + h) * S + q] = dl;
+  f32x16 dq[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dq[dt][v] = 0.f;
+  const unsigned k_base = lds_addr(Ks + (lane & 31) * LDR + half * 8);
+  const unsigned v_base = lds_addr(Vs + (lane & 31) * LDR + half * 8);
+  for (int kt = 0; kt < ntile; ++kt) {
+    const bf16* Kt = Ks + kt * 32 * LDR;
+    bf16x8 kr[4], vr[4], kc[4];
+    frag_rows_issue(k_base + kt * (32 * LDR * 2), kr);
+    frag_rows_issue(v_base + kt * (32 * LDR * 2), vr);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Kt, lane, dt, ks2, kc[2 * ks2 + dt]);
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+    lds_wait<8>(kr);
+    lds_wait<8>(vr);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[ks], dof[ks], dp, 0, 0, 0);
+    }
+    if (kt == ntile - 1 && (S & 31)) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float p = fast_exp2(fmaf(s[v], c, -lq2));
+      s[v] = p * (dp[v] - dl);  // dS^T
+    }
+    lds_wait<0>(kc);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 dsb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[2 * ks2 + dt], dsb, dq[dt], 0, 0, 0);
+    }
+  }
+  if (qok) store_owned_row(dqkv + ((int64_t)b * S + q) * 3 * D + h * DH, dq, scale, half);
+}
+
+__global__ __launch_bounds__(512) void attn_bwd_dkv_res_kernel(const bf16* __restrict__ qkv,
+                                                               const bf16* __restrict__ dctx,
+                                                               const float* __restrict__ lse,
+                                                               const float* __restrict__ delta,
+                                                               bf16* __restrict__ dqkv, int S, int H, int ntile) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Qs = reinterpret_cast<bf16*>(smem);
+  bf16* dOs = Qs + ntile * 32 * LDR;
+  float* ls = reinterpret_cast<float*>(dOs + ntile * 32 * LDR);   // row log-sum-exp in the log2 domain
+  float* dls = ls + ntile * 32;
+  const int D = H * DH;
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int nw = blockDim.x >> 6;
+  const int key = (blockIdx.x * nw + wave) * 32 + (lane & 31);
+  const bool kok = key < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const bf16* dobase = dctx + (int64_t)b * S * D + h * DH;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+  bf16x8 kf[4], vf[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    kf[ks] = own_row_frag(base + (int64_t)key * 3 * D + D, kok, lane, ks);
+    vf[ks] = own_row_frag(base + (int64_t)key * 3 * D + 2 * D, kok, lane, ks);
+  }
+  load_resident2(Qs, base, 3 * D, dOs, dobase, D, S, ntile * 32, tid, blockDim.x);
+  // a query row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
+  for (int r = tid; r < ntile * 32; r += blockDim.x) {
+    ls[r] = r < S ? lse[((int64_t)b * H + h) * S + r] * 1.44269504088896f : INFINITY;
+    dls[r] = r < S ? delta[((int64_t)b * H + h) * S + r] : 0.f;
+  }
+  __syncthreads();
+  if ((blockIdx.x * nw + wave) * 32 >= S) return;
+  f32x16 dk[2], dv[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+  const unsigned q_base = lds_addr(Qs + (lane & 31) * LDR + half * 8);
+  const unsigned do_base = lds_addr(dOs + (lane & 31) * LDR + half * 8);
+  for (int qt = 0; qt < ntile; ++qt) {
+    const bf16* Qt = Qs + qt * 32 * LDR;
+    const bf16* dOt = dOs + qt * 32 * LDR;
+    bf16x8 qr[4], dor[4], tc[8];   // rows of Q and dO; columns [ks2][dt] of dO, then of Q
+    frag_rows_issue(q_base + qt * (32 * LDR * 2), qr);
+    frag_rows_issue(do_base + qt * (32 * LDR * 2), dor);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) frag_cols_tr(dOt, lane, dt, ks2, tc[2 * ks2 + dt]);
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+    lds_wait<8>(qr);
+    lds_wait<8>(dor);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Qt, lane, dt, ks2, tc[4 + 2 * ks2 + dt]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[ks], kf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dor[ks], vf[ks], dp, 0, 0, 0);
+    }
+    f32x16 pr;
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const float4 l4 = *reinterpret_cast<const float4*>(ls + qt * 32 + 8 * g4 + 4 * half);
+      const float4 d4 = *reinterpret_cast<const float4*>(dls + qt * 32 + 8 * g4 + 4 * half);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int v = 4 * g4 + e;
+        const float p = fast_exp2(fmaf(s[v], c, -lv[e]));
+        pr[v] = p;
+        s[v] = p * (dp[v] - dv4[e]);  // dS
+      }
+    }
+    lds_wait<0>(tc);
+#pragma unroll
+    for (int ks2 = 0; ks2 < 2; ++ks2) {
+      const bf16x8 pb = pack8(pr, 8 * ks2), dsb = pack8(s, 8 * ks2);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt) {
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[2 * ks2 + dt], pb, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[4 + 2 * ks2 + dt], dsb, dk[dt], 0, 0, 0);
+      }
+    }
+  }
+  if (kok) {
+    bf16* row = dqkv + ((int64_t)b * S + key) * 3 * D + h * DH;
+    store_owned_row(row + D, dk, scale, half);
+    store_owned_row(row + 2 * D, dv, 1.0f, half);
+  }
+}
+
+// Sequence lengths the resident kernels take (the LDS image of two [S,64] matrices and two float rows must
+// fit in 160 KB, i.e. S <= 512).  Measured: forward wins at S = 197 (25 vs 33 us per layer at ViT-B, batch
+// 64) but loses at S = 384, where only one workgroup fits a CU (44 vs 39 us); backward wins at both.
+int g_attn_resident_max_s = 224;
+int g_attn_resident_max_s_bwd = 512;
+struct ResPlan { int ntile, nw, nblk; size_t lds; };
+ResPlan resident_plan(int S, bool with_rows) {
+  ResPlan r;
+  r.ntile = cdiv(S, 32);
+  r.nblk = cdiv(r.ntile, 8);
+  r.nw = cdiv(r.ntile, r.nblk);
+  r.lds = (size_t)2 * r.ntile * 32 * LDR * sizeof(bf16) + (with_rows ? (size_t)2 * r.ntile * 32 * sizeof(float) : 0);
+  return r;
+}
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
 }  // namespace
 
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, int H, hipStream_t st) {
+  if (S <= g_attn_resident_max_s) {
+    const ResPlan r = resident_plan(S, false);
+    if (allow_lds(attn_fwd_res_kernel, r.lds) == hipSuccess) {
+      hipLaunchKernelGGL(attn_fwd_res_kernel, dim3(r.nblk, H, nb), dim3(64 * r.nw), r.lds, st, (const bf16*)qkv, (bf16*)ctx,
+                         lse, S, H, r.ntile);
+      return;
+    }
+    (void)hipGetLastError();
+  }
   hipLaunchKernelGGL(attn_fwd_mfma_kernel, dim3(cdiv(S, 128), H, nb), dim3(256), 0, st, (const bf16*)qkv, (bf16*)ctx, lse,
                      S, H);
 }
 void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
                         int nb, int S, int H, hipStream_t st) {
+  if (S <= g_attn_resident_max_s_bwd) {
+    const ResPlan r = resident_plan(S, false), r2 = resident_plan(S, true);
+    if (allow_lds(attn_bwd_dq_res_kernel, r.lds) == hipSuccess && allow_lds(attn_bwd_dkv_res_kernel, r2.lds) == hipSuccess) {
+      hipLaunchKernelGGL(attn_bwd_dq_res_kernel, dim3(r.nblk, H, nb), dim3(64 * r.nw), r.lds, st, (const bf16*)qkv,
+                         (const bf16*)ctx, (const bf16*)dctx, lse, (bf16*)dqkv, delta, S, H, r.ntile);
+      hipLaunchKernelGGL(attn_bwd_dkv_res_kernel, dim3(r2.nblk, H, nb), dim3(64 * r2.nw), r2.lds, st, (const bf16*)qkv,
+                         (const bf16*)dctx, lse, delta, (bf16*)dqkv, S, H, r2.ntile);
+      return;
+    }
+    (void)hipGetLastError();
+  }
   dim3 grid(cdiv(S, 128), H, nb);
   hipLaunchKernelGGL(attn_bwd_dq_mfma_kernel, grid, dim3(256), 0, st, (const bf16*)qkv, (const bf16*)ctx,
                      (const bf16*)dctx, lse, (bf16*)dqkv, delta, S, H);
