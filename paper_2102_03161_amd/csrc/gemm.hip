@@ -422,7 +422,7 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
       int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
       if (g_cfg_override < 0) {
         v = (a.ta || a.N >= 3072) ? 2 : 1;
-        if (a.tb && a.N <= 1024 && a.K >= 2048 && a.M >= 4096) v = 3;
+        if (a.tb && a.N <= 1024 && a.K >= 768 && a.M >= 4096) v = 3;
       }
       gemm_dma(a, v, st);
       return;

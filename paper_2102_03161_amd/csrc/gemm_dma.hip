@@ -82,7 +82,14 @@ struct TileK {
   }
 };
 
-// ---- strided tile [32][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ ((k & 3) << 1) ----
+// ---- strided tile [32][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ swz(k) ----
+// A transpose read has its 16-lane groups address 4 k rows x 32 bytes; the groups of one half-wave differ by
+// 32 bytes in the row (or by 8 k rows).  Rows are a multiple of 256 bytes, so only the chunk index decides
+// the bank: swz moves the four k rows of a group to four different 64-byte quarters of the bank space and
+// the k+8 group to the other 32 bytes of each, which makes any two groups served together conflict-free
+// (checked against a bank model; the earlier (k & 3) << 1 left two-way conflicts, 21 % of the cycles of the
+// weight-gradient kernel by SQ_LDS_BANK_CONFLICT).
+__device__ __forceinline__ constexpr int swz(int k) { return ((k & 3) << 2) ^ (((k >> 3) & 1) << 1); }
 // Fragments come from ds_read_b64_tr_b16 (each lane gets four consecutive k of one row).  All fragment
 // reads are issued as inline assembly: the compiler would otherwise wait for every outstanding
 // global->LDS load before a transpose read, which serialises the pipeline, and explicit lgkmcnt waits
@@ -94,6 +101,7 @@ struct TileS {
   static constexpr int BYTES = kBK * ROWB, LOADS = kBK / KPL / NW;
   static constexpr int CPR = ROWS / 8;                           // 16-byte chunks per k row
   static_assert(kBK % (KPL * NW) == 0 && KPL >= 1, "tile must divide over the waves");
+  static_assert(CPR >= 16, "swz permutes chunks within groups of 16");
   const bf16* gp[LOADS];
   int64_t gstep;
   unsigned foff[NFRAG];    // fragment byte offsets (k-step 0, first half) per 32-row block
@@ -103,7 +111,7 @@ struct TileS {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       const int k = KPL * (wave * LOADS + i) + lane / CPR;
-      const int c = (lane % CPR) ^ ((k & 3) << 1);
+      const int c = (lane % CPR) ^ swz(k);
       int gr = r0 + 8 * c;
       gr = gr + 8 <= R ? gr : (R - 8);   // R >= 8 and R % 8 == 0 are checked by the host
       gp[i] = p + (int64_t)(k0 + k) * ld + gr;
@@ -114,7 +122,7 @@ struct TileS {
 #pragma unroll
     for (int j = 0; j < NFRAG; ++j) {
       const int col = rbase + j * 32 + (grp & 1) * 16 + 4 * (l16 & 3);
-      foff[j] = k * ROWB + ((((col >> 3) ^ ((k & 3) << 1))) << 4) + (col & 7) * 2;
+      foff[j] = k * ROWB + (((col >> 3) ^ swz(k)) << 4) + (col & 7) * 2;
     }
   }
   __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
@@ -132,7 +140,7 @@ struct TileS {
     for (int j = 0; j < NFRAG; ++j) {
       union { u32x2 h[2]; bf16x8 v; } t;
       const unsigned addr = base + foff[j] + 16 * ks * ROWB;
-      // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 rows is a constant offset (the swizzle only uses k & 3)
+      // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 and +16 rows are constant offsets (swz uses bits 0, 1, 3 of k)
       asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(t.h[0]) : "v"(addr));
       asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"(4 * ROWB));
       f[j] = t.v;
@@ -143,7 +151,7 @@ struct TileS {
     float s = 0.f;
 #pragma unroll
     for (int k = 0; k < kBK; ++k) {
-      const int c = (n >> 3) ^ ((k & 3) << 1);
+      const int c = (n >> 3) ^ swz(k);
       s += to_f32(*reinterpret_cast<const bf16*>(lds + k * ROWB + c * 16 + (n & 7) * 2));
     }
     return s;
