@@ -84,6 +84,7 @@ void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, 
 // dEp[s] = sum_b demb[b,s] for s < S (rows >= S untouched); dEw rows: deterministic
 // segmented sum over equal ids.  `dEw` must be zero on entry.
 // `ws`: 2*nb*S + 4 int32 of scratch.
+size_t bert_embed_ws_ints(int ntok, int vocab);
 void bert_embed_bwd(const int32_t* ids, const float* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S, int D,
                     int vocab, hipStream_t st);
 

@@ -160,7 +160,7 @@ void make_plan(const pt_config& c, Plan* p) {
     p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); p->DC = take((size_t)B * D * e);
   } else {
     p->PATCH = 0;
-    p->EMB = take(TD4); p->DEMB = take(TD4); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take((T + 4) * 8);
+    p->EMB = take(TD4); p->DEMB = take(TD4); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take(bert_embed_ws_ints((int)T, c.vocab) * 4);
     p->CFEAT = p->MUF = p->RSF = p->DC = 0;
     if (c.head == PT_HEAD_CLS) { p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); }
     else { p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4); }

@@ -383,31 +383,69 @@ void bert_embed(int dt, const int32_t* ids, const int64_t* map, const void* Ew, 
   else hipLaunchKernelGGL(bert_embed_kernel<bf16>, dim3(blocks), dim3(256), 0, st, ids, map, (const bf16*)Ew, (const bf16*)Ep, emb, nb, S, D, vocab);
 }
 
-// next[t] = smallest t' > t with the same token id (or -1); has_prev[t'] = 1 for it.
-__global__ void token_chain_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ next,
-                                   int32_t* __restrict__ has_prev, int ntok) {
+// Token-table gradient, reproducibly: tokens are grouped by id with a counting sort whose buckets are then put
+// in token order by rank (integer atomics only decide where a token waits inside its bucket, never a
+// floating-point order), and one workgroup per distinct id sums that id's rows in token order.
+//   ws layout (int32): count[vocab] | cursor[vocab] | offset[vocab] | bucket[ntok] | sorted[ntok] | rank[ntok]
+__global__ void token_count_kernel(const int32_t* __restrict__ ids, int32_t* __restrict__ count, int ntok, int vocab) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < ntok) atomicAdd(&count[clamp_id(ids[t], vocab)], 1);
+}
+// offset = exclusive prefix sum of count, one workgroup
+__global__ __launch_bounds__(1024) void token_offsets_kernel(const int32_t* __restrict__ count,
+                                                              int32_t* __restrict__ offset, int vocab) {
+  __shared__ int32_t part[1024];
+  const int per = (vocab + 1023) / 1024;
+  const int lo = threadIdx.x * per, hi = lo + per < vocab ? lo + per : vocab;
+  int32_t s = 0;
+  for (int v = lo; v < hi; ++v) s += count[v];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int o = 1; o < 1024; o <<= 1) {
+    const int32_t add = (int)threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+    __syncthreads();
+    part[threadIdx.x] += add;
+    __syncthreads();
+  }
+  int32_t run = threadIdx.x ? part[threadIdx.x - 1] : 0;
+  for (int v = lo; v < hi; ++v) { offset[v] = run; run += count[v]; }
+}
+__global__ void token_bucket_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ offset,
+                                    int32_t* __restrict__ cursor, int32_t* __restrict__ bucket, int ntok, int vocab) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= ntok) return;
-  const int32_t id = ids[t];
-  int32_t nx = -1;
-  for (int u = t + 1; u < ntok; ++u)
-    if (ids[u] == id) { nx = u; break; }
-  next[t] = nx;
-  if (nx >= 0) has_prev[nx] = 1;
+  const int id = clamp_id(ids[t], vocab);
+  bucket[offset[id] + atomicAdd(&cursor[id], 1)] = t;
 }
-// One workgroup per first occurrence of an id: sums the rows of its chain in token order.
+// rank[t] = number of smaller token indices in t's bucket; sorted[offset + rank] = t
+__global__ void token_rank_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ count,
+                                  const int32_t* __restrict__ offset, const int32_t* __restrict__ bucket,
+                                  int32_t* __restrict__ sorted, int32_t* __restrict__ rank, int ntok, int vocab) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= ntok) return;
+  const int id = clamp_id(ids[t], vocab);
+  const int n = count[id], base = offset[id];
+  int r = 0;
+  for (int j = 0; j < n; ++j) r += bucket[base + j] < t;
+  rank[t] = r;
+  sorted[base + r] = t;
+}
+// One workgroup per first occurrence of an id: sums the rows of its bucket in token order.
 __global__ __launch_bounds__(256) void embed_scatter_kernel(const int32_t* __restrict__ ids,
-                                                            const int32_t* __restrict__ next,
-                                                            const int32_t* __restrict__ has_prev,
+                                                            const int32_t* __restrict__ count,
+                                                            const int32_t* __restrict__ offset,
+                                                            const int32_t* __restrict__ sorted,
+                                                            const int32_t* __restrict__ rank,
                                                             const float* __restrict__ demb, float* __restrict__ dEw,
                                                             int D, int vocab) {
   const int t0 = blockIdx.x;
-  if (has_prev[t0]) return;
-  const int64_t row = clamp_id(ids[t0], vocab);
+  if (rank[t0] != 0) return;
+  const int id = clamp_id(ids[t0], vocab);
+  const int n = count[id], base = offset[id];
   for (int d = threadIdx.x; d < D; d += 256) {
     float acc = 0.f;
-    for (int t = t0; t >= 0; t = next[t]) acc += demb[(int64_t)t * D + d];
-    dEw[row * D + d] = acc;
+    for (int j = 0; j < n; ++j) acc += demb[(int64_t)sorted[base + j] * D + d];
+    dEw[(int64_t)id * D + d] = acc;
   }
 }
 __global__ void pos_sum_kernel(const float* __restrict__ demb, float* __restrict__ dEp, int nb, int S, int D) {
@@ -417,14 +455,25 @@ __global__ void pos_sum_kernel(const float* __restrict__ demb, float* __restrict
   for (int b = 0; b < nb; ++b) acc += demb[(int64_t)b * S * D + i];
   dEp[i] = acc;
 }
+size_t bert_embed_ws_ints(int ntok, int vocab) { return (size_t)3 * ((vocab + 3) & ~3) + (size_t)3 * ((ntok + 3) & ~3); }
 void bert_embed_bwd(const int32_t* ids, const float* demb, float* dEw, float* dEp, int32_t* ws, int nb, int S, int D,
                     int vocab, hipStream_t st) {
   const int ntok = nb * S;
-  int32_t* next = ws;
-  int32_t* has_prev = ws + ((ntok + 3) & ~3);  // keeps the second array 16-byte aligned
-  fill_zero(has_prev, (size_t)ntok * 4, st);
-  hipLaunchKernelGGL(token_chain_kernel, dim3(cdiv(ntok, 64)), dim3(64), 0, st, ids, next, has_prev, ntok);
-  hipLaunchKernelGGL(embed_scatter_kernel, dim3(ntok), dim3(256), 0, st, ids, next, has_prev, demb, dEw, D, vocab);
+  const size_t va = (size_t)((vocab + 3) & ~3), ta = (size_t)((ntok + 3) & ~3);   // 16-byte aligned sub-arrays
+  int32_t* count = ws;
+  int32_t* cursor = ws + va;
+  int32_t* offset = ws + 2 * va;
+  int32_t* bucket = ws + 3 * va;
+  int32_t* sorted = bucket + ta;
+  int32_t* rank = sorted + ta;
+  fill_zero(count, 2 * va * 4, st);   // count and cursor
+  const int tb = cdiv(ntok, 256);
+  hipLaunchKernelGGL(token_count_kernel, dim3(tb), dim3(256), 0, st, ids, count, ntok, vocab);
+  hipLaunchKernelGGL(token_offsets_kernel, dim3(1), dim3(1024), 0, st, count, offset, vocab);
+  hipLaunchKernelGGL(token_bucket_kernel, dim3(tb), dim3(256), 0, st, ids, offset, cursor, bucket, ntok, vocab);
+  hipLaunchKernelGGL(token_rank_kernel, dim3(tb), dim3(256), 0, st, ids, count, offset, bucket, sorted, rank, ntok, vocab);
+  hipLaunchKernelGGL(embed_scatter_kernel, dim3(ntok), dim3(256), 0, st, ids, count, offset, sorted, rank, demb, dEw, D,
+                     vocab);
   hipLaunchKernelGGL(pos_sum_kernel, dim3(cdiv(S * D, 256)), dim3(256), 0, st, demb, dEp, nb, S, D);
 }
 
