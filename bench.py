@@ -41,7 +41,8 @@ def parse():
     ap.add_argument("--micro-batches", type=int, default=1,
                     help="M > 1: a step is M micro-batches of the workload's batch accumulated into one optimizer step")
     ap.add_argument("--k", type=int, default=0, help="freeze boundary of the timed run")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the extra k = 6 / 9 measurements")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the extra measurements at other boundaries")
+    ap.add_argument("--sweep", default="", help="comma-separated boundaries of the sweep (default 1, L/4, L/2, 3L/4)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--host-tier", action="store_true",
                     help="keep every cached row in pinned host memory (window of 4 batches in HBM, next batch prefetched)")
@@ -172,7 +173,8 @@ def main():
     # ---- samples/s versus k (the boundary only moves up): uncached and cached ----
     if not a.no_sweep and a.k == 0:
         sweep = {"k0": round(sps, 1)}
-        for k in (1, w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4):
+        ks = [int(v) for v in a.sweep.split(",")] if a.sweep else [1, w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4]
+        for k in sorted(set(ks)):
             ctx.set_freeze_boundary(k)
             s_unc = timed(2, 8, use_cache=False)
             step(0, True); step(1, True); step(2, True); step(3, True)     # fill / advance the cache rows
