@@ -46,6 +46,11 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU baseline")
     ap.add_argument("--host-tier", action="store_true",
                     help="keep every cached row in pinned host memory (window of 4 batches in HBM, next batch prefetched)")
+    ap.add_argument("--schedule", default="",
+                    help="comma-separated boundaries, e.g. 0,3,6,9: after the main measurement, run --phase-steps steps "
+                         "at each boundary in turn (the boundary only moves up) and report samples/s per phase and the "
+                         "cost of each pt_set_freeze_boundary call")
+    ap.add_argument("--phase-steps", type=int, default=50)
     ap.add_argument("--profile-steps", type=int, default=3)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy four times (a kernel of known HBM traffic, for scaling "
@@ -169,6 +174,22 @@ def main():
                           "traffic": MEASURED_TRAFFIC.get((a.workload, a.k, dom)),
                           "avg_launch_us": round(1e3 * ms / n, 2), "launches_per_step": n // a.profile_steps,
                           "flops_per_launch": wk / n}
+
+    # ---- freeze schedule: fixed step counts per boundary, switch cost measured around the call ----
+    if a.schedule and a.k == 0:
+        phases = []
+        for k in [int(v) for v in a.schedule.split(",")]:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ctx.set_freeze_boundary(k)
+            torch.cuda.synchronize()
+            t_switch = time.perf_counter() - t0
+            s_phase = timed(0, a.phase_steps)
+            phases.append({"k": k, "steps": a.phase_steps, "samples_per_s": round(M * B / s_phase, 1),
+                           "step_tflops": round(flops_per_sample(w, k, False) * B * M / s_phase / 1e12, 1),
+                           "switch_ms": round(t_switch * 1e3, 3)})
+        result["schedule"] = phases
+        a.no_sweep = True   # the boundary has moved: the sweep below would start from the last phase
 
     # ---- samples/s versus k (the boundary only moves up): uncached and cached ----
     if not a.no_sweep and a.k == 0:
