@@ -93,3 +93,31 @@ def test_bf16_rounding_helper_is_round_to_nearest_even():
     assert np.array_equal(r, t)
     y = np.random.default_rng(1).standard_normal(10000).astype(np.float32)
     assert np.array_equal(synth.round_bf16(y), torch.tensor(y).to(torch.bfloat16).to(torch.float32).numpy())
+
+
+def test_host_tier_accumulator_and_head_configuration():
+    w = synth.workload("vit_b16")
+    base = binding.query_arena_bytes(binding.make_config(w, cache_slots=16))
+    row = w["S"] * w["D"] * 2
+    # the window rows of a host tier are the last rows of the cache arena
+    tiered = binding.query_arena_bytes(binding.make_config(w, cache_slots=16, host_slots=100, window_slots=2 * w["B"]))
+    assert tiered[3] == (16 + 2 * w["B"]) * row and tiered[:3] == base[:3]
+    # an accumulator adds one gradient-sized buffer to the state arena
+    acc = binding.query_arena_bytes(binding.make_config(w, cache_slots=16, grad_accum=True))
+    assert acc[1] * 3 == base[1] * 4 and acc[0] == base[0] and acc[2] == base[2]
+    for kw in (dict(host_slots=10, window_slots=2 * w["B"] - 1), dict(host_slots=0, window_slots=8),
+               dict(host_slots=-1, window_slots=0)):
+        with pytest.raises(binding.PtError) as e:
+            binding.query_arena_bytes(binding.make_config(w, cache_slots=16, **kw))
+        assert e.value.status == binding.PT_EINVAL
+    # heads: a BERT span head has two outputs, the classification head any number; unknown heads are refused
+    b = synth.workload("bert_base_qa")
+    cfg = binding.make_config(b)
+    cfg.n_out = 3
+    with pytest.raises(binding.PtError):
+        binding.query_arena_bytes(cfg)
+    cfg.head = binding.PT_HEAD_CLS
+    binding.query_arena_bytes(cfg)
+    cfg.head = 9
+    with pytest.raises(binding.PtError):
+        binding.query_arena_bytes(cfg)
