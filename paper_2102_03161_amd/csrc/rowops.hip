@@ -188,32 +188,33 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __r
 }
 
 // out[i] = sum over p of partial[p][i] in a fixed order: 32 columns per workgroup (one 128-byte line per
-// partial row), 8 interleaved row groups, each with four independent running sums so that several loads
-// are in flight; the sums are combined in a fixed order.  Column i goes to out0[i] for i < n0, to
-// out1[i - n0] for i < 2 n0, else to out2[i - 2 n0]; a null destination drops the column.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
-                                                              float* __restrict__ out0, int n0,
-                                                              float* __restrict__ out1, float* __restrict__ out2) {
-  __shared__ float red[8][33];
+// partial row), 32 interleaved row groups, each with eight independent running sums so that many loads are
+// in flight (the kernel is latency-bound: 9 MB over 72 workgroups); the sums are combined in a fixed order.
+// Column i goes to out0[i] for i < n0, to out1[i - n0] for i < 2 n0, else to out2[i - 2 n0]; a null
+// destination drops the column.
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
+                                                               float* __restrict__ out0, int n0,
+                                                               float* __restrict__ out1, float* __restrict__ out2) {
+  __shared__ float red[32][33];
   const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int i = blockIdx.x * 32 + c;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  float s[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) s[u] = 0.f;
   if (i < n) {
     int p = rg;
-    for (; p + 24 < np; p += 32) {
-      s0 += partial[(size_t)p * n + i];
-      s1 += partial[(size_t)(p + 8) * n + i];
-      s2 += partial[(size_t)(p + 16) * n + i];
-      s3 += partial[(size_t)(p + 24) * n + i];
+    for (; p + 7 * 32 < np; p += 8 * 32) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s[u] += partial[(size_t)(p + 32 * u) * n + i];
     }
-    for (; p < np; p += 8) s0 += partial[(size_t)p * n + i];
+    for (; p < np; p += 32) s[0] += partial[(size_t)p * n + i];
   }
-  red[rg][c] = (s0 + s1) + (s2 + s3);
+  red[rg][c] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
   __syncthreads();
   if (rg == 0 && i < n) {
     float t = red[0][c];
 #pragma unroll
-    for (int k = 1; k < 8; ++k) t += red[k][c];
+    for (int k = 1; k < 32; ++k) t += red[k][c];
     float* dst = i < n0 ? out0 : (i < 2 * n0 ? out1 : out2);
     if (dst) dst[i % n0] = t;
   }
@@ -244,7 +245,7 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
   else LN_BWD_V(bf16, bf16, bf16);
 #undef LN_BWD_V
 #undef LN_BWD
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(256), 0, st, partial, nb, 3 * D, dgamma, D,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(1024), 0, st, partial, nb, 3 * D, dgamma, D,
                      dbeta, dxsum);
 }
 
@@ -269,7 +270,7 @@ void colsum(int dt, const void* X, int64_t ld, int M, int N, float* out, float* 
   dim3 grid(cdiv(N, 256), nby);
   if (dt == 0) hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)X, ld, M, N, partial);
   else hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, st, (const bf16*)X, ld, M, N, partial);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 32)), dim3(256), 0, st, partial, nby, N, out, N,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(N, 32)), dim3(1024), 0, st, partial, nby, N, out, N,
                      (float*)nullptr, (float*)nullptr);
 }
 
@@ -601,7 +602,7 @@ void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* d
   const int nb = rows < kQaBlocks ? rows : kQaBlocks;
   if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, dx, partial, rows, D);
   else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, dx, partial, rows, D);
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 32)), dim3(256), 0, st, partial, nb, 2 * D + 2, dW,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 32)), dim3(1024), 0, st, partial, nb, 2 * D + 2, dW,
                      2 * D, db, (float*)nullptr);
 }
 
