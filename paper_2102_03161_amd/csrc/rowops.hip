@@ -292,8 +292,35 @@ __global__ void patchify_kernel(const float* __restrict__ img, const int64_t* __
     out[i] = from_f32<T>(img[((b * chans + c) * side + gy * p + py) * side + gx * p + px]);
   }
 }
+// four consecutive pixels of a patch row per thread (patch side and image side multiples of 4)
+template <typename T>
+__global__ void patchify4_kernel(const float* __restrict__ img, const int64_t* __restrict__ map, T* __restrict__ out,
+                                 int nb, int chans, int side, int p) {
+  const int g = side / p, pd4 = chans * p * p / 4, p4 = p / 4;
+  const int64_t total = (int64_t)nb * g * g * pd4;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+    const int j = (int)(i % pd4);
+    const int64_t pi = i / pd4;
+    const int gx = (int)(pi % g), gy = (int)((pi / g) % g);
+    const int64_t bo = pi / ((int64_t)g * g);
+    const int64_t b = map ? map[bo] : bo;
+    const int px = (j % p4) * 4, py = (j / p4) % p, c = j / (p4 * p);
+    const float4 v = *reinterpret_cast<const float4*>(img + ((b * chans + c) * side + gy * p + py) * side + gx * p + px);
+    const float a[4] = {v.x, v.y, v.z, v.w};
+    store4(out + i * 4, a);
+  }
+}
 void vit_patchify(int dt, const float* images, const int64_t* map, void* patches, int nb, int chans, int img, int patch,
                   hipStream_t st) {
+  if (patch % 4 == 0 && img % 4 == 0 && (reinterpret_cast<uintptr_t>(images) & 15) == 0 &&
+      (reinterpret_cast<uintptr_t>(patches) & 15) == 0) {
+    const int64_t total4 = (int64_t)nb * chans * img * img / 4;
+    const int blocks4 = (int)(cdiv64(total4, 256) < 65536 ? cdiv64(total4, 256) : 65536);
+    if (blocks4 <= 0) return;
+    if (dt == 0) hipLaunchKernelGGL(patchify4_kernel<float>, dim3(blocks4), dim3(256), 0, st, images, map, (float*)patches, nb, chans, img, patch);
+    else hipLaunchKernelGGL(patchify4_kernel<bf16>, dim3(blocks4), dim3(256), 0, st, images, map, (bf16*)patches, nb, chans, img, patch);
+    return;
+  }
   const int64_t total = (int64_t)nb * chans * img * img;
   const int blocks = (int)(cdiv64(total, 256) < 65536 ? cdiv64(total, 256) : 65536);
   if (blocks <= 0) return;
