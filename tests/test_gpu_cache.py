@@ -227,5 +227,18 @@ def test_host_tier_is_invisible_to_the_result(torch_mod, w):
     assert hs["rows_to_device"] > 0 and hs["rows_to_host"] >= 2 * (n_ids - 3)
     with pytest.raises(binding.PtError):
         tiered.frozen_forward(H.to_dev(torch, xs[:nb]), [0, 1, 2, n_ids])
+    with pytest.raises(binding.PtError):
+        tiered.cache_prefetch([n_ids])
+    # prefetch is best effort: ids of the HBM tier need nothing, and the window (2 B rows) bounds the rest
+    assert tiered.cache_prefetch([0, 1, 2]) == 0
+    assert tiered.cache_prefetch(list(range(3, n_ids))) == 2 * nb
+    assert tiered.cache_prefetch(list(range(3, n_ids))) == 0           # already staged / window full
+    call(list(range(3, 3 + nb)), 2)                                     # staged rows are used ...
+    call(list(range(n_ids - nb, n_ids)), 2)                             # ... and unstaged ones are fetched on demand
+    assert tiered.cache_stats() == plain.cache_stats()
     tiered.close()
+    plain.close()
+    # a context without a host tier has nothing to prefetch; one configured for it refuses to run unattached
+    plain = binding.Context(binding.make_config(w, B=nb, cache_slots=4))
+    assert plain.cache_prefetch([0, 1]) == 0
     plain.close()

@@ -386,3 +386,100 @@ def test_micro_batch_accumulation(torch_mod, wname, dtype):
     with pytest.raises(binding.PtError):     # grad_accum = 0: no accumulator in the state arena
         plain.accumulate_grads(first=True)
     plain.close()
+
+
+# ---- degenerate and boundary shapes -------------------------------------------------------------
+DEGENERATE = {
+    # one token, one head, one block: softmax over a single key, LayerNorm of the only row
+    "bert_s1": dict(arch="bert", L=1, D=64, H=1, F=64, S=1, n_out=3, img=0, patch=0, chans=0, vocab=5, max_pos=2,
+                    ln_eps=1e-12, B=2, optimizer="adamw", head="cls"),
+    # a single patch (S = 2), two classes
+    "vit_one_patch": dict(arch="vit", L=1, D=32, H=4, F=32, S=2, n_out=2, img=4, patch=4, chans=1, vocab=0, max_pos=0,
+                          ln_eps=1e-6, B=3, optimizer="sgdm"),
+    # head size 128 (the largest) and head size 32: the bf16 attention path for head sizes other than 64
+    "vit_dh128": dict(arch="vit", L=2, D=256, H=2, F=512, S=37, n_out=7, img=24, patch=4, chans=3, vocab=0, max_pos=0,
+                      ln_eps=1e-6, B=3, optimizer="adamw"),
+    "bert_dh32": dict(arch="bert", L=2, D=128, H=4, F=256, S=45, n_out=2, img=0, patch=0, chans=0, vocab=50, max_pos=64,
+                      ln_eps=1e-12, B=3, optimizer="adamw"),
+    # widths that are no multiple of any tile: D = 72 (head size 24), F = 100, 13 classes
+    "vit_ragged": dict(arch="vit", L=2, D=72, H=3, F=100, S=10, n_out=13, img=6, patch=2, chans=3, vocab=0, max_pos=0,
+                       ln_eps=1e-6, B=5, optimizer="sgdm"),
+}
+
+
+@pytest.mark.parametrize("name", list(DEGENERATE))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_degenerate_and_odd_shapes(torch_mod, name, dtype):
+    w = dict(DEGENERATE[name], dtype=dtype)
+    for k in (0, w["L"]):
+        run_case(torch_mod, w, k, w["B"], seed=13, tol=TOL[dtype])
+
+
+def test_span_head_over_one_position_gives_exact_zeros(torch_mod):
+    """S = 1 with the span head: each softmax runs over a single position, so the loss and every gradient are
+    exactly zero, on the GPU as in the oracle."""
+    torch = torch_mod
+    w = dict(DEGENERATE["bert_s1"], n_out=2, head="default", dtype="bf16")
+    ctx = binding.Context(binding.make_config(w))
+    vals = H.init_values(w, ctx, 3)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 3, w["B"])
+    hk = ctx.frozen_forward(H.to_dev(torch, x))
+    assert ctx.active_fwd_bwd(hk, H.to_dev(torch, y)) == 0.0
+    assert not np.any(ctx.layer_grad_norms())
+    for name, g in H.gpu_read_all(ctx, binding.KIND_GRAD).items():
+        assert not np.any(g), name
+    o = H.oracle_step(w, vals, x, y, 0)
+    assert o["loss"] == 0.0 and all(not np.any(g) for g in o["grads"].values())
+    ctx.close()
+
+
+def test_five_steps_track_the_oracle(torch_mod):
+    """Optimizer state over several steps (step counter, bias correction, momentum, dropped state) with a
+    boundary move in the middle.  Each step is checked from the GPU's own parameters: the loss against the
+    oracle evaluated at those parameters, and the update against the oracle's rule applied to the GPU's
+    gradients with the oracle's running state.  (Whole trajectories cannot be compared for AdamW: a gradient
+    that is exactly zero in fp64 is round-off in fp32, and an Adam step on round-off is sign-like.)"""
+    torch = torch_mod
+    for wname in ("vit_tiny", "bert_tiny"):
+        w = synth.workload(wname)
+        print(f"five steps {wname}", flush=True)
+        ctx = binding.Context(binding.make_config(w))
+        vals = H.init_values(w, ctx, 17)
+        H.load_params(ctx, vals)
+        cfg = oracle_cfg(w)
+        st = None
+        hp = H.f32_exact(**dict(H.HP, lr=0.01))
+        for step in range(5):
+            k = 0 if step < 3 else 1
+            x, y = H.batch_for(w, 17, w["B"], tag=f"s{step}")
+            ctx.set_freeze_boundary(k)
+            before = H.gpu_read_all(ctx, binding.KIND_PARAM)
+            hk = ctx.frozen_forward(H.to_dev(torch, x))
+            g_loss = ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+            ctx.layer_grad_norms()
+            g_grads = H.gpu_read_all(ctx, binding.KIND_GRAD)
+            ctx.optimizer_step(**hp)
+            after = H.gpu_read_all(ctx, binding.KIND_PARAM)
+            p = {n: a.astype(np.float64) for n, a in before.items()}
+            xx = x.astype(np.float64) if w["arch"] == "vit" else x
+            h, fs = orc.frozen_forward(cfg, p, xx, k)
+            o_loss, _, _ = orc.active_fwd_bwd(cfg, p, h, y, k, fs)
+            assert abs(g_loss - o_loss) <= 1e-4 * abs(o_loss), (wname, step, g_loss, o_loss)
+            if st is None:
+                st = orc.new_opt_state(p)
+            if step == 3:
+                orc.drop_frozen_state(cfg, st, 1)   # the boundary moved before this step
+            g64 = {n: a.astype(np.float64) for n, a in g_grads.items()}
+            if w["optimizer"] == "adamw":
+                orc.adamw_step(cfg, p, g64, st, k, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"])
+            else:
+                orc.sgdm_step(cfg, p, g64, st, k, hp["lr"], hp["momentum"], hp["weight_decay"])
+            for name, a in after.items():
+                d_ref = p[name] - before[name].astype(np.float64)
+                d_got = a.astype(np.float64) - before[name].astype(np.float64)
+                # the oracle's moments are exact, the GPU's carry fp32 round-off from every earlier step
+                lim = (step + 1) * (2e-5 * float(np.max(np.abs(d_ref))) + 2e-7 * float(np.max(np.abs(before[name]))))
+                assert float(np.max(np.abs(d_got - d_ref))) <= lim, (wname, step, name)
+        assert ctx.get_step_count() == 5
+        ctx.close()
