@@ -267,10 +267,10 @@ __global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, Split
                                                          m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
 }
 
-// out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread)
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
-                                                            float* __restrict__ out, int vec) {
-  const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+// out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread).  A second, short
+// vector (the column-sum partials of the same product) may ride along in the last workgroups.
+__device__ __forceinline__ void splitk_sum4(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
+                                            int vec, int64_t i) {
   if (vec && i + 3 < n) {
     float4 s = *reinterpret_cast<const float4*>(part + i);
     for (int z = 1; z < splits; ++z) {
@@ -286,10 +286,27 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
   }
 }
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
+                                                            float* __restrict__ out, int vec, int blocks_main,
+                                                            const float* __restrict__ part2, int64_t n2,
+                                                            float* __restrict__ out2, int vec2) {
+  if ((int)blockIdx.x < blocks_main) {
+    splitk_sum4(part, splits, n, out, vec, ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4);
+  } else {
+    const int64_t i = ((int64_t)(blockIdx.x - blocks_main) * 256 + threadIdx.x) * 4;
+    if (i < n2) splitk_sum4(part2, splits, n2, out2, vec2, i);
+  }
+}
 
-void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, hipStream_t st) {
-  const int vec = (n % 4 == 0 && (reinterpret_cast<uintptr_t>(part) % 16) == 0 && (reinterpret_cast<uintptr_t>(out) % 16) == 0) ? 1 : 0;
-  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)cdiv64(n, 1024)), dim3(256), 0, st, part, splits, n, out, vec);
+static int vec_ok4(const float* part, int64_t n, const float* out) {
+  return (n % 4 == 0 && (reinterpret_cast<uintptr_t>(part) % 16) == 0 && (reinterpret_cast<uintptr_t>(out) % 16) == 0) ? 1 : 0;
+}
+void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, const float* part2, int64_t n2, float* out2,
+                        hipStream_t st) {
+  const int blocks_main = (int)cdiv64(n, 1024);
+  const int blocks2 = part2 ? (int)cdiv64(n2, 1024) : 0;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)(blocks_main + blocks2)), dim3(256), 0, st, part, splits, n, out,
+                     vec_ok4(part, n, out), blocks_main, part2, part2 ? n2 : 0, out2, part2 ? vec_ok4(part2, n2, out2) : 0);
 }
 
 // ---------------------------------------------------------------------------
@@ -387,8 +404,7 @@ static void dispatch_mfma(const Gemm& a, hipStream_t st) {
     if (splits > 1) {
       launch_mfma<C, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
       // ldc == N is required for the slab layout
-      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, st);
-      if (a.colsum_out) gemm_splitk_reduce(cs_part, splits, a.N, a.colsum_out, st);
+      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
     } else {
       launch_mfma<C, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
     }

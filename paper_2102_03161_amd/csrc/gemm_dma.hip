@@ -345,8 +345,7 @@ static void dispatch_dma(const Gemm& a, hipStream_t st) {
     if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
     if (splits > 1) {
       launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
-      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, st);
-      if (a.colsum_out) gemm_splitk_reduce(cs_part, splits, a.N, a.colsum_out, st);
+      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
     } else {
       launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
     }

@@ -134,7 +134,8 @@ __device__ __forceinline__ void staged_epilogue(const GemmDev<bf16>& g, void* Cb
 
 // host side
 bool gemm_epilogue_vec_ok(const Gemm& a);
-void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, hipStream_t st);
+void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, const float* part2, int64_t n2, float* out2,
+                        hipStream_t st);
 bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
 
