@@ -401,6 +401,11 @@ DEGENERATE = {
                       ln_eps=1e-6, B=3, optimizer="adamw"),
     "bert_dh32": dict(arch="bert", L=2, D=128, H=4, F=256, S=45, n_out=2, img=0, patch=0, chans=0, vocab=50, max_pos=64,
                       ln_eps=1e-12, B=3, optimizer="adamw"),
+    # widths that are multiples of 32 but of no tile size: the DMA matrix-core path with clamped edge tiles
+    "vit_d96": dict(arch="vit", L=2, D=96, H=3, F=160, S=26, n_out=9, img=20, patch=4, chans=2, vocab=0, max_pos=0,
+                    ln_eps=1e-6, B=7, optimizer="adamw"),
+    "bert_d192": dict(arch="bert", L=2, D=192, H=3, F=224, S=41, n_out=2, img=0, patch=0, chans=0, vocab=60, max_pos=48,
+                      ln_eps=1e-12, B=5, optimizer="adamw"),
     # widths that are no multiple of any tile: D = 72 (head size 24), F = 100, 13 classes
     "vit_ragged": dict(arch="vit", L=2, D=72, H=3, F=100, S=10, n_out=13, img=6, patch=2, chans=3, vocab=0, max_pos=0,
                        ln_eps=1e-6, B=5, optimizer="sgdm"),
@@ -483,3 +488,13 @@ def test_five_steps_track_the_oracle(torch_mod):
                 assert float(np.max(np.abs(d_got - d_ref))) <= lim, (wname, step, name)
         assert ctx.get_step_count() == 5
         ctx.close()
+
+
+@pytest.mark.parametrize("S", [31, 32, 33, 224, 225, 288, 512, 513])
+def test_attention_sequence_length_edges_bf16(torch_mod, S):
+    """Head size 64 in bf16 across the sequence lengths where the attention kernels change shape: whole and
+    ragged 32-row tiles, the largest length served from LDS (224 forward, 512 backward), one more than each,
+    and a length whose owned rows split over two workgroups."""
+    w = dict(arch="bert", L=1, D=128, H=2, F=128, S=S, n_out=2, img=0, patch=0, chans=0, vocab=40, max_pos=S,
+             ln_eps=1e-12, B=2, dtype="bf16", optimizer="adamw")
+    run_case(torch_mod, w, 0, 2, seed=19 + S, tol=TOL["bf16"])
