@@ -439,6 +439,8 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
       if (g_cfg_override < 0) {
         v = (a.ta || a.N >= 3072) ? 2 : 1;
         if (a.tb && a.N <= 1024 && a.K >= 768 && a.M >= 4096) v = 3;
+        if (!a.ta && !a.tb && a.N >= 2048 && a.N < 3072 && a.M >= 4096) v = 3;   // QKV projection
+        if (a.ta && (int64_t)a.M * a.N <= 1024 * 1024) v = 1;                     // small weight gradients
       }
       gemm_dma(a, v, st);
       return;

@@ -264,6 +264,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
+    // nothing may be scheduled across this point: without it the compiler sinks the MFMAs above below the
+    // second wait, and every fragment read of the tile is then waited for before the first MFMA issues
+    __builtin_amdgcn_sched_barrier(0);
     wait_lds<0>(a1, b1);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
