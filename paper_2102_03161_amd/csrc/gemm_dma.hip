@@ -41,35 +41,44 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
   return (unsigned)(size_t)((__attribute__((address_space(3))) const void*)(p));
 }
 
-// ---- k-major tile [ROWS][32]: 64-byte rows, slot (row, c') holds chunk c' ^ ((row >> 2) & 3) ----
-template <int ROWS, int NW, int NFRAG>
+// ---- k-major tile [ROWS][BK]: rows of 2*BK bytes ----
+// BK = 64 makes a row segment a whole 128-byte cache line.  With BK = 32 every line is requested twice, half
+// a line at a time, one k-tile apart, and the L2 -> L1 path, which moves whole lines, carries twice the bytes:
+// a kernel that only issues these loads (the 12608 x 768 x 3072 product's 128x128 tiling, three workgroups
+// per CU) takes 76.6 us with 64-byte segments and 49.9 us with 128-byte ones, and the product itself ran in
+// 85 us, i.e. at the speed of its loads.
+// Slot (row, c') holds chunk c' ^ swzk(row); swzk spreads the 16 rows that the lanes of a quarter-wave read
+// together over all 64 banks.
+template <int ROWS, int NW, int NFRAG, int BK>
 struct TileK {
-  static constexpr int BYTES = ROWS * 64, LOADS = ROWS / 16 / NW;  // wave-wide loads per wave
-  static_assert(ROWS % (16 * NW) == 0, "rows must divide over the waves");
+  static constexpr int ROWB = BK * 2, CPR = ROWB / 16, RPL = 1024 / ROWB;   // row bytes, chunks per row, rows per load
+  static constexpr int BYTES = ROWS * ROWB, LOADS = ROWS / RPL / NW;        // wave-wide loads per wave
+  static constexpr int KS = BK / 16;                                        // k-steps per tile
+  static_assert(ROWS % (RPL * NW) == 0, "rows must divide over the waves");
+  static_assert(BK == 32 || BK == 64, "64- or 128-byte rows");
   const bf16* gp[LOADS];   // this lane's source of each load, advanced by one tile per issue
-  int64_t gstep;
-  unsigned foff[2];        // fragment byte offsets within the tile for k-step 0 / 1 (row block 0)
+  unsigned foff[KS];       // fragment byte offsets within the tile per k-step (row block 0)
 
+  static __device__ __forceinline__ constexpr int swzk(int row) { return BK == 32 ? ((row >> 2) & 3) : ((row >> 1) & 7); }
   __device__ __forceinline__ void setup(const bf16* p, int64_t ld, int R, int r0, int k0, int rbase, int wave,
                                         int lane) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
-      const int row = 16 * (wave * LOADS + i) + (lane >> 2);
-      const int c = (lane & 3) ^ ((row >> 2) & 3);
+      const int row = RPL * (wave * LOADS + i) + lane / CPR;
+      const int c = (lane % CPR) ^ swzk(row);
       int gr = r0 + row;
       gr = gr < R ? gr : R - 1;
       gp[i] = p + (int64_t)gr * ld + k0 + 8 * c;
     }
-    gstep = kBK;
     const int row = rbase + (lane & 31);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) foff[ks] = row * 64 + (((2 * ks + (lane >> 5)) ^ ((row >> 2) & 3)) << 4);
+    for (int ks = 0; ks < KS; ++ks) foff[ks] = row * ROWB + (((2 * ks + (lane >> 5)) ^ swzk(row)) << 4);
   }
   __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
       __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
-      gp[i] += gstep;
+      gp[i] += BK;
     }
   }
   // fragments of all row blocks for one k-step, issued as inline assembly (see TileS::read)
@@ -78,11 +87,11 @@ struct TileK {
     const unsigned addr = lds_addr(tile) + foff[ks];
 #pragma unroll
     for (int i = 0; i < NFRAG; ++i)
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[i]) : "v"(addr), "n"(i * 2048));
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(f[i]) : "v"(addr), "n"(i * 32 * ROWB));
   }
 };
 
-// ---- strided tile [32][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ swz(k) ----
+// ---- strided tile [BK][ROWS]: rows of ROWS*2 bytes, slot (k, c') holds chunk c' ^ swz(k) ----
 // A transpose read has its 16-lane groups address 4 k rows x 32 bytes; the groups of one half-wave differ by
 // 32 bytes in the row (or by 8 k rows).  Rows are a multiple of 256 bytes, so only the chunk index decides
 // the bank: swz moves the four k rows of a group to four different 64-byte quarters of the bank space and
@@ -95,12 +104,13 @@ __device__ __forceinline__ constexpr int swz(int k) { return ((k & 3) << 2) ^ ((
 // global->LDS load before a transpose read, which serialises the pipeline, and explicit lgkmcnt waits
 // let the reads of the second k-step overlap the MFMAs of the first.  LDS operations return in order,
 // so "at most n outstanding" means everything issued before the last n has arrived.
-template <int ROWS, int NW, int NFRAG>
+template <int ROWS, int NW, int NFRAG, int BK>
 struct TileS {
   static constexpr int ROWB = ROWS * 2, KPL = 1024 / ROWB;       // k rows per wave-wide load
-  static constexpr int BYTES = kBK * ROWB, LOADS = kBK / KPL / NW;
+  static constexpr int BYTES = BK * ROWB, LOADS = BK / KPL / NW;
   static constexpr int CPR = ROWS / 8;                           // 16-byte chunks per k row
-  static_assert(kBK % (KPL * NW) == 0 && KPL >= 1, "tile must divide over the waves");
+  static constexpr int KS = BK / 16;
+  static_assert(BK % (KPL * NW) == 0 && KPL >= 1, "tile must divide over the waves");
   static_assert(CPR >= 16, "swz permutes chunks within groups of 16");
   const bf16* gp[LOADS];
   int64_t gstep;
@@ -116,7 +126,7 @@ struct TileS {
       gr = gr + 8 <= R ? gr : (R - 8);   // R >= 8 and R % 8 == 0 are checked by the host
       gp[i] = p + (int64_t)(k0 + k) * ld + gr;
     }
-    gstep = (int64_t)kBK * ld;
+    gstep = (int64_t)BK * ld;
     const int l16 = lane & 15, grp = lane >> 4;
     const int k = 8 * (grp >> 1) + (l16 >> 2);
 #pragma unroll
@@ -140,7 +150,7 @@ struct TileS {
     for (int j = 0; j < NFRAG; ++j) {
       union { u32x2 h[2]; bf16x8 v; } t;
       const unsigned addr = base + foff[j] + 16 * ks * ROWB;
-      // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 and +16 rows are constant offsets (swz uses bits 0, 1, 3 of k)
+      // k rows 16*ks + 8*half + {0..3} and {4..7}: +4 and +16*ks rows are constant offsets (swz uses bits 0, 1, 3 of k)
       asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(t.h[0]) : "v"(addr));
       asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(addr), "n"(4 * ROWB));
       f[j] = t.v;
@@ -150,7 +160,7 @@ struct TileS {
   static __device__ __forceinline__ float colsum(const unsigned char* lds, int n) {
     float s = 0.f;
 #pragma unroll
-    for (int k = 0; k < kBK; ++k) {
+    for (int k = 0; k < BK; ++k) {
       const int c = (n >> 3) ^ swz(k);
       s += to_f32(*reinterpret_cast<const bf16*>(lds + k * ROWB + c * 16 + (n & 7) * 2));
     }
@@ -158,8 +168,8 @@ struct TileS {
   }
 };
 
-template <bool STRIDED, int ROWS, int NW, int NFRAG> struct TileSel { typedef TileK<ROWS, NW, NFRAG> type; };
-template <int ROWS, int NW, int NFRAG> struct TileSel<true, ROWS, NW, NFRAG> { typedef TileS<ROWS, NW, NFRAG> type; };
+template <bool STRIDED, int ROWS, int NW, int NFRAG, int BK> struct TileSel { typedef TileK<ROWS, NW, NFRAG, BK> type; };
+template <int ROWS, int NW, int NFRAG, int BK> struct TileSel<true, ROWS, NW, NFRAG, BK> { typedef TileS<ROWS, NW, NFRAG, BK> type; };
 
 // s_waitcnt lgkmcnt(PENDING) that the given fragments depend on, so that no MFMA using them can be
 // scheduled before it
@@ -172,20 +182,29 @@ __device__ __forceinline__ void wait_lds(bf16x8 (&a)[NA], bf16x8 (&b)[NB]) {
   for (int i = 0; i < NB; ++i) asm volatile("" : "+v"(b[i]));
 }
 
-template <int BM, int BN, int WGM, int WGN, int kNS, bool TA, bool TB, int EPI, typename TC>
+// s_waitcnt vmcnt(n), n < 64 (the count is split over two bit fields); expcnt and lgkmcnt are left open
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int BM, int BN, int WGM, int WGN, int kNS, int BK, bool TA, bool TB, int EPI, typename TC>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
                                                                   int group_n, int vec_ok) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
-  typedef typename TileSel<TA, BM, NW, TM>::type LA;    // A strided when stored [K,M]
-  typedef typename TileSel<!TB, BN, NW, TN>::type LB;   // B strided when stored [K,N]
+  typedef typename TileSel<TA, BM, NW, TM, BK>::type LA;    // A strided when stored [K,M]
+  typedef typename TileSel<!TB, BN, NW, TN, BK>::type LB;   // B strided when stored [K,N]
+  constexpr int KS = BK / 16;                                // k-steps (MFMA depth 16) per tile
   constexpr int STAGE = LA::BYTES + LB::BYTES;
   constexpr int STAGE_LD = WTN + 4;
   constexpr int EPI_BYTES = NW * 32 * STAGE_LD * 4;
   constexpr int LDS_BYTES = kNS * STAGE > EPI_BYTES ? kNS * STAGE : EPI_BYTES;
   constexpr int LPT = LA::LOADS + LB::LOADS;  // DMA loads per thread per tile
-  static_assert(LPT * 2 <= 15, "vmcnt immediates below assume few loads per tile");
-  static_assert(kBK == 32, "two k-steps per tile");
+  constexpr int RPS = LA::READS + LB::READS;  // LDS read instructions per k-step
+  static_assert(LPT * (kNS >= 4 ? 2 : 1) < 64, "vmcnt is a 6-bit counter");
+  static_assert(RPS <= 15, "lgkmcnt is a 4-bit counter");
+  static_assert(kNS >= 2 && LDS_BYTES <= 160 * 1024, "stages must fit the LDS");
   __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -213,7 +232,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk_all = g.K / kBK;
+  const int nk_all = g.K / BK;
   const int kt0 = split * sp.tiles_per_split;
   const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
   const int n = kt1 > kt0 ? kt1 - kt0 : 0;
@@ -222,8 +241,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 
   LA ta;
   LB tb;
-  ta.setup(g.A, g.lda, g.M, m0, kt0 * kBK, wm * WTM, wave, lane);
-  tb.setup(g.B, g.ldb, g.N, n0, kt0 * kBK, wn * WTN, wave, lane);
+  ta.setup(g.A, g.lda, g.M, m0, kt0 * BK, wm * WTM, wave, lane);
+  tb.setup(g.B, g.ldb, g.N, n0, kt0 * BK, wn * WTN, wave, lane);
 
   int fill = 0;  // stage the next issued tile goes to
 #pragma unroll
@@ -237,9 +256,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 
   for (int it = 0; it < n; ++it) {
     // this wave's loads of tile `it` have landed when at most the loads of the later tiles are pending
-    if (kNS >= 4 && it + 2 < n) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * LPT));
-    else if (it + 1 < n) __builtin_amdgcn_s_waitcnt(0x0F70 | LPT);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (kNS >= 4 && it + 2 < n) wait_vm<2 * LPT>();
+    else if (kNS >= 3 && it + 1 < n) wait_vm<LPT>();
+    else wait_vm<0>();
     compiler_fence();
     __builtin_amdgcn_s_barrier();   // everybody's loads of tile `it` have landed, and tile it-1 is fully consumed
     compiler_fence();
@@ -251,27 +270,32 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
     const unsigned char* sa = lds + cur * STAGE;
     const unsigned char* sb = sa + LA::BYTES;
     cur = cur + 1 == kNS ? 0 : cur + 1;
-    // all fragment reads of the tile are issued up front; the MFMAs of the first k-step start as soon as
-    // its fragments are in, while the second k-step's reads are still in flight
-    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
-    ta.read(sa, 0, a0);
-    tb.read(sb, 0, b0);
-    ta.read(sa, 1, a1);
-    tb.read(sb, 1, b1);
-    static_assert(LA::READS + LB::READS <= 15, "lgkmcnt is a 4-bit counter");
-    wait_lds<LA::READS + LB::READS>(a0, b0);
+    // Two fragment sets in registers.  The reads of k-steps 0 and 1 are issued up front; the MFMAs of a
+    // k-step start as soon as its fragments are in, and the reads of k-step s+2 are issued behind the
+    // MFMAs of k-step s into the set those MFMAs have just consumed, so LDS reads overlap matrix work.
+    // LDS operations return in order: "at most RPS outstanding" means the older set has arrived.
+    bf16x8 fa[2][TM], fb[2][TN];
+    ta.read(sa, 0, fa[0]);
+    tb.read(sb, 0, fb[0]);
+    ta.read(sa, 1, fa[1]);
+    tb.read(sb, 1, fb[1]);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) wait_lds<RPS>(fa[ks & 1], fb[ks & 1]);
+      else wait_lds<0>(fa[ks & 1], fb[ks & 1]);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[i], b0[j], acc[i][j], 0, 0, 0);
-    // nothing may be scheduled across this point: without it the compiler sinks the MFMAs above below the
-    // second wait, and every fragment read of the tile is then waited for before the first MFMA issues
-    __builtin_amdgcn_sched_barrier(0);
-    wait_lds<0>(a1, b1);
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[i], b1[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      // nothing may be scheduled across this point: without it the compiler sinks the MFMAs above below the
+      // next wait, and every fragment read of the tile is then waited for before the first MFMA issues
+      __builtin_amdgcn_sched_barrier(0);
+      if (ks + 2 < KS) {
+        ta.read(sa, ks + 2, fa[ks & 1]);
+        tb.read(sb, ks + 2, fb[ks & 1]);
+      }
+    }
     if constexpr (!TB) {
       if (do_colsum && tid < BN) cs += LB::colsum(sb, tid);
     }
@@ -291,12 +315,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 int g_group_n = 0;                  // forced column-group width (tuning); 0 = derive from g_group_bytes
 int64_t g_group_bytes = 1536 << 10;  // L2 bytes a column group's B panels may take
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool TA, bool TB, int EPI, typename TC>
+template <int BM, int BN, int WGM, int WGN, int NS, int BK, bool TA, bool TB, int EPI, typename TC>
 void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
   GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, cbase ? (void*)cbase : a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
                   (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
   const int tiles_m = cdiv(a.M, BM), tiles_n = cdiv(a.N, BN), total = tiles_m * tiles_n;
-  const int nk = a.K / kBK;
+  const int nk = a.K / BK;
   SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
   dim3 grid(8 * cdiv(total * splits, 8), 1, 1);
   // column-group width: the B panels of a group (whole K) should fit beside the streaming A panels in a 4 MB L2
@@ -307,7 +331,7 @@ void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* co
     if (group_n < 1) group_n = 1;
   }
   if (group_n > tiles_n) group_n = tiles_n;
-  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, TA, TB, EPI, TC>), grid, dim3(64 * WGM * WGN), 0, st, g, sp,
+  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, BK, TA, TB, EPI, TC>), grid, dim3(64 * WGM * WGN), 0, st, g, sp,
                      tiles_m, tiles_n, group_n, gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
@@ -331,51 +355,71 @@ void gemm_set_group(int tiles, long bytes) {
   if (bytes > 0) g_group_bytes = bytes;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS>
-static void dispatch_dma(const Gemm& a, hipStream_t st) {
-  if (a.ta) {
-    const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nk = a.K / kBK;
-    int splits = 1;
-    const int64_t mn = (int64_t)a.M * a.N;
-    if (a.ws) {
-      splits = g_split_target / tiles;
-      if (splits > nk / 8) splits = nk / 8;
-      if (splits > 16) splits = 16;
-      if (splits < 1) splits = 1;
-      while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
-    }
-    float* cs_part = nullptr;
-    if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
-    if (splits > 1) {
-      launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
-      gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
-    } else {
-      launch_dma<BM, BN, WGM, WGN, NS, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
-    }
-    return;
+// weight gradients (both operands strided in memory: whole cache lines whatever BK): BK = 32, three stages
+template <int BM, int BN, int WGM, int WGN>
+static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
+  constexpr int NS = 3, BK = 32;
+  const int tiles = cdiv(a.M, BM) * cdiv(a.N, BN), nk = a.K / BK;
+  int splits = 1;
+  const int64_t mn = (int64_t)a.M * a.N;
+  if (a.ws) {
+    splits = g_split_target / tiles;
+    if (splits > nk / 8) splits = nk / 8;
+    if (splits > 16) splits = 16;
+    if (splits < 1) splits = 1;
+    while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
   }
-  if (a.tb) {
-    if (a.c_f32) launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_RES, float>(a, 1, nullptr, 0, nullptr, st);
-    else if (a.epi == EPI_STORE) launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_STORE, bf16>(a, 1, nullptr, 0, nullptr, st);
-    else launch_dma<BM, BN, WGM, WGN, NS, false, true, EPI_MUL_DGELU, bf16>(a, 1, nullptr, 0, nullptr, st);
-    return;
-  }
-  if (a.c_f32) {
-    if (a.epi == EPI_BIAS) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS, float>(a, 1, nullptr, 0, nullptr, st);
-    else launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_RES, float>(a, 1, nullptr, 0, nullptr, st);
+  float* cs_part = nullptr;
+  if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
+  if (splits > 1) {
+    launch_dma<BM, BN, WGM, WGN, NS, BK, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
+    gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
   } else {
-    if (a.epi == EPI_BIAS) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS, bf16>(a, 1, nullptr, 0, nullptr, st);
-    else if (a.epi == EPI_BIAS_RES) launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_RES, bf16>(a, 1, nullptr, 0, nullptr, st);
-    else launch_dma<BM, BN, WGM, WGN, NS, false, false, EPI_BIAS_GELU, bf16>(a, 1, nullptr, 0, nullptr, st);
+    launch_dma<BM, BN, WGM, WGN, NS, BK, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
   }
 }
 
+// forward and input-gradient products (at least one k-major operand)
+template <int BM, int BN, int WGM, int WGN, int NS, int BK>
+static void dispatch_fwd(const Gemm& a, hipStream_t st) {
+#define PT_L(TB_, EPI_, TC_) launch_dma<BM, BN, WGM, WGN, NS, BK, false, TB_, EPI_, TC_>(a, 1, nullptr, 0, nullptr, st)
+  if (a.tb) {
+    if (a.c_f32) PT_L(true, EPI_RES, float);
+    else if (a.epi == EPI_STORE) PT_L(true, EPI_STORE, bf16);
+    else PT_L(true, EPI_MUL_DGELU, bf16);
+    return;
+  }
+  if (a.c_f32) {
+    if (a.epi == EPI_BIAS) PT_L(false, EPI_BIAS, float);
+    else PT_L(false, EPI_BIAS_RES, float);
+  } else {
+    if (a.epi == EPI_BIAS) PT_L(false, EPI_BIAS, bf16);
+    else if (a.epi == EPI_BIAS_RES) PT_L(false, EPI_BIAS_RES, bf16);
+    else PT_L(false, EPI_BIAS_GELU, bf16);
+  }
+#undef PT_L
+}
+
 void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
+  if (a.ta) {
+    switch (variant) {
+      case 2: dispatch_wgrad<256, 128, 4, 2>(a, st); break;
+      case 3: dispatch_wgrad<256, 256, 2, 4>(a, st); break;
+      default: dispatch_wgrad<128, 128, 2, 2>(a, st); break;
+    }
+    return;
+  }
+  if (a.K % 64 != 0) {   // 64-wide k tiles need K to be a multiple of 64
+    dispatch_fwd<128, 128, 2, 2, 3, 32>(a, st);
+    return;
+  }
+  // Measured at the ViT-B / BERT-base shapes: 64-wide k tiles (whole cache lines for k-major operands) pay
+  // for the 256x256 tiling (3-10 %); the smaller tilings then fit one workgroup less per CU and lose, so
+  // they keep 32-wide tiles and three stages.
   switch (variant) {
-    case 1: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
-    case 2: dispatch_dma<256, 128, 4, 2, 3>(a, st); break;
-    case 3: dispatch_dma<256, 256, 2, 4, 3>(a, st); break;
-    default: dispatch_dma<128, 128, 2, 2, 3>(a, st); break;
+    case 2: dispatch_fwd<256, 128, 4, 2, 3, 32>(a, st); break;
+    case 3: dispatch_fwd<256, 256, 2, 4, 2, 64>(a, st); break;
+    default: dispatch_fwd<128, 128, 2, 2, 3, 32>(a, st); break;
   }
 }
 
