@@ -29,9 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
 # read for the --calibrate-copy kernel; the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0, "gemm_nn"): 128898789 + 60812042,    # fetched + written, forward products
-    ("vit_b16", 0, "gemm_nt"): 160315929 + 33200671,    # input-gradient products
-    ("vit_b16", 0, "gemm_tn"): 170834110 + 63766387,    # weight-gradient products incl. their split-K reduction
+    ("vit_b16", 0, "gemm_nn"): 129244402 + 60812042,    # fetched + written, forward products
+    ("vit_b16", 0, "gemm_nt"): 160936801 + 33200671,    # input-gradient products
+    ("vit_b16", 0, "gemm_tn"): 169490624 + 62538963,    # weight-gradient products incl. their split-K reduction
 }
 
 
