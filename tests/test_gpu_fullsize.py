@@ -107,3 +107,25 @@ def test_full_batch_cache_hit_equals_recompute_and_trains_the_same(torch_mod, vi
     assert np.array_equal(ctx.read_tensor(dict((n, t) for t, n, *_ in ctx.tensors())["blk6.Wqkv"], binding.KIND_GRAD), g_miss)
     norms = ctx.layer_grad_norms()
     assert np.all(norms[:7] == 0.0) and np.all(norms[7:] > 0.0)
+
+
+def test_full_batch_step_is_bit_reproducible(torch_mod, vitb):
+    """Two runs of the full-size step from the same state give the same bits: every reduction has a fixed order
+    (split-K slabs, LayerNorm and bias partials, attention, norms), whatever order the workgroups run in."""
+    torch = torch_mod
+    w, ctx, vals, x, y = vitb
+    probe = ["front.W_pe", "front.pos", "blk0.Wqkv", "blk0.bqkv", "blk3.ln2_g", "blk5.W1", "blk7.Wo", "blk11.W2",
+             "blk11.b2", "head.W"]
+    tid = {name: t for t, name, *_ in ctx.tensors()}
+    other = binding.Context(binding.make_config(w, cache_slots=w["B"]))
+    H.load_params(other, {n: ctx.read_tensor(tid[n], binding.KIND_PARAM) for n in tid})
+    other.set_freeze_boundary(ctx.get_freeze_boundary())
+    outs = []
+    for c in (ctx, other, ctx):
+        loss = forward_backward(torch, c, w, x, y)
+        outs.append((loss, c.layer_grad_norms(), {n: c.read_tensor(tid[n], binding.KIND_GRAD) for n in probe}))
+    other.close()
+    for loss, norms, grads in outs[1:]:
+        assert loss == outs[0][0] and np.array_equal(norms, outs[0][1])
+        for n in probe:
+            assert np.array_equal(grads[n], outs[0][2][n]), n
