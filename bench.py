@@ -163,8 +163,10 @@ def main():
                                "avg_us": round(1e3 * ms / n, 2)}
             if name.startswith("gemm") or name.startswith("attn"):
                 breakdown[name]["tflops"] = round(wk / (ms * 1e-3) / 1e12, 2)
+                breakdown[name]["frac_of_bf16_peak"] = round(wk / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
             elif wk:
                 breakdown[name]["gbs"] = round(wk / (ms * 1e-3) / 1e9, 1)
+                breakdown[name]["frac_of_hbm_peak"] = round(wk / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
     result["breakdown"] = breakdown
     gemm_names = [n for n in ("gemm_tn", "gemm_nn", "gemm_nt") if prof[n][1]]
     dom = max(gemm_names, key=lambda n: prof[n][0])

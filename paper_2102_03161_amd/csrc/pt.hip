@@ -284,6 +284,27 @@ struct ProfScope {
   }
 };
 
+// memory-bound launches timed with their algorithmic bytes (what must be read and written once)
+void prof_ln_fwd(pt_ctx* c, int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
+                 int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
+  ProfScope ps_(c, PT_PROF_LN_FWD, (double)rows * D * ((x_f32 ? 4 : c->esz) + c->esz));
+  layernorm_fwd(dt, x_f32, x, ldx, gamma, beta, y, ldy, mean, rstd, rows, D, eps, st);
+}
+void prof_ln_bwd(pt_ctx* c, int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
+                 const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres, float* dx_s,
+                 void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial, int rows, int D,
+                 hipStream_t st) {
+  const double per = (dy_f32 ? 4 : c->esz) + (x_f32 ? 4 : c->esz) + (dres ? 4 : 0) + (dx_s ? 4 : 0) + (dx_o ? c->esz : 0);
+  ProfScope ps_(c, PT_PROF_LN_BWD, (double)rows * D * per);
+  layernorm_bwd(dt, dy_f32, x_f32, dy, lddy, x, ldx, mean, rstd, gamma, dres, lddres, dx_s, dx_o, lddx, dgamma, dbeta, dxsum,
+                partial, rows, D, st);
+}
+void prof_copy_rows(pt_ctx* c, void* dst, const int64_t* dst_idx, const void* src, const int64_t* src_idx, int nrows,
+                    size_t row_bytes, hipStream_t st) {
+  ProfScope ps_(c, PT_PROF_CACHE, 2.0 * nrows * row_bytes);
+  copy_rows(dst, dst_idx, src, src_idx, nrows, row_bytes, st);
+}
+
 // folds finished event pairs into the per-category totals (synchronises)
 void prof_collect(pt_ctx* c) {
   if (c->prof_used == 0) return;
@@ -334,11 +355,11 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
   if (g.arch == PT_VIT_PRELN) {
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st); }
+    { prof_ln_fwd(c, dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, mu1, rs1, Tn, D, g.ln_eps, st); }
     lin(c->w(s.U), D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
     { ProfScope ps_(c, PT_PROF_ATTN_FWD, 4.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st); }
     lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.Y), D, EPI_BIAS_RES, xin, nullptr);
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st); }
+    { prof_ln_fwd(c, dt, false, c->w(s.Y), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), c->w(s.WN), D, mu2, rs2, Tn, D, g.ln_eps, st); }
     lin(c->w(s.WN), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
     lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), xout, D, EPI_BIAS_RES, c->w(s.Y), nullptr);
   } else {
@@ -346,10 +367,10 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
     lin(xin, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, EPI_BIAS, nullptr, nullptr);
     { ProfScope ps_(c, PT_PROF_ATTN_FWD, 4.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_fwd(dt, c->w(s.QKV), c->w(s.CTX), lse, ns, g.S, g.H, D / g.H, st); }
     lin(c->w(s.CTX), D, c->blk(l, WO), c->blk(l, BO), c->w(s.U), D, EPI_BIAS_RES, xin, nullptr, true);
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st); }
+    { prof_ln_fwd(c, dt, true, c->w(s.U), D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.Y), D, mu1, rs1, Tn, D, g.ln_eps, st); }
     lin(c->w(s.Y), D, c->blk(l, W1), c->blk(l, B1), c->w(s.G), F, EPI_BIAS_GELU, nullptr, save ? c->w(s.HP) : nullptr);
     lin(c->w(s.G), F, c->blk(l, W2), c->blk(l, B2), c->w(s.WN), D, EPI_BIAS_RES, c->w(s.Y), nullptr, true);
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st); }
+    { prof_ln_fwd(c, dt, true, c->w(s.WN), D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, D, mu2, rs2, Tn, D, g.ln_eps, st); }
   }
 }
 
@@ -398,24 +419,24 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     dgrad(dout.o, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
     wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dLN2out
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
+    { prof_ln_bwd(c, dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
                   D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oD = dL/dY
     wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO), -1);
     dgrad(oD, D, c->blk(l, WO), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
+    { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
                   c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
   } else {
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
+    { prof_ln_bwd(c, dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
                   oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, Tn, D, st); }  // sC / oC = dL/d(Y+MLP)
     wgrad(c->w(s.G), F, oC, D, c->blk(l, W2), -1);
     dgrad(oC, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
     wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
+    { prof_ln_bwd(c, dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
                   D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oC = dL/d(x+Attn)
     wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO), -1);
     dgrad(oC, D, c->blk(l, WO), oD, D, EPI_STORE, nullptr, false);                      // oD = dL/dCTX
@@ -441,7 +462,7 @@ void front_forward(pt_ctx* c, const void* d_input, const int64_t* d_map, void* x
     vit_assemble(dt, c->w(p.EMB), c->cp(2), c->cp(3), xout, ns, g.S, D, st);
   } else {
     bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->wf(p.EMB), ns, g.S, D, g.vocab, st);
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
+    { prof_ln_fwd(c, dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
                   save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st); }
   }
 }
@@ -460,7 +481,7 @@ void front_backward(pt_ctx* c, const float* dx, int ns) {
     m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = c->gp(1);
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   } else {
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
+    { prof_ln_bwd(c, dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
                   nullptr, D, c->gp(2), c->gp(3), nullptr, c->wf(p.LNPART), ns * g.S, D, st); }
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
@@ -783,7 +804,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
       std::vector<int64_t> src(nb);
       for (int i = 0; i < nb; ++i) src[i] = row_r[i];
       const int64_t* dsrc = stg.put(src, &cerr);
-      { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st); }
+      { prof_copy_rows(c, c->w(p.HKOUT), nullptr, c->cache, dsrc, nb, row_bytes, c->st); }
       c->last_hk = c->w(p.HKOUT);
     } else {
       if (n_miss > 0) {
@@ -806,7 +827,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
         if (!dst.empty()) {
           const int64_t* ddst = stg.put(dst, &cerr);
           const int64_t* dsrc = stg.put(src, &cerr);
-          { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.X[j]), ddst, c->cache, dsrc, (int)dst.size(), row_bytes, c->st); }
+          { prof_copy_rows(c, c->w(p.X[j]), ddst, c->cache, dsrc, (int)dst.size(), row_bytes, c->st); }
         }
         // the sorted prefix of n_le samples (misses and rows written at or below j) runs block j
         if (j < k && n_le > 0) {
@@ -820,7 +841,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
           if (kw[order[i]] < k) { dst.push_back(row_w[order[i]]); src.push_back(i); }
         const int64_t* ddst = stg.put(dst, &cerr);
         const int64_t* dsrc = stg.put(src, &cerr);
-        { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st); }
+        { prof_copy_rows(c, c->cache, ddst, c->w(p.X[k]), dsrc, (int)dst.size(), row_bytes, c->st); }
       }
       if (identity) {
         c->last_hk = c->w(p.X[k]);
@@ -828,7 +849,7 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
         std::vector<int64_t> dst(nb);
         for (int i = 0; i < nb; ++i) dst[i] = order[i];
         const int64_t* ddst = stg.put(dst, &cerr);
-        { ProfScope ps_(c, PT_PROF_CACHE, 0.0); copy_rows(c->w(p.HKOUT), ddst, c->w(p.X[k]), nullptr, nb, row_bytes, c->st); }
+        { prof_copy_rows(c, c->w(p.HKOUT), ddst, c->w(p.X[k]), nullptr, nb, row_bytes, c->st); }
         c->last_hk = c->w(p.HKOUT);
       }
     }
@@ -887,7 +908,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   if (g.arch == PT_VIT_PRELN) {
     const int C = g.n_out;
     const int hg = c->head(0), hb = c->head(1), hW = c->head(2), hbias = c->head(3);
-    { ProfScope ps_(c, PT_PROF_LN_FWD, 0.0); layernorm_fwd(dt, false, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st); }
+    { prof_ln_fwd(c, dt, false, x, (int64_t)S * D, c->cp(hg), c->cp(hb), c->w(p.CFEAT), D, c->wf(p.MUF), c->wf(p.RSF), nb, D, g.ln_eps, st); }
     Gemm m;
     m.A = c->w(p.CFEAT); m.lda = D; m.B = c->cp(hW); m.ldb = C; m.C = c->w(p.LOGITS); m.ldc = C;
     m.M = nb; m.N = C; m.K = D; m.epi = EPI_BIAS; m.bias = c->cp(hbias); m.c_f32 = true;
@@ -906,7 +927,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     // only the CLS rows of dL/dx_L are non-zero
     fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
     fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
-    { ProfScope ps_(c, PT_PROF_LN_BWD, 0.0); layernorm_bwd(dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
+    { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
                   dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
                   c->wf(p.LNPART), nb, D, st); }
   } else if (g.head == PT_HEAD_CLS) {
