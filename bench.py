@@ -206,6 +206,8 @@ def main():
             s_unc = timed(2, 8, use_cache=False)
             step(0, True); step(1, True); step(2, True); step(3, True)     # fill / advance the cache rows
             s_hit = timed(2, 8, use_cache=True)
+            ms_re, ms_hit = ctx.time_frozen_forward(batches[0][0], batches[0][2], 3)
+            sweep[f"k{k}_prefix_ms"] = {"recompute": round(ms_re, 4), "cached": round(ms_hit, 4)}
             sweep[f"k{k}"] = round(M * B / s_unc, 1)
             sweep[f"k{k}_cached"] = round(M * B / s_hit, 1)
         result["samples_per_s_vs_k"] = sweep

@@ -126,6 +126,17 @@ pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
 pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const int64_t* sample_ids,
                             void** d_hk_out);
 
+/* The timing profiler of the cache (Sec. 3.4: caching is switched on only once it is faster than
+ * recomputing the frozen prefix; Sec. 4.3.5 reports from which boundary that held on the paper's
+ * cluster).  Runs pt_frozen_forward for this batch once to write or advance its rows, then `reps`
+ * times bypassing the cache and `reps` times from the cache (all hits), timed with events on the
+ * context's stream, and returns the mean milliseconds per call of each (HOST out).  The caller passes
+ * sample_ids = NULL to later calls while ms_cached >= ms_recompute.  Needs k >= 1 and a cache;
+ * synchronises; leaves the context as after a pt_frozen_forward of this batch. */
+pt_status pt_time_frozen_forward(pt_ctx* ctx, const void* d_input /*DEVICE*/, int32_t nb,
+                                 const int64_t* sample_ids /*HOST*/, int32_t reps, float* ms_recompute,
+                                 float* ms_cached);
+
 /* F_pipe: forward through blocks k..L-1 and the task head, loss, backward down
  * to block k (and the front end iff k == 0), for the batch of the preceding
  * pt_frozen_forward.

@@ -81,6 +81,7 @@ def load_library():
         "pt_read_activation": [vp, i32, P(C.c_float), sz],
         "pt_cache_row": [vp, i64, vp, sz, P(i32)],
         "pt_cache_stats": [vp, P(i64), P(i64), P(i64), P(i64)],
+        "pt_time_frozen_forward": [vp, vp, i32, P(i64), i32, P(C.c_float), P(C.c_float)],
         "pt_attach_host_tier": [vp, vp, sz],
         "pt_cache_prefetch": [vp, P(i64), i32, P(i32)],
         "pt_host_tier_stats": [vp, P(i64), P(i64), P(i64), P(i64)],
@@ -278,6 +279,14 @@ class Context:
         a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
         self._chk(self.lib.pt_cache_stats(self.h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)))
         return {"hits": a.value, "advances": b.value, "misses": c.value, "block_runs": d.value}
+
+    def time_frozen_forward(self, d_input, sample_ids, reps: int = 3):
+        """(ms per call recomputing the prefix, ms per call served from the cache) for this batch."""
+        ids = np.ascontiguousarray(sample_ids, dtype=np.int64)
+        a, b = C.c_float(), C.c_float()
+        self._chk(self.lib.pt_time_frozen_forward(self.h, C.c_void_p(d_input.data_ptr()), len(ids),
+                                                  ids.ctypes.data_as(C.POINTER(C.c_int64)), reps, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def cache_prefetch(self, sample_ids) -> int:
         ids = np.ascontiguousarray(sample_ids, dtype=np.int64)

@@ -888,6 +888,33 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
   return PT_OK;
 }
 
+pt_status pt_time_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const int64_t* sample_ids, int32_t reps,
+                                 float* ms_recompute, float* ms_cached) {
+  if (!c || !d_input || !sample_ids || !ms_recompute || !ms_cached || reps < 1) return PT_EINVAL;
+  if (c->k < 1) return fail(c, PT_ESTATE, "nothing is frozen: there is no prefix to time");
+  if (c->cfg.cache_slots + c->cfg.host_slots <= 0) return fail(c, PT_ESTATE, "the configuration has no cache");
+  void* hk = nullptr;
+  pt_status st = pt_frozen_forward(c, d_input, nb, sample_ids, &hk);   // rows are written / advanced here, untimed
+  if (st != PT_OK) return st;
+  hipEvent_t e[3] = {nullptr, nullptr, nullptr};
+  for (auto& ev : e) HIP_TRY(c, hipEventCreate(&ev));
+  hipError_t herr = hipEventRecord(e[0], c->st);
+  for (int i = 0; i < reps && st == PT_OK; ++i) st = pt_frozen_forward(c, d_input, nb, nullptr, &hk);
+  if (herr == hipSuccess) herr = hipEventRecord(e[1], c->st);
+  for (int i = 0; i < reps && st == PT_OK; ++i) st = pt_frozen_forward(c, d_input, nb, sample_ids, &hk);
+  if (herr == hipSuccess) herr = hipEventRecord(e[2], c->st);
+  if (herr == hipSuccess) herr = hipEventSynchronize(e[2]);
+  float a = 0.f, b = 0.f;
+  if (herr == hipSuccess) herr = hipEventElapsedTime(&a, e[0], e[1]);
+  if (herr == hipSuccess) herr = hipEventElapsedTime(&b, e[1], e[2]);
+  for (auto& ev : e) (void)hipEventDestroy(ev);
+  if (st != PT_OK) return st;
+  if (herr != hipSuccess) return fail(c, PT_EDEVICE, hipGetErrorString(herr));
+  *ms_recompute = a / (float)reps;
+  *ms_cached = b / (float)reps;
+  return PT_OK;
+}
+
 pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels, float* loss_out) {
   if (!c || !d_hk || !d_labels) return PT_EINVAL;
   if (c->phase < 1) return fail(c, PT_ESTATE, "pt_frozen_forward has not run for this step");

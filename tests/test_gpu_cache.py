@@ -242,3 +242,33 @@ def test_host_tier_is_invisible_to_the_result(torch_mod, w):
     plain = binding.Context(binding.make_config(w, B=nb, cache_slots=4))
     assert plain.cache_prefetch([0, 1]) == 0
     plain.close()
+
+
+def test_cache_timing_profiler(torch_mod):
+    """pt_time_frozen_forward: counts what it ran, leaves the batch's h_k in place, and refuses contexts with
+    nothing to time."""
+    torch = torch_mod
+    w = MID_VIT
+    nb, k, reps = w["B"], 2, 3
+    ctx = binding.Context(binding.make_config(w, cache_slots=32))
+    H.load_params(ctx, H.init_values(w, ctx, 29))
+    x, _ = H.batch_for(w, 29, nb)
+    dx = H.to_dev(torch, x)
+    ids = list(range(5, 5 + nb))
+    with pytest.raises(binding.PtError):          # k = 0: no prefix
+        ctx.time_frozen_forward(dx, ids, reps)
+    ctx.set_freeze_boundary(k)
+    ms_re, ms_hit = ctx.time_frozen_forward(dx, ids, reps)
+    assert ms_re > 0 and ms_hit > 0
+    st = ctx.cache_stats()
+    assert (st["misses"], st["hits"], st["advances"]) == (nb, reps * nb, 0)
+    assert st["block_runs"] == (1 + reps) * nb * k
+    h_after = raw_hk(ctx, w, nb)
+    ctx.frozen_forward(dx, None)
+    assert np.array_equal(raw_hk(ctx, w, nb), h_after)
+    ctx.close()
+    plain = binding.Context(binding.make_config(w))
+    plain.set_freeze_boundary(1)
+    with pytest.raises(binding.PtError):          # no cache configured
+        plain.time_frozen_forward(dx, ids, reps)
+    plain.close()

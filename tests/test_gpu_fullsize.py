@@ -129,3 +129,14 @@ def test_full_batch_step_is_bit_reproducible(torch_mod, vitb):
         assert loss == outs[0][0] and np.array_equal(norms, outs[0][1])
         for n in probe:
             assert np.array_equal(grads[n], outs[0][2][n]), n
+
+
+def test_full_batch_cache_is_faster_than_the_prefix_it_replaces(torch_mod, vitb):
+    """The timing profiler at full size: with an HBM cache a hit (a 19 MB gather) beats recomputing even one
+    frozen block, so the cache pays from the first boundary on (the paper's host-memory cache needed three)."""
+    torch = torch_mod
+    w, ctx, vals, x, y = vitb
+    assert ctx.get_freeze_boundary() >= 1
+    ms_re, ms_hit = ctx.time_frozen_forward(H.to_dev(torch, x), np.arange(w["B"]), 3)
+    print(f"k={ctx.get_freeze_boundary()}: recompute {ms_re:.3f} ms, cached {ms_hit:.3f} ms", flush=True)
+    assert ms_hit < ms_re
