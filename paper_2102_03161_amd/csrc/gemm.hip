@@ -431,16 +431,21 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.c_f32 && (a.epi == EPI_BIAS_GELU || a.epi == EPI_MUL_DGELU)) return;  // not used by the step
   if (gemm_uses_mfma(dt, a) && (!a.ta || a.ldc == a.N)) {
     if (g_cfg_override != 0 && gemm_dma_ok(a)) {
-      // default: 128x128 tiles, three per CU; wide outputs and the weight gradients do better with
-      // 256x128 tiles and eight waves; input gradients with a narrow output and a long K with 256x256
-      // tiles, one workgroup per CU (measured: fewer, larger workgroups win there although a third of
-      // the CUs stays idle)
+      // Weight gradients: 256x128 tiles (128x128 for small outputs), split over K.
+      // Forward and input-gradient products with at least 4096 rows and K a multiple of 64: the two-group
+      // kernel with 256x256 or 192x256 tiles, one workgroup per CU, whichever fills whole rounds of 256
+      // CUs better (M = 12608, N = 768: 198 tiles of 192x256 against 150 of 256x256); wide outputs with
+      // a short K do better with 256x128 tiles, two workgroups per CU, whose prologues and epilogues
+      // overlap.  Everything else: 128x128 tiles, three per CU.
       int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
       if (g_cfg_override < 0) {
         v = (a.ta || a.N >= 3072) ? 2 : 1;
-        if (a.tb && a.N <= 1024 && a.K >= 768 && a.M >= 4096) v = 3;
-        if (!a.ta && !a.tb && a.N >= 2048 && a.N < 3072 && a.M >= 4096) v = 3;   // QKV projection
-        if (a.ta && (int64_t)a.M * a.N <= 1024 * 1024) v = 1;                     // small weight gradients
+        if (a.ta && (int64_t)a.M * a.N <= 1024 * 1024) v = 1;
+        if (!a.ta && a.M >= 4096 && a.K % 64 == 0 && !(a.N >= 3072 && (a.K < 1024 || a.tb))) {
+          const int tn = cdiv(a.N, 256);
+          const int c192 = cdiv(cdiv(a.M, 192) * tn, 256) * 192, c256 = cdiv(cdiv(a.M, 256) * tn, 256) * 256;
+          v = c192 < c256 ? 6 : 5;
+        }
       }
       gemm_dma(a, v, st);
       return;

@@ -74,12 +74,13 @@ struct TileK {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) foff[ks] = row * ROWB + (((2 * ks + (lane >> 5)) ^ swzk(row)) << 4);
   }
+  __device__ __forceinline__ void issue_one(unsigned char* tile, int wave, int i) {
+    __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
+    gp[i] += BK;
+  }
   __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
-      gp[i] += BK;
-    }
+    for (int i = 0; i < LOADS; ++i) issue_one(tile, wave, i);
   }
   // fragments of all row blocks for one k-step, issued as inline assembly (see TileS::read)
   static constexpr int READS = NFRAG;   // LDS instructions per k-step
@@ -135,12 +136,13 @@ struct TileS {
       foff[j] = k * ROWB + (((col >> 3) ^ swz(k)) << 4) + (col & 7) * 2;
     }
   }
+  __device__ __forceinline__ void issue_one(unsigned char* tile, int wave, int i) {
+    __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
+    gp[i] += gstep;
+  }
   __device__ __forceinline__ void issue(unsigned char* tile, int wave) {
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-      __builtin_amdgcn_global_load_lds(PT_GLB(gp[i]), PT_LDS(tile + (wave * LOADS + i) * 1024), 16, 0, 0);
-      gp[i] += gstep;
-    }
+    for (int i = 0; i < LOADS; ++i) issue_one(tile, wave, i);
   }
   static constexpr int READS = 2 * NFRAG;
   // ks is a compile-time constant at every call site (unrolled), so the offsets fold to immediates
@@ -312,6 +314,210 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
                                              n0 + wn * WTN, lane, vec_ok);
 }
 
+
+// ---- 256x256x64 tiles, two wave groups in alternating roles ----
+// The eight waves form two groups of four, one wave of each group per SIMD.  Time is cut into phases that
+// end in a workgroup barrier.  In a phase one group only issues matrix instructions, on fragments it
+// already holds in registers (16 MFMAs, half a k tile), while the other group reads its next half tile's
+// fragments from LDS; at the barrier they swap.  The matrix cores therefore always have a wave whose
+// operands are complete, and LDS reads are spread evenly over time instead of arriving from all eight
+// waves right after a tile barrier.  Measured on the single-role pipeline above (12608 x 768 x 3072,
+// cycles per k tile and CU; 2048 are MFMA issue): MFMAs alone 2380, with LDS reads 2710, with the
+// global->LDS loads 2720-3250, all three 3500-3700.
+//
+// Tile t is consumed in four phases (group 0: read half 0, compute, read half 1, compute; group 1 one
+// phase behind).  A tiles live in a ring of three 32 KB stages and B tiles in a ring of two, 160 KB in
+// all: A (the activations, streamed from HBM) is requested two tiles ahead, B (weights, mostly L2 hits)
+// one tile ahead.  Loads are issued a few per phase, behind MFMAs where the issuing wave computes.  Per
+// wave and iteration the order is B(t+1) in phase 0, then A(t+2) over phases 1-3, so that "at most
+// LA::LOADS loads outstanding" at the end of phase 3 means A(t+1) and B(t+1) have landed.
+template <int BM, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
+                                                      int vec_ok) {
+  constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
+  constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
+  static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
+  typedef typename TileSel<TA, BM, NW, TM, BK>::type LA;
+  typedef typename TileSel<!TB, BN, NW, TN, BK>::type LB;
+  constexpr int STAGE_LD = WTN + 4;
+  constexpr int LDS_BYTES = NSA * LA::BYTES + NSB * LB::BYTES;
+  static_assert(NW * 32 * STAGE_LD * 4 <= LDS_BYTES && LDS_BYTES <= 160 * 1024, "LDS budget");
+  static_assert(LA::LOADS >= 3, "A loads are spread over three phases");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+  unsigned char* const ldsB = lds + NSA * LA::BYTES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
+  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int tt = work - split * total_tiles;
+  const int cg = tt / (group_n * tiles_m);
+  const int rem = tt - cg * group_n * tiles_m;
+  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
+  const int m0 = (rem / gw) * BM, n0 = (cg * group_n + rem % gw) * BN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk_all = g.K / BK;
+  const int kt0 = split * sp.tiles_per_split;
+  const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
+  const int n = kt1 > kt0 ? kt1 - kt0 : 0;
+  const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
+  float cs = 0.f;
+
+  LA ta;
+  LB tb;
+  ta.setup(g.A, g.lda, g.M, m0, kt0 * BK, wm * WTM, wave, lane);
+  tb.setup(g.B, g.ldb, g.N, n0, kt0 * BK, wn * WTN, wave, lane);
+
+  bf16x8 fa[2][TM], fb[2][TN];
+  // fragment reads of one half tile (k-steps 2*half and 2*half + 1), complete on return
+  auto fetch = [&](const unsigned char* sa, const unsigned char* sb, int half) {
+    ta.read(sa, 2 * half, fa[0]);
+    tb.read(sb, 2 * half, fb[0]);
+    ta.read(sa, 2 * half + 1, fa[1]);
+    tb.read(sb, 2 * half + 1, fb[1]);
+  };
+  auto fetched = [&]() {
+    wait_lds<0>(fa[0], fb[0]);
+    wait_lds<0>(fa[1], fb[1]);
+  };
+  // 16 MFMAs on the fragments held; `load(q)` for q in [0, nq) goes out between them
+  auto compute = [&](bool on, int nq, auto load) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+        const int slot = ks * TM + i;   // 0..7
+        if (slot < nq) {
+          if (on) load(slot);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+  };
+
+  if (n > 0) {
+    ta.issue(lds, wave);
+    tb.issue(ldsB, wave);
+  }
+  if (n > 1) {
+    ta.issue(lds + LA::BYTES, wave);
+    wait_vm<LA::LOADS>();
+  } else {
+    wait_vm<0>();
+  }
+  compiler_fence();
+  __builtin_amdgcn_s_barrier();
+  compiler_fence();
+
+  // The two groups run separate loops (straight-line code each, which the register allocator handles far
+  // better than one loop with a branch per phase); both execute four barriers per tile.
+  constexpr int A1 = LA::LOADS / 3, A2 = 2 * LA::LOADS / 3;
+  if (grp == 0) {
+    int ia = 0, ib = 0;   // stages of tile t
+    for (int t = 0; t < n; ++t) {
+      const bool moreB = t + 1 < n, moreA = t + 2 < n;
+      const unsigned char* sa = lds + ia * LA::BYTES;
+      const unsigned char* sb = ldsB + ib * LB::BYTES;
+      unsigned char* const dstB = ldsB + (ib ^ 1) * LB::BYTES;
+      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;   // stage (t + 2) % 3
+      // phase 0
+      fetch(sa, sb, 0);
+      if (moreB) tb.issue(dstB, wave);
+      fetched();
+      __builtin_amdgcn_s_barrier();
+      // phase 1
+      compute(moreA, A1, [&](int q) { ta.issue_one(dstA, wave, q); });
+      if constexpr (!TB) {
+        if (do_colsum) cs += LB::colsum(sb, tid);   // threads 0..255 are this group
+      }
+      __builtin_amdgcn_s_barrier();
+      // phase 2
+      fetch(sa, sb, 1);
+      if (moreA) {
+#pragma unroll
+        for (int q = A1; q < A2; ++q) ta.issue_one(dstA, wave, q);
+      }
+      fetched();
+      __builtin_amdgcn_s_barrier();
+      // phase 3
+      compute(moreA, LA::LOADS - A2, [&](int q) { ta.issue_one(dstA, wave, A2 + q); });
+      if (moreA) wait_vm<LA::LOADS>();
+      else wait_vm<0>();
+      compiler_fence();
+      __builtin_amdgcn_s_barrier();
+      compiler_fence();
+      ia = ia + 1 == NSA ? 0 : ia + 1;
+      ib ^= 1;
+    }
+  } else {
+    int ia = 0, ib = 0;
+    // phase 0 of tile 0: nothing to compute yet
+    if (n > 1) tb.issue(ldsB + LB::BYTES, wave);
+    if (n > 0) __builtin_amdgcn_s_barrier();
+    for (int t = 0; t < n; ++t) {
+      const bool moreA = t + 2 < n;
+      const unsigned char* sa = lds + ia * LA::BYTES;
+      const unsigned char* sb = ldsB + ib * LB::BYTES;
+      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;
+      // phase 1
+      fetch(sa, sb, 0);
+      if (moreA) {
+#pragma unroll
+        for (int q = 0; q < A1; ++q) ta.issue_one(dstA, wave, q);
+      }
+      fetched();
+      __builtin_amdgcn_s_barrier();
+      // phase 2
+      compute(moreA, A2 - A1, [&](int q) { ta.issue_one(dstA, wave, A1 + q); });
+      __builtin_amdgcn_s_barrier();
+      // phase 3
+      fetch(sa, sb, 1);
+      if (moreA) {
+#pragma unroll
+        for (int q = A2; q < LA::LOADS; ++q) ta.issue_one(dstA, wave, q);
+      }
+      fetched();
+      if (moreA) wait_vm<LA::LOADS>();
+      else wait_vm<0>();
+      compiler_fence();
+      __builtin_amdgcn_s_barrier();
+      compiler_fence();
+      // phase 0 of tile t + 1: second half of tile t, and B(t + 2) into the stage tile t's B has just left
+      if (t + 1 < n) {
+        unsigned char* const dstB = ldsB + ib * LB::BYTES;
+        compute(moreA, LB::LOADS, [&](int q) { tb.issue_one(dstB, wave, q); });
+        __builtin_amdgcn_s_barrier();
+      }
+      ia = ia + 1 == NSA ? 0 : ia + 1;
+      ib ^= 1;
+    }
+    if (n > 0) compute(false, 0, [](int) {});
+  }
+  compiler_fence();
+  __builtin_amdgcn_s_barrier();   // all fragment reads done: the LDS can be reused for the epilogue
+  compiler_fence();
+  if constexpr (!TB) {
+    if (do_colsum && tid < BN && n0 + tid < g.N) sp.colsum[(int64_t)split * g.N + n0 + tid] = cs;
+  }
+  void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
+                                : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
+  staged_epilogue<TM, TN, WTM, WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD, m0 + wm * WTM,
+                                             n0 + wn * WTN, lane, vec_ok);
+}
+
 int g_group_n = 0;                  // forced column-group width (tuning); 0 = derive from g_group_bytes
 int64_t g_group_bytes = 1536 << 10;  // L2 bytes a column group's B panels may take
 
@@ -333,6 +539,26 @@ void launch_dma(const Gemm& a, int splits, float* cbase, int64_t slab, float* co
   if (group_n > tiles_n) group_n = tiles_n;
   hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, NS, BK, TA, TB, EPI, TC>), grid, dim3(64 * WGM * WGN), 0, st, g, sp,
                      tiles_m, tiles_n, group_n, gemm_epilogue_vec_ok(a) ? 1 : 0);
+}
+
+template <int BM, bool TA, bool TB, int EPI, typename TC>
+void launch_pp(const Gemm& a, int splits, float* cbase, int64_t slab, float* colsum_part, hipStream_t st) {
+  constexpr int BN = 256, BK = 64;
+  GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, cbase ? (void*)cbase : a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
+                  (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
+  const int tiles_m = cdiv(a.M, BM), tiles_n = cdiv(a.N, BN), total = tiles_m * tiles_n;
+  const int nk = a.K / BK;
+  SplitArgs sp{splits, cdiv(nk, splits), slab, colsum_part};
+  dim3 grid(8 * cdiv(total * splits, 8), 1, 1);
+  int group_n = g_group_n;
+  if (group_n <= 0) {
+    const int64_t panel = (int64_t)BN * (a.K / splits) * 2;
+    group_n = (int)(g_group_bytes / (panel > 0 ? panel : 1));
+    if (group_n < 1) group_n = 1;
+  }
+  if (group_n > tiles_n) group_n = tiles_n;
+  hipLaunchKernelGGL((gemm_pp_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
+                     gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -379,6 +605,47 @@ static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
   }
 }
 
+static void dispatch_pp_wgrad(const Gemm& a, hipStream_t st) {
+  const int tiles = cdiv(a.M, 256) * cdiv(a.N, 256), nk = a.K / 64;
+  int splits = 1;
+  const int64_t mn = (int64_t)a.M * a.N;
+  if (a.ws) {
+    splits = g_split_target / tiles;
+    if (splits > nk / 4) splits = nk / 4;
+    if (splits > 16) splits = 16;
+    if (splits < 1) splits = 1;
+    while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
+  }
+  float* cs_part = nullptr;
+  if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
+  if (splits > 1) {
+    launch_pp<256, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
+    gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
+  } else {
+    launch_pp<256, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
+  }
+}
+
+template <int BM>
+static void dispatch_pp_fwd(const Gemm& a, hipStream_t st) {
+#define PT_L(TB_, EPI_, TC_) launch_pp<BM, false, TB_, EPI_, TC_>(a, 1, nullptr, 0, nullptr, st)
+  if (a.tb) {
+    if (a.c_f32) PT_L(true, EPI_RES, float);
+    else if (a.epi == EPI_STORE) PT_L(true, EPI_STORE, bf16);
+    else PT_L(true, EPI_MUL_DGELU, bf16);
+    return;
+  }
+  if (a.c_f32) {
+    if (a.epi == EPI_BIAS) PT_L(false, EPI_BIAS, float);
+    else PT_L(false, EPI_BIAS_RES, float);
+  } else {
+    if (a.epi == EPI_BIAS) PT_L(false, EPI_BIAS, bf16);
+    else if (a.epi == EPI_BIAS_RES) PT_L(false, EPI_BIAS_RES, bf16);
+    else PT_L(false, EPI_BIAS_GELU, bf16);
+  }
+#undef PT_L
+}
+
 // forward and input-gradient products (at least one k-major operand)
 template <int BM, int BN, int WGM, int WGN, int NS, int BK>
 static void dispatch_fwd(const Gemm& a, hipStream_t st) {
@@ -401,6 +668,12 @@ static void dispatch_fwd(const Gemm& a, hipStream_t st) {
 }
 
 void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
+  if ((variant == 5 || variant == 6) && a.K % 64 == 0) {
+    if (a.ta) dispatch_pp_wgrad(a, st);
+    else if (variant == 5) dispatch_pp_fwd<256>(a, st);
+    else dispatch_pp_fwd<192>(a, st);
+    return;
+  }
   if (a.ta) {
     switch (variant) {
       case 2: dispatch_wgrad<256, 128, 4, 2>(a, st); break;
