@@ -10,6 +10,7 @@
 //
 // The K loop runs in a fixed order and there is no split-K, so every output
 // element is a deterministic function of its own row and column only.
+#include <algorithm>
 #include "common.h"
 #include "kernels.h"
 #include "gemm_epilogue.h"
@@ -458,6 +459,25 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   else launch_generic_epi<bf16, bf16>(a, st);
   // column sums of B requested alongside a weight gradient: separate pass on this path
   if (a.colsum_out && a.ta && !a.tb && a.ws) colsum(dt, a.B, a.ldb, a.K, a.N, a.colsum_out, a.ws, st);
+}
+
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st) {
+  if (n <= 0) return;
+  bool mfma = dt != 0 && g_cfg_override != 0;
+  for (int i = 0; i < n && mfma; ++i) mfma = gemm_uses_mfma(dt, g[i]);
+  if (mfma && n > 1 && gemm_wgrad_group(g, n, st)) return;
+  for (int i = 0; i < n; ++i) gemm(dt, g[i], st);
+}
+
+size_t gemm_wgrad_batch_ws_floats(int D, int F) {
+  const int64_t shapes[4][2] = {{D, 3 * D}, {D, D}, {D, F}, {F, D}};
+  int64_t tiles = 0, per_split = 0;
+  for (auto& sh : shapes) {
+    tiles += ((sh[0] + 255) / 256) * ((sh[1] + 255) / 256);
+    per_split += sh[0] * sh[1] + sh[1];
+  }
+  const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 256 / std::max<int64_t>(tiles, 1)));
+  return (size_t)(splits * per_split);
 }
 
 }  // namespace pt

@@ -331,9 +331,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 // one tile ahead.  Loads are issued a few per phase, behind MFMAs where the issuing wave computes.  Per
 // wave and iteration the order is B(t+1) in phase 0, then A(t+2) over phases 1-3, so that "at most
 // LA::LOADS loads outstanding" at the end of phase 3 means A(t+1) and B(t+1) have landed.
+// one output tile (rows m0.., columns n0..) over the k tiles of `split`; all 512 threads of the workgroup
 template <int BM, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
-                                                      int vec_ok) {
+__device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int m0, int n0, int vec_ok) {
   constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
   constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
   static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
@@ -348,16 +348,6 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
-  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
-  const int per = (total_work + 7) >> 3;
-  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (work >= total_work) return;
-  const int split = work / total_tiles;
-  const int tt = work - split * total_tiles;
-  const int cg = tt / (group_n * tiles_m);
-  const int rem = tt - cg * group_n * tiles_m;
-  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
-  const int m0 = (rem / gw) * BM, n0 = (cg * group_n + rem % gw) * BN;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -518,6 +508,209 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs
                                              n0 + wn * WTN, lane, vec_ok);
 }
 
+template <int BM, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
+                                                      int vec_ok) {
+  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int tt = work - split * total_tiles;
+  const int cg = tt / (group_n * tiles_m);
+  const int rem = tt - cg * group_n * tiles_m;
+  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
+  pp_run<BM, TA, TB, EPI, TC>(g, sp, split, (rem / gw) * BM, (cg * group_n + rem % gw) * 256, vec_ok);
+}
+
+// Several weight gradients dW_p = X_p^T dY_p over the same tokens in one launch.  One encoder block has
+// only 108 output tiles of 256x256 in its four weight matrices; launched one matrix at a time each needs a
+// 7- to 16-way split over K to occupy the chip and then writes and re-reads that many fp32 slabs.  Together
+// they fill the CUs with a two-way split.
+constexpr int kMaxGroup = 4;
+struct GroupArgs {
+  GemmDev<bf16> g[kMaxGroup];   // C = this problem's slab area (or the destination when splits == 1)
+  float* colsum[kMaxGroup];
+  int64_t slab[kMaxGroup];
+  int tile0[kMaxGroup + 1];     // first tile of each problem in the launch's tile order
+  int tiles_n[kMaxGroup];
+  int vec_ok[kMaxGroup];
+  int nprob, splits, tiles_per_split;
+};
+__global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
+  const int total_tiles = ga.tile0[ga.nprob], total_work = total_tiles * ga.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int tt = work - split * total_tiles;
+  int p = 0;
+  while (p + 1 < ga.nprob && tt >= ga.tile0[p + 1]) ++p;
+  const int local = tt - ga.tile0[p];
+  const SplitArgs sp{ga.splits, ga.tiles_per_split, ga.slab[p], ga.colsum[p]};
+  pp_run<256, true, false, EPI_STORE, float>(ga.g[p], sp, split, (local / ga.tiles_n[p]) * 256, (local % ga.tiles_n[p]) * 256,
+                                             ga.vec_ok[p]);
+}
+
+template <int BM, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(512) void gemm_pp2_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
+                                                      int vec_ok) {
+  constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
+  constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
+  static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
+  typedef typename TileSel<TA, BM, NW, TM, BK>::type LA;
+  typedef typename TileSel<!TB, BN, NW, TN, BK>::type LB;
+  constexpr int STAGE_LD = WTN + 4;
+  constexpr int LDS_BYTES = NSA * LA::BYTES + NSB * LB::BYTES;
+  static_assert(NW * 32 * STAGE_LD * 4 <= LDS_BYTES && LDS_BYTES <= 160 * 1024, "LDS budget");
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+  unsigned char* const ldsB = lds + NSA * LA::BYTES;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
+  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int tt = work - split * total_tiles;
+  const int cg = tt / (group_n * tiles_m);
+  const int rem = tt - cg * group_n * tiles_m;
+  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
+  const int m0 = (rem / gw) * BM, n0 = (cg * group_n + rem % gw) * BN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk_all = g.K / BK;
+  const int kt0 = split * sp.tiles_per_split;
+  const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
+  const int n = kt1 > kt0 ? kt1 - kt0 : 0;
+  const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
+  float cs = 0.f;
+
+  LA ta;
+  LB tb;
+  ta.setup(g.A, g.lda, g.M, m0, kt0 * BK, wm * WTM, wave, lane);
+  tb.setup(g.B, g.ldb, g.N, n0, kt0 * BK, wn * WTN, wave, lane);
+
+  // Whole-tile phases: a group reads all four k-steps of a tile, then issues its 8*TM MFMAs; two barriers per
+  // tile instead of four.  B(t+1) is requested in the even phase of tile t, A(t+2) in the odd one.
+  bf16x8 fa[4][TM], fb[4][TN];
+  auto fetch = [&](const unsigned char* sa, const unsigned char* sb) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      ta.read(sa, ks, fa[ks]);
+      tb.read(sb, ks, fb[ks]);
+    }
+  };
+  auto fetched = [&]() {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) wait_lds<0>(fa[ks], fb[ks]);
+  };
+  auto compute = [&](bool on, int nq, auto load) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+        const int slot = ks * TM + i;
+        if (slot < nq) {
+          if (on) load(slot);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+  };
+
+  if (n > 0) {
+    ta.issue(lds, wave);
+    tb.issue(ldsB, wave);
+  }
+  if (n > 1) {
+    ta.issue(lds + LA::BYTES, wave);
+    wait_vm<LA::LOADS>();
+  } else {
+    wait_vm<0>();
+  }
+  compiler_fence();
+  __builtin_amdgcn_s_barrier();
+  compiler_fence();
+
+  if (grp == 0) {
+    int ia = 0, ib = 0;   // stages of tile t
+    for (int t = 0; t < n; ++t) {
+      const bool moreB = t + 1 < n, moreA = t + 2 < n;
+      const unsigned char* sa = lds + ia * LA::BYTES;
+      const unsigned char* sb = ldsB + ib * LB::BYTES;
+      unsigned char* const dstB = ldsB + (ib ^ 1) * LB::BYTES;
+      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;   // stage (t + 2) % 3
+      // even phase
+      fetch(sa, sb);
+      if (moreB) tb.issue(dstB, wave);
+      fetched();
+      __builtin_amdgcn_s_barrier();
+      // odd phase
+      compute(moreA, LA::LOADS, [&](int q) { ta.issue_one(dstA, wave, q); });
+      if constexpr (!TB) {
+        if (do_colsum) cs += LB::colsum(sb, tid);   // threads 0..255 are this group
+      }
+      if (moreA) wait_vm<LA::LOADS>();
+      else wait_vm<0>();
+      compiler_fence();
+      __builtin_amdgcn_s_barrier();
+      compiler_fence();
+      ia = ia + 1 == NSA ? 0 : ia + 1;
+      ib ^= 1;
+    }
+  } else {
+    int ia = 0, ib = 0;
+    // even phase of tile 0: nothing to compute yet
+    if (n > 1) tb.issue(ldsB + LB::BYTES, wave);
+    if (n > 0) __builtin_amdgcn_s_barrier();
+    for (int t = 0; t < n; ++t) {
+      const bool moreA = t + 2 < n;
+      const unsigned char* sa = lds + ia * LA::BYTES;
+      const unsigned char* sb = ldsB + ib * LB::BYTES;
+      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;
+      // odd phase
+      fetch(sa, sb);
+      if (moreA) ta.issue(dstA, wave);
+      fetched();
+      if (moreA) wait_vm<LA::LOADS>();
+      else wait_vm<0>();
+      compiler_fence();
+      __builtin_amdgcn_s_barrier();
+      compiler_fence();
+      // even phase of tile t + 1: tile t's MFMAs, and B(t + 2) into the stage tile t's B has just left
+      if (t + 1 < n) {
+        unsigned char* const dstB = ldsB + ib * LB::BYTES;
+        compute(moreA, LB::LOADS, [&](int q) { tb.issue_one(dstB, wave, q); });
+        __builtin_amdgcn_s_barrier();
+      }
+      ia = ia + 1 == NSA ? 0 : ia + 1;
+      ib ^= 1;
+    }
+    if (n > 0) compute(false, 0, [](int) {});
+  }
+  compiler_fence();
+  __builtin_amdgcn_s_barrier();   // all fragment reads done: the LDS can be reused for the epilogue
+  compiler_fence();
+  if constexpr (!TB) {
+    if (do_colsum && tid < BN && n0 + tid < g.N) sp.colsum[(int64_t)split * g.N + n0 + tid] = cs;
+  }
+  void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
+                                : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
+  staged_epilogue<TM, TN, WTM, WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD, m0 + wm * WTM,
+                                             n0 + wn * WTN, lane, vec_ok);
+}
+
 int g_group_n = 0;                  // forced column-group width (tuning); 0 = derive from g_group_bytes
 int64_t g_group_bytes = 1536 << 10;  // L2 bytes a column group's B panels may take
 
@@ -557,8 +750,14 @@ void launch_pp(const Gemm& a, int splits, float* cbase, int64_t slab, float* col
     if (group_n < 1) group_n = 1;
   }
   if (group_n > tiles_n) group_n = tiles_n;
-  hipLaunchKernelGGL((gemm_pp_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
-                     gemm_epilogue_vec_ok(a) ? 1 : 0);
+  // 192-row tiles leave room for a whole k tile of fragments in registers (whole-tile phases, 4-5 % faster);
+  // 256-row tiles do not
+  if constexpr (BM == 192)
+    hipLaunchKernelGGL((gemm_pp2_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
+                       gemm_epilogue_vec_ok(a) ? 1 : 0);
+  else
+    hipLaunchKernelGGL((gemm_pp_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
+                       gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -603,6 +802,56 @@ static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
   } else {
     launch_dma<BM, BN, WGM, WGN, NS, BK, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
   }
+}
+
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st) {
+  if (n < 1 || n > kMaxGroup) return false;
+  int64_t total = 0, per_split = 0;
+  for (int i = 0; i < n; ++i) {
+    const Gemm& m = a[i];
+    if (!m.ta || m.tb || !m.c_f32 || m.ldc != m.N || m.epi != EPI_STORE || !gemm_dma_ok(m) || m.K % 64 != 0) return false;
+    if (m.K != a[0].K || m.ws != a[0].ws || m.ws_floats != a[0].ws_floats || !m.ws) return false;
+    total += (int64_t)cdiv(m.M, 256) * cdiv(m.N, 256);
+    per_split += (int64_t)m.M * m.N + m.N;
+  }
+  const int nk = a[0].K / 64;
+  int splits = (int)(256 / total);
+  if (splits > nk / 4) splits = nk / 4;
+  if (splits > 16) splits = 16;
+  if (splits < 1) splits = 1;
+  while (splits > 1 && (size_t)(splits * per_split) > a[0].ws_floats) --splits;
+  GroupArgs ga{};
+  ga.nprob = n;
+  ga.splits = splits;
+  ga.tiles_per_split = cdiv(nk, splits);
+  float* ws = a[0].ws;
+  const float* part[kMaxGroup];
+  const float* cpart[kMaxGroup];
+  int t0 = 0;
+  for (int i = 0; i < n; ++i) {
+    const Gemm& m = a[i];
+    const int64_t mn = (int64_t)m.M * m.N;
+    float* cbase = splits > 1 ? ws : (float*)m.C;
+    float* cs = !m.colsum_out ? nullptr : (splits > 1 ? ws + splits * mn : m.colsum_out);
+    part[i] = cbase;
+    cpart[i] = cs;
+    ga.g[i] = GemmDev<bf16>{(const bf16*)m.A, (const bf16*)m.B, (void*)cbase, m.M, m.N, m.K, m.lda, m.ldb, m.ldc,
+                            nullptr, nullptr, nullptr, 0};
+    ga.colsum[i] = cs;
+    ga.slab[i] = splits > 1 ? mn : 0;
+    ga.tile0[i] = t0;
+    ga.tiles_n[i] = cdiv(m.N, 256);
+    ga.vec_ok[i] = gemm_epilogue_vec_ok(m) && aligned16(cbase) ? 1 : 0;
+    t0 += cdiv(m.M, 256) * cdiv(m.N, 256);
+    if (splits > 1) ws += splits * (mn + m.N);
+  }
+  ga.tile0[n] = t0;
+  hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(8 * cdiv(t0 * splits, 8)), dim3(512), 0, st, ga);
+  if (splits > 1)
+    for (int i = 0; i < n; ++i)
+      gemm_splitk_reduce(part[i], splits, (int64_t)a[i].M * a[i].N, (float*)a[i].C, a[i].colsum_out ? cpart[i] : nullptr, a[i].N,
+                         a[i].colsum_out, st);
+  return true;
 }
 
 static void dispatch_pp_wgrad(const Gemm& a, hipStream_t st) {

@@ -138,5 +138,6 @@ void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, co
                         hipStream_t st);
 bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st);
 
 }  // namespace pt

@@ -37,6 +37,12 @@ struct Gemm {
   float* colsum_out = nullptr;
 };
 void gemm(int dt, const Gemm& g, hipStream_t st);
+// n weight-gradient products (ta, fp32 C with ldc == N) over the same K and sharing one workspace.  With
+// bf16 operands up to four of them run as one launch (one encoder block has too few output tiles per matrix
+// to fill the chip without a deep split over K); otherwise they run one after the other.
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st);
+// workspace floats gemm_wgrad_batch may use for a block's four matrices (D x 3D, D x D, D x F, F x D)
+size_t gemm_wgrad_batch_ws_floats(int D, int F);
 // true when gemm() will run the matrix-core kernel for this problem
 bool gemm_uses_mfma(int dt, const Gemm& g);
 // tile-shape override for experiments: -1 = automatic

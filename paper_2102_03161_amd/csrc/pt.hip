@@ -52,7 +52,7 @@ struct Plan {
   // work arena
   std::vector<size_t> X;   // L+1 block inputs / outputs
   std::vector<Slot> slot;  // L+1 (slot L: scratch of the forward-only prefix)
-  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
+  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
   size_t LOSS, LOSSACC, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
@@ -148,7 +148,7 @@ void make_plan(const pt_config& c, Plan* p) {
   p->HKOUT = take(TD);
   const size_t TD4 = T * D * 4;
   p->sA = take(TD4); p->sB = take(TD4); p->sC = take(TD4); p->sD = take(TD4);
-  p->oA = take(TD); p->oB = take(TD); p->oC = take(TD); p->oD = take(TD); p->dF = take(TF);
+  p->oA = take(TD); p->oB = take(TD); p->oC = take(TD); p->oD = take(TD); p->oE = take(TD); p->dF = take(TF);
   p->dQKV = take(3 * TD); p->DELTA = take(BHS);
   if (c.arch == PT_VIT_PRELN) {
     const size_t np = (size_t)B * (S - 1);
@@ -182,6 +182,7 @@ void make_plan(const pt_config& c, Plan* p) {
       const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 1024 / tiles));
       need = std::max(need, (size_t)(splits * (sh[0] * sh[1] + sh[1])));
     }
+    need = std::max(need, gemm_wgrad_batch_ws_floats(D, F));
     p->gemmws_floats = need;
     p->GEMMWS = take(need * 4);
   }
@@ -396,15 +397,25 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
   const Plan& p = c->plan;
   float* lnp = c->wf(p.LNPART);
   float* sC = c->wf(p.sC); float* sD = c->wf(p.sD);
-  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
+  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* oE = c->w(p.oE); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
   // dW[K_in, N_out] = X^T dY ; db = colsum over tokens of dY (bias_dt 0: fp32 source, else T)
   // bid >= 0: also db = column sums of dY over the tokens, riding on the same product
+  // The four weight gradients of the block are collected and run together at its end: every dY they read
+  // stays in a buffer of its own until then, and one launch over all four fills the chip where each alone
+  // would need a deep split over the tokens.
+  Gemm wg[4];
+  int nwg = 0;
   auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid) {
-    Gemm m;
+    Gemm& m = wg[nwg++];
     m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
     m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
-    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
+  };
+  auto run_wgrads = [&]() {
+    double fl = 0;
+    for (int i = 0; i < nwg; ++i) fl += 2.0 * wg[i].M * wg[i].N * wg[i].K;
+    ProfScope ps_(c, gemm_cat(dt, wg[0]), fl);
+    gemm_wgrad_batch(dt, wg, nwg, st);
   };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
@@ -431,9 +442,9 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
                   c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
   } else {
     { prof_ln_bwd(c, dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
-                  oC, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, Tn, D, st); }  // sC / oC = dL/d(Y+MLP)
-    wgrad(c->w(s.G), F, oC, D, c->blk(l, W2), -1);
-    dgrad(oC, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
+                  oE, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, Tn, D, st); }  // sC / oE = dL/d(Y+MLP)
+    wgrad(c->w(s.G), F, oE, D, c->blk(l, W2), -1);
+    dgrad(oE, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
     wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
     { prof_ln_bwd(c, dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
@@ -444,6 +455,7 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
   }
+  run_wgrads();
 }
 
 // front end over `ns` samples; sample i reads input map[i] (device, or null = identity)
