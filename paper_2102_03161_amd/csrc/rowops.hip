@@ -29,54 +29,93 @@ __device__ __forceinline__ void store4(bf16* p, const float (&v)[4]) {
   *reinterpret_cast<uint2*>(p) = t.u;
 }
 
+// four elements as loaded (converted to fp32 only when used, so a prefetched row costs few registers)
+template <typename T> struct Raw4;
+template <> struct Raw4<float> {
+  float4 r;
+  __device__ __forceinline__ void ld(const float* p) { r = *reinterpret_cast<const float4*>(p); }
+  __device__ __forceinline__ void zero() { r = make_float4(0.f, 0.f, 0.f, 0.f); }
+  __device__ __forceinline__ void get(float (&v)[4]) const { v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w; }
+};
+template <> struct Raw4<bf16> {
+  uint2 r;
+  __device__ __forceinline__ void ld(const bf16* p) { r = *reinterpret_cast<const uint2*>(p); }
+  __device__ __forceinline__ void zero() { r = make_uint2(0u, 0u); }
+  __device__ __forceinline__ void get(float (&v)[4]) const {
+    v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+    v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+  }
+};
+
 // ---------------------------------------------------------------------------
 // LayerNorm forward: one wave per row, row held in registers (D <= 256*VPL)
 // ---------------------------------------------------------------------------
+constexpr int kLnFwdBlocks = 768;   // persistent workgroups (three per CU), four waves each
 template <typename T, typename TX, int VPL>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const TX* __restrict__ x, int64_t ldx, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y, int64_t ldy,
                                                      float* __restrict__ mean, float* __restrict__ rstd, int rows, int D,
                                                      float eps) {
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
   const int nvec = D >> 2;
-  const TX* xr = x + (int64_t)row * ldx;
-  float v[VPL][4];
-  float s = 0.f;
+  Raw4<T> gr[VPL], br[VPL];
 #pragma unroll
   for (int j = 0; j < VPL; ++j) {
     const int c = lane + 64 * j;
-    if (c < nvec) {
-      load4(xr + 4 * c, v[j]);
+    gr[j].zero(); br[j].zero();
+    if (c < nvec) { gr[j].ld(gamma + 4 * c); br[j].ld(beta + 4 * c); }
+  }
+  // a wave walks over its rows with the next row's loads in flight while it reduces and stores the current one
+  auto fetch = [&](int row, Raw4<TX> (&in)[VPL]) {
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      in[j].zero();
+      if (c < nvec) in[j].ld(x + (int64_t)row * ldx + 4 * c);
+    }
+  };
+  const int stride = gridDim.x * 4;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  Raw4<TX> cur[VPL], nxt[VPL];
+  if (row < rows) fetch(row, cur);
+  for (; row < rows; row += stride) {
+    const bool more = row + stride < rows;
+    if (more) fetch(row + stride, nxt);
+    float v[VPL][4];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      cur[j].get(v[j]);
       s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
-    } else {
-      v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.f;
     }
-  }
-  const float mu = wave_sum(s) / (float)D;
-  float q = 0.f;
+    const float mu = wave_sum(s) / (float)D;
+    float q = 0.f;
 #pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = lane + 64 * j;
-    if (c < nvec) {
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mu; q += d * d; }
+        for (int e = 0; e < 4; ++e) { const float d = v[j][e] - mu; q += d * d; }
+      }
     }
-  }
-  const float rs = rsqrtf(wave_sum(q) / (float)D + eps);
-  if (lane == 0 && mean) { mean[row] = mu; rstd[row] = rs; }
-  T* yr = y + (int64_t)row * ldy;
+    const float rs = rsqrtf(wave_sum(q) / (float)D + eps);
+    if (lane == 0 && mean) { mean[row] = mu; rstd[row] = rs; }
+    T* yr = y + (int64_t)row * ldy;
 #pragma unroll
-  for (int j = 0; j < VPL; ++j) {
-    const int c = lane + 64 * j;
-    if (c < nvec) {
-      float g[4], b[4], o[4];
-      load4(gamma + 4 * c, g);
-      load4(beta + 4 * c, b);
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float g[4], b[4], o[4];
+        gr[j].get(g);
+        br[j].get(b);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = (v[j][e] - mu) * rs * g[e] + b[e];
-      store4(yr + 4 * c, o);
+        for (int e = 0; e < 4; ++e) o[e] = (v[j][e] - mu) * rs * g[e] + b[e];
+        store4(yr + 4 * c, o);
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) cur[j] = nxt[j];
     }
   }
 }
@@ -84,22 +123,31 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const TX* __restrict__ x, i
 void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
                    int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
   if (rows <= 0) return;
-  dim3 grid(cdiv(rows, 4)), blk(256);
+  dim3 grid(cdiv(rows, 4) < kLnFwdBlocks ? cdiv(rows, 4) : kLnFwdBlocks), blk(256);
 #define LN_FWD(T, TX, V)                                                                                  \
   hipLaunchKernelGGL((ln_fwd_kernel<T, TX, V>), grid, blk, 0, st, (const TX*)x, ldx, (const T*)gamma, \
                      (const T*)beta, (T*)y, ldy, mean, rstd, rows, D, eps)
-  if (dt == 0) { if (D <= 1024) LN_FWD(float, float, 4); else LN_FWD(float, float, 8); }
-  else if (x_f32) { if (D <= 1024) LN_FWD(bf16, float, 4); else LN_FWD(bf16, float, 8); }
-  else { if (D <= 1024) LN_FWD(bf16, bf16, 4); else LN_FWD(bf16, bf16, 8); }
+#define LN_FWD_V(T, TX)                               \
+  do {                                                \
+    if (D <= 768) LN_FWD(T, TX, 3);                   \
+    else if (D <= 1024) LN_FWD(T, TX, 4);             \
+    else LN_FWD(T, TX, 8);                            \
+  } while (0)
+  if (dt == 0) LN_FWD_V(float, float);
+  else if (x_f32) LN_FWD_V(bf16, float);
+  else LN_FWD_V(bf16, bf16);
+#undef LN_FWD_V
 #undef LN_FWD
 }
 
 // ---------------------------------------------------------------------------
 // LayerNorm backward
 // ---------------------------------------------------------------------------
-constexpr int kLnBwdBlocks = 1024;  // workgroups (partial rows) at most
+constexpr int kLnBwdBlocks = 512;   // workgroups (partial rows) at most: two per CU, each wave with two rows in flight
 constexpr int kLnBwdWaves = 4;      // waves per workgroup, one row per wave at a time
 size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 3 * D; }
+static int g_ln_bwd_blocks = 0;   // tuning hook: workgroups of the backward kernel (0 = default)
+void ln_set_bwd_blocks(int b) { g_ln_bwd_blocks = b; }
 
 // dy may be the fp32 gradient stream or a T tensor; the result goes to an fp32 stream
 // buffer (dx_s), a T copy for the matrix-core operands (dx_o), or both (either may be null).
@@ -121,8 +169,36 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __r
     for (int e = 0; e < 4; ++e) { ag[j][e] = 0.f; ab[j][e] = 0.f; as[j][e] = 0.f; g[j][e] = 0.f; }
     if (c < nvec) load4(gamma + 4 * c, g[j]);
   }
-  for (int row = blockIdx.x * kLnBwdWaves + wave; row < rows; row += gridDim.x * kLnBwdWaves) {
-    const float mu = mean[row], rs = rstd[row];
+  // The loads of a wave's next row go out before the current row is worked on: a wave handles only three or
+  // four rows, one after the other, and without this it has nothing in flight while it reduces and stores.
+  struct RowIn {
+    Raw4<TX> x[VPL];
+    Raw4<TDY> d[VPL];
+    Raw4<float> r[VPL];
+    float mu, rs;
+  };
+  auto fetch = [&](int row, RowIn& in) {
+    in.mu = mean[row];
+    in.rs = rstd[row];
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      in.x[j].zero(); in.d[j].zero(); in.r[j].zero();
+      if (c < nvec) {
+        in.x[j].ld(x + (int64_t)row * ldx + 4 * c);
+        in.d[j].ld(dy + (int64_t)row * lddy + 4 * c);
+        if (dres) in.r[j].ld(dres + (int64_t)row * lddres + 4 * c);
+      }
+    }
+  };
+  const int stride = gridDim.x * kLnBwdWaves;
+  int row = blockIdx.x * kLnBwdWaves + wave;
+  RowIn cur, nxt;
+  if (row < rows) fetch(row, cur);
+  for (; row < rows; row += stride) {
+    const bool more = row + stride < rows;
+    if (more) fetch(row + stride, nxt);
+    const float mu = cur.mu, rs = cur.rs;
     float xh[VPL][4], dh[VPL][4];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -130,8 +206,8 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __r
       const int c = lane + 64 * j;
       if (c < nvec) {
         float xv[4], dv[4];
-        load4(x + (int64_t)row * ldx + 4 * c, xv);
-        load4(dy + (int64_t)row * lddy + 4 * c, dv);
+        cur.x[j].get(xv);
+        cur.d[j].get(dv);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           xh[j][e] = (xv[e] - mu) * rs;
@@ -143,27 +219,24 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __r
         }
       }
     }
-    if (!dx_s && !dx_o) continue;  // only the parameter gradients are wanted
-    const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
+    if (dx_s || dx_o) {   // else only the parameter gradients are wanted
+      const float m1 = wave_sum(s1) / (float)D, m2 = wave_sum(s2) / (float)D;
 #pragma unroll
-    for (int j = 0; j < VPL; ++j) {
-      const int c = lane + 64 * j;
-      if (c < nvec) {
-        float o[4];
+      for (int j = 0; j < VPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < nvec) {
+          float o[4], res[4];
+          cur.r[j].get(res);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = (dh[j][e] - m1 - xh[j][e] * m2) * rs;
-        if (dres) {
-          float r[4];
-          load4(dres + (int64_t)row * lddres + 4 * c, r);
+          for (int e = 0; e < 4; ++e) o[e] = (dh[j][e] - m1 - xh[j][e] * m2) * rs + res[e];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] += r[e];
+          for (int e = 0; e < 4; ++e) as[j][e] += o[e];
+          if (dx_s) store4(dx_s + (int64_t)row * lddx + 4 * c, o);
+          if (dx_o) store4(dx_o + (int64_t)row * lddx + 4 * c, o);
         }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) as[j][e] += o[e];
-        if (dx_s) store4(dx_s + (int64_t)row * lddx + 4 * c, o);
-        if (dx_o) store4(dx_o + (int64_t)row * lddx + 4 * c, o);
       }
     }
+    if (more) cur = nxt;
   }
   // combine the waves of the workgroup in wave order (fixed, so reproducible)
   for (int w = 0; w < kLnBwdWaves; ++w) {
@@ -225,7 +298,8 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
                    float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
                    int rows, int D, hipStream_t st) {
   if (rows <= 0) return;
-  const int nb = cdiv(rows, kLnBwdWaves) < kLnBwdBlocks ? cdiv(rows, kLnBwdWaves) : kLnBwdBlocks;
+  const int cap = g_ln_bwd_blocks > 0 && g_ln_bwd_blocks < kLnBwdBlocks ? g_ln_bwd_blocks : kLnBwdBlocks;
+  const int nb = cdiv(rows, kLnBwdWaves) < cap ? cdiv(rows, kLnBwdWaves) : cap;
   const size_t shm = (size_t)3 * D * sizeof(float);
 #define LN_BWD(T, TDY, TX, V)                                                                                      \
   hipLaunchKernelGGL((ln_bwd_kernel<T, TDY, TX, V>), dim3(nb), dim3(64 * kLnBwdWaves), shm, st, (const TDY*)dy, lddy,           \
