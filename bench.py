@@ -29,9 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
 # read for the --calibrate-copy kernel; the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0, "gemm_nn"): 129244402 + 60812042,    # fetched + written, forward products
-    ("vit_b16", 0, "gemm_nt"): 160936801 + 33200671,    # input-gradient products
-    ("vit_b16", 0, "gemm_tn"): 169490624 + 62538963,    # weight-gradient products incl. their split-K reduction
+    ("vit_b16", 0, "gemm_nn"): 123739897 + 60812042,    # fetched + written, forward products
+    ("vit_b16", 0, "gemm_nt"): 161423765 + 33200671,    # input-gradient products
+    ("vit_b16", 0, "gemm_tn"): 478206636 + 75607319,    # weight gradients (one grouped launch per block) incl. their split-K reductions
 }
 
 
@@ -172,9 +172,9 @@ def main():
     dom = max(gemm_names, key=lambda n: prof[n][0])
     ms, n, wk = prof[dom]
     ach = wk / (ms * 1e-3) / 1e12
-    result["roofline"] = {"kernel": {"gemm_tn": "gemm_dma_kernel<TA=true,TB=false> (weight gradient dW = x^T dy)",
-                                     "gemm_nn": "gemm_dma_kernel<TA=false,TB=false> (forward y = x W)",
-                                     "gemm_nt": "gemm_dma_kernel<TA=false,TB=true> (input gradient dx = dy W^T)"}[dom],
+    result["roofline"] = {"kernel": {"gemm_tn": "weight-gradient GEMMs dW = x^T dy (gemm_wgrad_group_kernel + splitk_reduce_kernel)",
+                                     "gemm_nn": "forward GEMMs y = x W (gemm_pp_kernel / gemm_pp2_kernel / gemm_dma_kernel, TA=false TB=false)",
+                                     "gemm_nt": "input-gradient GEMMs dx = dy W^T (gemm_pp2_kernel / gemm_dma_kernel, TB=true)"}[dom],
                           "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                           "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                           "traffic": MEASURED_TRAFFIC.get((a.workload, a.k, dom)),
