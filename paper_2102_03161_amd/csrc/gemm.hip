@@ -310,6 +310,43 @@ void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, co
                      vec_ok4(part, n, out), blocks_main, part2, part2 ? n2 : 0, out2, part2 ? vec_ok4(part2, n2, out2) : 0);
 }
 
+// the reductions of up to four products in one launch (same split count)
+struct ReduceGroup {
+  const float* part[4]; float* out[4]; int64_t n[4]; int vec[4];
+  const float* part2[4]; float* out2[4]; int64_t n2[4]; int vec2[4];
+  int block0[5];      // first workgroup of each product
+  int blocks_main[4];
+  int nprob, splits;
+};
+__global__ __launch_bounds__(256) void splitk_reduce_group_kernel(ReduceGroup rg) {
+  int p = 0;
+  while (p + 1 < rg.nprob && (int)blockIdx.x >= rg.block0[p + 1]) ++p;
+  const int b = (int)blockIdx.x - rg.block0[p];
+  if (b < rg.blocks_main[p]) {
+    splitk_sum4(rg.part[p], rg.splits, rg.n[p], rg.out[p], rg.vec[p], ((int64_t)b * 256 + threadIdx.x) * 4);
+  } else {
+    const int64_t i = ((int64_t)(b - rg.blocks_main[p]) * 256 + threadIdx.x) * 4;
+    if (i < rg.n2[p]) splitk_sum4(rg.part2[p], rg.splits, rg.n2[p], rg.out2[p], rg.vec2[p], i);
+  }
+}
+void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,
+                              const float* const* part2, const int64_t* n2, float* const* out2, hipStream_t st) {
+  ReduceGroup rg{};
+  rg.nprob = nprob;
+  rg.splits = splits;
+  int b0 = 0;
+  for (int i = 0; i < nprob; ++i) {
+    rg.part[i] = part[i]; rg.out[i] = out[i]; rg.n[i] = n[i]; rg.vec[i] = vec_ok4(part[i], n[i], out[i]);
+    rg.part2[i] = part2[i]; rg.out2[i] = out2[i]; rg.n2[i] = part2[i] ? n2[i] : 0;
+    rg.vec2[i] = part2[i] ? vec_ok4(part2[i], n2[i], out2[i]) : 0;
+    rg.block0[i] = b0;
+    rg.blocks_main[i] = (int)cdiv64(n[i], 1024);
+    b0 += rg.blocks_main[i] + (part2[i] ? (int)cdiv64(n2[i], 1024) : 0);
+  }
+  rg.block0[nprob] = b0;
+  hipLaunchKernelGGL(splitk_reduce_group_kernel, dim3((unsigned)b0), dim3(256), 0, st, rg);
+}
+
 // ---------------------------------------------------------------------------
 // dispatch
 // ---------------------------------------------------------------------------

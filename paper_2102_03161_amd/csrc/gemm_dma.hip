@@ -847,10 +847,19 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st) {
   }
   ga.tile0[n] = t0;
   hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(8 * cdiv(t0 * splits, 8)), dim3(512), 0, st, ga);
-  if (splits > 1)
-    for (int i = 0; i < n; ++i)
-      gemm_splitk_reduce(part[i], splits, (int64_t)a[i].M * a[i].N, (float*)a[i].C, a[i].colsum_out ? cpart[i] : nullptr, a[i].N,
-                         a[i].colsum_out, st);
+  if (splits > 1) {
+    int64_t mn[kMaxGroup], nn[kMaxGroup];
+    float* out[kMaxGroup];
+    float* out2[kMaxGroup];
+    for (int i = 0; i < n; ++i) {
+      mn[i] = (int64_t)a[i].M * a[i].N;
+      nn[i] = a[i].N;
+      out[i] = (float*)a[i].C;
+      out2[i] = a[i].colsum_out;
+      if (!a[i].colsum_out) cpart[i] = nullptr;
+    }
+    gemm_splitk_reduce_group(n, splits, part, mn, out, cpart, nn, out2, st);
+  }
   return true;
 }
 

@@ -139,5 +139,8 @@ void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, co
 bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
 bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st);
+// the split-K reductions of up to four products (part2 entries may be null) in one launch
+void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,
+                              const float* const* part2, const int64_t* n2, float* const* out2, hipStream_t st);
 
 }  // namespace pt
