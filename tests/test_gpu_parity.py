@@ -420,6 +420,17 @@ def test_degenerate_and_odd_shapes(torch_mod, name, dtype):
         run_case(torch_mod, w, k, w["B"], seed=13, tol=TOL[dtype])
 
 
+def test_many_tokens_with_ragged_widths(torch_mod):
+    """8320 tokens (a multiple of 64) with widths that are no multiple of the 256-column tiles: forward and
+    input-gradient products go through the two-group matrix-core kernels (192- and 256-row tiles, clamped
+    edge tiles in both directions) and the block's weight gradients through the grouped launch with a
+    15-way split over the tokens."""
+    w = dict(arch="vit", L=2, D=128, H=2, F=1728, S=65, n_out=10, img=32, patch=4, chans=3, vocab=0, max_pos=0,
+             ln_eps=1e-6, B=128, optimizer="adamw", dtype="bf16")
+    for k in (0, 1):
+        run_case(torch_mod, w, k, w["B"], seed=19, tol=TOL["bf16"])
+
+
 def test_span_head_over_one_position_gives_exact_zeros(torch_mod):
     """S = 1 with the span head: each softmax runs over a single position, so the loss and every gradient are
     exactly zero, on the GPU as in the oracle."""
