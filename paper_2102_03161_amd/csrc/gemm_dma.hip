@@ -331,7 +331,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
 // one tile ahead.  Loads are issued a few per phase, behind MFMAs where the issuing wave computes.  Per
 // wave and iteration the order is B(t+1) in phase 0, then A(t+2) over phases 1-3, so that "at most
 // LA::LOADS loads outstanding" at the end of phase 3 means A(t+1) and B(t+1) have landed.
-// one output tile (rows m0.., columns n0..) over the k tiles of `split`; all 512 threads of the workgroup
+//
+// pp_run computes one output tile (rows m0.., columns n0..) over the k tiles of `split`; all 512 threads of
+// the workgroup take part.
 template <int BM, bool TA, bool TB, int EPI, typename TC>
 __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int m0, int n0, int vec_ok) {
   constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
@@ -508,21 +510,6 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
                                              n0 + wn * WTN, lane, vec_ok);
 }
 
-template <int BM, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
-                                                      int vec_ok) {
-  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
-  const int per = (total_work + 7) >> 3;
-  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (work >= total_work) return;
-  const int split = work / total_tiles;
-  const int tt = work - split * total_tiles;
-  const int cg = tt / (group_n * tiles_m);
-  const int rem = tt - cg * group_n * tiles_m;
-  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
-  pp_run<BM, TA, TB, EPI, TC>(g, sp, split, (rem / gw) * BM, (cg * group_n + rem % gw) * 256, vec_ok);
-}
-
 // Several weight gradients dW_p = X_p^T dY_p over the same tokens in one launch.  One encoder block has
 // only 108 output tiles of 256x256 in its four weight matrices; launched one matrix at a time each needs a
 // 7- to 16-way split over K to occupy the chip and then writes and re-reads that many fp32 slabs.  Together
@@ -552,9 +539,10 @@ __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
                                              ga.vec_ok[p]);
 }
 
+// The same tile with whole-tile phases (see below); needs the fragments of a whole k tile in registers, which
+// only 192-row tiles leave room for.
 template <int BM, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(512) void gemm_pp2_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
-                                                      int vec_ok) {
+__device__ __forceinline__ void pp2_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int m0, int n0, int vec_ok) {
   constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
   constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
   static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
@@ -568,16 +556,6 @@ __global__ __launch_bounds__(512) void gemm_pp2_kernel(GemmDev<bf16> g, SplitArg
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
   const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
-  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
-  const int per = (total_work + 7) >> 3;
-  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (work >= total_work) return;
-  const int split = work / total_tiles;
-  const int tt = work - split * total_tiles;
-  const int cg = tt / (group_n * tiles_m);
-  const int rem = tt - cg * group_n * tiles_m;
-  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
-  const int m0 = (rem / gw) * BM, n0 = (cg * group_n + rem % gw) * BN;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -711,6 +689,25 @@ __global__ __launch_bounds__(512) void gemm_pp2_kernel(GemmDev<bf16> g, SplitArg
                                              n0 + wn * WTN, lane, vec_ok);
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin by their index; the index is remapped so that one XCD works
+// through a contiguous range of {split, column group, tile row, tile column} (see gemm_dma_kernel).
+template <int BM, bool WHOLE, bool TA, bool TB, int EPI, typename TC>
+__global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n, int group_n,
+                                                      int vec_ok) {
+  const int total_tiles = tiles_m * tiles_n, total_work = total_tiles * sp.splits;
+  const int per = (total_work + 7) >> 3;
+  const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (work >= total_work) return;
+  const int split = work / total_tiles;
+  const int tt = work - split * total_tiles;
+  const int cg = tt / (group_n * tiles_m);
+  const int rem = tt - cg * group_n * tiles_m;
+  const int gw = tiles_n - cg * group_n < group_n ? tiles_n - cg * group_n : group_n;
+  const int m0 = (rem / gw) * BM, n0 = (cg * group_n + rem % gw) * 256;
+  if constexpr (WHOLE) pp2_run<BM, TA, TB, EPI, TC>(g, sp, split, m0, n0, vec_ok);
+  else pp_run<BM, TA, TB, EPI, TC>(g, sp, split, m0, n0, vec_ok);
+}
+
 int g_group_n = 0;                  // forced column-group width (tuning); 0 = derive from g_group_bytes
 int64_t g_group_bytes = 1536 << 10;  // L2 bytes a column group's B panels may take
 
@@ -752,12 +749,8 @@ void launch_pp(const Gemm& a, int splits, float* cbase, int64_t slab, float* col
   if (group_n > tiles_n) group_n = tiles_n;
   // 192-row tiles leave room for a whole k tile of fragments in registers (whole-tile phases, 4-5 % faster);
   // 256-row tiles do not
-  if constexpr (BM == 192)
-    hipLaunchKernelGGL((gemm_pp2_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
-                       gemm_epilogue_vec_ok(a) ? 1 : 0);
-  else
-    hipLaunchKernelGGL((gemm_pp_kernel<BM, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n, group_n,
-                       gemm_epilogue_vec_ok(a) ? 1 : 0);
+  hipLaunchKernelGGL((gemm_pp_kernel<BM, BM == 192, TA, TB, EPI, TC>), grid, dim3(512), 0, st, g, sp, tiles_m, tiles_n,
+                     group_n, gemm_epilogue_vec_ok(a) ? 1 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -863,27 +856,6 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st) {
   return true;
 }
 
-static void dispatch_pp_wgrad(const Gemm& a, hipStream_t st) {
-  const int tiles = cdiv(a.M, 256) * cdiv(a.N, 256), nk = a.K / 64;
-  int splits = 1;
-  const int64_t mn = (int64_t)a.M * a.N;
-  if (a.ws) {
-    splits = g_split_target / tiles;
-    if (splits > nk / 4) splits = nk / 4;
-    if (splits > 16) splits = 16;
-    if (splits < 1) splits = 1;
-    while (splits > 1 && (size_t)(splits * (mn + a.N)) > a.ws_floats) --splits;
-  }
-  float* cs_part = nullptr;
-  if (a.colsum_out) cs_part = splits > 1 ? a.ws + splits * mn : a.colsum_out;
-  if (splits > 1) {
-    launch_pp<256, true, false, EPI_STORE, float>(a, splits, a.ws, mn, cs_part, st);
-    gemm_splitk_reduce(a.ws, splits, mn, (float*)a.C, a.colsum_out ? cs_part : nullptr, a.N, a.colsum_out, st);
-  } else {
-    launch_pp<256, true, false, EPI_STORE, float>(a, 1, nullptr, 0, cs_part, st);
-  }
-}
-
 template <int BM>
 static void dispatch_pp_fwd(const Gemm& a, hipStream_t st) {
 #define PT_L(TB_, EPI_, TC_) launch_pp<BM, false, TB_, EPI_, TC_>(a, 1, nullptr, 0, nullptr, st)
@@ -926,32 +898,21 @@ static void dispatch_fwd(const Gemm& a, hipStream_t st) {
 }
 
 void gemm_dma(const Gemm& a, int variant, hipStream_t st) {
+  // variants: 1 = 128x128 tiles, 2 = 256x128, 5 / 6 = the two-group kernel with 256 / 192-row tiles
+  if (a.ta) {   // a single weight gradient (a block's four go through gemm_wgrad_group)
+    if (variant == 1) dispatch_wgrad<128, 128, 2, 2>(a, st);
+    else dispatch_wgrad<256, 128, 4, 2>(a, st);
+    return;
+  }
   if ((variant == 5 || variant == 6) && a.K % 64 == 0) {
-    if (a.ta) dispatch_pp_wgrad(a, st);
-    else if (variant == 5) dispatch_pp_fwd<256>(a, st);
+    if (variant == 5) dispatch_pp_fwd<256>(a, st);
     else dispatch_pp_fwd<192>(a, st);
     return;
   }
-  if (a.ta) {
-    switch (variant) {
-      case 2: dispatch_wgrad<256, 128, 4, 2>(a, st); break;
-      case 3: dispatch_wgrad<256, 256, 2, 4>(a, st); break;
-      default: dispatch_wgrad<128, 128, 2, 2>(a, st); break;
-    }
-    return;
-  }
-  if (a.K % 64 != 0) {   // 64-wide k tiles need K to be a multiple of 64
-    dispatch_fwd<128, 128, 2, 2, 3, 32>(a, st);
-    return;
-  }
-  // Measured at the ViT-B / BERT-base shapes: 64-wide k tiles (whole cache lines for k-major operands) pay
-  // for the 256x256 tiling (3-10 %); the smaller tilings then fit one workgroup less per CU and lose, so
-  // they keep 32-wide tiles and three stages.
-  switch (variant) {
-    case 2: dispatch_fwd<256, 128, 4, 2, 3, 32>(a, st); break;
-    case 3: dispatch_fwd<256, 256, 2, 4, 2, 64>(a, st); break;
-    default: dispatch_fwd<128, 128, 2, 2, 3, 32>(a, st); break;
-  }
+  // The single-role tilings keep 32-wide k tiles and three stages: with 64-wide tiles they fit one workgroup
+  // less per CU and lose more than the whole-line loads gain.
+  if (variant == 2 && a.K % 64 == 0) dispatch_fwd<256, 128, 4, 2, 3, 32>(a, st);
+  else dispatch_fwd<128, 128, 2, 2, 3, 32>(a, st);
 }
 
 }  // namespace pt
