@@ -46,6 +46,8 @@ struct SplitArgs {
   float* colsum;      // [splits][N] column sums of B over the split's k range (TB == false only), or null
 };
 
+typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));   // operand type of the nontemporal builtins
+
 // 8 consecutive output columns of one row: epilogue math and 16-byte stores
 template <int EPI, typename TC>
 __device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cbase, int row, int col, float (&v)[8]) {
@@ -56,8 +58,11 @@ __device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cb
     for (int e = 0; e < 8; ++e) v[e] += to_f32(b.h[e]);
   }
   if (EPI == EPI_BIAS_RES || (EPI == EPI_RES && sizeof(TC) == 2) || EPI == EPI_MUL_DGELU) {
-    union { uint4 u; bf16 h[8]; } a;
-    a.u = *reinterpret_cast<const uint4*>(g.aux + (int64_t)row * g.ld_aux + col);
+    union { uint4 u; u32x4_nt v; bf16 h[8]; } a;
+    const bf16* ap = g.aux + (int64_t)row * g.ld_aux + col;
+    // the saved pre-activation is read exactly once, here: past the caches; a residual input was just written
+    if (EPI == EPI_MUL_DGELU) a.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(ap));
+    else a.u = *reinterpret_cast<const uint4*>(ap);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       if (EPI == EPI_MUL_DGELU) v[e] *= dgelu_f(to_f32(a.h[e])); else v[e] += to_f32(a.h[e]);
@@ -73,7 +78,10 @@ __device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cb
       union { uint4 u; bf16 h[8]; } o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
-      *reinterpret_cast<uint4*>(g.aux_out + (int64_t)row * g.ld_aux + col) = o.u;
+      // the pre-activation is read again only in the backward pass: written past the caches
+      union { uint4 u; u32x4_nt v; } nt;
+      nt.u = o.u;
+      __builtin_nontemporal_store(nt.v, reinterpret_cast<u32x4_nt*>(g.aux_out + (int64_t)row * g.ld_aux + col));
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
