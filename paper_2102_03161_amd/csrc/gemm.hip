@@ -509,7 +509,8 @@ void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st) {
   if (n <= 0) return;
   bool mfma = dt != 0 && g_cfg_override != 0;
   for (int i = 0; i < n && mfma; ++i) mfma = gemm_uses_mfma(dt, g[i]);
-  if (mfma && n > 1 && gemm_wgrad_group(g, n, st)) return;
+  // one product alone goes to the grouped kernel too when its contraction is long (the tokens of a batch)
+  if (mfma && (n > 1 || g[0].K >= 2048) && gemm_wgrad_group(g, n, st)) return;
   for (int i = 0; i < n; ++i) gemm(dt, g[i], st);
 }
 

@@ -113,6 +113,16 @@ void fill_zero(void* p, size_t bytes, hipStream_t st);
 // dst[dst_idx[i]] = src[src_idx[i]] for rows of row_bytes (multiple of 16); idx null = identity
 void copy_rows(void* dst, const int64_t* dst_idx, const void* src, const int64_t* src_idx, int nrows,
                size_t row_bytes, hipStream_t st);
+// nrows rows of row_bytes each from src + i * src_stride to dst + i * dst_stride (bytes), several such copies
+// per launch: gathers every S-th row of a tensor into a dense block and scatters it back
+struct RowCopy {
+  const void* src;
+  void* dst;
+  int64_t src_stride, dst_stride;
+  int row_bytes;
+};
+constexpr int kMaxRowCopies = 12;
+void strided_rows_copy(const RowCopy* d, int n, int nrows, hipStream_t st);
 void f32_to_bf16(const float* src, void* dst, size_t n, hipStream_t st);
 void bf16_to_f32(const void* src, float* dst, size_t n, hipStream_t st);
 

@@ -52,7 +52,9 @@ struct Plan {
   // work arena
   std::vector<size_t> X;   // L+1 block inputs / outputs
   std::vector<Slot> slot;  // L+1 (slot L: scratch of the forward-only prefix)
-  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, dF, dQKV, DELTA;  // s*: fp32 gradient stream, o*: T operand copies
+  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, dF, dQKV, DELTA;
+  // dense copies of the first token's rows (top block's backward under a first-token head)
+  size_t rG, rHP, rDF, rXa, rXb, rCTX, rDO, rOC, rOD, rDCTX, rS0, rS1, rS2, rST;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
   size_t LOSS, LOSSACC, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
@@ -150,6 +152,14 @@ void make_plan(const pt_config& c, Plan* p) {
   p->sA = take(TD4); p->sB = take(TD4); p->sC = take(TD4); p->sD = take(TD4);
   p->oA = take(TD); p->oB = take(TD); p->oC = take(TD); p->oD = take(TD); p->oE = take(TD); p->dF = take(TF);
   p->dQKV = take(3 * TD); p->DELTA = take(BHS);
+  {
+    const size_t BD = (size_t)B * D, BF = (size_t)B * F;
+    p->rG = take(BF * e); p->rHP = take(BF * e); p->rDF = take(BF * e);
+    p->rXa = take(BD * 4); p->rXb = take(BD * 4); p->rCTX = take(BD * e); p->rDO = take(BD * e);
+    p->rOC = take(BD * e); p->rOD = take(BD * e); p->rDCTX = take(BD * e);
+    p->rS0 = take(BD * 4); p->rS1 = take(BD * 4); p->rS2 = take(BD * 4);
+    p->rST = take((size_t)B * 4 * 4);
+  }
   if (c.arch == PT_VIT_PRELN) {
     const size_t np = (size_t)B * (S - 1);
     p->PATCH = take(np * c.chans * c.patch * c.patch * e);
@@ -456,6 +466,101 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
   }
   run_wgrads();
+}
+
+
+// ---------------------------------------------------------------------------
+// Backward of the top block when the head reads only each sample's first token (ViT class token, BERT
+// sequence classification): dL/dx_L is zero in every other row, so everything between the block's output and
+// its attention (both MLP products and their weight gradients, the LayerNorms, the output projection) involves
+// ns rows instead of ns * S.  Those rows are gathered into dense buffers, pushed through the same kernels, and
+// scattered back in front of the attention backward, which needs every token.  dout rows other than the first
+// tokens' must be zero on entry (the head backward zero-fills them); they are reused as the zero background
+// of the scattered tensors.  The results equal those of block_backward (rows of zeros contribute nothing).
+// ---------------------------------------------------------------------------
+void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns,
+                               bool need_dx, float* lower_b2) {
+  const pt_config& g = c->cfg;
+  const int D = g.D, F = g.F, S = g.S, Tn = ns * g.S, dt = c->dt;
+  const int64_t e = c->esz, SD = (int64_t)S * D;
+  hipStream_t st = c->st;
+  const Plan& p = c->plan;
+  float* lnp = c->wf(p.LNPART);
+  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dQKV = c->w(p.dQKV);
+  void* rG = c->w(p.rG); void* rHP = c->w(p.rHP); void* rDF = c->w(p.rDF); void* rXa = c->w(p.rXa); void* rXb = c->w(p.rXb);
+  void* rCTX = c->w(p.rCTX); void* rDO = c->w(p.rDO); void* rOC = c->w(p.rOC); void* rOD = c->w(p.rOD);
+  void* rDCTX = c->w(p.rDCTX);
+  float* rS0 = c->wf(p.rS0); float* rS1 = c->wf(p.rS1); float* rS2 = c->wf(p.rS2);
+  float* rmu1 = c->wf(p.rST); float* rrs1 = rmu1 + ns; float* rmu2 = rrs1 + ns; float* rrs2 = rmu2 + ns;
+  auto wgrad = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid, int rows) {
+    Gemm m;
+    m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
+    m.M = Kin; m.N = Nout; m.K = rows; m.c_f32 = true;
+    m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
+    ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K);
+    gemm_wgrad_batch(dt, &m, 1, st);
+  };
+  auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32, int rows) {
+    Gemm m;
+    m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
+    m.M = rows; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin; m.c_f32 = out_f32;
+    ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K);
+    gemm(dt, m, st);
+  };
+  auto row = [&](const void* src, int64_t src_elems, int esz_, void* dst, int cols) {   // gather descriptor
+    return RowCopy{src, dst, src_elems * esz_, (int64_t)cols * esz_, cols * esz_};
+  };
+  auto back = [&](const void* src, int cols, int esz_, void* dst, int64_t dst_elems) {   // scatter descriptor
+    return RowCopy{src, dst, (int64_t)cols * esz_, dst_elems * esz_, cols * esz_};
+  };
+  if (g.arch == PT_VIT_PRELN) {
+    const RowCopy in[] = {row(dout.o, SD, e, rDO, D), row(dout.s, SD, 4, rS0, D), row(c->w(s.G), (int64_t)S * F, e, rG, F),
+                          row(c->w(s.HP), (int64_t)S * F, e, rHP, F), row(c->w(s.WN), SD, e, rXa, D),
+                          row(c->w(s.Y), SD, e, rXb, D), row(c->w(s.CTX), SD, e, rCTX, D),
+                          row(c->wf(s.MU2), S, 4, rmu2, 1), row(c->wf(s.RS2), S, 4, rrs2, 1)};
+    strided_rows_copy(in, 9, ns, st);
+    wgrad(rG, F, rDO, D, c->blk(l, W2), -1, ns);
+    dgrad(rDO, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
+    wgrad(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);
+    dgrad(rDF, F, c->blk(l, W1), rOC, D, EPI_STORE, nullptr, false, ns);                 // dL/dLN2out
+    { prof_ln_bwd(c, dt, false, false, rOC, D, rXb, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), rS0, D, rS1, rOD, D,
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOD = dL/dY
+    wgrad(rCTX, D, rOD, D, c->blk(l, WO), -1, ns);
+    dgrad(rOD, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
+    // dout.s becomes dL/dY and dout.o dL/dCTX: their other rows are zero already
+    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD), back(rDCTX, D, e, dout.o, SD)};
+    strided_rows_copy(out, 2, ns, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dout.o, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
+    wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
+    dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false, Tn);            // dL/dU
+    { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dout.s, D,
+                  need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
+                  c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
+  } else {
+    // post-LN: U = x + Attn(x) and WN = Y + MLP(Y) are the fp32 sums in front of the two LayerNorms
+    const RowCopy in[] = {row(dout.s, SD, 4, rS0, D), row(c->w(s.WN), SD, 4, rXa, D), row(c->w(s.U), SD, 4, rXb, D),
+                          row(c->w(s.G), (int64_t)S * F, e, rG, F), row(c->w(s.HP), (int64_t)S * F, e, rHP, F),
+                          row(c->w(s.Y), SD, e, rDO, D), row(c->w(s.CTX), SD, e, rCTX, D),
+                          row(c->wf(s.MU2), S, 4, rmu2, 1), row(c->wf(s.RS2), S, 4, rrs2, 1),
+                          row(c->wf(s.MU1), S, 4, rmu1, 1), row(c->wf(s.RS1), S, 4, rrs1, 1)};
+    strided_rows_copy(in, 11, ns, st);
+    { prof_ln_bwd(c, dt, true, true, rS0, D, rXa, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), nullptr, 0, rS1, rOD, D,
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, ns, D, st); }  // rS1 / rOD = dL/d(Y+MLP)
+    wgrad(rG, F, rOD, D, c->blk(l, W2), -1, ns);
+    dgrad(rOD, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
+    wgrad(rDO, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);                              // rDO holds the rows of Y here
+    dgrad(rDF, F, c->blk(l, W1), rS2, D, EPI_RES, rS1, true, ns);                          // rS2 = dL/dY
+    { prof_ln_bwd(c, dt, true, true, rS2, D, rXb, D, rmu1, rrs1, c->cp(c->blk(l, LN1_G)), nullptr, 0, rS1, rOC, D,
+                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOC = dL/d(x+Attn)
+    wgrad(rCTX, D, rOC, D, c->blk(l, WO), -1, ns);
+    dgrad(rOC, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
+    fill_zero(oD, (size_t)Tn * D * e, st);
+    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD), back(rDCTX, D, e, oD, SD)};
+    strided_rows_copy(out, 2, ns, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
+    wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
+    if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, dout.s, true, Tn);
+  }
 }
 
 // front end over `ns` samples; sample i reads input map[i] (device, or null = identity)
@@ -1003,7 +1108,10 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     const void* xin = (l == k) ? d_hk : c->w(p.X[l]);
     const bool need_dx = (l > k) || (k == 0);
     float* lower_b2 = (g.arch == PT_VIT_PRELN && l > k) ? c->gp(c->blk(l - 1, B2)) : nullptr;
-    block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
+    // under a first-token head only those tokens' rows of dL/dx_L are non-zero
+    const bool first_rows = l == L - 1 && S >= 4 && (g.arch == PT_VIT_PRELN || g.head == PT_HEAD_CLS);
+    if (first_rows) block_backward_first_rows(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
+    else block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     std::swap(dcur, dnext);
   }
   if (k == 0) front_backward(c, dcur.s, nb);

@@ -757,6 +757,31 @@ void copy_rows(void* dst, const int64_t* dst_idx, const void* src, const int64_t
                      (const uint4*)src, src_idx, rv);
 }
 
+// several strided row copies in one launch: blockIdx.y picks the copy, blockIdx.x the row
+struct RowCopyBatch {
+  RowCopy d[kMaxRowCopies];
+  int n;
+};
+__global__ __launch_bounds__(256) void strided_rows_kernel(RowCopyBatch b) {
+  const RowCopy c = b.d[blockIdx.y];
+  const char* s = (const char*)c.src + (int64_t)blockIdx.x * c.src_stride;
+  char* d = (char*)c.dst + (int64_t)blockIdx.x * c.dst_stride;
+  if (((c.row_bytes | c.src_stride | c.dst_stride | (int64_t)(uintptr_t)c.src | (int64_t)(uintptr_t)c.dst) & 3) == 0) {
+    for (int i = threadIdx.x; i < c.row_bytes / 4; i += 256)
+      reinterpret_cast<uint32_t*>(d)[i] = reinterpret_cast<const uint32_t*>(s)[i];
+  } else {
+    for (int i = threadIdx.x; i < c.row_bytes; i += 256) d[i] = s[i];
+  }
+}
+void strided_rows_copy(const RowCopy* d, int n, int nrows, hipStream_t st) {
+  if (n <= 0 || nrows <= 0) return;
+  RowCopyBatch b{};
+  b.n = n < kMaxRowCopies ? n : kMaxRowCopies;
+  for (int i = 0; i < b.n; ++i) b.d[i] = d[i];
+  hipLaunchKernelGGL(strided_rows_kernel, dim3(nrows, b.n), dim3(256), 0, st, b);
+  if (n > kMaxRowCopies) strided_rows_copy(d + kMaxRowCopies, n - kMaxRowCopies, nrows, st);
+}
+
 __global__ void f32_to_bf16_kernel(const float* __restrict__ s, bf16* __restrict__ d, size_t n) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     d[i] = from_f32<bf16>(s[i]);
