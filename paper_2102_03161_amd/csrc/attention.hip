@@ -279,6 +279,132 @@ static void attention_fwd_t(const void* qkv, void* ctx, float* lse, int nb, int 
   hipLaunchKernelGGL(attn_fwd_kernel<T>, dim3(cdiv(S, TQ), H, nb), dim3(256), shm, st, (const T*)qkv, (T*)ctx, lse, S, H,
                      dh, Spad);
 }
+// ---------------------------------------------------------------------------
+// backward when only each sample's first query has a non-zero output gradient (the top block under a
+// first-token head).  One workgroup per (sample, head): p_t = exp(q.k_t * scale - lse), dV_t = p_t dO,
+// dS_t = p_t (dO.v_t - dO.o), dK_t = scale dS_t q, dQ_0 = scale sum_t dS_t k_t, dQ_t = 0 otherwise.
+// do_rows is dense: [nb, D], the first tokens' rows only.  One thread per key; the sum over keys for dQ_0
+// is taken by dh threads in key order (fixed, so reproducible).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
+  union { uint4 u; bf16 h[8]; } t;
+  t.u = *reinterpret_cast<const uint4*>(p);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = to_f32(t.h[i]);
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+  union { uint4 u; bf16 h[8]; } t;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) t.h[i] = from_f32<bf16>(v[i]);
+  *reinterpret_cast<uint4*>(p) = t.u;
+}
+// VEC: dh is a multiple of 8, so every head slice of a row starts on a 16-byte boundary and is moved in
+// 8-element pieces
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __restrict__ qkv, const T* __restrict__ ctx,
+                                                                   const T* __restrict__ do_rows,
+                                                                   const float* __restrict__ lse, T* __restrict__ dqkv,
+                                                                   int S, int H, int dh) {
+  extern __shared__ float sm[];
+  float* qs = sm;            // [dh]
+  float* dos = qs + dh;      // [dh]
+  float* dss = dos + dh;     // [S]
+  __shared__ float delta_s;
+  const int D = H * dh;
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+  const T* base = qkv + (int64_t)b * S * 3 * D + h * dh;
+  T* obase = dqkv + (int64_t)b * S * 3 * D + h * dh;
+  const float scale = rsqrtf((float)dh);
+  for (int d = tid; d < dh; d += 256) {
+    qs[d] = to_f32(base[d]);
+    dos[d] = to_f32(do_rows[(int64_t)b * D + h * dh + d]);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const T* o = ctx + (int64_t)b * S * D + h * dh;
+    float s = 0.f;
+    for (int d = 0; d < dh; ++d) s = fmaf(dos[d], to_f32(o[d]), s);
+    delta_s = s;
+  }
+  __syncthreads();
+  const float l0 = lse[((int64_t)b * H + h) * S], dl = delta_s;
+  if (VEC) {
+    // dh / 8 lanes share a key: each moves one 16-byte piece of the key's rows, so a wave reads and writes
+    // whole rows; the two dot products are finished with lane exchanges inside the group
+    const int lpr = dh >> 3, j = tid % lpr, d0 = 8 * j;
+    for (int t0 = 0; t0 < S; t0 += 256 / lpr) {
+      const int t = t0 + tid / lpr;
+      const bool ok = t < S;
+      const T* kr = base + (int64_t)(ok ? t : 0) * 3 * D + D;
+      float kv[8], vv[8];
+      load8(kr + d0, kv);
+      load8(kr + D + d0, vv);
+      float sc = 0.f, dp = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { sc = fmaf(qs[d0 + i], kv[i], sc); dp = fmaf(dos[d0 + i], vv[i], dp); }
+      for (int o = 1; o < lpr; o <<= 1) { sc += __shfl_xor(sc, o, 64); dp += __shfl_xor(dp, o, 64); }
+      if (!ok) continue;
+      const float pt = __expf(sc * scale - l0);
+      const float ds = pt * (dp - dl);
+      if (j == 0) dss[t] = ds;
+      T* dq = obase + (int64_t)t * 3 * D;
+      const float dsk = ds * scale;
+      float z[8], a[8], c2[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { z[i] = 0.f; a[i] = dsk * qs[d0 + i]; c2[i] = pt * dos[d0 + i]; }
+      if (t > 0) store8(dq + d0, z);
+      store8(dq + D + d0, a);
+      store8(dq + 2 * D + d0, c2);
+    }
+  } else {
+    for (int t = tid; t < S; t += 256) {
+      const T* kr = base + (int64_t)t * 3 * D + D;
+      const T* vr = kr + D;
+      float sc = 0.f, dp = 0.f;
+      for (int d = 0; d < dh; ++d) { sc = fmaf(qs[d], to_f32(kr[d]), sc); dp = fmaf(dos[d], to_f32(vr[d]), dp); }
+      const float pt = __expf(sc * scale - l0);
+      const float ds = pt * (dp - dl);
+      dss[t] = ds;
+      T* dq = obase + (int64_t)t * 3 * D;
+      T* dk = dq + D;
+      T* dv = dk + D;
+      const float dsk = ds * scale;
+      for (int d = 0; d < dh; ++d) {
+        if (t > 0) dq[d] = from_f32<T>(0.f);
+        dk[d] = from_f32<T>(dsk * qs[d]);
+        dv[d] = from_f32<T>(pt * dos[d]);
+      }
+    }
+  }
+  __syncthreads();
+  for (int d = tid; d < dh; d += 256) {
+    float acc = 0.f;
+    for (int t = 0; t < S; ++t) acc = fmaf(dss[t], to_f32(base[(int64_t)t * 3 * D + D + d]), acc);
+    obase[d] = from_f32<T>(acc * scale);
+  }
+}
+void attention_bwd_first_query(int dt, const void* qkv, const void* ctx, const void* do_rows, const float* lse, void* dqkv,
+                               int nb, int S, int H, int dh, hipStream_t st) {
+  if (nb <= 0) return;
+  const size_t shm = sizeof(float) * ((size_t)2 * dh + S);
+  // the vector form needs 8 | dh, dh / 8 lanes per key dividing the wave, and 16-byte aligned tensors
+  const bool vec = dh % 8 == 0 && 64 % (dh / 8) == 0 && (reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(dqkv)) % 16 == 0;
+#define PT_FQ(T, V)                                                                                                   \
+  hipLaunchKernelGGL((attn_bwd_first_query_kernel<T, V>), dim3(H, nb), dim3(256), shm, st, (const T*)qkv, (const T*)ctx, \
+                     (const T*)do_rows, lse, (T*)dqkv, S, H, dh)
+  if (dt == 0) { if (vec) PT_FQ(float, true); else PT_FQ(float, false); }
+  else { if (vec) PT_FQ(bf16, true); else PT_FQ(bf16, false); }
+#undef PT_FQ
+}
+
 // matrix-core kernels for bf16, head size 64 (attention_mfma.hip)
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, int H, hipStream_t st);
 void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,

@@ -53,6 +53,9 @@ void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or 
                    int dh, hipStream_t st);
 void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv,
                    float* delta_ws /*[nb,H,S]*/, int nb, int S, int H, int dh, hipStream_t st);
+// the same when only each sample's first query has an output gradient: do_rows [nb, D] holds those rows
+void attention_bwd_first_query(int dt, const void* qkv, const void* ctx, const void* do_rows, const float* lse, void* dqkv,
+                               int nb, int S, int H, int dh, hipStream_t st);
 
 // ---- LayerNorm over rows of length D
 // y[r] = LN(x[r]); rows addressed r*ldx / r*ldy (elements).  x is fp32 when x_f32, else T.

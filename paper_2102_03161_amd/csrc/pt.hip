@@ -486,7 +486,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
   hipStream_t st = c->st;
   const Plan& p = c->plan;
   float* lnp = c->wf(p.LNPART);
-  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dQKV = c->w(p.dQKV);
+  void* oC = c->w(p.oC); void* dQKV = c->w(p.dQKV);
   void* rG = c->w(p.rG); void* rHP = c->w(p.rHP); void* rDF = c->w(p.rDF); void* rXa = c->w(p.rXa); void* rXb = c->w(p.rXb);
   void* rCTX = c->w(p.rCTX); void* rDO = c->w(p.rDO); void* rOC = c->w(p.rOC); void* rOD = c->w(p.rOD);
   void* rDCTX = c->w(p.rDCTX);
@@ -527,10 +527,10 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
                   c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOD = dL/dY
     wgrad(rCTX, D, rOD, D, c->blk(l, WO), -1, ns);
     dgrad(rOD, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
-    // dout.s becomes dL/dY and dout.o dL/dCTX: their other rows are zero already
-    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD), back(rDCTX, D, e, dout.o, SD)};
-    strided_rows_copy(out, 2, ns, st);
-    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), dout.o, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
+    // dout.s becomes dL/dY: its other rows are zero already
+    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
+    strided_rows_copy(out, 1, ns, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), c->w(s.CTX), rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false, Tn);            // dL/dU
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dout.s, D,
@@ -554,10 +554,9 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
                   c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOC = dL/d(x+Attn)
     wgrad(rCTX, D, rOC, D, c->blk(l, WO), -1, ns);
     dgrad(rOC, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
-    fill_zero(oD, (size_t)Tn * D * e, st);
-    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD), back(rDCTX, D, e, oD, SD)};
-    strided_rows_copy(out, 2, ns, st);
-    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
+    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
+    strided_rows_copy(out, 1, ns, st);
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), c->w(s.CTX), rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, dout.s, true, Tn);
   }
