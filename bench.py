@@ -29,9 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
 # read for the --calibrate-copy kernel; the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0, "gemm_nn"): 123739897 + 60812042,    # fetched + written, forward products
-    ("vit_b16", 0, "gemm_nt"): 161423765 + 33200671,    # input-gradient products
-    ("vit_b16", 0, "gemm_tn"): 478206636 + 75607319,    # weight gradients (one grouped launch per block) incl. their split-K reductions
+    ("vit_b16", 0, "gemm_nn"): 123323005 + 60812045,    # fetched + written, forward products
+    ("vit_b16", 0, "gemm_nt"): 150441580 + 30841375,    # input-gradient products
+    ("vit_b16", 0, "gemm_tn"): 372357941 + 62683528,    # weight gradients (one grouped launch per block) incl. their split-K reductions
 }
 
 
