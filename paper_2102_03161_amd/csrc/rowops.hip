@@ -443,7 +443,41 @@ __global__ void vit_front_bwd_kernel(const float* __restrict__ dX, T* __restrict
   dpos[i] = acc;
   if (s == 0) dcls[d] = acc;
 }
+// the same with four columns per thread and eight samples' loads in flight (D a multiple of 4)
+template <typename T>
+__global__ __launch_bounds__(256) void vit_front_bwd4_kernel(const float* __restrict__ dX, T* __restrict__ dE,
+                                                             float* __restrict__ dpos, float* __restrict__ dcls, int nb,
+                                                             int S, int D) {
+  const int nv = D >> 2;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S * nv) return;
+  const int s = i / nv, d = 4 * (i % nv);
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int b0 = 0; b0 < nb; b0 += 8) {
+    float v[8][4];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      v[u][0] = v[u][1] = v[u][2] = v[u][3] = 0.f;
+      if (b0 + u < nb) load4(dX + ((int64_t)(b0 + u) * S + s) * D + d, v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      if (b0 + u >= nb) break;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[e] += v[u][e];   // sample order, as in the scalar kernel
+      if (s > 0) store4(dE + ((int64_t)(b0 + u) * (S - 1) + (s - 1)) * D + d, v[u]);
+    }
+  }
+  store4(dpos + (int64_t)s * D + d, acc);
+  if (s == 0) store4(dcls + d, acc);
+}
 void vit_front_bwd(int dt, const float* dX, void* dE, float* dpos, float* dcls, int nb, int S, int D, hipStream_t st) {
+  if (D % 4 == 0) {
+    dim3 grid4(cdiv(S * (D / 4), 256));
+    if (dt == 0) hipLaunchKernelGGL(vit_front_bwd4_kernel<float>, grid4, dim3(256), 0, st, dX, (float*)dE, dpos, dcls, nb, S, D);
+    else hipLaunchKernelGGL(vit_front_bwd4_kernel<bf16>, grid4, dim3(256), 0, st, dX, (bf16*)dE, dpos, dcls, nb, S, D);
+    return;
+  }
   dim3 grid(cdiv(S * D, 256));
   if (dt == 0) hipLaunchKernelGGL(vit_front_bwd_kernel<float>, grid, dim3(256), 0, st, dX, (float*)dE, dpos, dcls, nb, S, D);
   else hipLaunchKernelGGL(vit_front_bwd_kernel<bf16>, grid, dim3(256), 0, st, dX, (bf16*)dE, dpos, dcls, nb, S, D);
