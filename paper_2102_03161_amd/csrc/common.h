@@ -75,6 +75,13 @@ __device__ __forceinline__ float gelu_f(float h) {
   float e;
   return h * gelu_cdf(h, &e);
 }
+// GELU(h) and its derivative from one evaluation of Phi and of the exponential
+__device__ __forceinline__ float gelu_both(float h, float* d_out) {
+  float e;
+  const float cdf = gelu_cdf(h, &e);
+  *d_out = fmaf(h * 0.39894228040143268f, e, cdf);
+  return h * cdf;
+}
 __device__ __forceinline__ float dgelu_f(float h) {
   float e;
   const float cdf = gelu_cdf(h, &e);

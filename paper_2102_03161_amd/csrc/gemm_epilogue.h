@@ -32,10 +32,13 @@ __device__ __forceinline__ void epilogue_store(const GemmDev<T>& g, int row, int
     else v += to_f32(g.aux[(int64_t)row * g.ld_aux + col]);
   }
   if (EPI == EPI_BIAS_GELU) {
-    if (g.aux_out) g.aux_out[(int64_t)row * g.ld_aux + col] = from_f32<T>(v);  // pre-activation for the backward pass
-    v = gelu_f(v);
+    // what the backward pass needs of the pre-activation is GELU'(h): it is stored instead of h, so that the
+    // input-gradient epilogue is one multiplication and the exponential is evaluated once per element
+    float dg;
+    v = gelu_both(v, &dg);
+    if (g.aux_out) g.aux_out[(int64_t)row * g.ld_aux + col] = from_f32<T>(dg);
   }
-  if (EPI == EPI_MUL_DGELU) v *= dgelu_f(to_f32(g.aux[(int64_t)row * g.ld_aux + col]));
+  if (EPI == EPI_MUL_DGELU) v *= to_f32(g.aux[(int64_t)row * g.ld_aux + col]);   // aux = GELU'(h) saved by the forward
   reinterpret_cast<TC*>(g.C)[(int64_t)row * g.ldc + col] = from_f32<TC>(v);
 }
 
@@ -60,12 +63,12 @@ __device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cb
   if (EPI == EPI_BIAS_RES || (EPI == EPI_RES && sizeof(TC) == 2) || EPI == EPI_MUL_DGELU) {
     union { uint4 u; u32x4_nt v; bf16 h[8]; } a;
     const bf16* ap = g.aux + (int64_t)row * g.ld_aux + col;
-    // the saved pre-activation is read exactly once, here: past the caches; a residual input was just written
+    // the saved GELU'(h) is read exactly once, here: past the caches; a residual input was just written
     if (EPI == EPI_MUL_DGELU) a.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(ap));
     else a.u = *reinterpret_cast<const uint4*>(ap);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      if (EPI == EPI_MUL_DGELU) v[e] *= dgelu_f(to_f32(a.h[e])); else v[e] += to_f32(a.h[e]);
+      if (EPI == EPI_MUL_DGELU) v[e] *= to_f32(a.h[e]); else v[e] += to_f32(a.h[e]);
     }
   }
   if (EPI == EPI_RES && sizeof(TC) == 4) {
@@ -74,17 +77,18 @@ __device__ __forceinline__ void epilogue_store8(const GemmDev<bf16>& g, void* Cb
     v[0] += a0.x; v[1] += a0.y; v[2] += a0.z; v[3] += a0.w; v[4] += a1.x; v[5] += a1.y; v[6] += a1.z; v[7] += a1.w;
   }
   if (EPI == EPI_BIAS_GELU) {
+    float dg[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_both(v[e], &dg[e]);
     if (g.aux_out) {
       union { uint4 u; bf16 h[8]; } o;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(v[e]);
-      // the pre-activation is read again only in the backward pass: written past the caches
+      for (int e = 0; e < 8; ++e) o.h[e] = from_f32<bf16>(dg[e]);
+      // GELU'(h) is read again only in the backward pass: written past the caches
       union { uint4 u; u32x4_nt v; } nt;
       nt.u = o.u;
       __builtin_nontemporal_store(nt.v, reinterpret_cast<u32x4_nt*>(g.aux_out + (int64_t)row * g.ld_aux + col));
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
   }
   if (sizeof(TC) == 4) {
     float* c = reinterpret_cast<float*>(Cbase) + (int64_t)row * g.ldc + col;

@@ -11,8 +11,8 @@ enum Epi {
   EPI_STORE = 0,      // C = acc
   EPI_BIAS = 1,       // C = acc + bias[n]
   EPI_BIAS_RES = 2,   // C = acc + bias[n] + aux[m,n]
-  EPI_BIAS_GELU = 3,  // h = acc + bias[n]; aux_out[m,n] = h (if non-null); C = GELU(h)
-  EPI_MUL_DGELU = 4,  // C = acc * GELU'(aux[m,n])
+  EPI_BIAS_GELU = 3,  // h = acc + bias[n]; aux_out[m,n] = GELU'(h) (if non-null); C = GELU(h)
+  EPI_MUL_DGELU = 4,  // C = acc * aux[m,n], aux = the GELU'(h) that EPI_BIAS_GELU saved
   EPI_RES = 5         // C = acc + aux[m,n]
 };
 

@@ -41,7 +41,7 @@ enum BlockTensor { LN1_G, LN1_B, WQKV, BQKV, WO, BO, LN2_G, LN2_B, W1, B1, W2, B
 
 // byte offsets into the work arena of the tensors one block keeps
 struct Slot {
-  size_t U, QKV, CTX, Y, WN, HP, G, LSE, MU1, RS1, MU2, RS2;
+  size_t U, QKV, CTX, Y, WN, HP, G, LSE, MU1, RS1, MU2, RS2;   // HP: GELU'(pre-activation), G: GELU(pre-activation)
 };
 
 struct Plan {
