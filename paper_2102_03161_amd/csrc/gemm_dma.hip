@@ -190,8 +190,15 @@ __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// The LDS footprint allows two workgroups per CU with 256x128 tiles (eight waves each) and three with
+// 128x128 tiles (four waves each).  The second launch bound is the number of waves per SIMD that this
+// amounts to: the register allocation is held to it, whatever the epilogue would like to use.
+constexpr int dma_waves_per_simd(int lds_bytes, int waves) {
+  return (lds_bytes <= 48 * 1024 ? 3 : (lds_bytes <= 80 * 1024 ? 2 : 1)) * waves / 4;
+}
 template <int BM, int BN, int WGM, int WGN, int kNS, int BK, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
+__global__ __launch_bounds__(64 * WGM * WGN, dma_waves_per_simd((BM + BN) * BK * 2 * kNS, WGM * WGN))
+void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
                                                                   int group_n, int vec_ok) {
   constexpr int NW = WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN, TM = WTM / 32, TN = WTN / 32;
@@ -310,8 +317,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmDev<bf16> 
   }
   void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
                                 : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
-  staged_epilogue<TM, TN, WTM, WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD, m0 + wm * WTM,
-                                             n0 + wn * WTN, lane, vec_ok);
+  // four waves per SIMD leave 128 registers each: only the long-latency read of the saved GELU' is double-buffered
+  constexpr int NBUF = (EPI == EPI_MUL_DGELU || dma_waves_per_simd((BM + BN) * BK * 2 * kNS, NW) < 4) ? 2 : 1;
+  staged_epilogue<TM, TN, WTM, WTN, EPI, TC, NBUF>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD,
+                                                   m0 + wm * WTM, n0 + wn * WTN, lane, vec_ok);
 }
 
 
