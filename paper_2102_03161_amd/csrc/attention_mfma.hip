@@ -510,7 +510,7 @@ __global__ __launch_bounds__(512) void attn_fwd_res_kernel(const bf16* __restric
   }
 }
 
-__global__ __launch_bounds__(512) void attn_bwd_dq_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+__global__ __launch_bounds__(512, 4) void attn_bwd_dq_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                               const bf16* __restrict__ dctx,
                                                               const float* __restrict__ lse, bf16* __restrict__ dqkv,
                                                               float* __restrict__ delta, int S, int H, int ntile) {
@@ -550,23 +550,29 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_res_kernel(const bf16* __rest
   const unsigned v_base = lds_addr(Vs + (lane & 31) * LDR + half * 8);
   for (int kt = 0; kt < ntile; ++kt) {
     const bf16* Kt = Ks + kt * 32 * LDR;
+    // Fragments are fetched in the order they are used and each set's registers are free again before the
+    // next set arrives: 16 registers of fragments in flight instead of 48, which is what lets two
+    // workgroups share a CU (one loads its head while the other computes).
     bf16x8 kr[4], vr[4], kc[4];
     frag_rows_issue(k_base + kt * (32 * LDR * 2), kr);
     frag_rows_issue(v_base + kt * (32 * LDR * 2), vr);
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+    lds_wait<4>(kr);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+    lds_wait<0>(vr);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[ks], dof[ks], dp, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks2 = 0; ks2 < 2; ++ks2)
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Kt, lane, dt, ks2, kc[2 * ks2 + dt]);
-    f32x16 s, dp;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-    lds_wait<8>(kr);
-    lds_wait<8>(vr);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[ks], dof[ks], dp, 0, 0, 0);
-    }
     if (kt == ntile - 1 && (S & 31)) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;

@@ -160,7 +160,7 @@ template <bool T, int ROWS, int BK, int NT> struct LoaderSel { typedef KMajor<RO
 template <int ROWS, int BK, int NT> struct LoaderSel<true, ROWS, BK, NT> { typedef Strided<ROWS, BK, NT> type; };
 
 template <typename C, bool TA, bool TB, int EPI, typename TC>
-__global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n, int total_tiles,
+__global__ __launch_bounds__(C::NT, 4) void gemm_mfma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_n, int total_tiles,
                                                           int vec_ok) {
   typedef typename LoaderSel<TA, C::BM, C::BK, C::NT>::type LA;     // A strided when stored [K,M]
   typedef typename LoaderSel<!TB, C::BN, C::BK, C::NT>::type LB;    // B strided when stored [K,N]
@@ -264,8 +264,9 @@ __global__ __launch_bounds__(C::NT) void gemm_mfma_kernel(GemmDev<bf16> g, Split
 
   void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
                                 : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
-  staged_epilogue<C::TM, C::TN, C::WTM, C::WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD,
-                                                         m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
+  // one operand buffer: this kernel lives on having four small workgroups per CU
+  staged_epilogue<C::TM, C::TN, C::WTM, C::WTN, EPI, TC, 1>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD,
+                                                            m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
 }
 
 // out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread).  A second, short
