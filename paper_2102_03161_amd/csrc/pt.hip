@@ -1067,9 +1067,11 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
     dg.M = nb; dg.N = D; dg.K = C;
     { ProfScope ps_(c, gemm_cat(dt, dg), 2.0 * dg.M * dg.N * dg.K); gemm(dt, dg, st); }
-    // only the CLS rows of dL/dx_L are non-zero
+    // only the CLS rows of dL/dx_L are non-zero.  The fp32 stream is the zero background the top block's
+    // backward adds into; of the low-precision copy that backward reads nothing but the CLS rows when it
+    // runs on first-token rows (S >= 4, below), so the fill is kept for the full-width backward only.
     fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
-    fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
+    if (S < 4) fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
     { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
                   dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
                   c->wf(p.LNPART), nb, D, st); }
