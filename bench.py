@@ -29,9 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
 # read for the --calibrate-copy kernel; the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0, "gemm_nn"): 123323005 + 60812045,    # fetched + written, forward products
-    ("vit_b16", 0, "gemm_nt"): 150441580 + 30841375,    # input-gradient products
-    ("vit_b16", 0, "gemm_tn"): 372357941 + 62683528,    # weight gradients (one grouped launch per block) incl. their split-K reductions
+    ("vit_b16", 0, "gemm_nn"): 123381556 + 60812221,    # fetched + written, forward products
+    ("vit_b16", 0, "gemm_nt"): 150321388 + 30841375,    # input-gradient products
+    ("vit_b16", 0, "gemm_tn"): 372474406 + 62749515,    # weight gradients (one grouped launch per block) incl. their split-K reductions
 }
 
 
@@ -173,8 +173,8 @@ def main():
     ms, n, wk = prof[dom]
     ach = wk / (ms * 1e-3) / 1e12
     result["roofline"] = {"kernel": {"gemm_tn": "weight-gradient GEMMs dW = x^T dy (gemm_wgrad_group_kernel + splitk_reduce_kernel)",
-                                     "gemm_nn": "forward GEMMs y = x W (gemm_pp_kernel / gemm_pp2_kernel / gemm_dma_kernel, TA=false TB=false)",
-                                     "gemm_nt": "input-gradient GEMMs dx = dy W^T (gemm_pp2_kernel / gemm_dma_kernel, TB=true)"}[dom],
+                                     "gemm_nn": "forward GEMMs y = x W (gemm_pp_kernel / gemm_dma_kernel, TA=false TB=false)",
+                                     "gemm_nt": "input-gradient GEMMs dx = dy W^T (gemm_pp_kernel / gemm_dma_kernel, TB=true)"}[dom],
                           "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                           "frac": round(ach / PEAK_BF16_TFLOPS, 4),
                           "traffic": MEASURED_TRAFFIC.get((a.workload, a.k, dom)),
