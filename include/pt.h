@@ -198,7 +198,9 @@ pt_status pt_read_tensor(pt_ctx* ctx, int32_t id, int32_t kind, float* dst);
 pt_status pt_get_step_count(const pt_ctx* ctx, int64_t* t);
 pt_status pt_set_step_count(pt_ctx* ctx, int64_t t);
 
-/* Activations of the last step widened to fp32 (parity checks). */
+/* Activations of the last step widened to fp32 (parity checks).  PT_ACT_HL: when the head reads only each
+ * sample's first token (ViT; BERT with the classification head), S >= 4 and the top block is active, that
+ * block computes only those rows of its output: rows [b, 0, :] are defined, the others unspecified. */
 enum { PT_ACT_HK = 0 /*[nb,S,D]*/, PT_ACT_HL = 1 /*[nb,S,D]*/, PT_ACT_LOGITS = 2 /*ViT [nb,n_out]; BERT [nb,S,2]*/,
        PT_ACT_DHK = 3 /*[nb,S,D] gradient wrt the boundary activation; valid when k == 0 or arch-internal*/ };
 pt_status pt_read_activation(pt_ctx* ctx, int32_t which, float* dst /*HOST*/, size_t numel);

@@ -279,13 +279,7 @@ static void attention_fwd_t(const void* qkv, void* ctx, float* lse, int nb, int 
   hipLaunchKernelGGL(attn_fwd_kernel<T>, dim3(cdiv(S, TQ), H, nb), dim3(256), shm, st, (const T*)qkv, (T*)ctx, lse, S, H,
                      dh, Spad);
 }
-// ---------------------------------------------------------------------------
-// backward when only each sample's first query has a non-zero output gradient (the top block under a
-// first-token head).  One workgroup per (sample, head): p_t = exp(q.k_t * scale - lse), dV_t = p_t dO,
-// dS_t = p_t (dO.v_t - dO.o), dK_t = scale dS_t q, dQ_0 = scale sum_t dS_t k_t, dQ_t = 0 otherwise.
-// do_rows is dense: [nb, D], the first tokens' rows only.  One thread per key; the sum over keys for dQ_0
-// is taken by dh threads in key order (fixed, so reproducible).
-// ---------------------------------------------------------------------------
+// 8 consecutive elements as floats / from floats (16-byte accesses for bf16)
 __device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
   const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -306,10 +300,117 @@ __device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
   for (int i = 0; i < 8; ++i) t.h[i] = from_f32<bf16>(v[i]);
   *reinterpret_cast<uint4*>(p) = t.u;
 }
+// ---------------------------------------------------------------------------
+// forward for each sample's first query only (the top block under a first-token head: no other row of its
+// output is read).  One workgroup per (sample, head): s_t = scale q.k_t, p = softmax(s), o = sum_t p_t v_t.
+// ctx_rows is dense: [nb, D]; the log-sum-exp goes to entry (b, h, 0) of the [nb, H, S] array the backward
+// kernels read.  dh / 8 lanes share a key (whole rows are read); partial sums over keys are combined in
+// a fixed order.
+// ---------------------------------------------------------------------------
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void attn_fwd_first_query_kernel(const T* __restrict__ qkv, T* __restrict__ ctx_rows,
+                                                                   float* __restrict__ lse, int S, int H, int dh) {
+  extern __shared__ float sm[];
+  float* qs = sm;            // [dh]
+  float* sc = qs + dh;       // [S] scores, then unnormalised probabilities
+  float* part = sc + S;      // [256 / (dh / 8)][dh] partial outputs of the key groups (VEC)
+  __shared__ float red[4];
+  const int D = H * dh;
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+  const T* base = qkv + (int64_t)b * S * 3 * D + h * dh;
+  const float scale = rsqrtf((float)dh);
+  for (int d = tid; d < dh; d += 256) qs[d] = to_f32(base[d]);
+  __syncthreads();
+  const int lpr = VEC ? dh >> 3 : 1, j = tid % lpr, d0 = 8 * j, kpi = 256 / lpr;   // keys per iteration
+  if (VEC) {
+    for (int t0 = 0; t0 < S; t0 += kpi) {
+      const int t = t0 + tid / lpr;
+      const bool ok = t < S;
+      float kv[8];
+      load8(base + (int64_t)(ok ? t : 0) * 3 * D + D + d0, kv);
+      float s = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s = fmaf(qs[d0 + i], kv[i], s);
+      for (int o = 1; o < lpr; o <<= 1) s += __shfl_xor(s, o, 64);
+      if (ok && j == 0) sc[t] = s * scale;
+    }
+  } else {
+    for (int t = tid; t < S; t += 256) {
+      const T* kr = base + (int64_t)t * 3 * D + D;
+      float s = 0.f;
+      for (int d = 0; d < dh; ++d) s = fmaf(qs[d], to_f32(kr[d]), s);
+      sc[t] = s * scale;
+    }
+  }
+  __syncthreads();
+  float lm = -INFINITY;
+  for (int t = tid; t < S; t += 256) lm = fmaxf(lm, sc[t]);
+  const float m = block_max<4>(lm, red);
+  float ls = 0.f;
+  for (int t = tid; t < S; t += 256) {
+    const float p = __expf(sc[t] - m);
+    sc[t] = p;
+    ls += p;
+  }
+  const float l = block_sum<4>(ls, red);   // its barriers also publish sc
+  const float inv = 1.0f / l;
+  T* o = ctx_rows + (int64_t)b * D + h * dh;
+  if (VEC) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int t0 = 0; t0 < S; t0 += kpi) {
+      const int t = t0 + tid / lpr;
+      if (t < S) {
+        float vv[8];
+        load8(base + (int64_t)t * 3 * D + 2 * D + d0, vv);
+        const float p = sc[t];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = fmaf(p, vv[i], acc[i]);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part[(tid / lpr) * dh + d0 + i] = acc[i];
+    __syncthreads();
+    for (int d = tid; d < dh; d += 256) {
+      float a = 0.f;
+      for (int g = 0; g < kpi; ++g) a += part[g * dh + d];
+      o[d] = from_f32<T>(a * inv);
+    }
+  } else {
+    for (int d = tid; d < dh; d += 256) {
+      float a = 0.f;
+      for (int t = 0; t < S; ++t) a = fmaf(sc[t], to_f32(base[(int64_t)t * 3 * D + 2 * D + d]), a);
+      o[d] = from_f32<T>(a * inv);
+    }
+  }
+  if (tid == 0 && lse) lse[((int64_t)b * H + h) * S] = m + __logf(l);
+}
+void attention_fwd_first_query(int dt, const void* qkv, void* ctx_rows, float* lse, int nb, int S, int H, int dh,
+                               hipStream_t st) {
+  if (nb <= 0) return;
+  const bool vec = dh % 8 == 0 && 64 % (dh / 8) == 0 &&
+                   (reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(ctx_rows)) % 16 == 0;
+  const size_t shm = sizeof(float) * ((size_t)dh + S + (vec ? (size_t)(256 / (dh / 8)) * dh : 0));
+#define PT_FQF(T, V)                                                                                                 \
+  hipLaunchKernelGGL((attn_fwd_first_query_kernel<T, V>), dim3(H, nb), dim3(256), shm, st, (const T*)qkv, (T*)ctx_rows, \
+                     lse, S, H, dh)
+  if (dt == 0) { if (vec) PT_FQF(float, true); else PT_FQF(float, false); }
+  else { if (vec) PT_FQF(bf16, true); else PT_FQF(bf16, false); }
+#undef PT_FQF
+}
+
+// ---------------------------------------------------------------------------
+// backward when only each sample's first query has a non-zero output gradient (the top block under a
+// first-token head).  One workgroup per (sample, head): p_t = exp(q.k_t * scale - lse), dV_t = p_t dO,
+// dS_t = p_t (dO.v_t - dO.o), dK_t = scale dS_t q, dQ_0 = scale sum_t dS_t k_t, dQ_t = 0 otherwise.
+// ctx_rows and do_rows are dense: [nb, D], the first tokens' rows only.  One thread per key; the sum over
+// keys for dQ_0 is taken by dh threads in key order (fixed, so reproducible).
+// ---------------------------------------------------------------------------
 // VEC: dh is a multiple of 8, so every head slice of a row starts on a 16-byte boundary and is moved in
 // 8-element pieces
 template <typename T, bool VEC>
-__global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __restrict__ qkv, const T* __restrict__ ctx,
+__global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __restrict__ qkv, const T* __restrict__ ctx_rows,
                                                                    const T* __restrict__ do_rows,
                                                                    const float* __restrict__ lse, T* __restrict__ dqkv,
                                                                    int S, int H, int dh) {
@@ -329,7 +430,7 @@ __global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __re
   }
   __syncthreads();
   if (tid == 0) {
-    const T* o = ctx + (int64_t)b * S * D + h * dh;
+    const T* o = ctx_rows + (int64_t)b * D + h * dh;
     float s = 0.f;
     for (int d = 0; d < dh; ++d) s = fmaf(dos[d], to_f32(o[d]), s);
     delta_s = s;
@@ -391,14 +492,14 @@ __global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __re
     obase[d] = from_f32<T>(acc * scale);
   }
 }
-void attention_bwd_first_query(int dt, const void* qkv, const void* ctx, const void* do_rows, const float* lse, void* dqkv,
-                               int nb, int S, int H, int dh, hipStream_t st) {
+void attention_bwd_first_query(int dt, const void* qkv, const void* ctx_rows, const void* do_rows, const float* lse,
+                               void* dqkv, int nb, int S, int H, int dh, hipStream_t st) {
   if (nb <= 0) return;
   const size_t shm = sizeof(float) * ((size_t)2 * dh + S);
   // the vector form needs 8 | dh, dh / 8 lanes per key dividing the wave, and 16-byte aligned tensors
   const bool vec = dh % 8 == 0 && 64 % (dh / 8) == 0 && (reinterpret_cast<uintptr_t>(qkv) | reinterpret_cast<uintptr_t>(dqkv)) % 16 == 0;
 #define PT_FQ(T, V)                                                                                                   \
-  hipLaunchKernelGGL((attn_bwd_first_query_kernel<T, V>), dim3(H, nb), dim3(256), shm, st, (const T*)qkv, (const T*)ctx, \
+  hipLaunchKernelGGL((attn_bwd_first_query_kernel<T, V>), dim3(H, nb), dim3(256), shm, st, (const T*)qkv, (const T*)ctx_rows, \
                      (const T*)do_rows, lse, (T*)dqkv, S, H, dh)
   if (dt == 0) { if (vec) PT_FQ(float, true); else PT_FQ(float, false); }
   else { if (vec) PT_FQ(bf16, true); else PT_FQ(bf16, false); }

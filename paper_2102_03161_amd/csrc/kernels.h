@@ -53,9 +53,12 @@ void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or 
                    int dh, hipStream_t st);
 void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv,
                    float* delta_ws /*[nb,H,S]*/, int nb, int S, int H, int dh, hipStream_t st);
-// the same when only each sample's first query has an output gradient: do_rows [nb, D] holds those rows
-void attention_bwd_first_query(int dt, const void* qkv, const void* ctx, const void* do_rows, const float* lse, void* dqkv,
-                               int nb, int S, int H, int dh, hipStream_t st);
+// the same for each sample's first query only (nothing else of the output is read, or has a gradient):
+// ctx_rows and do_rows [nb, D] hold the first tokens' rows; lse entry (b, h, 0) of [nb,H,S] is written / read
+void attention_fwd_first_query(int dt, const void* qkv, void* ctx_rows, float* lse, int nb, int S, int H, int dh,
+                               hipStream_t st);
+void attention_bwd_first_query(int dt, const void* qkv, const void* ctx_rows, const void* do_rows, const float* lse,
+                               void* dqkv, int nb, int S, int H, int dh, hipStream_t st);
 
 // ---- LayerNorm over rows of length D
 // y[r] = LN(x[r]); rows addressed r*ldx / r*ldy (elements).  x is fp32 when x_f32, else T.

@@ -470,13 +470,62 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
 
 
 // ---------------------------------------------------------------------------
+// Forward of the top block when the head reads only each sample's first token (ViT class token, BERT
+// sequence classification): of this block's output nothing but those ns rows is ever read, so everything
+// behind the attention (output projection, LayerNorms, both MLP products) runs on ns rows, and the attention
+// itself on one query per sample; keys and values still need every token, hence the full LayerNorm and QKV
+// product in front.  The first-token rows of the intermediate tensors are kept dense, in the row buffers
+// block_backward_first_rows works on, instead of in the block's slot; xout gets its first-token rows only.
+// ---------------------------------------------------------------------------
+void block_forward_first_rows(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s, int ns) {
+  const pt_config& g = c->cfg;
+  const int D = g.D, F = g.F, S = g.S, Tn = ns * g.S, dt = c->dt;
+  const int64_t SD = (int64_t)S * D;
+  hipStream_t st = c->st;
+  const Plan& p = c->plan;
+  void* rG = c->w(p.rG); void* rHP = c->w(p.rHP); void* rXa = c->w(p.rXa); void* rXb = c->w(p.rXb);
+  void* rCTX = c->w(p.rCTX); void* rDO = c->w(p.rDO);
+  float* rmu1 = c->wf(p.rST); float* rrs1 = rmu1 + ns; float* rmu2 = rrs1 + ns; float* rrs2 = rmu2 + ns;
+  auto lin = [&](const void* A, int64_t lda, int K, int wid, int bid, void* C, int64_t ldc, int N, int M, Epi epi,
+                 const void* aux, void* aux_out, int64_t ld_aux, bool out_f32) {
+    Gemm m;
+    m.A = A; m.lda = lda; m.B = c->cp(wid); m.ldb = N; m.C = C; m.ldc = ldc; m.M = M; m.N = N; m.K = K;
+    m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = ld_aux; m.c_f32 = out_f32;
+    { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
+  };
+  auto attn = [&]() {
+    ProfScope ps_(c, PT_PROF_ATTN_FWD, 4.0 * ns * g.H * (double)g.S * (D / g.H));
+    attention_fwd_first_query(dt, c->w(s.QKV), rCTX, c->wf(s.LSE), ns, g.S, g.H, D / g.H, st);
+  };
+  if (g.arch == PT_VIT_PRELN) {
+    { prof_ln_fwd(c, dt, false, xin, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), Tn, D, g.ln_eps, st); }
+    lin(c->w(s.U), D, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, 3 * D, Tn, EPI_BIAS, nullptr, nullptr, 3 * D, false);
+    attn();
+    lin(rCTX, D, D, c->blk(l, WO), c->blk(l, BO), rXb, D, D, ns, EPI_BIAS_RES, xin, nullptr, SD, false);          // rows of Y
+    { prof_ln_fwd(c, dt, false, rXb, D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), rXa, D, rmu2, rrs2, ns, D, g.ln_eps, st); }
+    lin(rXa, D, D, c->blk(l, W1), c->blk(l, B1), rG, F, F, ns, EPI_BIAS_GELU, nullptr, rHP, F, false);
+    lin(rG, F, F, c->blk(l, W2), c->blk(l, B2), xout, SD, D, ns, EPI_BIAS_RES, rXb, nullptr, D, false);
+  } else {
+    lin(xin, D, D, c->blk(l, WQKV), c->blk(l, BQKV), c->w(s.QKV), 3 * D, 3 * D, Tn, EPI_BIAS, nullptr, nullptr, 3 * D, false);
+    attn();
+    lin(rCTX, D, D, c->blk(l, WO), c->blk(l, BO), rXb, D, D, ns, EPI_BIAS_RES, xin, nullptr, SD, true);           // rows of U, fp32
+    { prof_ln_fwd(c, dt, true, rXb, D, c->cp(c->blk(l, LN1_G)), c->cp(c->blk(l, LN1_B)), rDO, D, rmu1, rrs1, ns, D, g.ln_eps, st); }  // rows of Y
+    lin(rDO, D, D, c->blk(l, W1), c->blk(l, B1), rG, F, F, ns, EPI_BIAS_GELU, nullptr, rHP, F, false);
+    lin(rG, F, F, c->blk(l, W2), c->blk(l, B2), rXa, D, D, ns, EPI_BIAS_RES, rDO, nullptr, D, true);               // rows of WN, fp32
+    { prof_ln_fwd(c, dt, true, rXa, D, c->cp(c->blk(l, LN2_G)), c->cp(c->blk(l, LN2_B)), xout, SD, rmu2, rrs2, ns, D, g.ln_eps, st); }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Backward of the top block when the head reads only each sample's first token (ViT class token, BERT
 // sequence classification): dL/dx_L is zero in every other row, so everything between the block's output and
 // its attention (both MLP products and their weight gradients, the LayerNorms, the output projection) involves
-// ns rows instead of ns * S.  Those rows are gathered into dense buffers, pushed through the same kernels, and
-// scattered back in front of the attention backward, which needs every token.  dout rows other than the first
-// tokens' must be zero on entry (the head backward zero-fills them); they are reused as the zero background
-// of the scattered tensors.  The results equal those of block_backward (rows of zeros contribute nothing).
+// ns rows instead of ns * S.  The gradient rows are gathered into dense buffers (the saved activations' rows
+// are dense already: block_forward_first_rows left them in the row buffers), pushed through the same kernels,
+// and scattered back in front of the attention backward, which needs every token.  Rows of dout's fp32 stream
+// other than the first tokens' must be zero on entry (the head backward zero-fills them); they are reused
+// as the zero background of the scattered tensor.  The results equal those of block_backward (rows of zeros
+// contribute nothing).
 // ---------------------------------------------------------------------------
 void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns,
                                bool need_dx, float* lower_b2) {
@@ -514,11 +563,9 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     return RowCopy{src, dst, (int64_t)cols * esz_, dst_elems * esz_, cols * esz_};
   };
   if (g.arch == PT_VIT_PRELN) {
-    const RowCopy in[] = {row(dout.o, SD, e, rDO, D), row(dout.s, SD, 4, rS0, D), row(c->w(s.G), (int64_t)S * F, e, rG, F),
-                          row(c->w(s.HP), (int64_t)S * F, e, rHP, F), row(c->w(s.WN), SD, e, rXa, D),
-                          row(c->w(s.Y), SD, e, rXb, D), row(c->w(s.CTX), SD, e, rCTX, D),
-                          row(c->wf(s.MU2), S, 4, rmu2, 1), row(c->wf(s.RS2), S, 4, rrs2, 1)};
-    strided_rows_copy(in, 9, ns, st);
+    // rG, rHP (GELU out and GELU'), rXa (LN2 out), rXb (Y), rCTX and the LN2 statistics come from the forward
+    const RowCopy in[] = {row(dout.o, SD, e, rDO, D), row(dout.s, SD, 4, rS0, D)};
+    strided_rows_copy(in, 2, ns, st);
     wgrad(rG, F, rDO, D, c->blk(l, W2), -1, ns);
     dgrad(rDO, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
     wgrad(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);
@@ -530,7 +577,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     // dout.s becomes dL/dY: its other rows are zero already
     const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
     strided_rows_copy(out, 1, ns, st);
-    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), c->w(s.CTX), rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), rCTX, rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false, Tn);            // dL/dU
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dout.s, D,
@@ -538,12 +585,9 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
                   c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
   } else {
     // post-LN: U = x + Attn(x) and WN = Y + MLP(Y) are the fp32 sums in front of the two LayerNorms
-    const RowCopy in[] = {row(dout.s, SD, 4, rS0, D), row(c->w(s.WN), SD, 4, rXa, D), row(c->w(s.U), SD, 4, rXb, D),
-                          row(c->w(s.G), (int64_t)S * F, e, rG, F), row(c->w(s.HP), (int64_t)S * F, e, rHP, F),
-                          row(c->w(s.Y), SD, e, rDO, D), row(c->w(s.CTX), SD, e, rCTX, D),
-                          row(c->wf(s.MU2), S, 4, rmu2, 1), row(c->wf(s.RS2), S, 4, rrs2, 1),
-                          row(c->wf(s.MU1), S, 4, rmu1, 1), row(c->wf(s.RS1), S, 4, rrs1, 1)};
-    strided_rows_copy(in, 11, ns, st);
+    // rXa (WN), rXb (U), rG, rHP, rDO (rows of Y), rCTX and both LayerNorms' statistics come from the forward
+    const RowCopy in[] = {row(dout.s, SD, 4, rS0, D)};
+    strided_rows_copy(in, 1, ns, st);
     { prof_ln_bwd(c, dt, true, true, rS0, D, rXa, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), nullptr, 0, rS1, rOD, D,
                   c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, ns, D, st); }  // rS1 / rOD = dL/d(Y+MLP)
     wgrad(rG, F, rOD, D, c->blk(l, W2), -1, ns);
@@ -556,7 +600,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     dgrad(rOC, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
     const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
     strided_rows_copy(out, 1, ns, st);
-    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), c->w(s.CTX), rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
+    { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), rCTX, rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, dout.s, true, Tn);
   }
@@ -1041,8 +1085,11 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   hipStream_t st = c->st;
   // forward through the active blocks, keeping what the backward pass reads
   const void* x = d_hk;
+  // under a first-token head the top block runs on those tokens' rows behind its attention, both ways
+  const bool top_first_rows = S >= 4 && (g.arch == PT_VIT_PRELN || g.head == PT_HEAD_CLS);
   for (int l = k; l < L; ++l) {
-    block_forward(c, l, x, c->w(p.X[l + 1]), p.slot[l], nb, true);
+    if (l == L - 1 && top_first_rows) block_forward_first_rows(c, l, x, c->w(p.X[l + 1]), p.slot[l], nb);
+    else block_forward(c, l, x, c->w(p.X[l + 1]), p.slot[l], nb, true);
     x = c->w(p.X[l + 1]);
   }
   GradBufs dcur{c->wf(p.sA), c->w(p.oA)};
@@ -1110,7 +1157,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     const bool need_dx = (l > k) || (k == 0);
     float* lower_b2 = (g.arch == PT_VIT_PRELN && l > k) ? c->gp(c->blk(l - 1, B2)) : nullptr;
     // under a first-token head only those tokens' rows of dL/dx_L are non-zero
-    const bool first_rows = l == L - 1 && S >= 4 && (g.arch == PT_VIT_PRELN || g.head == PT_HEAD_CLS);
+    const bool first_rows = l == L - 1 && top_first_rows;
     if (first_rows) block_backward_first_rows(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     else block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     std::swap(dcur, dnext);

@@ -74,6 +74,13 @@ def oracle_update(w, o, vals, gpu_grads, k, hp=HP, state=None):
     o["params_from_gpu_grads"] = p
 
 
+def first_token_rows_only(w, k):
+    """True when the step computes only each sample's first row of the top block's output: the head reads
+    nothing else (ViT class token, BERT sequence classification), so an active top block works on those rows
+    behind its attention and leaves the other rows of ACT_HL unspecified."""
+    return (w["arch"] == "vit" or w.get("head") == "cls") and w["S"] >= 4 and k < w["L"]
+
+
 def gpu_step(torch, ctx, w, x, y, k, hp=HP, sample_ids=None):
     ctx.set_freeze_boundary(k)
     dx = to_dev(torch, x)
@@ -85,6 +92,8 @@ def gpu_step(torch, ctx, w, x, y, k, hp=HP, sample_ids=None):
     out = dict(loss=loss)
     out["hk"] = ctx.read_activation(binding.ACT_HK, (nb, S, D))
     out["hL"] = ctx.read_activation(binding.ACT_HL, (nb, S, D))
+    if first_token_rows_only(w, k):
+        out["hL"] = out["hL"][:, :1, :]
     out["logits"] = ctx.read_activation(binding.ACT_LOGITS, (nb, w["n_out"]) if (w["arch"] == "vit" or w.get("head") == "cls") else (nb, S, 2))
     out["norms"] = ctx.layer_grad_norms()
     out["grads"] = gpu_read_all(ctx, binding.KIND_GRAD)
@@ -100,7 +109,7 @@ def compare_step(w, g, o, k, tol, check_params=True):
     errs = {}
     errs["loss"] = abs(g["loss"] - o["loss"]) / abs(o["loss"])
     errs["hk"] = rel_err(g["hk"], o["hk"])
-    errs["hL"] = rel_err(g["hL"], o["aux"]["h_L"])
+    errs["hL"] = rel_err(g["hL"], o["aux"]["h_L"][:, :g["hL"].shape[1], :])
     errs["logits"] = rel_err(g["logits"], o["aux"]["logits"])
     gmax = max(float(np.max(np.abs(a))) for a in o["grads"].values())
     for name, a in g["grads"].items():
