@@ -71,6 +71,10 @@ void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* g
 // dxsum (may be null): fp32 [D] column sums of the result over the rows, i.e. the bias gradient of the
 // linear map that produced this LayerNorm's input side.
 size_t ln_partial_floats(int D);
+// x_s[i * row_stride + d] += r[i * D + d] for i < n (fp32), x_o (T, may be null) gets the rounded sums of those
+// rows, colsum[d] (may be null) += sum_i r[i * D + d]: adds a gradient that only every row_stride / D-th row has
+void add_rows(int dt, const float* r, float* x_s, void* x_o, int64_t row_stride, float* colsum, int n, int D,
+              hipStream_t st);
 void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                    const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
                    float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,

@@ -520,18 +520,20 @@ void block_forward_first_rows(pt_ctx* c, int l, const void* xin, void* xout, con
 // Backward of the top block when the head reads only each sample's first token (ViT class token, BERT
 // sequence classification): dL/dx_L is zero in every other row, so everything between the block's output and
 // its attention (both MLP products and their weight gradients, the LayerNorms, the output projection) involves
-// ns rows instead of ns * S.  The gradient rows are gathered into dense buffers (the saved activations' rows
-// are dense already: block_forward_first_rows left them in the row buffers), pushed through the same kernels,
-// and scattered back in front of the attention backward, which needs every token.  Rows of dout's fp32 stream
-// other than the first tokens' must be zero on entry (the head backward zero-fills them); they are reused
-// as the zero background of the scattered tensor.  The results equal those of block_backward (rows of zeros
-// contribute nothing).
+// ns rows instead of ns * S.  Those rows are kept dense (block_forward_first_rows left the saved
+// activations' rows in the row buffers) and pushed through the same kernels; the attention backward, which
+// needs every token, takes the one row of dL/dCTX per sample that is not zero.  Pre-LN: the head's backward
+// has put the first tokens' rows of dL/dx_L into rS0 / rDO, and the last LayerNorm backward adds dL/dY in
+// those rows only (dout is not read).  Post-LN: the rows are gathered from dout.s, whose other rows must be
+// zero on entry (the head backward zero-fills them) and serve as the zero background of the residual
+// gradient that the last product adds.  The results equal those of block_backward (rows of zeros contribute
+// nothing).
 // ---------------------------------------------------------------------------
 void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs dout, GradBufs dx, int ns,
                                bool need_dx, float* lower_b2) {
   const pt_config& g = c->cfg;
   const int D = g.D, F = g.F, S = g.S, Tn = ns * g.S, dt = c->dt;
-  const int64_t e = c->esz, SD = (int64_t)S * D;
+  const int64_t SD = (int64_t)S * D;
   hipStream_t st = c->st;
   const Plan& p = c->plan;
   float* lnp = c->wf(p.LNPART);
@@ -563,9 +565,8 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     return RowCopy{src, dst, (int64_t)cols * esz_, dst_elems * esz_, cols * esz_};
   };
   if (g.arch == PT_VIT_PRELN) {
-    // rG, rHP (GELU out and GELU'), rXa (LN2 out), rXb (Y), rCTX and the LN2 statistics come from the forward
-    const RowCopy in[] = {row(dout.o, SD, e, rDO, D), row(dout.s, SD, 4, rS0, D)};
-    strided_rows_copy(in, 2, ns, st);
+    // rG, rHP (GELU out and GELU'), rXa (LN2 out), rXb (Y), rCTX and the LN2 statistics come from the forward,
+    // rDO / rS0 (the first tokens' rows of dL/dx_L) from the head's backward: nothing to gather
     wgrad(rG, F, rDO, D, c->blk(l, W2), -1, ns);
     dgrad(rDO, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
     wgrad(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);
@@ -574,15 +575,15 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
                   c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOD = dL/dY
     wgrad(rCTX, D, rOD, D, c->blk(l, WO), -1, ns);
     dgrad(rOD, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
-    // dout.s becomes dL/dY: its other rows are zero already
-    const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
-    strided_rows_copy(out, 1, ns, st);
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), rCTX, rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false, Tn);            // dL/dU
-    { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), dout.s, D,
+    // dL/dY (rS1), the residual branch of dL/dx, is non-zero in the first tokens' rows only: it is added to
+    // those rows (and to the column sums) after the LayerNorm backward instead of being read as a full tensor
+    { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
                   c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
+    if (need_dx) add_rows(dt, rS1, dx.s, dx.o, SD, lower_b2, ns, D, st);
   } else {
     // post-LN: U = x + Attn(x) and WN = Y + MLP(Y) are the fp32 sums in front of the two LayerNorms
     // rXa (WN), rXb (U), rG, rHP, rDO (rows of Y), rCTX and both LayerNorms' statistics come from the forward
@@ -1114,14 +1115,18 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     dg.A = c->w(p.DZ); dg.lda = C; dg.B = c->cp(hW); dg.ldb = C; dg.tb = true; dg.C = c->w(p.DC); dg.ldc = D;
     dg.M = nb; dg.N = D; dg.K = C;
     { ProfScope ps_(c, gemm_cat(dt, dg), 2.0 * dg.M * dg.N * dg.K); gemm(dt, dg, st); }
-    // only the CLS rows of dL/dx_L are non-zero.  The fp32 stream is the zero background the top block's
-    // backward adds into; of the low-precision copy that backward reads nothing but the CLS rows when it
-    // runs on first-token rows (S >= 4, below), so the fill is kept for the full-width backward only.
-    fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
-    if (S < 4) fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
-    { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
-                  dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
-                  c->wf(p.LNPART), nb, D, st); }
+    // only the CLS rows of dL/dx_L are non-zero: when the top block's backward runs on those rows (below) they
+    // go, dense, straight into its row buffers; otherwise into a zero-filled full-size gradient
+    if (top_first_rows && k < L) {
+      { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0,
+                    c->wf(p.rS0), c->w(p.rDO), D, c->gp(hg), c->gp(hb), c->gp(c->blk(L - 1, B2)), c->wf(p.LNPART), nb, D, st); }
+    } else {
+      fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
+      fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
+      { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
+                    dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
+                    c->wf(p.LNPART), nb, D, st); }
+    }
   } else if (g.head == PT_HEAD_CLS) {
     // sequence classification: the first token's final activation -> linear classifier -> cross-entropy
     const int C = g.n_out;

@@ -752,6 +752,29 @@ void mean_reduce(const float* rows, int n, float* out, hipStream_t st) {
   hipLaunchKernelGGL(mean_reduce_kernel, dim3(1), dim3(256), 0, st, rows, n, out);
 }
 
+// blockIdx.y < n: row blockIdx.y; blockIdx.y == n: the column sums
+template <typename T>
+__global__ __launch_bounds__(256) void add_rows_kernel(const float* __restrict__ r, float* __restrict__ x_s, T* __restrict__ x_o,
+                                                       int64_t row_stride, float* __restrict__ colsum, int n, int D) {
+  const int d = blockIdx.x * 256 + threadIdx.x, i = blockIdx.y;
+  if (d >= D) return;
+  if (i < n) {
+    const float t = x_s[i * row_stride + d] + r[(int64_t)i * D + d];
+    x_s[i * row_stride + d] = t;
+    if (x_o) x_o[i * row_stride + d] = from_f32<T>(t);
+  } else if (colsum) {
+    float s = 0.f;
+    for (int j = 0; j < n; ++j) s += r[(int64_t)j * D + d];
+    colsum[d] += s;
+  }
+}
+void add_rows(int dt, const float* r, float* x_s, void* x_o, int64_t row_stride, float* colsum, int n, int D,
+              hipStream_t st) {
+  if (n <= 0 || D <= 0) return;
+  if (dt == 0) hipLaunchKernelGGL(add_rows_kernel<float>, dim3(cdiv(D, 256), n + 1), dim3(256), 0, st, r, x_s, (float*)x_o, row_stride, colsum, n, D);
+  else hipLaunchKernelGGL(add_rows_kernel<bf16>, dim3(cdiv(D, 256), n + 1), dim3(256), 0, st, r, x_s, (bf16*)x_o, row_stride, colsum, n, D);
+}
+
 // ---------------------------------------------------------------------------
 // plumbing
 // ---------------------------------------------------------------------------
