@@ -476,6 +476,7 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
       // CUs better (M = 12608, N = 768: 198 tiles of 192x256 against 150 of 256x256); wide outputs with
       // a short K do better with 256x128 tiles, two workgroups per CU, whose prologues and epilogues
       // overlap.  Everything else: 128x128 tiles, three per CU.
+      if (g_cfg_override < 0 && gemm_dma_skinny(a, st)) return;
       int v = g_cfg_override >= 10 ? g_cfg_override - 10 : 1;
       if (g_cfg_override < 0) {
         v = (a.ta || a.N >= 3072) ? 2 : 1;

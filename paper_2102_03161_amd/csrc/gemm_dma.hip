@@ -764,6 +764,24 @@ void launch_pp(const Gemm& a, int splits, float* cbase, int64_t slab, float* col
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// sums the fp32 slabs of a split product in slab order and applies the product's epilogue
+template <int EPI, typename TC>
+__global__ __launch_bounds__(256) void split_epilogue_kernel(GemmDev<bf16> g, const float* __restrict__ part, int splits,
+                                                             int64_t slab) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= slab) return;
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += part[s * slab + i];
+  epilogue_store<bf16, TC, EPI>(g, (int)(i / g.N), (int)(i % g.N), v);
+}
+template <int EPI, typename TC>
+void launch_split_epilogue(const Gemm& a, const float* part, int splits, hipStream_t st) {
+  GemmDev<bf16> g{(const bf16*)a.A, (const bf16*)a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc,
+                  (const bf16*)a.bias, (const bf16*)a.aux, (bf16*)a.aux_out, a.ld_aux};
+  const int64_t mn = (int64_t)a.M * a.N;
+  hipLaunchKernelGGL((split_epilogue_kernel<EPI, TC>), dim3((unsigned)cdiv64(mn, 256)), dim3(256), 0, st, g, part, splits, mn);
+}
+
 }  // namespace
 
 bool gemm_dma_ok(const Gemm& a) {
@@ -904,6 +922,39 @@ static void dispatch_fwd(const Gemm& a, hipStream_t st) {
     else PT_L(false, EPI_BIAS_GELU, bf16);
   }
 #undef PT_L
+}
+
+// Few rows and a long contraction (the products of a top block that works on first-token rows, e.g.
+// 64 x 768 x 3072): the six workgroups of the output would each walk all of K one tile latency at a time
+// (45 us).  K is split over more workgroups into fp32 slabs in the caller's workspace, and a small kernel
+// sums the slabs in order and applies the epilogue.
+bool gemm_dma_skinny(const Gemm& a, hipStream_t st) {
+  if (a.ta || a.M > 128 || !a.ws || !gemm_dma_ok(a)) return false;
+  const int nk = a.K / 32;
+  int splits = nk / 12;   // at least 12 k tiles per split
+  if (splits > 16) splits = 16;
+  const int64_t mn = (int64_t)a.M * a.N;
+  while (splits > 1 && (size_t)(splits * mn) > a.ws_floats) --splits;
+  if (splits < 2) return false;
+  Gemm p = a;
+  p.C = a.ws; p.ldc = a.N; p.c_f32 = true; p.epi = EPI_STORE; p.bias = nullptr; p.aux = nullptr; p.aux_out = nullptr;
+  if (a.tb) launch_dma<128, 128, 2, 2, 3, 32, false, true, EPI_STORE, float>(p, splits, a.ws, mn, nullptr, st);
+  else launch_dma<128, 128, 2, 2, 3, 32, false, false, EPI_STORE, float>(p, splits, a.ws, mn, nullptr, st);
+#define PT_SE(EPI_, TC_) launch_split_epilogue<EPI_, TC_>(a, a.ws, splits, st)
+  if (a.tb) {
+    if (a.c_f32) PT_SE(EPI_RES, float);
+    else if (a.epi == EPI_STORE) PT_SE(EPI_STORE, bf16);
+    else PT_SE(EPI_MUL_DGELU, bf16);
+  } else if (a.c_f32) {
+    if (a.epi == EPI_BIAS) PT_SE(EPI_BIAS, float);
+    else PT_SE(EPI_BIAS_RES, float);
+  } else {
+    if (a.epi == EPI_BIAS) PT_SE(EPI_BIAS, bf16);
+    else if (a.epi == EPI_BIAS_RES) PT_SE(EPI_BIAS_RES, bf16);
+    else PT_SE(EPI_BIAS_GELU, bf16);
+  }
+#undef PT_SE
+  return true;
 }
 
 void gemm_dma(const Gemm& a, int variant, hipStream_t st) {

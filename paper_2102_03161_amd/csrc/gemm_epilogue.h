@@ -223,6 +223,8 @@ void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, co
                         hipStream_t st);
 bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
+// few rows, long K, workspace given: split-K with a summing epilogue pass; false if the shape is not taken
+bool gemm_dma_skinny(const Gemm& a, hipStream_t st);
 bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st);
 // the split-K reductions of up to four products (part2 entries may be null) in one launch
 void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,

@@ -491,6 +491,7 @@ void block_forward_first_rows(pt_ctx* c, int l, const void* xin, void* xout, con
     Gemm m;
     m.A = A; m.lda = lda; m.B = c->cp(wid); m.ldb = N; m.C = C; m.ldc = ldc; m.M = M; m.N = N; m.K = K;
     m.epi = epi; m.bias = c->cp(bid); m.aux = aux; m.aux_out = aux_out; m.ld_aux = ld_aux; m.c_f32 = out_f32;
+    if (M == ns) { m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; }   // lets a few-row product split its K
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   };
   auto attn = [&]() {
@@ -555,6 +556,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     Gemm m;
     m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
     m.M = rows; m.N = Kin; m.K = Nout; m.epi = epi; m.aux = aux; m.ld_aux = Kin; m.c_f32 = out_f32;
+    if (rows == ns) { m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; }   // lets a few-row product split its K
     ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K);
     gemm(dt, m, st);
   };
