@@ -770,8 +770,15 @@ __global__ __launch_bounds__(256) void split_epilogue_kernel(GemmDev<bf16> g, co
                                                              int64_t slab) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= slab) return;
+  // eight slabs' loads in flight at a time; the additions keep the slab order
   float v = 0.f;
-  for (int s = 0; s < splits; ++s) v += part[s * slab + i];
+  for (int s0 = 0; s0 < splits; s0 += 8) {
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = s0 + u < splits ? part[(s0 + u) * slab + i] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v += t[u];
+  }
   epilogue_store<bf16, TC, EPI>(g, (int)(i / g.N), (int)(i % g.N), v);
 }
 template <int EPI, typename TC>

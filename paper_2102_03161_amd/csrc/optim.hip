@@ -39,7 +39,13 @@ __global__ __launch_bounds__(256) void finalize_norms_kernel(const float* __rest
   }
   const int64_t lo = group_first[grp], hi = group_first[grp + 1];
   double s = 0.0;
-  for (int64_t c = lo + threadIdx.x; c < hi; c += 256) s += (double)chunk_sq[c];
+  for (int64_t c0 = lo + threadIdx.x; c0 < hi; c0 += 8 * 256) {   // eight loads in flight, added in chunk order
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = c0 + u * 256 < hi ? chunk_sq[c0 + u * 256] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (double)t[u];
+  }
   red[threadIdx.x] = s;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {

@@ -764,7 +764,13 @@ __global__ __launch_bounds__(256) void add_rows_kernel(const float* __restrict__
     if (x_o) x_o[i * row_stride + d] = from_f32<T>(t);
   } else if (colsum) {
     float s = 0.f;
-    for (int j = 0; j < n; ++j) s += r[(int64_t)j * D + d];
+    for (int j0 = 0; j0 < n; j0 += 8) {   // eight loads in flight, added in row order
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = j0 + u < n ? r[(int64_t)(j0 + u) * D + d] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += t[u];
+    }
     colsum[d] += s;
   }
 }
