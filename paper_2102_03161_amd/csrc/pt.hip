@@ -248,6 +248,7 @@ struct pt_ctx {
   int64_t n_hit = 0, n_adv = 0, n_miss = 0, n_runs = 0;
   // pinned host staging for index arrays, double-buffered by call parity
   int64_t* h_idx[2] = {nullptr, nullptr};
+  float* h_norms = nullptr;   // pinned host memory the norm kernel writes into (no copy command before the wait)
   hipEvent_t idx_ev[2] = {nullptr, nullptr};
   bool idx_ev_used[2] = {false, false};
   int idx_turn = 0;
@@ -728,6 +729,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
       if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
       if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
     }
+    if (c->h_norms) (void)hipHostFree(c->h_norms);
     delete c;
   };
 #define CREATE_TRY(expr)                         \
@@ -738,6 +740,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
     CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_idx[i]), (c->plan.idx_capacity / 2) * 8, hipHostMallocDefault));
     CREATE_TRY(hipEventCreateWithFlags(&c->idx_ev[i], hipEventDisableTiming));
   }
+  CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_norms), (size_t)(cfg->L + 2) * 4, hipHostMallocDefault));
   fill_zero(d_params, c->plan.params_bytes, c->st);
   fill_zero(d_state, c->plan.state_bytes, c->st);
   // chunk tables
@@ -762,6 +765,7 @@ pt_status pt_destroy(pt_ctx* c) {
     if (c->h_idx[i]) (void)hipHostFree(c->h_idx[i]);
     if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
   }
+  if (c->h_norms) (void)hipHostFree(c->h_norms);
   for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   if (c->copy_st) {
     (void)hipStreamSynchronize(c->copy_st);
@@ -1192,10 +1196,12 @@ pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
   const int G = c->cfg.L + 2, k = c->k;
   const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
   { ProfScope ps_(c, PT_PROF_NORMS, 4.0 * (total - first) * kChunk); sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st); }
+  // the last kernel writes the L + 2 norms straight into pinned host memory: the only thing between the GPU
+  // finishing and the caller going on is the wait itself (a copy command into pageable memory cost 15-25 us)
   finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
-                 c->wf(c->plan.NORMS), c->st);
-  HIP_TRY(c, hipMemcpyAsync(norms_out, c->w(c->plan.NORMS), (size_t)G * 4, hipMemcpyDeviceToHost, c->st));
+                 c->h_norms, c->st);
   HIP_TRY(c, hipStreamSynchronize(c->st));
+  std::memcpy(norms_out, c->h_norms, (size_t)G * 4);
   return PT_OK;
 }
 
