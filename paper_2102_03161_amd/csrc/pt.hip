@@ -248,7 +248,7 @@ struct pt_ctx {
   int64_t n_hit = 0, n_adv = 0, n_miss = 0, n_runs = 0;
   // pinned host staging for index arrays, double-buffered by call parity
   int64_t* h_idx[2] = {nullptr, nullptr};
-  float* h_norms = nullptr;   // pinned host memory the norm kernel writes into (no copy command before the wait)
+  float* h_norms = nullptr;   // pinned host memory: L + 2 norms, written by the norm kernel itself, and the loss
   hipEvent_t idx_ev[2] = {nullptr, nullptr};
   bool idx_ev_used[2] = {false, false};
   int idx_turn = 0;
@@ -740,7 +740,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
     CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_idx[i]), (c->plan.idx_capacity / 2) * 8, hipHostMallocDefault));
     CREATE_TRY(hipEventCreateWithFlags(&c->idx_ev[i], hipEventDisableTiming));
   }
-  CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_norms), (size_t)(cfg->L + 2) * 4, hipHostMallocDefault));
+  CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_norms), (size_t)(cfg->L + 3) * 4, hipHostMallocDefault));   // norms, loss
   fill_zero(d_params, c->plan.params_bytes, c->st);
   fill_zero(d_state, c->plan.state_bytes, c->st);
   // chunk tables
@@ -1184,8 +1184,11 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
 pt_status pt_last_loss(pt_ctx* c, float* loss_out) {
   if (!c || !loss_out) return PT_EINVAL;
   if (c->phase < 2) return fail(c, PT_ESTATE, "no loss has been computed");
-  HIP_TRY(c, hipMemcpyAsync(loss_out, c->w(c->plan.LOSS), 4, hipMemcpyDeviceToHost, c->st));
+  // through the pinned buffer (its slot behind the norms): a copy into pageable memory takes several times as long
+  float* h = c->h_norms + c->cfg.L + 2;
+  HIP_TRY(c, hipMemcpyAsync(h, c->w(c->plan.LOSS), 4, hipMemcpyDeviceToHost, c->st));
   HIP_TRY(c, hipStreamSynchronize(c->st));
+  *loss_out = *h;
   return PT_OK;
 }
 
