@@ -140,3 +140,43 @@ def test_full_batch_cache_is_faster_than_the_prefix_it_replaces(torch_mod, vitb)
     ms_re, ms_hit = ctx.time_frozen_forward(H.to_dev(torch, x), np.arange(w["B"]), 3)
     print(f"k={ctx.get_freeze_boundary()}: recompute {ms_re:.3f} ms, cached {ms_hit:.3f} ms", flush=True)
     assert ms_hit < ms_re
+
+
+def test_micro_batch_128_ties_to_micro_batch_64(torch_mod):
+    """The ViT-B/16 shapes at micro-batch 128 (25216 tokens; other tile counts and rounds than at 64): sampled
+    samples against the oracle, and the gradient against the mean of the two 64-sample halves, the
+    configuration the tests above tie to the oracle."""
+    torch = torch_mod
+    w = synth.workload("vit_b16_b128")
+    print("full-size ViT-B/16 B=128 k=0", flush=True)
+    ctx = binding.Context(binding.make_config(w))
+    vals = H.init_values(w, ctx, 9)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 9, w["B"])
+    B, S, D = w["B"], w["S"], w["D"]
+    forward_backward(torch, ctx, w, x, y)
+    logits = ctx.read_activation(binding.ACT_LOGITS, (B, w["n_out"]))
+    h0 = ctx.read_activation(binding.ACT_HK, (B, S, D))
+    cfg = oracle_cfg(w)
+    p = {n: a.astype(np.float64) for n, a in vals.items()}
+    for i in (70, B - 1):
+        o_h0, _ = orc.frozen_forward(cfg, p, x[i:i + 1].astype(np.float64), 0)
+        o_hL = orc.prefix_forward(cfg, p, o_h0, 0, cfg.L)
+        _, o_z, _ = orc.head_loss_forward(cfg, p, o_hL, y[i:i + 1])
+        assert rel_err(h0[i], o_h0[0]) < 2e-2
+        assert rel_err(logits[i], o_z[0]) < 2e-2, i
+    tid = {name: t for t, name, *_ in ctx.tensors()}
+    probe = ["front.W_pe", "blk0.Wqkv", "blk4.W2", "blk8.Wo", "blk11.W1", "blk11.Wqkv", "head.W"]
+    full = {n: ctx.read_tensor(tid[n], binding.KIND_GRAD) for n in probe}
+    acc = {n: np.zeros_like(full[n], dtype=np.float64) for n in probe}
+    for c in range(2):
+        sl = slice(64 * c, 64 * c + 64)
+        forward_backward(torch, ctx, w, x[sl], y[sl])
+        for n in probe:
+            acc[n] += ctx.read_tensor(tid[n], binding.KIND_GRAD)
+    gmax = max(float(np.max(np.abs(a))) for a in full.values())
+    for n in probe:
+        ref = acc[n] / 2
+        err = float(np.max(np.abs(full[n] - ref))) / max(float(np.max(np.abs(ref))), 1e-2 * gmax)
+        assert err < 2e-2, (n, err)
+    ctx.close()
