@@ -164,6 +164,15 @@ def main():
             if name.startswith("gemm") or name.startswith("attn"):
                 breakdown[name]["tflops"] = round(wk / (ms * 1e-3) / 1e12, 2)
                 breakdown[name]["frac_of_bf16_peak"] = round(wk / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
+                if name.startswith("attn"):
+                    # attention sits below the ridge (98 FLOP/B at S = 197): also its compulsory bytes against
+                    # HBM.  Forward reads qkv and writes ctx (8 D bytes per token), backward reads qkv, ctx, dctx
+                    # and writes dqkv (16 D); the top block under a first-token head moves less than this.
+                    per_tok = (8 if name == "attn_fwd" else 16) * w["D"]
+                    blocks = (w["L"] - a.k) * M * a.profile_steps
+                    byts = float(per_tok) * B * w["S"] * blocks
+                    breakdown[name]["gbs"] = round(byts / (ms * 1e-3) / 1e9, 1)
+                    breakdown[name]["frac_of_hbm_peak"] = round(byts / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
             elif wk:
                 breakdown[name]["gbs"] = round(wk / (ms * 1e-3) / 1e9, 1)
                 breakdown[name]["frac_of_hbm_peak"] = round(wk / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
