@@ -689,11 +689,215 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_res_kernel(const bf16* __res
   }
 }
 
+// ---------------------------------------------------------------------------
+// Fused backward for short sequences (S <= 256): one workgroup per (sample, head) holds Q, K, V and dO of the
+// head in LDS at once, so the packed qkv and dO are read from memory once instead of once per kernel and the
+// row statistics (log-sum-exp, delta = dO.O) never leave the chip.  Wave w owns rows 32w..32w+31: first as
+// queries (the dQ loop of attn_bwd_dq_res_kernel over the key tiles), then as keys (the dK/dV loop of
+// attn_bwd_dkv_res_kernel over the query tiles).  No atomics; the scores are recomputed in the second pass.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void load_resident4(bf16* dst[4], const bf16* const src[4], const int64_t ld[4], int nrows,
+                                               int rows_pad, int tid, int nthreads) {
+  const int total = rows_pad * 8;
+  for (int c0 = tid; c0 < total; c0 += 2 * nthreads) {
+    uint4 v[4][2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        v[m][u] = make_uint4(0, 0, 0, 0);
+        if (c < total && row < nrows) v[m][u] = *reinterpret_cast<const uint4*>(src[m] + (int64_t)row * ld[m] + ch * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
+      if (c < total) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) *reinterpret_cast<uint4*>(dst[m] + row * LDR + ch * 8) = v[m][u];
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                                 const bf16* __restrict__ dctx,
+                                                                 const float* __restrict__ lse, bf16* __restrict__ dqkv,
+                                                                 int S, int H, int ntile) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tile_elems = ntile * 32 * LDR;
+  bf16* Qs = reinterpret_cast<bf16*>(smem);
+  bf16* Ks = Qs + tile_elems;
+  bf16* Vs = Ks + tile_elems;
+  bf16* dOs = Vs + tile_elems;
+  float* ls = reinterpret_cast<float*>(dOs + tile_elems);   // row log-sum-exp in the log2 domain
+  float* dls = ls + ntile * 32;                             // row delta
+  const int D = H * DH;
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+  const int own = wave * 32 + (lane & 31);   // the row this lane owns, as a query and as a key
+  const bool ok = own < S;
+  const bool active = wave * 32 < S;
+  const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+  const bf16* dobase = dctx + (int64_t)b * S * D + h * DH;
+  bf16* obase = dqkv + (int64_t)b * S * 3 * D + h * DH;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+
+  // own query row, its dO and O straight from memory (the lines are the ones the resident load brings in)
+  bf16x8 qf[4], dof[4];
+  float part = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    qf[ks] = own_row_frag(base + (int64_t)own * 3 * D, ok, lane, ks);
+    dof[ks] = own_row_frag(dobase + (int64_t)own * D, ok, lane, ks);
+    const bf16x8 of = own_row_frag(ctx + ((int64_t)b * S + own) * D + h * DH, ok, lane, ks);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
+  }
+  {
+    bf16* dst[4] = {Qs, Ks, Vs, dOs};
+    const bf16* const src[4] = {base, base + D, base + 2 * D, dobase};
+    const int64_t ld[4] = {3 * (int64_t)D, 3 * (int64_t)D, 3 * (int64_t)D, (int64_t)D};
+    load_resident4(dst, src, ld, S, ntile * 32, tid, blockDim.x);
+  }
+  const float dl = part + __shfl_xor(part, 32, 64);
+  const float lq2 = (ok ? lse[((int64_t)b * H + h) * S + own] : 0.f) * 1.44269504088896f;
+  // a row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
+  if (half == 0) {
+    ls[own] = ok ? lq2 : INFINITY;
+    dls[own] = ok ? dl : 0.f;
+  }
+  __syncthreads();
+
+  // ---- pass 1: the wave's rows as queries ----
+  if (active) {
+    f32x16 dq[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dq[dt][v] = 0.f;
+    const unsigned k_base = lds_addr(Ks + (lane & 31) * LDR + half * 8);
+    const unsigned v_base = lds_addr(Vs + (lane & 31) * LDR + half * 8);
+    for (int kt = 0; kt < ntile; ++kt) {
+      const bf16* Kt = Ks + kt * 32 * LDR;
+      bf16x8 kr[4], vr[4], kc[4];
+      frag_rows_issue(k_base + kt * (32 * LDR * 2), kr);
+      frag_rows_issue(v_base + kt * (32 * LDR * 2), vr);
+      f32x16 s, dp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = 0.f;
+      lds_wait<4>(kr);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+      lds_wait<0>(vr);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[ks], dof[ks], dp, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Kt, lane, dt, ks2, kc[2 * ks2 + dt]);
+      if (kt == ntile - 1 && (S & 31)) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = fast_exp2(fmaf(s[v], c, -lq2));
+        s[v] = p * (dp[v] - dl);  // dS^T
+      }
+      lds_wait<0>(kc);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const bf16x8 dsb = pack8(s, 8 * ks2);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[2 * ks2 + dt], dsb, dq[dt], 0, 0, 0);
+      }
+    }
+    if (ok) store_owned_row(obase + (int64_t)own * 3 * D, dq, scale, half);
+  }
+
+  // ---- pass 2: the wave's rows as keys ----
+  if (active) {
+    bf16x8 kf[4], vf[4];
+    frag_rows_issue(lds_addr(Ks + own * LDR + half * 8), kf);
+    frag_rows_issue(lds_addr(Vs + own * LDR + half * 8), vf);
+    lds_wait<0>(kf);
+    lds_wait<0>(vf);
+    f32x16 dk[2], dv[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+    const unsigned q_base = lds_addr(Qs + (lane & 31) * LDR + half * 8);
+    const unsigned do_base = lds_addr(dOs + (lane & 31) * LDR + half * 8);
+    for (int qt = 0; qt < ntile; ++qt) {
+      const bf16* Qt = Qs + qt * 32 * LDR;
+      const bf16* dOt = dOs + qt * 32 * LDR;
+      bf16x8 qr[4], dor[4], tc[8];   // rows of Q and dO; columns [ks2][dt] of dO, then of Q
+      frag_rows_issue(q_base + qt * (32 * LDR * 2), qr);
+      frag_rows_issue(do_base + qt * (32 * LDR * 2), dor);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) frag_cols_tr(dOt, lane, dt, ks2, tc[2 * ks2 + dt]);
+      f32x16 s, dp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+      lds_wait<8>(qr);
+      lds_wait<8>(dor);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) frag_cols_tr(Qt, lane, dt, ks2, tc[4 + 2 * ks2 + dt]);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[ks], kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dor[ks], vf[ks], dp, 0, 0, 0);
+      }
+      f32x16 pr;
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const float4 l4 = *reinterpret_cast<const float4*>(ls + qt * 32 + 8 * g4 + 4 * half);
+        const float4 d4 = *reinterpret_cast<const float4*>(dls + qt * 32 + 8 * g4 + 4 * half);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * g4 + e;
+          const float p = fast_exp2(fmaf(s[v], c, -lv[e]));
+          pr[v] = p;
+          s[v] = p * (dp[v] - dv4[e]);  // dS
+        }
+      }
+      lds_wait<0>(tc);
+#pragma unroll
+      for (int ks2 = 0; ks2 < 2; ++ks2) {
+        const bf16x8 pb = pack8(pr, 8 * ks2), dsb = pack8(s, 8 * ks2);
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[2 * ks2 + dt], pb, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[4 + 2 * ks2 + dt], dsb, dk[dt], 0, 0, 0);
+        }
+      }
+    }
+    if (ok) {
+      bf16* row = obase + (int64_t)own * 3 * D;
+      store_owned_row(row + D, dk, scale, half);
+      store_owned_row(row + 2 * D, dv, 1.0f, half);
+    }
+  }
+}
+
 // Sequence lengths the resident kernels take (the LDS image of two [S,64] matrices and two float rows must
 // fit in 160 KB, i.e. S <= 512).  Measured: forward wins at S = 197 (25 vs 33 us per layer at ViT-B, batch
 // 64) but loses at S = 384, where only one workgroup fits a CU (44 vs 39 us); backward wins at both.
 int g_attn_resident_max_s = 224;
 int g_attn_resident_max_s_bwd = 512;
+int g_attn_fused_max_s_bwd = 256;   // four [S,64] images and two float rows in 160 KB, eight waves
 struct ResPlan { int ntile, nw, nblk; size_t lds; };
 ResPlan resident_plan(int S, bool with_rows) {
   ResPlan r;
@@ -725,6 +929,16 @@ void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, i
 }
 void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
                         int nb, int S, int H, hipStream_t st) {
+  if (S <= g_attn_fused_max_s_bwd) {
+    const int ntile = cdiv(S, 32);
+    const size_t lds = (size_t)4 * ntile * 32 * LDR * sizeof(bf16) + (size_t)2 * ntile * 32 * sizeof(float);
+    if (allow_lds(attn_bwd_fused_res_kernel, lds) == hipSuccess) {
+      hipLaunchKernelGGL(attn_bwd_fused_res_kernel, dim3(H, nb), dim3(64 * ntile), lds, st, (const bf16*)qkv,
+                         (const bf16*)ctx, (const bf16*)dctx, lse, (bf16*)dqkv, S, H, ntile);
+      return;
+    }
+    (void)hipGetLastError();
+  }
   if (S <= g_attn_resident_max_s_bwd) {
     const ResPlan r = resident_plan(S, false), r2 = resident_plan(S, true);
     if (allow_lds(attn_bwd_dq_res_kernel, r.lds) == hipSuccess && allow_lds(attn_bwd_dkv_res_kernel, r2.lds) == hipSuccess) {
