@@ -691,36 +691,16 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_res_kernel(const bf16* __res
 
 // ---------------------------------------------------------------------------
 // Fused backward for short sequences (S <= 256): one workgroup per (sample, head) holds Q, K, V and dO of the
-// head in LDS at once, so the packed qkv and dO are read from memory once instead of once per kernel and the
+// head in LDS, so the packed qkv and dO are read from memory once instead of once per kernel and the
 // row statistics (log-sum-exp, delta = dO.O) never leave the chip.  Wave w owns rows 32w..32w+31: first as
 // queries (the dQ loop of attn_bwd_dq_res_kernel over the key tiles), then as keys (the dK/dV loop of
 // attn_bwd_dkv_res_kernel over the query tiles).  No atomics; the scores are recomputed in the second pass.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void load_resident4(bf16* dst[4], const bf16* const src[4], const int64_t ld[4], int nrows,
-                                               int rows_pad, int tid, int nthreads) {
-  const int total = rows_pad * 8;
-  for (int c0 = tid; c0 < total; c0 += 2 * nthreads) {
-    uint4 v[4][2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
-#pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        v[m][u] = make_uint4(0, 0, 0, 0);
-        if (c < total && row < nrows) v[m][u] = *reinterpret_cast<const uint4*>(src[m] + (int64_t)row * ld[m] + ch * 8);
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int c = c0 + u * nthreads, row = c >> 3, ch = c & 7;
-      if (c < total) {
-#pragma unroll
-        for (int m = 0; m < 4; ++m) *reinterpret_cast<uint4*>(dst[m] + row * LDR + ch * 8) = v[m][u];
-      }
-    }
-  }
+// v, or zeros (a select of the four words in registers; a conditional on the struct goes through memory)
+__device__ __forceinline__ uint4 keep(uint4 v, bool on) {
+  const unsigned m = on ? 0xffffffffu : 0u;
+  return make_uint4(v.x & m, v.y & m, v.z & m, v.w & m);
 }
-
 __global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                                  const bf16* __restrict__ dctx,
                                                                  const float* __restrict__ lse, bf16* __restrict__ dqkv,
@@ -744,31 +724,66 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __r
   bf16* obase = dqkv + (int64_t)b * S * 3 * D + h * DH;
   const float scale = 0.125f, c = scale * 1.44269504088896f;
 
-  // own query row, its dO and O straight from memory (the lines are the ones the resident load brings in)
+  // The loads the first pass waits for go out together: the lane's own query row with its dO and O (the
+  // lines are the ones the image loads bring in), its log-sum-exp, and the K and V images (a workgroup has
+  // one wave per 32 rows, so four 16-byte chunks per thread cover an image).  Rows past the end read row
+  // S - 1 and are zeroed afterwards: unconditional loads let the compiler count exactly which ones a wait
+  // needs, where loads under a branch make it wait for all of them.  The Q and dO images, which only the
+  // second pass reads, are requested once K and V are in LDS and stay in registers over the first pass.  The barriers are bare s_barrier instructions behind an LDS wait:
+  // __syncthreads() would also wait for the loads still in flight.
+  const int ownc = ok ? own : S - 1;
+  union Frag { uint4 u; bf16x8 v; };
+  Frag qf_[4], dof_[4], of_[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int off = ks * 16 + half * 8;
+    qf_[ks].u = *reinterpret_cast<const uint4*>(base + (int64_t)ownc * 3 * D + off);
+    dof_[ks].u = *reinterpret_cast<const uint4*>(dobase + (int64_t)ownc * D + off);
+    of_[ks].u = *reinterpret_cast<const uint4*>(ctx + ((int64_t)b * S + ownc) * D + h * DH + off);
+  }
+  const float lse_own = lse[((int64_t)b * H + h) * S + ownc];
+  uint4 vk[4], vv[4], vq[4], vd[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int ch = tid + u * (int)blockDim.x, row = ch >> 3, col = (ch & 7) * 8, rc = row < S ? row : S - 1;
+    vk[u] = *reinterpret_cast<const uint4*>(base + (int64_t)rc * 3 * D + D + col);
+    vv[u] = *reinterpret_cast<const uint4*>(base + (int64_t)rc * 3 * D + 2 * D + col);
+  }
   bf16x8 qf[4], dof[4];
   float part = 0.f;
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    qf[ks] = own_row_frag(base + (int64_t)own * 3 * D, ok, lane, ks);
-    dof[ks] = own_row_frag(dobase + (int64_t)own * D, ok, lane, ks);
-    const bf16x8 of = own_row_frag(ctx + ((int64_t)b * S + own) * D + h * DH, ok, lane, ks);
+    qf_[ks].u = keep(qf_[ks].u, ok);
+    dof_[ks].u = keep(dof_[ks].u, ok);
+    of_[ks].u = keep(of_[ks].u, ok);
+    qf[ks] = qf_[ks].v;
+    dof[ks] = dof_[ks].v;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
+    for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of_[ks].v[i]);
   }
-  {
-    bf16* dst[4] = {Qs, Ks, Vs, dOs};
-    const bf16* const src[4] = {base, base + D, base + 2 * D, dobase};
-    const int64_t ld[4] = {3 * (int64_t)D, 3 * (int64_t)D, 3 * (int64_t)D, (int64_t)D};
-    load_resident4(dst, src, ld, S, ntile * 32, tid, blockDim.x);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int ch = tid + u * (int)blockDim.x, row = ch >> 3, col = (ch & 7) * 8;
+    *reinterpret_cast<uint4*>(Ks + row * LDR + col) = keep(vk[u], row < S);
+    *reinterpret_cast<uint4*>(Vs + row * LDR + col) = keep(vv[u], row < S);
+  }
+  __builtin_amdgcn_sched_barrier(0);   // the second pass's images are requested once K and V have left their registers
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int ch = tid + u * (int)blockDim.x, row = ch >> 3, col = (ch & 7) * 8, rc = row < S ? row : S - 1;
+    vq[u] = *reinterpret_cast<const uint4*>(base + (int64_t)rc * 3 * D + col);
+    vd[u] = *reinterpret_cast<const uint4*>(dobase + (int64_t)rc * D + col);
   }
   const float dl = part + __shfl_xor(part, 32, 64);
-  const float lq2 = (ok ? lse[((int64_t)b * H + h) * S + own] : 0.f) * 1.44269504088896f;
+  const float lq2 = (ok ? lse_own : 0.f) * 1.44269504088896f;
   // a row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
   if (half == 0) {
     ls[own] = ok ? lq2 : INFINITY;
     dls[own] = ok ? dl : 0.f;
   }
-  __syncthreads();
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 
   // ---- pass 1: the wave's rows as queries ----
   if (active) {
@@ -822,6 +837,15 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __r
   }
 
   // ---- pass 2: the wave's rows as keys ----
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int ch = tid + u * (int)blockDim.x, row = ch >> 3, col = (ch & 7) * 8;
+    *reinterpret_cast<uint4*>(Qs + row * LDR + col) = keep(vq[u], row < S);
+    *reinterpret_cast<uint4*>(dOs + row * LDR + col) = keep(vd[u], row < S);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   if (active) {
     bf16x8 kf[4], vf[4];
     frag_rows_issue(lds_addr(Ks + own * LDR + half * 8), kf);
