@@ -26,11 +26,12 @@ void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t 
 }
 
 // one workgroup per layer: fp64 sum of its chunk partials in a fixed order
-__global__ __launch_bounds__(256) void finalize_norms_kernel(const float* __restrict__ chunk_sq,
+constexpr int kFinThreads = 1024;   // one workgroup per group; the front end of BERT spans 23k chunks
+__global__ __launch_bounds__(kFinThreads) void finalize_norms_kernel(const float* __restrict__ chunk_sq,
                                                              const int64_t* __restrict__ group_first, int G,
                                                              int first_active, int front_active,
                                                              float* __restrict__ norms) {
-  __shared__ double red[256];
+  __shared__ double red[kFinThreads];
   const int grp = blockIdx.x;
   const bool active = (grp == 0) ? (front_active != 0) : (grp >= first_active);
   if (!active) {
@@ -39,16 +40,16 @@ __global__ __launch_bounds__(256) void finalize_norms_kernel(const float* __rest
   }
   const int64_t lo = group_first[grp], hi = group_first[grp + 1];
   double s = 0.0;
-  for (int64_t c0 = lo + threadIdx.x; c0 < hi; c0 += 8 * 256) {   // eight loads in flight, added in chunk order
+  for (int64_t c0 = lo + threadIdx.x; c0 < hi; c0 += 8 * kFinThreads) {   // eight loads in flight, added in chunk order
     float t[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) t[u] = c0 + u * 256 < hi ? chunk_sq[c0 + u * 256] : 0.f;
+    for (int u = 0; u < 8; ++u) t[u] = c0 + u * kFinThreads < hi ? chunk_sq[c0 + u * kFinThreads] : 0.f;
 #pragma unroll
     for (int u = 0; u < 8; ++u) s += (double)t[u];
   }
   red[threadIdx.x] = s;
   __syncthreads();
-  for (int o = 128; o > 0; o >>= 1) {
+  for (int o = kFinThreads / 2; o > 0; o >>= 1) {
     if ((int)threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
     __syncthreads();
   }
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void finalize_norms_kernel(const float* __rest
 }
 void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk, int G, int first_active, int front_active,
                     float* norms, hipStream_t st) {
-  hipLaunchKernelGGL(finalize_norms_kernel, dim3(G), dim3(256), 0, st, chunk_sq, group_first_chunk, G, first_active,
+  hipLaunchKernelGGL(finalize_norms_kernel, dim3(G), dim3(kFinThreads), 0, st, chunk_sq, group_first_chunk, G, first_active,
                      front_active, norms);
 }
 

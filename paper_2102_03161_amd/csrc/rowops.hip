@@ -527,24 +527,47 @@ __global__ void token_count_kernel(const int32_t* __restrict__ ids, int32_t* __r
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t < ntok) atomicAdd(&count[clamp_id(ids[t], vocab)], 1);
 }
-// offset = exclusive prefix sum of count, one workgroup
+// offset = exclusive prefix sum of count, one workgroup: each of its 16 waves owns a contiguous range of ids,
+// sums it (pass 1), and after the wave totals are known scans it 64 ids at a time (pass 2); loads go out
+// eight at a time
 __global__ __launch_bounds__(1024) void token_offsets_kernel(const int32_t* __restrict__ count,
                                                               int32_t* __restrict__ offset, int vocab) {
-  __shared__ int32_t part[1024];
-  const int per = (vocab + 1023) / 1024;
-  const int lo = threadIdx.x * per, hi = lo + per < vocab ? lo + per : vocab;
+  __shared__ int32_t wsum[16];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int chunk = ((vocab + 1023) / 1024) * 64;   // ids per wave, a multiple of 64
+  const int lo = wave * chunk, hi = lo + chunk < vocab ? lo + chunk : vocab;
   int32_t s = 0;
-  for (int v = lo; v < hi; ++v) s += count[v];
-  part[threadIdx.x] = s;
-  __syncthreads();
-  for (int o = 1; o < 1024; o <<= 1) {
-    const int32_t add = (int)threadIdx.x >= o ? part[threadIdx.x - o] : 0;
-    __syncthreads();
-    part[threadIdx.x] += add;
-    __syncthreads();
+  for (int v0 = lo; v0 < hi; v0 += 512) {
+    int32_t c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { const int v = v0 + 64 * u + lane; c[u] = count[v < hi ? v : lo]; }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { const int v = v0 + 64 * u + lane; s += v < hi ? c[u] : 0; }
   }
-  int32_t run = threadIdx.x ? part[threadIdx.x - 1] : 0;
-  for (int v = lo; v < hi; ++v) { offset[v] = run; run += count[v]; }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (lane == 0) wsum[wave] = s;
+  __syncthreads();
+  int32_t run = 0;
+  for (int w = 0; w < wave; ++w) run += wsum[w];
+  for (int v0 = lo; v0 < hi; v0 += 512) {
+    int32_t c[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { const int v = v0 + 64 * u + lane; c[u] = count[v < hi ? v : lo]; }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = v0 + 64 * u + lane;
+      const int32_t x = v < hi ? c[u] : 0;
+      int32_t inc = x;   // inclusive scan over the wave's 64 ids
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int32_t t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+      }
+      if (v < hi) offset[v] = run + inc - x;
+      run += __shfl(inc, 63, 64);
+    }
+  }
 }
 __global__ void token_bucket_kernel(const int32_t* __restrict__ ids, const int32_t* __restrict__ offset,
                                     int32_t* __restrict__ cursor, int32_t* __restrict__ bucket, int ntok, int vocab) {
@@ -693,50 +716,112 @@ void qa_ce(int dt, const float* z, const int32_t* labels, float* loss_rows, floa
   hipLaunchKernelGGL(qa_ce_kernel, dim3(nb), dim3(256), 0, st, z, labels, loss_rows, dz, nb, S);
 }
 
-constexpr int kQaBlocks = 256;
+constexpr int kQaBlocks = 512;   // workgroups (partial rows) at most; four waves each, one row per wave at a time
 size_t qa_partial_floats(int D) { return (size_t)kQaBlocks * (2 * D + 2); }
 
-template <typename T>
+// dx = dz W^T, and per workgroup the partial sums of dW = x^T dz and db = column sums of dz.  One wave per row,
+// four columns per lane and slot, the next row's loads in flight while the current one is used.
+template <typename T, int VPL>
 __global__ __launch_bounds__(256) void qa_head_bwd_kernel(const T* __restrict__ x, const T* __restrict__ W,
                                                           const float* __restrict__ dz, float* __restrict__ dx,
                                                           float* __restrict__ partial, int rows, int D) {
-  // each thread owns columns d = tid, tid+256, ... (at most 8: D <= 2048)
-  float w0[8], w1[8], a0[8], a1[8];
+  extern __shared__ float red[];   // [2*D + 2], laid out like W and b
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nvec = D >> 2;
+  float w0[VPL][4], w1[VPL][4], a0[VPL][4], a1[VPL][4];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int d = threadIdx.x + 256 * j;
-    a0[j] = a1[j] = 0.f;
-    w0[j] = d < D ? to_f32(W[2 * d]) : 0.f;
-    w1[j] = d < D ? to_f32(W[2 * d + 1]) : 0.f;
+  for (int j = 0; j < VPL; ++j) {
+    const int c = lane + 64 * j;
+    float t0[4] = {0.f, 0.f, 0.f, 0.f}, t1[4] = {0.f, 0.f, 0.f, 0.f};
+    if (c < nvec) { load4(W + 8 * c, t0); load4(W + 8 * c + 4, t1); }   // W is [D, 2]
+    w0[j][0] = t0[0]; w1[j][0] = t0[1]; w0[j][1] = t0[2]; w1[j][1] = t0[3];
+    w0[j][2] = t1[0]; w1[j][2] = t1[1]; w0[j][3] = t1[2]; w1[j][3] = t1[3];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { a0[j][e] = 0.f; a1[j][e] = 0.f; }
   }
+  struct RowIn {
+    Raw4<T> x[VPL];
+    float g0, g1;
+  };
+  auto fetch = [&](int row, RowIn& in) {
+    in.g0 = dz[2 * (int64_t)row];
+    in.g1 = dz[2 * (int64_t)row + 1];
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      in.x[j].zero();
+      if (c < nvec) in.x[j].ld(x + (int64_t)row * D + 4 * c);
+    }
+  };
   float b0 = 0.f, b1 = 0.f;
-  for (int t = blockIdx.x; t < rows; t += gridDim.x) {
-    const float g0 = dz[2 * (int64_t)t], g1 = dz[2 * (int64_t)t + 1];
+  const int stride = gridDim.x * 4;
+  int row = blockIdx.x * 4 + wave;
+  RowIn cur, nxt;
+  if (row < rows) fetch(row, cur);
+  for (; row < rows; row += stride) {
+    const bool more = row + stride < rows;
+    if (more) fetch(row + stride, nxt);
+    const float g0 = cur.g0, g1 = cur.g1;
     b0 += g0; b1 += g1;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int d = threadIdx.x + 256 * j;
-      if (d < D) {
-        const float xv = to_f32(x[(int64_t)t * D + d]);
-        a0[j] += xv * g0;
-        a1[j] += xv * g1;
-        dx[(int64_t)t * D + d] = g0 * w0[j] + g1 * w1[j];
+    for (int j = 0; j < VPL; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float xv[4], o[4];
+        cur.x[j].get(xv);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a0[j][e] += xv[e] * g0;
+          a1[j][e] += xv[e] * g1;
+          o[e] = g0 * w0[j][e] + g1 * w1[j][e];
+        }
+        store4(dx + (int64_t)row * D + 4 * c, o);
       }
     }
+    if (more) cur = nxt;
   }
-  float* p = partial + (size_t)blockIdx.x * (2 * D + 2);
+  // combine the waves of the workgroup in wave order (fixed, so reproducible)
+  for (int w = 0; w < 4; ++w) {
+    if (wave == w) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int d = threadIdx.x + 256 * j;
-    if (d < D) { p[2 * d] = a0[j]; p[2 * d + 1] = a1[j]; }
+      for (int j = 0; j < VPL; ++j) {
+        const int c = lane + 64 * j;
+        if (c < nvec) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = 2 * (4 * c + e);
+            red[i] = (w ? red[i] : 0.f) + a0[j][e];
+            red[i + 1] = (w ? red[i + 1] : 0.f) + a1[j][e];
+          }
+        }
+      }
+      if (lane == 0) {
+        red[2 * D] = (w ? red[2 * D] : 0.f) + b0;
+        red[2 * D + 1] = (w ? red[2 * D + 1] : 0.f) + b1;
+      }
+    }
+    __syncthreads();
   }
-  if (threadIdx.x == 0) { p[2 * D] = b0; p[2 * D + 1] = b1; }
+  for (int i = threadIdx.x; i < 2 * D + 2; i += 256) partial[(size_t)blockIdx.x * (2 * D + 2) + i] = red[i];
 }
 void qa_head_bwd(int dt, const void* x, const void* W, const float* dz, float* dx, float* dW, float* db, float* partial,
                  int rows, int D, hipStream_t st) {
-  const int nb = rows < kQaBlocks ? rows : kQaBlocks;
-  if (dt == 0) hipLaunchKernelGGL(qa_head_bwd_kernel<float>, dim3(nb), dim3(256), 0, st, (const float*)x, (const float*)W, dz, dx, partial, rows, D);
-  else hipLaunchKernelGGL(qa_head_bwd_kernel<bf16>, dim3(nb), dim3(256), 0, st, (const bf16*)x, (const bf16*)W, dz, dx, partial, rows, D);
+  if (rows <= 0) return;
+  const int nb = cdiv(rows, 4) < kQaBlocks ? cdiv(rows, 4) : kQaBlocks;
+  const size_t shm = (size_t)(2 * D + 2) * sizeof(float);
+#define QA_BWD(T, V)                                                                                              \
+  hipLaunchKernelGGL((qa_head_bwd_kernel<T, V>), dim3(nb), dim3(256), shm, st, (const T*)x, (const T*)W, dz, dx, \
+                     partial, rows, D)
+#define QA_BWD_V(T)                       \
+  do {                                    \
+    if (D <= 768) QA_BWD(T, 3);           \
+    else if (D <= 1024) QA_BWD(T, 4);     \
+    else QA_BWD(T, 8);                    \
+  } while (0)
+  if (dt == 0) QA_BWD_V(float);
+  else QA_BWD_V(bf16);
+#undef QA_BWD_V
+#undef QA_BWD
   hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(2 * D + 2, 32)), dim3(1024), 0, st, partial, nb, 2 * D + 2, dW,
                      2 * D, db, (float*)nullptr);
 }
