@@ -409,6 +409,13 @@ DEGENERATE = {
     # widths that are no multiple of any tile: D = 72 (head size 24), F = 100, 13 classes
     "vit_ragged": dict(arch="vit", L=2, D=72, H=3, F=100, S=10, n_out=13, img=6, patch=2, chans=3, vocab=0, max_pos=0,
                        ln_eps=1e-6, B=5, optimizer="sgdm"),
+    # wide rows: the row kernels (LayerNorm, span-head gradient) with four and with eight vectors per lane
+    "bert_d1024": dict(arch="bert", L=1, D=1024, H=8, F=256, S=9, n_out=2, img=0, patch=0, chans=0, vocab=30, max_pos=12,
+                       ln_eps=1e-12, B=3, optimizer="adamw"),
+    "bert_d2048": dict(arch="bert", L=1, D=2048, H=16, F=160, S=6, n_out=2, img=0, patch=0, chans=0, vocab=30, max_pos=8,
+                       ln_eps=1e-12, B=2, optimizer="adamw"),
+    "vit_d1280": dict(arch="vit", L=1, D=1280, H=10, F=128, S=5, n_out=6, img=4, patch=2, chans=3, vocab=0, max_pos=0,
+                      ln_eps=1e-6, B=3, optimizer="adamw"),
 }
 
 
