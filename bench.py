@@ -1,8 +1,10 @@
 """Benchmark of the freeze-boundary training step on one MI355X.
 
 A step is one pass of the whole hot path: pt_frozen_forward (front end, frozen
-blocks or a cache gather), pt_active_fwd_bwd, pt_layer_grad_norms and
-pt_optimizer_step, on a synthetic batch already resident in HBM.  The default
+blocks or a cache gather), pt_active_fwd_bwd, pt_layer_grad_norms (its begin
+half before and its end half, the host's wait, after the enqueue of
+pt_optimizer_step) and pt_optimizer_step, on a synthetic batch already resident
+in HBM.  The default
 workload is ViT-B/16, bf16 with fp32 accumulation, micro-batch 64, AdamW, k = 0.
 
 Prints ONE JSON line (see the keys below).  `roofline` describes the dominant
@@ -110,9 +112,9 @@ def main():
                 ctx.accumulate_grads(first=(j == 0))
         if M > 1:
             ctx.finish_accumulation(want_loss=False)
-        norms = ctx.layer_grad_norms()        # synchronises: the freeze rule reads these on the host
-        ctx.optimizer_step(**hp)
-        return norms
+        ctx.layer_grad_norms_begin()          # the norm kernels, then the update, are enqueued before the host
+        ctx.optimizer_step(**hp)              # waits for the norms, so the stream does not run dry meanwhile
+        return ctx.layer_grad_norms_end()     # synchronises: the freeze rule reads these on the host
 
     def timed(n_warm, n_steps, use_cache=False):
         for i in range(n_warm):

@@ -26,6 +26,8 @@
  *    non-OK return the context is unchanged.  pt_last_error gives a message.
  *  - Call order per step: pt_frozen_forward -> pt_active_fwd_bwd ->
  *    [pt_layer_grad_norms] -> pt_optimizer_step.  Out of order: PT_ESTATE.
+ *    (pt_layer_grad_norms_begin takes the place of pt_layer_grad_norms in this
+ *    order; its _end half may come any time later.)
  *  - Layouts: activations [B,S,D] row-major; linear maps y = x W + b with W
  *    stored [in,out] row-major; packed QKV weight columns [Q|K|V], head h owns
  *    columns h*dh..(h+1)*dh-1 of each third.  In PT_BF16 mode activations are
@@ -154,6 +156,18 @@ pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
  * norms_out HOST, L+2 floats: [front end, block 0 .. block L-1, head]; frozen
  * layers (and the front end when k >= 1) read exactly 0.  Synchronises. */
 pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
+
+/* The same in two halves, for callers that do not want the stream to run dry
+ * while the host waits: pt_layer_grad_norms_begin enqueues the norm kernels
+ * (same preconditions as pt_layer_grad_norms) and returns at once;
+ * pt_layer_grad_norms_end waits for exactly those kernels and copies the L+2
+ * norms to norms_out (HOST).  Anything may be enqueued in between, normally
+ * pt_optimizer_step, which does not change the gradients the norms are taken
+ * of; the values equal what pt_layer_grad_norms would have returned at the
+ * point of _begin.  One set of norms can be pending at a time: a second _begin
+ * (or pt_layer_grad_norms) before _end, or _end without _begin, is PT_ESTATE. */
+pt_status pt_layer_grad_norms_begin(pt_ctx* ctx);
+pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
 
 /* Micro-batch gradient accumulation (Sec. 2.1 pipeline parallelism and Sec. 3.2.3:
  * a mini-batch is processed as M micro-batches whose gradients are combined

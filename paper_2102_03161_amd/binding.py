@@ -68,6 +68,8 @@ def load_library():
         "pt_active_fwd_bwd": [vp, vp, vp, P(C.c_float)],
         "pt_last_loss": [vp, P(C.c_float)],
         "pt_layer_grad_norms": [vp, P(C.c_float)],
+        "pt_layer_grad_norms_begin": [vp],
+        "pt_layer_grad_norms_end": [vp, P(C.c_float)],
         "pt_optimizer_step": [vp, P(PtOptHparams)],
         "pt_accumulate_grads": [vp, i32],
         "pt_finish_accumulation": [vp, P(C.c_float)],
@@ -211,6 +213,14 @@ class Context:
     def layer_grad_norms(self) -> np.ndarray:
         out = np.zeros(self.cfg.L + 2, dtype=np.float32)
         self._chk(self.lib.pt_layer_grad_norms(self.h, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def layer_grad_norms_begin(self):
+        self._chk(self.lib.pt_layer_grad_norms_begin(self.h))
+
+    def layer_grad_norms_end(self) -> np.ndarray:
+        out = np.zeros(self.cfg.L + 2, dtype=np.float32)
+        self._chk(self.lib.pt_layer_grad_norms_end(self.h, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
 
     def accumulate_grads(self, first: bool):

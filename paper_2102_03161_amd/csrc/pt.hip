@@ -249,6 +249,8 @@ struct pt_ctx {
   // pinned host staging for index arrays, double-buffered by call parity
   int64_t* h_idx[2] = {nullptr, nullptr};
   float* h_norms = nullptr;   // pinned host memory: L + 2 norms, written by the norm kernel itself, and the loss
+  hipEvent_t norms_ev = nullptr;   // recorded behind the norm kernels by pt_layer_grad_norms_begin
+  bool norms_pending = false;      // begun and not yet fetched
   hipEvent_t idx_ev[2] = {nullptr, nullptr};
   bool idx_ev_used[2] = {false, false};
   int idx_turn = 0;
@@ -730,6 +732,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
       if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
     }
     if (c->h_norms) (void)hipHostFree(c->h_norms);
+    if (c->norms_ev) (void)hipEventDestroy(c->norms_ev);
     delete c;
   };
 #define CREATE_TRY(expr)                         \
@@ -741,6 +744,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
     CREATE_TRY(hipEventCreateWithFlags(&c->idx_ev[i], hipEventDisableTiming));
   }
   CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_norms), (size_t)(cfg->L + 3) * 4, hipHostMallocDefault));   // norms, loss
+  CREATE_TRY(hipEventCreateWithFlags(&c->norms_ev, hipEventDisableTiming));
   fill_zero(d_params, c->plan.params_bytes, c->st);
   fill_zero(d_state, c->plan.state_bytes, c->st);
   // chunk tables
@@ -766,6 +770,7 @@ pt_status pt_destroy(pt_ctx* c) {
     if (c->idx_ev[i]) (void)hipEventDestroy(c->idx_ev[i]);
   }
   if (c->h_norms) (void)hipHostFree(c->h_norms);
+  if (c->norms_ev) (void)hipEventDestroy(c->norms_ev);
   for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   if (c->copy_st) {
     (void)hipStreamSynchronize(c->copy_st);
@@ -1192,9 +1197,10 @@ pt_status pt_last_loss(pt_ctx* c, float* loss_out) {
   return PT_OK;
 }
 
-pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
-  if (!c || !norms_out) return PT_EINVAL;
+pt_status pt_layer_grad_norms_begin(pt_ctx* c) {
+  if (!c) return PT_EINVAL;
   if (c->phase != 2) return fail(c, PT_ESTATE, "gradient norms need a completed pt_active_fwd_bwd");
+  if (c->norms_pending) return fail(c, PT_ESTATE, "the norms of an earlier pt_layer_grad_norms_begin have not been fetched");
   const auto& gf = c->plan.group_first_chunk;
   const int G = c->cfg.L + 2, k = c->k;
   const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
@@ -1203,9 +1209,24 @@ pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
   // finishing and the caller going on is the wait itself (a copy command into pageable memory cost 15-25 us)
   finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
                  c->h_norms, c->st);
-  HIP_TRY(c, hipStreamSynchronize(c->st));
-  std::memcpy(norms_out, c->h_norms, (size_t)G * 4);
+  HIP_TRY(c, hipEventRecord(c->norms_ev, c->st));
+  c->norms_pending = true;
   return PT_OK;
+}
+
+pt_status pt_layer_grad_norms_end(pt_ctx* c, float* norms_out) {
+  if (!c || !norms_out) return PT_EINVAL;
+  if (!c->norms_pending) return fail(c, PT_ESTATE, "pt_layer_grad_norms_begin has not run");
+  HIP_TRY(c, hipEventSynchronize(c->norms_ev));
+  std::memcpy(norms_out, c->h_norms, (size_t)(c->cfg.L + 2) * 4);
+  c->norms_pending = false;
+  return PT_OK;
+}
+
+pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
+  if (!c || !norms_out) return PT_EINVAL;
+  const pt_status s = pt_layer_grad_norms_begin(c);
+  return s == PT_OK ? pt_layer_grad_norms_end(c, norms_out) : s;
 }
 
 pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {

@@ -266,6 +266,49 @@ def test_state_machine_and_argument_errors(torch_mod):
     ctx.close()
 
 
+def test_gradient_norms_in_two_halves(torch_mod):
+    """pt_layer_grad_norms_begin / _end with the optimizer step enqueued in between return, bit for bit, what
+    pt_layer_grad_norms returns for the same gradients, and the parameters end up the same; misuse of the
+    pair is a state error."""
+    torch = torch_mod
+    w = synth.workload("bert_tiny")
+    hp = dict(H.HP)
+    results = []
+    for split in (False, True):
+        ctx = binding.Context(binding.make_config(w))
+        vals = H.init_values(w, ctx, 2)
+        H.load_params(ctx, vals)
+        x, y = H.batch_for(w, 2, w["B"])
+        ctx.set_freeze_boundary(1)
+        hk = ctx.frozen_forward(H.to_dev(torch, x))
+        ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+        if split:
+            with pytest.raises(binding.PtError) as e:
+                ctx.layer_grad_norms_end()
+            assert e.value.status == binding.PT_ESTATE
+            ctx.layer_grad_norms_begin()
+            for again in (ctx.layer_grad_norms_begin, ctx.layer_grad_norms):
+                with pytest.raises(binding.PtError) as e:
+                    again()
+                assert e.value.status == binding.PT_ESTATE
+            ctx.optimizer_step(**hp)
+            norms = ctx.layer_grad_norms_end()
+            with pytest.raises(binding.PtError) as e:
+                ctx.layer_grad_norms_end()
+            assert e.value.status == binding.PT_ESTATE
+        else:
+            norms = ctx.layer_grad_norms()
+            ctx.optimizer_step(**hp)
+        params = {name: ctx.read_tensor(t, binding.KIND_PARAM) for t, name, *_ in ctx.tensors()}
+        results.append((norms, params))
+        ctx.close()
+    (n0, p0), (n1, p1) = results
+    assert n0[0] == 0.0 and n0[1] == 0.0 and np.all(n0[2:] > 0)
+    assert np.array_equal(n0, n1)
+    for name in p0:
+        assert np.array_equal(p0[name], p1[name]), name
+
+
 def test_runs_are_bit_reproducible(torch_mod):
     torch = torch_mod
     for w in (MID_VIT, MID_BERT):
