@@ -269,6 +269,7 @@ __global__ __launch_bounds__(C::NT, 4) void gemm_mfma_kernel(GemmDev<bf16> g, Sp
                                                             m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
 }
 
+typedef float f32x4_nt __attribute__((ext_vector_type(4)));
 // out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread).  A second, short
 // vector (the column-sum partials of the same product) may ride along in the last workgroups.
 __device__ __forceinline__ void splitk_sum4(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
@@ -279,7 +280,10 @@ __device__ __forceinline__ void splitk_sum4(const float* __restrict__ part, int 
       const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)z * n + i);
       s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
     }
-    *reinterpret_cast<float4*>(out + i) = s;
+    // a weight gradient is next read by the norm and update passes, after the rest of the backward pass
+    // has gone through the caches: stored past them
+    f32x4_nt o; o.x = s.x; o.y = s.y; o.z = s.z; o.w = s.w;
+    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_nt*>(out + i));
   } else {
     for (int64_t j = i; j < n && j < i + 4; ++j) {
       float s = part[j];
