@@ -151,11 +151,11 @@ __global__ __launch_bounds__(256) void grad_accumulate_kernel(float* __restrict_
                                                               int64_t first_chunk, float weight, int first,
                                                               const float* __restrict__ loss, float* __restrict__ loss_acc) {
   const int64_t i = (first_chunk + blockIdx.x) * kChunk + 4 * threadIdx.x;
-  const float4 gv = *reinterpret_cast<const float4*>(g + i);
+  const float4 gv = ld_nt4(g + i);
   float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (!first) av = *reinterpret_cast<const float4*>(acc + i);
+  if (!first) av = ld_nt4(acc + i);
   av.x += weight * gv.x; av.y += weight * gv.y; av.z += weight * gv.z; av.w += weight * gv.w;
-  *reinterpret_cast<float4*>(acc + i) = av;
+  st_nt4(acc + i, av);
   if (blockIdx.x == 0 && threadIdx.x == 0) *loss_acc = (first ? 0.f : *loss_acc) + weight * *loss;
 }
 void grad_accumulate_chunks(float* acc, const float* g, int64_t first_chunk, int64_t n_chunks, float weight, bool first,
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(256) void grad_average_kernel(float* __restrict__ g
                                                            int64_t first_chunk, float inv, float* __restrict__ loss,
                                                            const float* __restrict__ loss_acc) {
   const int64_t i = (first_chunk + blockIdx.x) * kChunk + 4 * threadIdx.x;
-  float4 av = *reinterpret_cast<const float4*>(acc + i);
+  float4 av = ld_nt4(acc + i);
   av.x *= inv; av.y *= inv; av.z *= inv; av.w *= inv;
   *reinterpret_cast<float4*>(g + i) = av;
   if (blockIdx.x == 0 && threadIdx.x == 0) *loss = *loss_acc * inv;
