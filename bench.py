@@ -112,8 +112,8 @@ def main():
                 ctx.accumulate_grads(first=(j == 0))
         if M > 1:
             ctx.finish_accumulation(want_loss=False)
-        ctx.layer_grad_norms_begin()          # the norm kernels, then the update, are enqueued before the host
-        ctx.optimizer_step(**hp)              # waits for the norms, so the stream does not run dry meanwhile
+        ctx.layer_grad_norms_begin()          # asks for the norms of the gradients as they are now
+        ctx.optimizer_step(**hp)              # its pass over the gradient also leaves the sums of squares
         return ctx.layer_grad_norms_end()     # synchronises: the freeze rule reads these on the host
 
     def timed(n_warm, n_steps, use_cache=False):

@@ -158,14 +158,18 @@ pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
 pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
 
 /* The same in two halves, for callers that do not want the stream to run dry
- * while the host waits: pt_layer_grad_norms_begin enqueues the norm kernels
- * (same preconditions as pt_layer_grad_norms) and returns at once;
- * pt_layer_grad_norms_end waits for exactly those kernels and copies the L+2
- * norms to norms_out (HOST).  Anything may be enqueued in between, normally
- * pt_optimizer_step, which does not change the gradients the norms are taken
- * of; the values equal what pt_layer_grad_norms would have returned at the
- * point of _begin.  One set of norms can be pending at a time: a second _begin
- * (or pt_layer_grad_norms) before _end, or _end without _begin, is PT_ESTATE. */
+ * while the host waits, nor the gradient to be read twice:
+ * pt_layer_grad_norms_begin (same preconditions as pt_layer_grad_norms) asks
+ * for the norms of the gradients as they are now and returns at once;
+ * pt_layer_grad_norms_end waits for them and copies the L+2 norms to norms_out
+ * (HOST).  If pt_optimizer_step comes between the two, its pass over the
+ * gradient (which it reads and does not change) leaves the sums of squares as a
+ * by-product and the host's wait comes after the update is queued; any other
+ * call that would change the gradients or the boundary first has the norm
+ * kernels enqueued ahead of it.  Either way the values are, bit for bit, what
+ * pt_layer_grad_norms would have returned at the point of _begin.  One set of
+ * norms can be pending at a time: a second _begin (or pt_layer_grad_norms)
+ * before _end, or _end without _begin, is PT_ESTATE. */
 pt_status pt_layer_grad_norms_begin(pt_ctx* ctx);
 pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
 

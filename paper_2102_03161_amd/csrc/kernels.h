@@ -151,9 +151,11 @@ struct OptArgs {
   float lr, momentum, beta1, beta2, eps, weight_decay;
   float bias_c1, bias_c2;  // 1-beta1^t, 1-beta2^t
 };
+// chunk_sq non-null: the update also leaves each chunk's sum of squared gradients there, as sumsq_chunks would
 void adamw_chunks(float* w, const float* g, float* m, float* v, void* shadow /*bf16 or null*/,
-                  const uint8_t* chunk_decay, int64_t first_chunk, int64_t n_chunks, OptArgs a, hipStream_t st);
+                  const uint8_t* chunk_decay, int64_t first_chunk, int64_t n_chunks, OptArgs a, float* chunk_sq,
+                  hipStream_t st);
 void sgdm_chunks(float* w, const float* g, float* m, void* shadow, const uint8_t* chunk_decay, int64_t first_chunk,
-                 int64_t n_chunks, OptArgs a, hipStream_t st);
+                 int64_t n_chunks, OptArgs a, float* chunk_sq, hipStream_t st);
 
 }  // namespace pt

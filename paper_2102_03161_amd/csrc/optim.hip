@@ -23,15 +23,21 @@ __device__ __forceinline__ void st_nt4(float* p, const float4& v) {
   __builtin_nontemporal_store(t, reinterpret_cast<f32x4_nt*>(p));
 }
 
+// sum of the squares of a chunk's 1024 gradient values, 4 per thread, in a fixed order (the norm pass and the
+// updates that take the norms along share it, so both give the same bits)
+__device__ __forceinline__ void chunk_sumsq(const float4& v, float* red, float* __restrict__ chunk_sq, int64_t c) {
+  float s = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+  s = block_sum<4>(s, red);
+  if (threadIdx.x == 0) chunk_sq[c] = s;
+}
+
 __global__ __launch_bounds__(256) void sumsq_kernel(const float* __restrict__ g, float* __restrict__ chunk_sq,
                                                     int64_t first_chunk) {
   __shared__ float red[4];
   const int64_t c = first_chunk + blockIdx.x;
   // cached loads: what stays of the gradient in the last-level cache is read again by the update
   const float4 v = reinterpret_cast<const float4*>(g + c * kChunk)[threadIdx.x];
-  float s = (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-  s = block_sum<4>(s, red);
-  if (threadIdx.x == 0) chunk_sq[c] = s;
+  chunk_sumsq(v, red, chunk_sq, c);
 }
 void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t n_chunks, hipStream_t st) {
   if (n_chunks <= 0) return;
@@ -80,10 +86,14 @@ __device__ __forceinline__ void store_shadow4(bf16* p, float a, float b, float c
   *reinterpret_cast<uint2*>(p) = t.u;
 }
 
+// SQ: also leave the chunk's sum of squared gradients in chunk_sq (the norm pass folded into the update, which
+// reads the gradient anyway)
+template <bool SQ>
 __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ w, const float* __restrict__ g,
                                                     float* __restrict__ m, float* __restrict__ v,
                                                     bf16* __restrict__ shadow, const uint8_t* __restrict__ chunk_decay,
-                                                    int64_t first_chunk, OptArgs a) {
+                                                    int64_t first_chunk, OptArgs a, float* __restrict__ chunk_sq) {
+  __shared__ float red[4];
   // last chunk first: the norm pass went through the gradient front to back, so its tail is what the
   // last-level cache still holds
   const int64_t c = first_chunk + (gridDim.x - 1 - blockIdx.x);
@@ -93,6 +103,7 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ w, const
   const float4 gv = ld_nt4(g + i);
   float4 mv = ld_nt4(m + i);
   float4 vv = ld_nt4(v + i);
+  if (SQ) chunk_sumsq(gv, red, chunk_sq, c);
   float* wp = &wv.x; const float* gp = &gv.x; float* mp = &mv.x; float* vp = &vv.x;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -109,16 +120,22 @@ __global__ __launch_bounds__(256) void adamw_kernel(float* __restrict__ w, const
   if (shadow) store_shadow4(shadow + i, wv.x, wv.y, wv.z, wv.w);
 }
 void adamw_chunks(float* w, const float* g, float* m, float* v, void* shadow, const uint8_t* chunk_decay,
-                  int64_t first_chunk, int64_t n_chunks, OptArgs a, hipStream_t st) {
+                  int64_t first_chunk, int64_t n_chunks, OptArgs a, float* chunk_sq, hipStream_t st) {
   if (n_chunks <= 0) return;
-  hipLaunchKernelGGL(adamw_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, v, (bf16*)shadow, chunk_decay,
-                     first_chunk, a);
+  if (chunk_sq)
+    hipLaunchKernelGGL(adamw_kernel<true>, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, v, (bf16*)shadow,
+                       chunk_decay, first_chunk, a, chunk_sq);
+  else
+    hipLaunchKernelGGL(adamw_kernel<false>, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, v, (bf16*)shadow,
+                       chunk_decay, first_chunk, a, chunk_sq);
 }
 
+template <bool SQ>
 __global__ __launch_bounds__(256) void sgdm_kernel(float* __restrict__ w, const float* __restrict__ g,
                                                    float* __restrict__ m, bf16* __restrict__ shadow,
                                                    const uint8_t* __restrict__ chunk_decay, int64_t first_chunk,
-                                                   OptArgs a) {
+                                                   OptArgs a, float* __restrict__ chunk_sq) {
+  __shared__ float red[4];
   // last chunk first: the norm pass went through the gradient front to back, so its tail is what the
   // last-level cache still holds
   const int64_t c = first_chunk + (gridDim.x - 1 - blockIdx.x);
@@ -127,6 +144,7 @@ __global__ __launch_bounds__(256) void sgdm_kernel(float* __restrict__ w, const 
   float4 wv = ld_nt4(w + i);
   const float4 gv = ld_nt4(g + i);
   float4 mv = ld_nt4(m + i);
+  if (SQ) chunk_sumsq(gv, red, chunk_sq, c);
   float* wp = &wv.x; const float* gp = &gv.x; float* mp = &mv.x;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -140,10 +158,14 @@ __global__ __launch_bounds__(256) void sgdm_kernel(float* __restrict__ w, const 
   if (shadow) store_shadow4(shadow + i, wv.x, wv.y, wv.z, wv.w);
 }
 void sgdm_chunks(float* w, const float* g, float* m, void* shadow, const uint8_t* chunk_decay, int64_t first_chunk,
-                 int64_t n_chunks, OptArgs a, hipStream_t st) {
+                 int64_t n_chunks, OptArgs a, float* chunk_sq, hipStream_t st) {
   if (n_chunks <= 0) return;
-  hipLaunchKernelGGL(sgdm_kernel, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, (bf16*)shadow, chunk_decay,
-                     first_chunk, a);
+  if (chunk_sq)
+    hipLaunchKernelGGL(sgdm_kernel<true>, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, (bf16*)shadow, chunk_decay,
+                       first_chunk, a, chunk_sq);
+  else
+    hipLaunchKernelGGL(sgdm_kernel<false>, dim3((unsigned)n_chunks), dim3(256), 0, st, w, g, m, (bf16*)shadow, chunk_decay,
+                       first_chunk, a, chunk_sq);
 }
 
 // acc = (first ? 0 : acc) + weight * g over whole chunks; lane 0 of workgroup 0 folds the loss the same way

@@ -251,6 +251,7 @@ struct pt_ctx {
   float* h_norms = nullptr;   // pinned host memory: L + 2 norms, written by the norm kernel itself, and the loss
   hipEvent_t norms_ev = nullptr;   // recorded behind the norm kernels by pt_layer_grad_norms_begin
   bool norms_pending = false;      // begun and not yet fetched
+  bool norms_deferred = false;     // pending, and the norm kernels are not enqueued yet: the next update takes them along
   hipEvent_t idx_ev[2] = {nullptr, nullptr};
   bool idx_ev_used[2] = {false, false};
   int idx_turn = 0;
@@ -345,6 +346,7 @@ pt_status fail(const pt_ctx* c, pt_status s, const std::string& m) {
   if (c) c->err = m;
   return s;
 }
+pt_status flush_deferred_norms(pt_ctx* c);   // norms begun but not enqueued yet: enqueue them now
 #define HIP_TRY(ctx, expr)                                                                  \
   do {                                                                                      \
     hipError_t e_ = (expr);                                                                 \
@@ -797,6 +799,7 @@ pt_status pt_set_freeze_boundary(pt_ctx* c, int32_t k) {
   if (k < c->k) return fail(c, PT_EINVAL, "the boundary never moves down");
   if (k == c->k) return PT_OK;
   if (c->acc_samples) return fail(c, PT_ESTATE, "the boundary cannot move while gradients are being accumulated");
+  { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
   // newly frozen: front end (if the old boundary was 0) and blocks k_old..k-1
   const auto& gf = c->plan.group_first_chunk;
   const int64_t lo = (c->k == 0 ? gf[0] : gf[c->k + 1]) * kChunk, hi = gf[k + 1] * kChunk;
@@ -1091,6 +1094,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   if (!c || !d_hk || !d_labels) return PT_EINVAL;
   if (c->phase < 1) return fail(c, PT_ESTATE, "pt_frozen_forward has not run for this step");
   if (reinterpret_cast<uintptr_t>(d_hk) % 16) return fail(c, PT_EINVAL, "d_hk must be 16-byte aligned");
+  { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
   const pt_config& g = c->cfg;
   const Plan& p = c->plan;
   const int L = g.L, D = g.D, S = g.S, k = c->k, nb = c->nb, dt = c->dt;
@@ -1197,26 +1201,55 @@ pt_status pt_last_loss(pt_ctx* c, float* loss_out) {
   return PT_OK;
 }
 
+namespace {
+// the norm kernels over the active chunks; with_sumsq = false when the chunk sums are already there
+pt_status enqueue_norms(pt_ctx* c, bool with_sumsq) {
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  if (with_sumsq) { ProfScope ps_(c, PT_PROF_NORMS, 4.0 * (total - first) * kChunk); sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st); }
+  // the last kernel writes the L + 2 norms straight into pinned host memory: the only thing between the GPU
+  // finishing and the caller going on is the wait itself (a copy command into pageable memory cost 15-25 us)
+  if (with_sumsq) {
+    finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
+                   c->h_norms, c->st);
+  } else {   // the pass over the gradient was the update's: only this kernel is booked under the norms
+    ProfScope ps_(c, PT_PROF_NORMS, 0.0);
+    finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
+                   c->h_norms, c->st);
+  }
+  HIP_TRY(c, hipEventRecord(c->norms_ev, c->st));
+  return PT_OK;
+}
+
+}  // namespace
+
+// The begin half only notes the request.  If the update comes next, it reads the gradient anyway and leaves
+// the per-chunk sums of squares as a by-product (one pass over the gradient instead of two); otherwise the
+// end half, or whatever else would change the gradient or the boundary first, enqueues the norm pass itself.
 pt_status pt_layer_grad_norms_begin(pt_ctx* c) {
   if (!c) return PT_EINVAL;
   if (c->phase != 2) return fail(c, PT_ESTATE, "gradient norms need a completed pt_active_fwd_bwd");
   if (c->norms_pending) return fail(c, PT_ESTATE, "the norms of an earlier pt_layer_grad_norms_begin have not been fetched");
-  const auto& gf = c->plan.group_first_chunk;
-  const int G = c->cfg.L + 2, k = c->k;
-  const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
-  { ProfScope ps_(c, PT_PROF_NORMS, 4.0 * (total - first) * kChunk); sumsq_chunks(c->grads, c->wf(c->plan.CHUNKSQ), first, total - first, c->st); }
-  // the last kernel writes the L + 2 norms straight into pinned host memory: the only thing between the GPU
-  // finishing and the caller going on is the wait itself (a copy command into pageable memory cost 15-25 us)
-  finalize_norms(c->wf(c->plan.CHUNKSQ), reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0,
-                 c->h_norms, c->st);
-  HIP_TRY(c, hipEventRecord(c->norms_ev, c->st));
   c->norms_pending = true;
+  c->norms_deferred = true;
   return PT_OK;
 }
+
+namespace {
+// called by every entry point that is about to change the gradients or the boundary while norms are deferred
+pt_status flush_deferred_norms(pt_ctx* c) {
+  if (!c->norms_pending || !c->norms_deferred) return PT_OK;
+  c->norms_deferred = false;
+  return enqueue_norms(c, true);
+}
+}  // namespace
 
 pt_status pt_layer_grad_norms_end(pt_ctx* c, float* norms_out) {
   if (!c || !norms_out) return PT_EINVAL;
   if (!c->norms_pending) return fail(c, PT_ESTATE, "pt_layer_grad_norms_begin has not run");
+  const pt_status s = flush_deferred_norms(c);
+  if (s != PT_OK) return s;
   HIP_TRY(c, hipEventSynchronize(c->norms_ev));
   std::memcpy(norms_out, c->h_norms, (size_t)(c->cfg.L + 2) * 4);
   c->norms_pending = false;
@@ -1242,11 +1275,19 @@ pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {
   a.bias_c1 = (float)(1.0 - std::pow((double)hp->beta1, (double)t));
   a.bias_c2 = (float)(1.0 - std::pow((double)hp->beta2, (double)t));
   const uint8_t* decay = reinterpret_cast<const uint8_t*>(c->w(c->plan.CHUNKDECAY));
+  // norms asked for and not yet enqueued: this pass over the gradient also leaves the per-chunk sums of squares
+  const bool take_norms = c->norms_pending && c->norms_deferred;
+  float* chunk_sq = take_norms ? c->wf(c->plan.CHUNKSQ) : nullptr;
   if (c->cfg.optimizer == PT_ADAMW)
-    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 30.0 : 28.0) * (total - first) * kChunk); adamw_chunks(c->master, c->grads, c->mom1, c->mom2, c->shadow, decay, first, total - first, a, c->st); }
+    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 30.0 : 28.0) * (total - first) * kChunk); adamw_chunks(c->master, c->grads, c->mom1, c->mom2, c->shadow, decay, first, total - first, a, chunk_sq, c->st); }
   else
-    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 22.0 : 20.0) * (total - first) * kChunk); sgdm_chunks(c->master, c->grads, c->mom1, c->shadow, decay, first, total - first, a, c->st); }
+    { ProfScope ps_(c, PT_PROF_OPT, (c->shadow ? 22.0 : 20.0) * (total - first) * kChunk); sgdm_chunks(c->master, c->grads, c->mom1, c->shadow, decay, first, total - first, a, chunk_sq, c->st); }
   HIP_TRY(c, hipGetLastError());
+  if (take_norms) {
+    c->norms_deferred = false;
+    const pt_status ns = enqueue_norms(c, false);
+    if (ns != PT_OK) return ns;
+  }
   c->step = t;
   c->phase = 0;
   if (c->prof_on) prof_collect(c);
@@ -1274,6 +1315,7 @@ pt_status pt_finish_accumulation(pt_ctx* c, float* mean_loss_out) {
   if (!c) return PT_EINVAL;
   if (!c->gacc || c->acc_samples == 0) return fail(c, PT_ESTATE, "no accumulation in progress");
   if (c->phase != 0) return fail(c, PT_ESTATE, "a micro-batch is in flight: accumulate it first");
+  { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
   const auto& gf = c->plan.group_first_chunk;
   const int G = c->cfg.L + 2, k = c->k;
   const int64_t lo = k == 0 ? 0 : gf[k + 1], total = gf[G];
@@ -1333,6 +1375,7 @@ pt_status pt_write_tensor(pt_ctx* c, int32_t id, int32_t kind, const float* src)
   float* base = kind_base(c, kind);
   if (!base) return fail(c, PT_EINVAL, "tensor kind not writable in this configuration");
   const TensorDesc& t = c->plan.tensors[id];
+  if (kind == PT_KIND_GRAD) { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }
   HIP_TRY(c, hipMemcpyAsync(base + t.offset, src, (size_t)t.numel * 4, hipMemcpyHostToDevice, c->st));
   if (kind == PT_KIND_PARAM && c->shadow) f32_to_bf16(c->master + t.offset, c->shadow + t.offset * 2, (size_t)t.numel, c->st);
   HIP_TRY(c, hipStreamSynchronize(c->st));

@@ -266,12 +266,13 @@ def test_state_machine_and_argument_errors(torch_mod):
     ctx.close()
 
 
-def test_gradient_norms_in_two_halves(torch_mod):
-    """pt_layer_grad_norms_begin / _end with the optimizer step enqueued in between return, bit for bit, what
-    pt_layer_grad_norms returns for the same gradients, and the parameters end up the same; misuse of the
-    pair is a state error."""
+@pytest.mark.parametrize("wname,optimizer", [("bert_tiny", "adamw"), ("vit_tiny", "sgdm")])
+def test_gradient_norms_in_two_halves(torch_mod, wname, optimizer):
+    """pt_layer_grad_norms_begin / _end with the optimizer step in between (whose pass over the gradient then
+    also produces the sums of squares) return, bit for bit, what pt_layer_grad_norms returns for the same
+    gradients, and the parameters end up the same; misuse of the pair is a state error."""
     torch = torch_mod
-    w = synth.workload("bert_tiny")
+    w = dict(synth.workload(wname), optimizer=optimizer)
     hp = dict(H.HP)
     results = []
     for split in (False, True):
@@ -307,6 +308,37 @@ def test_gradient_norms_in_two_halves(torch_mod):
     assert np.array_equal(n0, n1)
     for name in p0:
         assert np.array_equal(p0[name], p1[name]), name
+
+
+def test_pending_gradient_norms_are_of_the_gradients_at_begin(torch_mod):
+    """Norms that were begun and not yet fetched keep describing the gradients and the boundary of that
+    moment when the boundary moves, or the next backward pass runs, before they are fetched."""
+    torch = torch_mod
+    w = synth.workload("bert_tiny")
+    ctx = binding.Context(binding.make_config(w))
+    vals = H.init_values(w, ctx, 5)
+    H.load_params(ctx, vals)
+    xa, ya = H.batch_for(w, 5, w["B"])
+    xb, yb = H.batch_for(w, 6, w["B"])
+
+    def backward(x, y):
+        hk = ctx.frozen_forward(H.to_dev(torch, x))
+        ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+
+    backward(xa, ya)
+    want = ctx.layer_grad_norms()
+    assert np.all(want > 0)
+    ctx.layer_grad_norms_begin()
+    ctx.set_freeze_boundary(1)            # clears the gradients of the front end and block 0
+    assert np.array_equal(ctx.layer_grad_norms_end(), want)
+    backward(xa, ya)                      # the same batch above the new boundary
+    after = ctx.layer_grad_norms()
+    assert after[0] == 0.0 and after[1] == 0.0 and np.array_equal(after[2:], want[2:])
+    ctx.layer_grad_norms_begin()
+    backward(xb, yb)                      # overwrites the gradients of the active layers
+    assert np.array_equal(ctx.layer_grad_norms_end(), after)
+    assert not np.array_equal(ctx.layer_grad_norms(), after)
+    ctx.close()
 
 
 def test_runs_are_bit_reproducible(torch_mod):
