@@ -557,6 +557,22 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K);
     gemm_wgrad_batch(dt, &m, 1, st);
   };
+  // The three weight gradients over the first tokens' rows are tiny (ns tokens deep): they are noted here and
+  // go out as one grouped launch once the last of their operands exists (each has row buffers of its own).
+  Gemm rows_wg[3];
+  int n_rows_wg = 0;
+  double rows_wg_flops = 0.0;
+  auto wgrad_rows = [&](const void* X, int Kin, const void* dY, int Nout, int wid, int bid) {
+    Gemm& m = rows_wg[n_rows_wg++];
+    m.A = X; m.lda = Kin; m.ta = true; m.B = dY; m.ldb = Nout; m.C = c->gp(wid); m.ldc = Nout;
+    m.M = Kin; m.N = Nout; m.K = ns; m.c_f32 = true;
+    m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
+    rows_wg_flops += 2.0 * m.M * m.N * m.K;
+  };
+  auto wgrad_rows_launch = [&]() {
+    ProfScope ps_(c, gemm_cat(dt, rows_wg[0]), rows_wg_flops);
+    gemm_wgrad_batch(dt, rows_wg, n_rows_wg, st);
+  };
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32, int rows) {
     Gemm m;
     m.A = dY; m.lda = Nout; m.B = c->cp(wid); m.ldb = Nout; m.tb = true; m.C = dX; m.ldc = Kin;
@@ -574,13 +590,14 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
   if (g.arch == PT_VIT_PRELN) {
     // rG, rHP (GELU out and GELU'), rXa (LN2 out), rXb (Y), rCTX and the LN2 statistics come from the forward,
     // rDO / rS0 (the first tokens' rows of dL/dx_L) from the head's backward: nothing to gather
-    wgrad(rG, F, rDO, D, c->blk(l, W2), -1, ns);
+    wgrad_rows(rG, F, rDO, D, c->blk(l, W2), -1);
     dgrad(rDO, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
-    wgrad(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);
+    wgrad_rows(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(rDF, F, c->blk(l, W1), rOC, D, EPI_STORE, nullptr, false, ns);                 // dL/dLN2out
     { prof_ln_bwd(c, dt, false, false, rOC, D, rXb, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), rS0, D, rS1, rOD, D,
                   c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOD = dL/dY
-    wgrad(rCTX, D, rOD, D, c->blk(l, WO), -1, ns);
+    wgrad_rows(rCTX, D, rOD, D, c->blk(l, WO), -1);
+    wgrad_rows_launch();
     dgrad(rOD, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * (D / g.H)); attention_bwd_first_query(dt, c->w(s.QKV), rCTX, rDCTX, c->wf(s.LSE), dQKV, ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV), Tn);
@@ -598,13 +615,14 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     strided_rows_copy(in, 1, ns, st);
     { prof_ln_bwd(c, dt, true, true, rS0, D, rXa, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), nullptr, 0, rS1, rOD, D,
                   c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, ns, D, st); }  // rS1 / rOD = dL/d(Y+MLP)
-    wgrad(rG, F, rOD, D, c->blk(l, W2), -1, ns);
+    wgrad_rows(rG, F, rOD, D, c->blk(l, W2), -1);
     dgrad(rOD, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
-    wgrad(rDO, D, rDF, F, c->blk(l, W1), c->blk(l, B1), ns);                              // rDO holds the rows of Y here
+    wgrad_rows(rDO, D, rDF, F, c->blk(l, W1), c->blk(l, B1));                              // rDO holds the rows of Y here
     dgrad(rDF, F, c->blk(l, W1), rS2, D, EPI_RES, rS1, true, ns);                          // rS2 = dL/dY
     { prof_ln_bwd(c, dt, true, true, rS2, D, rXb, D, rmu1, rrs1, c->cp(c->blk(l, LN1_G)), nullptr, 0, rS1, rOC, D,
                   c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOC = dL/d(x+Attn)
-    wgrad(rCTX, D, rOC, D, c->blk(l, WO), -1, ns);
+    wgrad_rows(rCTX, D, rOC, D, c->blk(l, WO), -1);
+    wgrad_rows_launch();
     dgrad(rOC, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
     const RowCopy out[] = {back(rS1, D, 4, dout.s, SD)};
     strided_rows_copy(out, 1, ns, st);
