@@ -31,9 +31,9 @@ PEAK_HBM_GBS = 8000.0
 # --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this script, scaled by what the same counters
 # read for the --calibrate-copy kernel; the figures and commands are in profiles/.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0, "gemm_nn"): 115101626 + 57009780,    # fetched + written, forward products
-    ("vit_b16", 0, "gemm_nt"): 150223222 + 30901561,    # input-gradient products
-    ("vit_b16", 0, "gemm_tn"): 372836824 + 62767330,    # weight gradients (one grouped launch per block) incl. their split-K reductions
+    ("vit_b16", 0, "gemm_nn"): 115097149 + 57009860,    # fetched + written, forward products
+    ("vit_b16", 0, "gemm_nt"): 150142135 + 30901561,    # input-gradient products
+    ("vit_b16", 0, "gemm_tn"): 422498938 + 71133510,    # weight gradients (one grouped launch per block) incl. their split-K reductions
 }
 
 
