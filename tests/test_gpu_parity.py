@@ -310,6 +310,29 @@ def test_gradient_norms_in_two_halves(torch_mod, wname, optimizer):
         assert np.array_equal(p0[name], p1[name]), name
 
 
+def test_gradient_norms_from_the_update_pass_in_bf16(torch_mod):
+    """bf16 mode (the update also writes the bf16 shadow), mid-size model, boundary 1: the norms that the
+    update's own pass over the gradient produces equal the separate norm pass bit for bit, and match the
+    oracle's norms of the same step."""
+    torch = torch_mod
+    w = dict(MID_VIT, dtype="bf16")
+    ctx = binding.Context(binding.make_config(w))
+    vals = H.init_values(w, ctx, 8)
+    H.load_params(ctx, vals)
+    x, y = H.batch_for(w, 8, w["B"])
+    ctx.set_freeze_boundary(1)
+    hk = ctx.frozen_forward(H.to_dev(torch, x))
+    ctx.active_fwd_bwd(hk, H.to_dev(torch, y))
+    separate = ctx.layer_grad_norms()
+    ctx.layer_grad_norms_begin()
+    ctx.optimizer_step(**H.HP)
+    folded = ctx.layer_grad_norms_end()
+    assert np.array_equal(separate, folded)
+    o = H.oracle_step(w, vals, x, y, 1)
+    assert rel_err(folded, o["norms"]) < TOL["bf16"]
+    ctx.close()
+
+
 def test_pending_gradient_norms_are_of_the_gradients_at_begin(torch_mod):
     """Norms that were begun and not yet fetched keep describing the gradients and the boundary of that
     moment when the boundary moves, or the next backward pass runs, before they are fetched."""
