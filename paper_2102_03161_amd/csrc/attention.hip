@@ -437,34 +437,49 @@ __global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __re
   }
   __syncthreads();
   const float l0 = lse[((int64_t)b * H + h) * S], dl = delta_s;
+  float dqa_out[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (VEC) {
     // dh / 8 lanes share a key: each moves one 16-byte piece of the key's rows, so a wave reads and writes
     // whole rows; the two dot products are finished with lane exchanges inside the group
-    const int lpr = dh >> 3, j = tid % lpr, d0 = 8 * j;
-    for (int t0 = 0; t0 < S; t0 += 256 / lpr) {
-      const int t = t0 + tid / lpr;
-      const bool ok = t < S;
-      const T* kr = base + (int64_t)(ok ? t : 0) * 3 * D + D;
-      float kv[8], vv[8];
-      load8(kr + d0, kv);
-      load8(kr + D + d0, vv);
-      float sc = 0.f, dp = 0.f;
+    const int lpr = dh >> 3, j = tid % lpr, d0 = 8 * j, kpp = 256 / lpr;   // kpp keys per pass
+    float dqa[8];   // this thread's share of dQ of the first token: sum over its keys of dS k
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { sc = fmaf(qs[d0 + i], kv[i], sc); dp = fmaf(dos[d0 + i], vv[i], dp); }
-      for (int o = 1; o < lpr; o <<= 1) { sc += __shfl_xor(sc, o, 64); dp += __shfl_xor(dp, o, 64); }
-      if (!ok) continue;
-      const float pt = __expf(sc * scale - l0);
-      const float ds = pt * (dp - dl);
-      if (j == 0) dss[t] = ds;
-      T* dq = obase + (int64_t)t * 3 * D;
-      const float dsk = ds * scale;
-      float z[8], a[8], c2[8];
+    for (int i = 0; i < 8; ++i) dqa[i] = 0.f;
+    for (int t0 = 0; t0 < S; t0 += 4 * kpp) {   // four passes' rows in flight together
+      float kv[4][8], vv[4][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { z[i] = 0.f; a[i] = dsk * qs[d0 + i]; c2[i] = pt * dos[d0 + i]; }
-      if (t > 0) store8(dq + d0, z);
-      store8(dq + D + d0, a);
-      store8(dq + 2 * D + d0, c2);
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + u * kpp + tid / lpr;
+        const T* kr = base + (int64_t)(t < S ? t : 0) * 3 * D + D;
+        load8(kr + d0, kv[u]);
+        load8(kr + D + d0, vv[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + u * kpp + tid / lpr;
+        float sc = 0.f, dp = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { sc = fmaf(qs[d0 + i], kv[u][i], sc); dp = fmaf(dos[d0 + i], vv[u][i], dp); }
+        for (int o = 1; o < lpr; o <<= 1) { sc += __shfl_xor(sc, o, 64); dp += __shfl_xor(dp, o, 64); }
+        if (t < S) {
+          const float pt = __expf(sc * scale - l0);
+          const float ds = pt * (dp - dl);
+          T* dq = obase + (int64_t)t * 3 * D;
+          const float dsk = ds * scale;
+          float z[8], a[8], c2[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            z[i] = 0.f; a[i] = dsk * qs[d0 + i]; c2[i] = pt * dos[d0 + i];
+            dqa[i] = fmaf(ds, kv[u][i], dqa[i]);
+          }
+          if (t > 0) store8(dq + d0, z);
+          store8(dq + D + d0, a);
+          store8(dq + 2 * D + d0, c2);
+        }
+      }
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dqa_out[i] = dqa[i];
   } else {
     for (int t = tid; t < S; t += 256) {
       const T* kr = base + (int64_t)t * 3 * D + D;
@@ -484,6 +499,20 @@ __global__ __launch_bounds__(256) void attn_bwd_first_query_kernel(const T* __re
         dv[d] = from_f32<T>(pt * dos[d]);
       }
     }
+  }
+  if (VEC) {
+    // dQ of the first token: the threads' partial sums, combined in a fixed order (thread = pass slot * lpr + j)
+    __shared__ float dqp[256 * 8];
+    const int lpr = dh >> 3, kpp = 256 / lpr;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dqp[tid * 8 + i] = dqa_out[i];
+    __syncthreads();
+    for (int d = tid; d < dh; d += 256) {
+      float acc = 0.f;
+      for (int g = 0; g < kpp; ++g) acc += dqp[(g * lpr + (d >> 3)) * 8 + (d & 7)];
+      obase[d] = from_f32<T>(acc * scale);
+    }
+    return;
   }
   __syncthreads();
   for (int d = tid; d < dh; d += 256) {
