@@ -525,6 +525,27 @@ def test_degenerate_and_odd_shapes(torch_mod, name, dtype):
         run_case(torch_mod, w, k, w["B"], seed=13, tol=TOL[dtype])
 
 
+FIRST_ROWS_64 = {
+    # 64 samples: the top block's three row-wise weight gradients are 64 tokens deep and go out as one grouped
+    # launch; head sizes 8, 32, 64, 128 give 1, 4, 8, 16 lanes per key in the first-query attention backward
+    "vit_dh8": dict(arch="vit", L=2, D=32, H=4, F=64, S=17, n_out=5, img=16, patch=4, chans=3, vocab=0, max_pos=0,
+                    ln_eps=1e-6, B=64, optimizer="adamw"),
+    "vit_dh32": dict(arch="vit", L=2, D=128, H=4, F=256, S=17, n_out=10, img=16, patch=4, chans=3, vocab=0, max_pos=0,
+                     ln_eps=1e-6, B=64, optimizer="adamw"),
+    "bert_cls_dh64": dict(arch="bert", L=2, D=128, H=2, F=320, S=24, n_out=3, img=0, patch=0, chans=0, vocab=50,
+                          max_pos=24, ln_eps=1e-12, B=64, optimizer="adamw", head="cls"),
+    "vit_dh128": dict(arch="vit", L=1, D=256, H=2, F=256, S=10, n_out=4, img=6, patch=2, chans=3, vocab=0, max_pos=0,
+                      ln_eps=1e-6, B=64, optimizer="sgdm"),
+}
+
+
+@pytest.mark.parametrize("name", list(FIRST_ROWS_64))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_first_token_rows_with_64_samples(torch_mod, name, dtype):
+    w = dict(FIRST_ROWS_64[name], dtype=dtype)
+    run_case(torch_mod, w, 0, w["B"], seed=23, tol=TOL[dtype])
+
+
 def test_many_tokens_with_ragged_widths(torch_mod):
     """8320 tokens (a multiple of 64) with widths that are no multiple of the 256-column tiles: forward and
     input-gradient products go through the two-group matrix-core kernels (192- and 256-row tiles, clamped
