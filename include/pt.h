@@ -22,8 +22,12 @@
  *  - All device work is enqueued on the stream given to pt_create.  Calls that
  *    return host scalars (loss, norms, reads) synchronise that stream.
  *  - Errors: every call returns a pt_status; nothing throws or aborts across
- *    the ABI.  Arguments are validated before anything is enqueued, so on a
- *    non-OK return the context is unchanged.  pt_last_error gives a message.
+ *    the ABI.  Arguments and resources (arena sizes, LDS needs of the attention
+ *    kernels, window slots of the host tier) are validated before anything is
+ *    enqueued, so on PT_EINVAL / PT_ESTATE / PT_ENOMEM / PT_ECACHE_MISS the
+ *    context is unchanged.  PT_EDEVICE reports a failed HIP call or kernel:
+ *    work may have been enqueued by then, the step's results are undefined and
+ *    the context should be destroyed.  pt_last_error gives a message.
  *  - Call order per step: pt_frozen_forward -> pt_active_fwd_bwd ->
  *    [pt_layer_grad_norms] -> pt_optimizer_step.  Out of order: PT_ESTATE.
  *    (pt_layer_grad_norms_begin takes the place of pt_layer_grad_norms in this
@@ -44,6 +48,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+
+/* The shared library is built with hidden visibility: these entry points are all it exports. */
+#define PT_API __attribute__((visibility("default")))
 
 typedef struct pt_ctx pt_ctx;
 
@@ -68,7 +75,8 @@ typedef struct {
   int32_t arch;        /* PT_VIT_PRELN | PT_BERT_POSTLN                              */
   int32_t dtype;       /* PT_F32 | PT_BF16                                           */
   int32_t L, D, H, F;  /* blocks, hidden, heads, MLP width; D % H == 0, D/H % 8 == 0 and <= 128, D <= 2048, F % 4 == 0 */
-  int32_t S;           /* sequence length (ViT: (img/patch)^2 + 1)                   */
+  int32_t S;           /* sequence length (ViT: (img/patch)^2 + 1).  Without matrix-core attention (PT_F32, or
+                          D/H != 64) a strip of 32 score rows lives in LDS: S <= about 1100 at D/H = 64      */
   int32_t B;           /* largest batch any call will pass                           */
   int32_t n_out;       /* classes (ViT, BERT with PT_HEAD_CLS) or 2 (BERT span QA)   */
   int32_t img, patch, chans;  /* ViT front end                                       */
@@ -92,17 +100,17 @@ typedef struct {
  * moments, + one gradient accumulator when grad_accum is set), work (activations, saved tensors, scratch), cache (cache_slots rows
  * of S*D activations).  Each must be 256-byte aligned.  PT_EINVAL on a bad
  * configuration. */
-pt_status pt_query_arena_bytes(const pt_config* cfg /*HOST*/, size_t* params, size_t* state,
+PT_API pt_status pt_query_arena_bytes(const pt_config* cfg /*HOST*/, size_t* params, size_t* state,
                                size_t* work, size_t* cache /*HOST out*/);
 
 /* Creates a context over the arenas (DEVICE pointers, sizes as queried).  The
  * params and state arenas are cleared (enqueued); parameters are then set with
  * pt_write_tensor.  hip_stream is a hipStream_t (NULL = default stream).  The
  * boundary starts at k = 0 and the step counter at 0 (Eq. 1: L_frozen^(0)=0). */
-pt_status pt_create(const pt_config* cfg /*HOST*/, void* d_params, void* d_state, void* d_work,
+PT_API pt_status pt_create(const pt_config* cfg /*HOST*/, void* d_params, void* d_state, void* d_work,
                     void* d_cache /*DEVICE, may be NULL iff cache_slots==0*/, void* hip_stream,
                     pt_ctx** out /*HOST out*/);
-pt_status pt_destroy(pt_ctx* ctx);
+PT_API pt_status pt_destroy(pt_ctx* ctx);
 
 /* Moves the freeze boundary: blocks 0..k-1 (and, for k >= 1, the front end)
  * become F_frozen.  0 <= k <= L and k >= current boundary, otherwise PT_EINVAL
@@ -111,11 +119,17 @@ pt_status pt_destroy(pt_ctx* ctx);
  * optimizer moments of newly frozen tensors are cleared and never used again
  * (Sec. 3.2.1); cache rows written at a smaller k become stale and are advanced
  * on their next use (Sec. 3.4). */
-pt_status pt_set_freeze_boundary(pt_ctx* ctx, int32_t k);
-pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
+PT_API pt_status pt_set_freeze_boundary(pt_ctx* ctx, int32_t k);
+PT_API pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
 
 /* F_frozen for one batch of nb <= B samples.
  *  d_input    DEVICE. ViT: fp32 images [nb,chans,img,img]; BERT: int32 ids [nb,S].
+ *             Read by kernels enqueued in this call only (the ids that the
+ *             token-table gradient needs at k == 0 are copied into the work
+ *             arena), so the buffer may be released or reused, in stream
+ *             order, once the call returns.  Token ids are not read on the
+ *             host: an id outside [0,vocab) is clamped to the nearest valid
+ *             row of the table instead of being reported.
  *  sample_ids HOST, nb unique ids in [0,cache_slots+host_slots), or NULL to bypass the
  *             cache.  Ignored when k == 0 (nothing is frozen, the front end is
  *             being trained).  Per sample: a row written at the current k is a
@@ -125,7 +139,7 @@ pt_status pt_get_freeze_boundary(const pt_ctx* ctx, int32_t* k /*HOST out*/);
  *  d_hk_out   HOST out: DEVICE pointer to the boundary activation [nb,S,D]
  *             inside the work arena, valid until the next pt_frozen_forward.
  * Results per sample do not depend on the sample's position in the batch. */
-pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const int64_t* sample_ids,
+PT_API pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const int64_t* sample_ids,
                             void** d_hk_out);
 
 /* The timing profiler of the cache (Sec. 3.4: caching is switched on only once it is faster than
@@ -135,7 +149,7 @@ pt_status pt_frozen_forward(pt_ctx* ctx, const void* d_input, int32_t nb, const 
  * context's stream, and returns the mean milliseconds per call of each (HOST out).  The caller passes
  * sample_ids = NULL to later calls while ms_cached >= ms_recompute.  Needs k >= 1 and a cache;
  * synchronises; leaves the context as after a pt_frozen_forward of this batch. */
-pt_status pt_time_frozen_forward(pt_ctx* ctx, const void* d_input /*DEVICE*/, int32_t nb,
+PT_API pt_status pt_time_frozen_forward(pt_ctx* ctx, const void* d_input /*DEVICE*/, int32_t nb,
                                  const int64_t* sample_ids /*HOST*/, int32_t reps, float* ms_recompute,
                                  float* ms_cached);
 
@@ -148,14 +162,14 @@ pt_status pt_time_frozen_forward(pt_ctx* ctx, const void* d_input /*DEVICE*/, in
  *  loss_out  HOST out, mean loss over the batch; the call synchronises.  May be
  *            NULL: then nothing synchronises and pt_last_loss fetches it later.
  * Gradients of all active tensors are overwritten (not accumulated). */
-pt_status pt_active_fwd_bwd(pt_ctx* ctx, const void* d_hk, const int32_t* d_labels, float* loss_out);
-pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
+PT_API pt_status pt_active_fwd_bwd(pt_ctx* ctx, const void* d_hk, const int32_t* d_labels, float* loss_out);
+PT_API pt_status pt_last_loss(pt_ctx* ctx, float* loss_out /*HOST out*/);
 
 /* L2 norm of the gradient of every layer taken as one vector (Eq. 1's ||g_l||,
  * on the raw gradient of the mean loss of the last pt_active_fwd_bwd).
  * norms_out HOST, L+2 floats: [front end, block 0 .. block L-1, head]; frozen
  * layers (and the front end when k >= 1) read exactly 0.  Synchronises. */
-pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
+PT_API pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
 
 /* The same in two halves, for callers that do not want the stream to run dry
  * while the host waits, nor the gradient to be read twice:
@@ -170,8 +184,8 @@ pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
  * pt_layer_grad_norms would have returned at the point of _begin.  One set of
  * norms can be pending at a time: a second _begin (or pt_layer_grad_norms)
  * before _end, or _end without _begin, is PT_ESTATE. */
-pt_status pt_layer_grad_norms_begin(pt_ctx* ctx);
-pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
+PT_API pt_status pt_layer_grad_norms_begin(pt_ctx* ctx);
+PT_API pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
 
 /* Micro-batch gradient accumulation (Sec. 2.1 pipeline parallelism and Sec. 3.2.3:
  * a mini-batch is processed as M micro-batches whose gradients are combined
@@ -185,50 +199,52 @@ pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
  * (mean_loss_out HOST, may be NULL; a non-NULL pointer synchronises).  Only the
  * active tensors are touched.  PT_ESTATE if called out of order, if grad_accum
  * is 0, or if the boundary is moved while a sum is in progress. */
-pt_status pt_accumulate_grads(pt_ctx* ctx, int32_t first);
-pt_status pt_finish_accumulation(pt_ctx* ctx, float* mean_loss_out);
+PT_API pt_status pt_accumulate_grads(pt_ctx* ctx, int32_t first);
+PT_API pt_status pt_finish_accumulation(pt_ctx* ctx, float* mean_loss_out);
 
 /* One optimizer step over the active tensors only; frozen bytes are untouched.
  * SGD-momentum: v <- mu v + g (+ wd w on decayed tensors), w <- w - lr v.
  * AdamW: decoupled decay, bias-corrected moments, one shared step counter.
  * Decayed tensors: weight matrices and the token table.  Also refreshes the
  * bf16 shadow in PT_BF16 mode. */
-pt_status pt_optimizer_step(pt_ctx* ctx, const pt_opt_hparams* hp /*HOST*/);
+PT_API pt_status pt_optimizer_step(pt_ctx* ctx, const pt_opt_hparams* hp /*HOST*/);
 
-/* Eq. 1 with the readings: argmin over blocks k_prev..L-1, bound truncated to
- * an integer, ties to the lowest index.  norms HOST, L+2 floats as returned by
- * pt_layer_grad_norms.  Pure host arithmetic; does not move the boundary. */
-pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, float alpha, int32_t* k_next);
+/* Eq. 1 with the readings: argmin over blocks k_prev..L-1, bound
+ * floor(k_prev + alpha (L - k_prev)) evaluated in double precision (alpha is a
+ * double so that e.g. 0.7 * 10 is not read as 6.9999998), ties to the lowest
+ * index.  norms HOST, L+2 floats as returned by pt_layer_grad_norms.  Pure host
+ * arithmetic; does not move the boundary.  PT_EINVAL unless 0 < alpha < 1. */
+PT_API pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, double alpha, int32_t* k_next);
 
 /* ---- tensor table and state access (synchronising host copies) ---------- */
 enum { PT_KIND_PARAM = 0, PT_KIND_GRAD = 1, PT_KIND_MOMENT1 = 2, PT_KIND_MOMENT2 = 3,
        PT_KIND_SHADOW = 4 /* bf16 shadow widened to fp32; PT_BF16 mode only */ };
 
-pt_status pt_num_tensors(const pt_ctx* ctx, int32_t* n /*HOST out*/);
+PT_API pt_status pt_num_tensors(const pt_ctx* ctx, int32_t* n /*HOST out*/);
 /* name: HOST buffer of name_cap bytes (NUL-terminated on return); group is the
  * grad-norm slot (0 front, 1+l block l, L+1 head). */
-pt_status pt_tensor_info(const pt_ctx* ctx, int32_t id, char* name, size_t name_cap, int64_t* numel,
+PT_API pt_status pt_tensor_info(const pt_ctx* ctx, int32_t id, char* name, size_t name_cap, int64_t* numel,
                          int32_t* rows, int32_t* cols, int32_t* group, int32_t* decayed);
 /* fp32 HOST buffers of numel elements.  pt_write_tensor(PT_KIND_PARAM) also
  * refreshes the bf16 shadow.  PT_KIND_SHADOW is read-only. */
-pt_status pt_write_tensor(pt_ctx* ctx, int32_t id, int32_t kind, const float* src);
-pt_status pt_read_tensor(pt_ctx* ctx, int32_t id, int32_t kind, float* dst);
-pt_status pt_get_step_count(const pt_ctx* ctx, int64_t* t);
-pt_status pt_set_step_count(pt_ctx* ctx, int64_t t);
+PT_API pt_status pt_write_tensor(pt_ctx* ctx, int32_t id, int32_t kind, const float* src);
+PT_API pt_status pt_read_tensor(pt_ctx* ctx, int32_t id, int32_t kind, float* dst);
+PT_API pt_status pt_get_step_count(const pt_ctx* ctx, int64_t* t);
+PT_API pt_status pt_set_step_count(pt_ctx* ctx, int64_t t);
 
 /* Activations of the last step widened to fp32 (parity checks).  PT_ACT_HL: when the head reads only each
  * sample's first token (ViT; BERT with the classification head), S >= 4 and the top block is active, that
  * block computes only those rows of its output: rows [b, 0, :] are defined, the others unspecified. */
 enum { PT_ACT_HK = 0 /*[nb,S,D]*/, PT_ACT_HL = 1 /*[nb,S,D]*/, PT_ACT_LOGITS = 2 /*ViT [nb,n_out]; BERT [nb,S,2]*/,
        PT_ACT_DHK = 3 /*[nb,S,D] gradient wrt the boundary activation; valid when k == 0 or arch-internal*/ };
-pt_status pt_read_activation(pt_ctx* ctx, int32_t which, float* dst /*HOST*/, size_t numel);
+PT_API pt_status pt_read_activation(pt_ctx* ctx, int32_t which, float* dst /*HOST*/, size_t numel);
 
 /* Cache inspection.  pt_cache_row copies the raw row bytes (S*D elements of the
  * activation type) to HOST and reports the boundary it was written at;
  * PT_ECACHE_MISS if the slot is empty.  pt_cache_stats: counters since creation
  * of per-sample decisions and of (sample, block) forward evaluations spent in
  * pt_frozen_forward. */
-pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k);
+PT_API pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_bytes, int32_t* written_at_k);
 
 /* Host tier of the cache (Sec. 3.4, App. E: when the cached activations do not
  * fit the fast tier they live one level down and pass through a sliding window
@@ -245,11 +261,11 @@ pt_status pt_cache_row(pt_ctx* ctx, int64_t sample_id, void* dst, size_t dst_byt
  * miss) and the bytes of h_k do not depend on the tier.  pt_host_tier_stats:
  * rows moved each way, rows staged by pt_cache_prefetch, and how many of those
  * were then used. */
-pt_status pt_attach_host_tier(pt_ctx* ctx, void* h_rows /*pinned HOST*/, size_t bytes);
-pt_status pt_cache_prefetch(pt_ctx* ctx, const int64_t* sample_ids /*HOST*/, int32_t n, int32_t* staged_out);
-pt_status pt_host_tier_stats(const pt_ctx* ctx, int64_t* rows_to_device, int64_t* rows_to_host,
+PT_API pt_status pt_attach_host_tier(pt_ctx* ctx, void* h_rows /*pinned HOST*/, size_t bytes);
+PT_API pt_status pt_cache_prefetch(pt_ctx* ctx, const int64_t* sample_ids /*HOST*/, int32_t n, int32_t* staged_out);
+PT_API pt_status pt_host_tier_stats(const pt_ctx* ctx, int64_t* rows_to_device, int64_t* rows_to_host,
                              int64_t* prefetched, int64_t* prefetched_used);
-pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, int64_t* misses,
+PT_API pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, int64_t* misses,
                          int64_t* block_runs);
 
 /* Optional kernel timing.  While enabled, every launcher call of the listed
@@ -261,12 +277,14 @@ pt_status pt_cache_stats(const pt_ctx* ctx, int64_t* hits, int64_t* advances, in
 enum { PT_PROF_GEMM_GENERIC = 0, PT_PROF_GEMM_NN = 1 /* y = x W */, PT_PROF_GEMM_NT = 2 /* dx = dy W^T */,
        PT_PROF_GEMM_TN = 3 /* dW = x^T dy */, PT_PROF_ATTN_FWD = 4, PT_PROF_ATTN_BWD = 5, PT_PROF_LN_FWD = 6,
        PT_PROF_LN_BWD = 7, PT_PROF_COLSUM = 8, PT_PROF_OPT = 9, PT_PROF_NORMS = 10, PT_PROF_CACHE = 11,
-       PT_PROF_COUNT = 12 };
-pt_status pt_profile_enable(pt_ctx* ctx, int32_t on);
-pt_status pt_profile_reset(pt_ctx* ctx);
-pt_status pt_profile_read(pt_ctx* ctx, int32_t category, double* total_ms, int64_t* launches, double* work /*HOST out*/);
+       PT_PROF_WGRAD_BLOCK = 12 /* the four weight gradients of one block as one grouped kernel launch; the
+                                   reduction of its split-K slabs is booked under the next category */,
+       PT_PROF_SPLITK_REDUCE = 13, PT_PROF_COUNT = 14 };
+PT_API pt_status pt_profile_enable(pt_ctx* ctx, int32_t on);
+PT_API pt_status pt_profile_reset(pt_ctx* ctx);
+PT_API pt_status pt_profile_read(pt_ctx* ctx, int32_t category, double* total_ms, int64_t* launches, double* work /*HOST out*/);
 
-const char* pt_last_error(const pt_ctx* ctx);
+PT_API const char* pt_last_error(const pt_ctx* ctx);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,7 @@ PT_HEAD_DEFAULT, PT_HEAD_CLS = 0, 1
 KIND_PARAM, KIND_GRAD, KIND_MOMENT1, KIND_MOMENT2, KIND_SHADOW = range(5)
 ACT_HK, ACT_HL, ACT_LOGITS, ACT_DHK = range(4)
 PROF_CATEGORIES = ("gemm_generic", "gemm_nn", "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd",
-                   "colsum", "opt", "norms", "cache")
+                   "colsum", "opt", "norms", "cache", "wgrad_block", "splitk_reduce")
 _STATUS = {0: "PT_OK", 1: "PT_EINVAL", 2: "PT_ESTATE", 3: "PT_ENOMEM", 4: "PT_EDEVICE", 5: "PT_ECACHE_MISS"}
 
 
@@ -73,7 +73,7 @@ def load_library():
         "pt_optimizer_step": [vp, P(PtOptHparams)],
         "pt_accumulate_grads": [vp, i32],
         "pt_finish_accumulation": [vp, P(C.c_float)],
-        "pt_next_boundary": [P(C.c_float), i32, i32, C.c_float, P(i32)],
+        "pt_next_boundary": [P(C.c_float), i32, i32, C.c_double, P(i32)],
         "pt_num_tensors": [vp, P(i32)],
         "pt_tensor_info": [vp, i32, C.c_char_p, sz, P(i64), P(i32), P(i32), P(i32), P(i32)],
         "pt_write_tensor": [vp, i32, i32, P(C.c_float)],

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpt.so")
 SOURCES = ["gemm.hip", "gemm_dma.hip", "attention.hip", "attention_mfma.hip", "rowops.hip", "optim.hip", "pt.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-Wall", "-Wno-unused-function",
          # keep fp32 vector math scalar per lane: no packed-fp32 instruction selection
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # Per-file additions.  The attention kernels keep long-lived MFMA accumulators next to short-lived score tiles;
@@ -44,13 +44,14 @@ def build(force: bool = True, jobs: int = 4) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h", "gemm_epilogue.h")] + [os.path.join(HERE, "..", "include", "pt.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h", "gemm_epilogue.h", "libpt.map")] + [os.path.join(HERE, "..", "include", "pt.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(lambda a: _compile(*a), zip(srcs, objs)))
-    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
+    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC",
+                        "-Wl,--version-script=" + os.path.join(CSRC, "libpt.map"), "-o", LIB, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)

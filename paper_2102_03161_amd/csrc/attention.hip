@@ -7,6 +7,8 @@
 // recomputes the probabilities from the saved row log-sum-exp and is split in
 // a dq kernel (per query tile) and a dk/dv kernel (per key tile) so that no
 // atomics are needed and results are reproducible.
+#include <algorithm>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -272,8 +274,9 @@ static void attention_fwd_t(const void* qkv, void* ctx, float* lse, int nb, int 
   const size_t shm = sizeof(float) * ((size_t)TQ * dh + (size_t)TK * (dh + 1) + (size_t)TQ * Spad + TQ);
   static size_t configured = 0;
   if (shm > 65536 && shm > configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                        (int)shm);
+    // a refusal stays behind as the runtime's last error, which the calling entry point reports; nothing is launched
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)shm) != hipSuccess) return;
     configured = shm;
   }
   hipLaunchKernelGGL(attn_fwd_kernel<T>, dim3(cdiv(S, TQ), H, nb), dim3(256), shm, st, (const T*)qkv, (T*)ctx, lse, S, H,
@@ -540,6 +543,20 @@ void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, i
 void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
                         int nb, int S, int H, hipStream_t st);
 
+size_t attention_generic_lds_bytes(int S, int dh) {
+  const size_t Spad = (size_t)cdiv(S, TK) * TK;
+  const size_t fwd = sizeof(float) * ((size_t)TQ * dh + (size_t)TK * (dh + 1) + (size_t)TQ * Spad + TQ);
+  const size_t dq = sizeof(float) * ((size_t)2 * TQ * dh + (size_t)2 * TK * (dh + 1) + (size_t)TQ * TK + 2 * TQ);
+  const size_t dkv = sizeof(float) * ((size_t)4 * TQ * (dh + 1) + (size_t)2 * TQ * TQ + 2 * TQ);
+  return std::max(std::max(fwd, dq), dkv);
+}
+size_t attention_first_query_lds_bytes(int S, int dh) {
+  const size_t fwd = sizeof(float) * ((size_t)dh + S + (dh % 8 == 0 ? (size_t)(256 / (dh / 8)) * dh : 0));
+  const size_t bwd = sizeof(float) * ((size_t)2 * dh + S);
+  return std::max(fwd, bwd);
+}
+bool attention_uses_mfma(int dt, int dh) { return dt == 1 && dh == 64; }
+
 void attention_fwd(int dt, const void* qkv, void* ctx, float* lse, int nb, int S, int H, int dh, hipStream_t st) {
   if (nb <= 0) return;
   if (dt == 1 && dh == 64) { attention_fwd_mfma(qkv, ctx, lse, nb, S, H, st); return; }
@@ -554,8 +571,8 @@ static void attention_bwd_t(const void* qkv, const void* ctx, const void* dctx, 
   const size_t shm2 = sizeof(float) * ((size_t)4 * TQ * (dh + 1) + (size_t)2 * TQ * TQ + 2 * TQ);
   static size_t configured = 0;
   if (shm1 > 65536 && shm1 > configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<T>),
-                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm1);
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<T>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm1) != hipSuccess) return;
     configured = shm1;
   }
   dim3 grid(cdiv(S, TQ), H, nb);

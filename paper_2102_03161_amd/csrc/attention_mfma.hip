@@ -919,9 +919,9 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __r
 // Sequence lengths the resident kernels take (the LDS image of two [S,64] matrices and two float rows must
 // fit in 160 KB, i.e. S <= 512).  Measured: forward wins at S = 197 (25 vs 33 us per layer at ViT-B, batch
 // 64) but loses at S = 384, where only one workgroup fits a CU (44 vs 39 us); backward wins at both.
-int g_attn_resident_max_s = 224;
-int g_attn_resident_max_s_bwd = 512;
-int g_attn_fused_max_s_bwd = 256;   // four [S,64] images and two float rows in 160 KB, eight waves
+constexpr int g_attn_resident_max_s = 224;
+constexpr int g_attn_resident_max_s_bwd = 512;
+constexpr int g_attn_fused_max_s_bwd = 256;   // four [S,64] images and two float rows in 160 KB, eight waves
 struct ResPlan { int ntile, nw, nblk; size_t lds; };
 ResPlan resident_plan(int S, bool with_rows) {
   ResPlan r;

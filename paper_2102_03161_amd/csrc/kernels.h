@@ -40,19 +40,25 @@ void gemm(int dt, const Gemm& g, hipStream_t st);
 // n weight-gradient products (ta, fp32 C with ldc == N) over the same K and sharing one workspace.  With
 // bf16 operands up to four of them run as one launch (one encoder block has too few output tiles per matrix
 // to fill the chip without a deep split over K); otherwise they run one after the other.
-void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st);
+// `mid` (may be null): an event recorded behind the product kernels and in front of the reduction of the
+// split-K slabs, so that a caller can time the two parts separately.
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid = nullptr);
 // workspace floats gemm_wgrad_batch may use for a block's four matrices (D x 3D, D x D, D x F, F x D)
 size_t gemm_wgrad_batch_ws_floats(int D, int F);
 // true when gemm() will run the matrix-core kernel for this problem
 bool gemm_uses_mfma(int dt, const Gemm& g);
-// tile-shape override for experiments: -1 = automatic
-void gemm_set_config(int c);
 
 // ---- attention (softmax(q k^T / sqrt(dh)) v, no mask) over packed qkv [nb,S,3D]
 void attention_fwd(int dt, const void* qkv, void* ctx, float* lse /*[nb,H,S] or null*/, int nb, int S, int H,
                    int dh, hipStream_t st);
 void attention_bwd(int dt, const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv,
                    float* delta_ws /*[nb,H,S]*/, int nb, int S, int H, int dh, hipStream_t st);
+// Dynamic LDS bytes the kernels without matrix cores (fp32 mode, or a head size other than 64) and the
+// first-query kernels ask for at sequence length S; the orchestrator rejects configurations above the 160 KB
+// of a CU before anything is launched.
+size_t attention_generic_lds_bytes(int S, int dh);
+size_t attention_first_query_lds_bytes(int S, int dh);
+bool attention_uses_mfma(int dt, int dh);
 // the same for each sample's first query only (nothing else of the output is read, or has a gradient):
 // ctx_rows and do_rows [nb, D] hold the first tokens' rows; lse entry (b, h, 0) of [nb,H,S] is written / read
 void attention_fwd_first_query(int dt, const void* qkv, void* ctx_rows, float* lse, int nb, int S, int H, int dh,

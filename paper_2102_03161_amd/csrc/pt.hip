@@ -55,7 +55,7 @@ struct Plan {
   size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, dF, dQKV, DELTA;
   // dense copies of the first token's rows (top block's backward under a first-token head)
   size_t rG, rHP, rDF, rXa, rXb, rCTX, rDO, rOC, rOD, rDCTX, rS0, rS1, rS2, rST;  // s*: fp32 gradient stream, o*: T operand copies
-  size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS;       // front ends (EMB: ViT patch embeddings / BERT embedding sum)
+  size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS, IDS;  // front ends (EMB: ViT patch embeddings / BERT embedding sum; IDS: the batch's token ids)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
   size_t LOSS, LOSSACC, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
   size_t idx_capacity = 0, stage_floats = 0, gemmws_floats = 0;
@@ -85,6 +85,12 @@ bool validate(const pt_config& c, std::string* why) {
   if (c.host_slots == 0 && c.window_slots != 0) return bad("window_slots without host_slots");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps");
   if ((int64_t)c.B * c.S > (1 << 24)) return bad("B*S too large");
+  // attention kernels that keep a score row (or strip) of the whole sequence in LDS
+  constexpr size_t kLdsPerCu = 160 * 1024;
+  if (!attention_uses_mfma(c.dtype == PT_BF16 ? 1 : 0, dh) && attention_generic_lds_bytes(c.S, dh) > kLdsPerCu)
+    return bad("sequence too long for the attention kernels of this mode (fp32, or head size other than 64)");
+  if (c.S >= 4 && (c.arch == PT_VIT_PRELN || c.head == PT_HEAD_CLS) && attention_first_query_lds_bytes(c.S, dh) > kLdsPerCu)
+    return bad("sequence too long for the first-token attention kernels");
   return true;
 }
 
@@ -165,12 +171,13 @@ void make_plan(const pt_config& c, Plan* p) {
     p->PATCH = take(np * c.chans * c.patch * c.patch * e);
     p->EMB = take(np * D * e);
     p->DEMB = take(np * D * e);
-    p->MUE = p->RSE = p->CHAINWS = 0;
+    p->MUE = p->RSE = p->CHAINWS = p->IDS = 0;
     p->CFEAT = take((size_t)B * D * e); p->MUF = take((size_t)B * 4); p->RSF = take((size_t)B * 4);
     p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); p->DC = take((size_t)B * D * e);
   } else {
     p->PATCH = 0;
     p->EMB = take(TD4); p->DEMB = take(TD4); p->MUE = take(T * 4); p->RSE = take(T * 4); p->CHAINWS = take(bert_embed_ws_ints((int)T, c.vocab) * 4);
+    p->IDS = take(T * 4);
     p->CFEAT = p->MUF = p->RSF = p->DC = 0;
     if (c.head == PT_HEAD_CLS) { p->LOGITS = take((size_t)B * c.n_out * 4); p->DZ = take((size_t)B * c.n_out * e); }
     else { p->LOGITS = take(T * 2 * 4); p->DZ = take(T * 2 * 4); }
@@ -231,7 +238,6 @@ struct pt_ctx {
   int64_t step = 0;
   int phase = 0;  // 0 idle, 1 frozen forward done, 2 backward done
   int nb = 0;
-  const void* last_input = nullptr;
   void* last_hk = nullptr;
   void* last_dhk = nullptr;
   std::vector<int32_t> slot_k;  // boundary a cache row was written at, -1 = empty (HBM rows, then host rows)
@@ -257,7 +263,7 @@ struct pt_ctx {
   int idx_turn = 0;
   mutable std::string err;
   // optional per-category kernel timing with HIP events on the context's stream
-  struct ProfRec { hipEvent_t a, b; int cat; double work; };
+  struct ProfRec { hipEvent_t a, b, m; int cat, cat2; double work; };   // m, cat2: optional split of the bracket in two
   bool prof_on = false;
   std::vector<ProfRec> prof_pool;
   size_t prof_used = 0;
@@ -286,13 +292,20 @@ struct ProfScope {
     if (!c->prof_on) return;
     if (c->prof_used == c->prof_pool.size()) {
       pt_ctx::ProfRec n{};
-      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess || hipEventCreate(&n.m) != hipSuccess) return;
       c->prof_pool.push_back(n);
     }
     r = &c->prof_pool[c->prof_used++];
     r->cat = cat;
+    r->cat2 = -1;
     r->work = work;
     (void)hipEventRecord(r->a, c->st);
+  }
+  // the bracket is cut in two at an event the launcher records: [a, m) stays in the scope's category, [m, b) goes to cat2
+  hipEvent_t split(int cat2) {
+    if (!r) return nullptr;
+    r->cat2 = cat2;
+    return r->m;
   }
   ~ProfScope() {
     if (r) (void)hipEventRecord(r->b, c->st);
@@ -326,8 +339,16 @@ void prof_collect(pt_ctx* c) {
   (void)hipStreamSynchronize(c->st);
   for (size_t i = 0; i < c->prof_used; ++i) {
     const auto& r = c->prof_pool[i];
-    float ms = 0.f;
-    if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+    float ms = 0.f, ms2 = 0.f;
+    if (r.cat2 >= 0) {
+      if (hipEventElapsedTime(&ms, r.a, r.m) == hipSuccess && hipEventElapsedTime(&ms2, r.m, r.b) == hipSuccess) {
+        c->prof_ms[r.cat] += ms;
+        c->prof_work[r.cat] += r.work;
+        c->prof_n[r.cat] += 1;
+        c->prof_ms[r.cat2] += ms2;
+        c->prof_n[r.cat2] += 1;
+      }
+    } else if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
       c->prof_ms[r.cat] += ms;
       c->prof_work[r.cat] += r.work;
       c->prof_n[r.cat] += 1;
@@ -429,8 +450,11 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
   auto run_wgrads = [&]() {
     double fl = 0;
     for (int i = 0; i < nwg; ++i) fl += 2.0 * wg[i].M * wg[i].N * wg[i].K;
-    ProfScope ps_(c, gemm_cat(dt, wg[0]), fl);
-    gemm_wgrad_batch(dt, wg, nwg, st);
+    // the four products of a whole block in the matrix-core path: the grouped kernel is timed on its own, the
+    // reduction of its split-K slabs separately
+    const bool grouped = nwg == 4 && gemm_cat(dt, wg[0]) == PT_PROF_GEMM_TN;
+    ProfScope ps_(c, grouped ? PT_PROF_WGRAD_BLOCK : gemm_cat(dt, wg[0]), fl);
+    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr);
   };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
@@ -648,6 +672,8 @@ void front_forward(pt_ctx* c, const void* d_input, const int64_t* d_map, void* x
     vit_assemble(dt, c->w(p.EMB), c->cp(2), c->cp(3), xout, ns, g.S, D, st);
   } else {
     bert_embed(dt, (const int32_t*)d_input, d_map, c->cp(0), c->cp(1), c->wf(p.EMB), ns, g.S, D, g.vocab, st);
+    // the token-table gradient needs the ids again: keep a copy, so the caller's buffer may go once this call returns
+    if (save) (void)hipMemcpyAsync(c->w(p.IDS), d_input, (size_t)ns * g.S * 4, hipMemcpyDeviceToDevice, st);
     { prof_ln_fwd(c, dt, true, c->w(p.EMB), D, c->cp(2), c->cp(3), xout, D, save ? c->wf(p.MUE) : nullptr,
                   save ? c->wf(p.RSE) : nullptr, ns * g.S, D, g.ln_eps, st); }
   }
@@ -671,7 +697,7 @@ void front_backward(pt_ctx* c, const float* dx, int ns) {
                   nullptr, D, c->gp(2), c->gp(3), nullptr, c->wf(p.LNPART), ns * g.S, D, st); }
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
-    bert_embed_bwd((const int32_t*)c->last_input, c->wf(p.DEMB), c->gp(0), c->gp(1),
+    bert_embed_bwd(reinterpret_cast<const int32_t*>(c->w(p.IDS)), c->wf(p.DEMB), c->gp(0), c->gp(1),
                    reinterpret_cast<int32_t*>(c->w(p.CHAINWS)), ns, g.S, D, g.vocab, st);
   }
 }
@@ -707,9 +733,8 @@ struct IdxStager {
 }  // namespace
 
 // ===========================================================================
-// C ABI
+// C ABI (pt.h declares every entry point with C linkage and default visibility; nothing else is exported)
 // ===========================================================================
-extern "C" {
 
 pt_status pt_query_arena_bytes(const pt_config* cfg, size_t* params, size_t* state, size_t* work, size_t* cache) {
   if (!cfg || !params || !state || !work || !cache) return PT_EINVAL;
@@ -791,7 +816,7 @@ pt_status pt_destroy(pt_ctx* c) {
   }
   if (c->h_norms) (void)hipHostFree(c->h_norms);
   if (c->norms_ev) (void)hipEventDestroy(c->norms_ev);
-  for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto& r : c->prof_pool) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); (void)hipEventDestroy(r.m); }
   if (c->copy_st) {
     (void)hipStreamSynchronize(c->copy_st);
     for (auto& w : c->win) if (w.ev) (void)hipEventDestroy(w.ev);
@@ -950,6 +975,18 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
       // a row that will be (re)written gets a window slot to be copied back from.  All window slots are
       // chosen before the main stream is made to wait for the copy stream, so none of them is in flight
       // when a kernel below touches it.
+      // Every window slot this call can need is known to exist before any is taken: a host-tier sample
+      // needs one slot (its staged row, or a fresh one to be written back from), and any slot that does not
+      // hold a row of this batch can be had (free, reclaimed after its write-back, or evicted).
+      {
+        int64_t needed = 0, own = 0;
+        for (int i = 0; i < nb; ++i) {
+          if (sample_ids[i] < g.cache_slots) continue;
+          if (c->win_of.count(sample_ids[i])) ++own;
+          else if (kw[i] >= 0 || kw[i] < k) ++needed;
+        }
+        if (needed + own > (int64_t)c->win.size()) return fail(c, PT_ENOMEM, "the window cannot hold this batch's host-tier rows");
+      }
       c->call_stamp++;
       hipError_t herr = hipSuccess;
       for (int i = 0; i < nb; ++i) {
@@ -1075,7 +1112,6 @@ pt_status pt_frozen_forward(pt_ctx* c, const void* d_input, int32_t nb, const in
   }
   HIP_TRY(c, hipGetLastError());
   c->nb = nb;
-  c->last_input = d_input;
   c->phase = 1;
   *d_hk_out = c->last_hk;
   return PT_OK;
@@ -1347,10 +1383,10 @@ pt_status pt_finish_accumulation(pt_ctx* c, float* mean_loss_out) {
   return PT_OK;
 }
 
-pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, float alpha, int32_t* k_next) {
-  if (!norms || !k_next || L < 1 || k_prev < 0 || k_prev > L || !(alpha > 0.f && alpha < 1.f)) return PT_EINVAL;
+pt_status pt_next_boundary(const float* norms, int32_t L, int32_t k_prev, double alpha, int32_t* k_next) {
+  if (!norms || !k_next || L < 1 || k_prev < 0 || k_prev > L || !(alpha > 0.0 && alpha < 1.0)) return PT_EINVAL;
   if (k_prev == L) { *k_next = L; return PT_OK; }
-  const int bound = (int)std::floor((double)k_prev + (double)alpha * (double)(L - k_prev));
+  const int bound = (int)std::floor((double)k_prev + alpha * (double)(L - k_prev));
   int arg = k_prev;
   for (int l = k_prev + 1; l < L; ++l)
     if (norms[1 + l] < norms[1 + arg]) arg = l;
@@ -1504,5 +1540,3 @@ pt_status pt_profile_read(pt_ctx* c, int32_t category, double* total_ms, int64_t
   if (work) *work = c->prof_work[category];
   return PT_OK;
 }
-
-}  // extern "C"

@@ -146,8 +146,7 @@ void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* g
 constexpr int kLnBwdBlocks = 512;   // workgroups (partial rows) at most: two per CU, each wave with two rows in flight
 constexpr int kLnBwdWaves = 4;      // waves per workgroup, one row per wave at a time
 size_t ln_partial_floats(int D) { return (size_t)kLnBwdBlocks * 3 * D; }
-static int g_ln_bwd_blocks = 0;   // tuning hook: workgroups of the backward kernel (0 = default)
-void ln_set_bwd_blocks(int b) { g_ln_bwd_blocks = b; }
+constexpr int g_ln_bwd_blocks = 0;   // workgroups of the backward kernel (0 = default)
 
 // dy may be the fp32 gradient stream or a T tensor; the result goes to an fp32 stream
 // buffer (dx_s), a T copy for the matrix-core operands (dx_o), or both (either may be null).

@@ -103,27 +103,70 @@ def gpu_step(torch, ctx, w, x, y, k, hp=HP, sample_ids=None):
     return out
 
 
-def compare_step(w, g, o, k, tol, check_params=True):
-    """Per-tensor max-abs error relative to the tensor's largest magnitude."""
+def exactly_cancelling(w, k):
+    """Gradient tensors whose true value is zero by exact cancellation, so that what any implementation
+    computes for them is round-off of the summands.  Under the span head the loss of a sample depends on
+    the logits only through softmaxes over the sequence axis, whose gradients sum to zero over the tokens:
+    the head bias (the sum of dz over the tokens) and the shift of the last post-LN LayerNorm (the sum of
+    dL/dh_L = dz W^T over the tokens) vanish identically.  The oracle returns ~1e-18 for them."""
+    if w["arch"] == "bert" and w.get("head", "default") != "cls":
+        names = {"head.b"}
+        if w["L"] - 1 >= k:
+            names.add(f"blk{w['L'] - 1}.ln2_b")
+        return names
+    return set()
+
+
+def grad_errors(w, got, ref, cfg, k, rss=None):
+    """Per-tensor max |a - b| / max |b| over the active gradient tensors.  Frozen tensors must hold exact zeros.
+    A tensor whose elements are sums that cancel is measured against the root-sum-square of its summands when
+    that is larger than the tensor's own peak (rss: per tensor, from the exact intermediates); without rss only
+    the tensors that cancel to exactly zero get a floor (one-hundredth of the model's largest gradient)."""
+    errs = {}
+    gmax = max(float(np.max(np.abs(a))) for a in ref.values())
+    zero = exactly_cancelling(w, k)
+    for name, a in got.items():
+        if orc.is_active(name, cfg, k):
+            r = ref[name]
+            peak = float(np.max(np.abs(r)))
+            if rss is not None:
+                scale = max(peak, float(np.max(rss[name])))
+            elif name in zero:
+                assert peak < 1e-9 * gmax, (name, peak)      # the oracle agrees that it cancels
+                scale = 1e-2 * gmax
+            else:
+                scale = peak
+            errs["grad:" + name] = float(np.max(np.abs(np.asarray(a, dtype=np.float64) - r))) / max(scale, 1e-300)
+        else:
+            assert not np.any(a), f"frozen tensor {name} has a gradient"
+    return errs
+
+
+def compare_step(w, g, o, k, tol, check_params=True, model=None, rss=None):
+    """Per-tensor max-abs error relative to the tensor's largest magnitude, against the exact oracle `o`.
+    model (bf16 mode, shapes other than the named workloads at their batch): the bf16 storage model's step; a
+    value passes if it is within `tol` of the exact oracle or within `tol` of the model, i.e. if exact
+    arithmetic, or exact arithmetic plus the rounding of what bf16 mode stores, explains it."""
     cfg = o["cfg"]
     errs = {}
     errs["loss"] = abs(g["loss"] - o["loss"]) / abs(o["loss"])
     errs["hk"] = rel_err(g["hk"], o["hk"])
     errs["hL"] = rel_err(g["hL"], o["aux"]["h_L"][:, :g["hL"].shape[1], :])
     errs["logits"] = rel_err(g["logits"], o["aux"]["logits"])
-    gmax = max(float(np.max(np.abs(a))) for a in o["grads"].values())
-    for name, a in g["grads"].items():
-        if orc.is_active(name, cfg, k):
-            # Some gradients vanish by cancellation (the last post-LN bias and the QA head bias under a
-            # softmax over the sequence axis sum to exactly zero): their computed value is round-off of
-            # summands at the scale of the model's gradient, so no tensor is held tighter than to
-            # one-hundredth of the largest gradient magnitude: in fp32 mode that is an absolute error of
-            # 1e-4 * 1e-2 * gmax = 1e-6 gmax, about 8 fp32 ulps of the gradient scale.
-            ref = o["grads"][name]
-            scale = max(float(np.max(np.abs(ref))), 1e-2 * gmax)
-            errs["grad:" + name] = float(np.max(np.abs(a.astype(np.float64) - ref))) / scale
-        else:
-            assert not np.any(a), f"frozen tensor {name} has a gradient"
+    errs.update(grad_errors(w, g["grads"], o["grads"], cfg, k, rss))
+    if model is not None:
+        alt = {"loss": abs(g["loss"] - model["loss"]) / abs(model["loss"]), "hk": rel_err(g["hk"], model["hk"]),
+               "hL": rel_err(g["hL"], model["aux"]["h_L"][:, :g["hL"].shape[1], :]),
+               "logits": rel_err(g["logits"], model["aux"]["logits"])}
+        alt.update(grad_errors(w, g["grads"], model["grads"], cfg, k, rss))
+        by_model = sorted(n for n in errs if errs[n] > tol and alt[n] <= tol)
+        if by_model:
+            print(f"  within {tol} of the storage model but not of the exact oracle: "
+                  + ", ".join(f"{n} ({errs[n]:.2e} / {alt[n]:.2e})" for n in by_model), flush=True)
+        both = sorted(n for n in errs if errs[n] > tol and alt[n] > tol)
+        if both:
+            print("  outside both: " + ", ".join(f"{n} ({errs[n]:.2e} / {alt[n]:.2e})" for n in both), flush=True)
+        errs = {n: min(e, alt[n]) for n, e in errs.items()}
     on = o["norms"]
     for i in range(len(on)):
         if on[i] == 0.0:
@@ -143,3 +186,21 @@ def compare_step(w, g, o, k, tol, check_params=True):
     bad = {n: e for n, e in errs.items() if not (e <= tol)}
     assert not bad, f"tolerance {tol} exceeded: {bad}"
     return errs
+
+
+def storage_model_step(w, vals, x, y, k):
+    """The bf16 storage model's step in the shape compare_step takes for the oracle's."""
+    from tests import bf16_storage_model as model
+    cfg = oracle_cfg(w)
+    p = {n: a.astype(np.float64) for n, a in vals.items()}
+    xx = x.astype(np.float64) if w["arch"] == "vit" else x
+    loss, grads, aux = model.step(cfg, p, xx, y, k)
+    return dict(cfg=cfg, hk=aux["h_k"], loss=loss, grads=grads, norms=orc.layer_grad_norms(cfg, grads, k),
+                aux={"h_L": aux["h_L"], "logits": aux["logits"]})
+
+
+def summand_rss(w, vals, x, y, k):
+    from tests import bf16_storage_model as model
+    p = {n: a.astype(np.float64) for n, a in vals.items()}
+    xx = x.astype(np.float64) if w["arch"] == "vit" else x
+    return model.summand_rss(oracle_cfg(w), p, xx, y, k)

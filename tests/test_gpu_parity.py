@@ -38,7 +38,11 @@ def run_case(torch, w, k, nb, seed, tol, hp=H.HP):
     g = H.gpu_step(torch, ctx, w, x, y, k, hp)
     o = H.oracle_step(w, vals, x, y, k, hp)
     H.oracle_update(w, o, vals, g["grads"], k, hp)
-    errs = H.compare_step(w, g, o, k, tol)
+    # gradients that cancel are measured against the root-sum-square of their summands; in bf16 mode a value
+    # may also be explained by the bf16 storage model (see tests/bf16_storage_model.py)
+    rss = H.summand_rss(w, vals, x, y, k)
+    model = H.storage_model_step(w, vals, x, y, k) if w["dtype"] == "bf16" else None
+    errs = H.compare_step(w, g, o, k, tol, model=model, rss=rss)
     # frozen parameters: bytes untouched by the step
     for name, a in g["params"].items():
         if not orc.is_active(name, o["cfg"], k):
@@ -95,23 +99,18 @@ def test_mid_bert_classification_head_bf16(torch_mod, k):
     run_case(torch_mod, dict(MID_BERT, n_out=5, head="cls"), k, 5, seed=7, tol=TOL["bf16"])
 
 
-def test_bert_large_reduced_batch_fp32(torch_mod):
-    """BERT-large span QA (24 blocks, D = 1024, 16 heads, S = 512) at full width in fp32 mode: one sample,
-    20 frozen blocks, held to the fp32 bar."""
-    run_case(torch_mod, synth.workload("bert_large_qa", dtype="f32"), 20, 1, seed=8, tol=TOL["f32"])
-
-
-# bf16 round-off performs a random walk along the residual stream: two roundings of the stream plus the
-# rounded branch inputs per block.  The 2e-2 bar is stated for the 12-block models; at 24 blocks the forward
-# activations alone have drifted by 1.2 % at h_L (measured, max-norm metric) and gradients, which amplify
-# that through the softmaxes over S = 512, reach 3.8 %.  The bound below is that depth's, not a kernel
-# tolerance: the same kernels meet 2e-2 on the 12-block models and 1e-4 in fp32 mode at these shapes.
-BERT_LARGE_BF16_TOL = 5e-2
+@pytest.mark.parametrize("k", [0, 12, 20])
+def test_bert_large_reduced_batch_fp32(torch_mod, k):
+    """BERT-large span QA (24 blocks, D = 1024, 16 heads, S = 512) at full width in fp32 mode, one sample: all
+    24 blocks active, half of them, and the top four; held to the fp32 bar."""
+    run_case(torch_mod, synth.workload("bert_large_qa", dtype="f32"), k, 1, seed=8, tol=TOL["f32"])
 
 
 def test_bert_large_reduced_batch_bf16(torch_mod):
-    errs = run_case(torch_mod, synth.workload("bert_large_qa"), 12, 2, seed=8, tol=BERT_LARGE_BF16_TOL)
-    assert errs["hk"] <= TOL["bf16"] and errs["hL"] <= TOL["bf16"] and errs["loss"] <= TOL["bf16"]
+    """The same shapes in bf16 mode, two samples, 12 of the 24 blocks active, at the bf16 bar of the 12-block
+    workloads (gradient sums that cancel are measured against the root-sum-square of their summands, as in
+    every case of this file)."""
+    run_case(torch_mod, synth.workload("bert_large_qa"), 12, 2, seed=8, tol=TOL["bf16"])
 
 
 def test_single_sample_and_boundary_at_L(torch_mod):
@@ -202,7 +201,7 @@ def test_two_steps_with_boundary_switch_bf16(torch_mod):
     g0 = H.gpu_step(torch, ctx, w, x, y, 0)
     o0 = H.oracle_step(w, vals, x, y, 0)
     H.oracle_update(w, o0, vals, g0["grads"], 0)
-    H.compare_step(w, g0, o0, 0, TOL["bf16"])
+    H.compare_step(w, g0, o0, 0, TOL["bf16"], model=H.storage_model_step(w, vals, x, y, 0), rss=H.summand_rss(w, vals, x, y, 0))
     # continue from the GPU's own state
     master = g0["params"]
     shadow = H.gpu_read_all(ctx, binding.KIND_SHADOW)
@@ -222,7 +221,7 @@ def test_two_steps_with_boundary_switch_bf16(torch_mod):
     g1 = H.gpu_step(torch, ctx, w, x2, y2, 2)
     o1 = H.oracle_step(w, master, x2, y2, 2, state=st_a, compute_vals=shadow)
     H.oracle_update(w, o1, master, g1["grads"], 2, state=st_b)
-    H.compare_step(w, g1, o1, 2, TOL["bf16"])
+    H.compare_step(w, g1, o1, 2, TOL["bf16"], model=H.storage_model_step(w, shadow, x2, y2, 2), rss=H.summand_rss(w, shadow, x2, y2, 2))
     # moments of the newly frozen tensors are gone
     m1 = H.gpu_read_all(ctx, binding.KIND_MOMENT1)
     for n in master:

@@ -26,6 +26,11 @@ def test_library_exports_every_declared_symbol():
     assert len(names) >= 20 and "pt_frozen_forward" in names and "pt_last_error" in names
     for n in names:
         assert hasattr(lib, n), n
+    # ... and nothing else: helpers, kernels' host stubs and tuning hooks stay inside the library
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    exported = sorted(line.split()[-1] for line in out.splitlines() if line.strip())
+    assert exported == names, sorted(set(exported) ^ set(names))
 
 
 @pytest.mark.parametrize("name", list(synth.WORKLOADS))
@@ -77,6 +82,21 @@ def test_next_boundary_matches_the_rule_on_random_norms():
         k = binding.next_boundary(n, 12, k, 1 / 3)
         seq.append(k)
     assert seq == [4, 6, 8, 9, 10, 10]
+    # decimal fractions whose product with the layer count is an integer: the bound is that integer (exact
+    # rational arithmetic), not one less as it would be with alpha narrowed to single precision
+    from fractions import Fraction
+    flat = np.ones(34, dtype=np.float32)
+    flat[-2] = 0.5                      # argmin at the top block: the bound decides
+    for a_txt in ("0.7", "0.9", "0.3", "0.6", "0.1"):
+        for L in (10, 20, 30):
+            for k_prev in (0, 10):
+                if k_prev >= L:
+                    continue
+                nn = np.ones(L + 2, dtype=np.float32)
+                nn[L] = 0.5
+                want = int(k_prev + Fraction(a_txt) * (L - k_prev))
+                assert binding.next_boundary(nn, L, k_prev, float(a_txt)) == want, (a_txt, L, k_prev)
+                assert orc.next_boundary(nn, k_prev, L, float(a_txt)) == want, (a_txt, L, k_prev)
     with pytest.raises(binding.PtError):
         binding.next_boundary(n, 12, 13, 0.5)
     with pytest.raises(binding.PtError):
