@@ -187,6 +187,20 @@ PT_API pt_status pt_layer_grad_norms(pt_ctx* ctx, float* norms_out);
 PT_API pt_status pt_layer_grad_norms_begin(pt_ctx* ctx);
 PT_API pt_status pt_layer_grad_norms_end(pt_ctx* ctx, float* norms_out);
 
+/* pt_layer_grad_norms for callers that cannot allocate device memory and have
+ * no scratch to lend (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels, with the per-chunk partial
+ * sums in a 2 MB array that the library holds in static device memory on every
+ * GPU it runs on, instead of in the work arena.  Same preconditions, arguments
+ * and results (bit for bit) as pt_layer_grad_norms; calls no allocating
+ * routine.  Limit: models of at most 2^19 * 1024 = 536 870 912 parameters after
+ * padding each tensor to a multiple of 1024 (larger: PT_EINVAL, nothing
+ * enqueued).  All contexts on one GPU share the array and it keeps the last
+ * call's contents (nothing needs clearing: every value read was written by the
+ * same call): calls that overlap on one GPU race and must be serialised by the
+ * caller.  Synchronises. */
+PT_API pt_status pt_layer_grad_norms_static(pt_ctx* ctx, float* norms_out /*HOST, L+2*/);
+
 /* Micro-batch gradient accumulation (Sec. 2.1 pipeline parallelism and Sec. 3.2.3:
  * a mini-batch is processed as M micro-batches whose gradients are combined
  * before the single optimizer step).  For configurations with grad_accum = 1:

@@ -70,6 +70,7 @@ def load_library():
         "pt_layer_grad_norms": [vp, P(C.c_float)],
         "pt_layer_grad_norms_begin": [vp],
         "pt_layer_grad_norms_end": [vp, P(C.c_float)],
+        "pt_layer_grad_norms_static": [vp, P(C.c_float)],
         "pt_optimizer_step": [vp, P(PtOptHparams)],
         "pt_accumulate_grads": [vp, i32],
         "pt_finish_accumulation": [vp, P(C.c_float)],
@@ -213,6 +214,11 @@ class Context:
     def layer_grad_norms(self) -> np.ndarray:
         out = np.zeros(self.cfg.L + 2, dtype=np.float32)
         self._chk(self.lib.pt_layer_grad_norms(self.h, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def layer_grad_norms_static(self) -> np.ndarray:
+        out = np.zeros(self.cfg.L + 2, dtype=np.float32)
+        self._chk(self.lib.pt_layer_grad_norms_static(self.h, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
 
     def layer_grad_norms_begin(self):

@@ -153,6 +153,10 @@ void sumsq_chunks(const float* g, float* chunk_sq, int64_t first_chunk, int64_t 
 // norms[grp] = sqrt(sum of chunk_sq over the chunk range of grp) for active groups, 0 otherwise
 void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk /*[G+1] device*/, int G, int first_active,
                     int front_active, float* norms, hipStream_t st);
+// Device address, on the current GPU, of the library's own array of static_chunk_capacity() per-chunk sums
+// (resolved once per device; no allocation).  Calls that use it on one GPU must not overlap.
+int64_t static_chunk_capacity();
+hipError_t static_chunk_sums(float** out);
 struct OptArgs {
   float lr, momentum, beta1, beta2, eps, weight_decay;
   float bias_c1, bias_c2;  // 1-beta1^t, 1-beta2^t

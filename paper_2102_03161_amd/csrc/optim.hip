@@ -6,6 +6,8 @@
 // suffix, so both passes are single launches that stream the arena once with
 // 16-byte accesses.  Padding is zero in every arena and stays zero under both
 // update rules.
+#include <mutex>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -78,6 +80,40 @@ void finalize_norms(const float* chunk_sq, const int64_t* group_first_chunk, int
                     float* norms, hipStream_t st) {
   hipLaunchKernelGGL(finalize_norms_kernel, dim3(G), dim3(kFinThreads), 0, st, chunk_sq, group_first_chunk, G, first_active,
                      front_active, norms);
+}
+
+// ---- per-chunk sums for callers that may not allocate ----------------------------------------------------
+// pt_layer_grad_norms_static keeps its per-chunk partial sums here instead of in the caller's work arena.
+// Every GPU the library runs on holds its own copy of this array (2 MB) at its own address until the process
+// ends; host code may only use the address hipGetSymbolAddress reports for the current device, never the
+// array's name.  All calls on one GPU share the array, so calls that overlap on one GPU race.
+constexpr int64_t kStaticChunks = 512 * 1024;   // 2^19 chunks of 1024 values: models up to 536 870 912 padded parameters
+static __device__ __align__(256) float scratch[kStaticChunks];
+
+constexpr int kMaxDevices = 64;
+static float* g_scratch_ptr[kMaxDevices] = {};
+static bool g_scratch_known[kMaxDevices] = {};
+
+int64_t static_chunk_capacity() { return kStaticChunks; }
+
+hipError_t static_chunk_sums(float** out) {
+  static std::mutex mu;
+  std::lock_guard<std::mutex> lock(mu);
+  *out = nullptr;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_known[dev]) {
+    float* ptr = nullptr;
+    e = hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = ptr;
+    g_scratch_known[dev] = true;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 __device__ __forceinline__ void store_shadow4(bf16* p, float a, float b, float c, float d) {

@@ -255,6 +255,7 @@ struct pt_ctx {
   // pinned host staging for index arrays, double-buffered by call parity
   int64_t* h_idx[2] = {nullptr, nullptr};
   float* h_norms = nullptr;   // pinned host memory: L + 2 norms, written by the norm kernel itself, and the loss
+  float* static_sq = nullptr;      // this GPU's copy of the library's static per-chunk sums (pt_layer_grad_norms_static)
   hipEvent_t norms_ev = nullptr;   // recorded behind the norm kernels by pt_layer_grad_norms_begin
   bool norms_pending = false;      // begun and not yet fetched
   bool norms_deferred = false;     // pending, and the norm kernels are not enqueued yet: the next update takes them along
@@ -790,6 +791,7 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
   }
   CREATE_TRY(hipHostMalloc(reinterpret_cast<void**>(&c->h_norms), (size_t)(cfg->L + 3) * 4, hipHostMallocDefault));   // norms, loss
   CREATE_TRY(hipEventCreateWithFlags(&c->norms_ev, hipEventDisableTiming));
+  CREATE_TRY(static_chunk_sums(&c->static_sq));   // set-up of pt_layer_grad_norms_static: resolved here, with this GPU current
   fill_zero(d_params, c->plan.params_bytes, c->st);
   fill_zero(d_state, c->plan.state_bytes, c->st);
   // chunk tables
@@ -1314,6 +1316,28 @@ pt_status pt_layer_grad_norms(pt_ctx* c, float* norms_out) {
   if (!c || !norms_out) return PT_EINVAL;
   const pt_status s = pt_layer_grad_norms_begin(c);
   return s == PT_OK ? pt_layer_grad_norms_end(c, norms_out) : s;
+}
+
+// pt_layer_grad_norms for callers that may not allocate and have no workspace to lend: the per-chunk sums go
+// to the library's static array on this GPU (address resolved in pt_create).  Nothing has to be cleared: the
+// first kernel overwrites the sum of every active chunk and the second reads active chunks only.
+pt_status pt_layer_grad_norms_static(pt_ctx* c, float* norms_out) {
+  if (!c || !norms_out) return PT_EINVAL;
+  if (c->phase != 2) return fail(c, PT_ESTATE, "gradient norms need a completed pt_active_fwd_bwd");
+  if (c->norms_pending) return fail(c, PT_ESTATE, "the norms of an earlier pt_layer_grad_norms_begin have not been fetched");
+  const auto& gf = c->plan.group_first_chunk;
+  const int G = c->cfg.L + 2, k = c->k;
+  const int64_t first = k == 0 ? 0 : gf[k + 1], total = gf[G];
+  if (total > static_chunk_capacity())
+    return fail(c, PT_EINVAL, "model too large for pt_layer_grad_norms_static: " + std::to_string(total) + " chunks of 1024 parameters, the static array holds " + std::to_string(static_chunk_capacity()));
+  if (!c->static_sq) return fail(c, PT_EDEVICE, "the static array's address is unknown");
+  sumsq_chunks(c->grads, c->static_sq, first, total - first, c->st);   // no timing scope here: it may create events
+  finalize_norms(c->static_sq, reinterpret_cast<const int64_t*>(c->w(c->plan.GROUPFIRST)), G, k + 1, k == 0, c->h_norms, c->st);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipEventRecord(c->norms_ev, c->st));
+  HIP_TRY(c, hipEventSynchronize(c->norms_ev));
+  std::memcpy(norms_out, c->h_norms, (size_t)(c->cfg.L + 2) * 4);
+  return PT_OK;
 }
 
 pt_status pt_optimizer_step(pt_ctx* c, const pt_opt_hparams* hp) {
