@@ -22,8 +22,8 @@ What it follows in the paper (PipeTransformer, arXiv 2102.03161):
 Freezing is exact: the step at boundary k is the ordinary forward, backward and
 update of the whole network with the derivatives of layers below k simply not
 evaluated.  So this file is that definition written out in numpy, in whatever
-floating type the caller's arrays have (fp64 for parity, fp32 for the timed CPU
-baseline).  The paper delegates the block arithmetic to the ViT and BERT
+floating type the caller's arrays have (fp64 in the parity tests and in the
+timed CPU baseline).  The paper delegates the block arithmetic to the ViT and BERT
 papers; the choices it leaves open (exact-erf GELU, no dropout, no attention
 mask, biased LayerNorm variance, mean-of-two cross-entropies for span QA,
 final LayerNorm before the ViT classifier, front end trained iff k == 0) are

@@ -315,45 +315,30 @@ void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, co
                      vec_ok4(part, n, out), blocks_main, part2, part2 ? n2 : 0, out2, part2 ? vec_ok4(part2, n2, out2) : 0);
 }
 
-// the reductions of up to four products in one launch (same number of slabs each)
+// the reductions of up to four products in one launch (same split count)
 struct ReduceGroup {
   const float* part[4]; float* out[4]; int64_t n[4]; int vec[4];
   const float* part2[4]; float* out2[4]; int64_t n2[4]; int vec2[4];
   int block0[5];      // first workgroup of each product
   int blocks_main[4];
   int nprob, splits;
-  // per-tile slab counts (a launch cut into balanced runs, where tiles have different numbers of segments)
-  int use_nseg, tile0[4], tiles_n[4], ncol[4];
-  uint8_t nseg[kMaxReduceTiles];
 };
 __global__ __launch_bounds__(256) void splitk_reduce_group_kernel(ReduceGroup rg) {
   int p = 0;
   while (p + 1 < rg.nprob && (int)blockIdx.x >= rg.block0[p + 1]) ++p;
   const int b = (int)blockIdx.x - rg.block0[p];
   if (b < rg.blocks_main[p]) {
-    const int64_t i = ((int64_t)b * 256 + threadIdx.x) * 4;
-    int splits = rg.splits;
-    if (rg.use_nseg && i < rg.n[p]) {   // the four values of a thread lie in one row and one 256-column tile
-      const int row = (int)(i / rg.ncol[p]), col = (int)(i - (int64_t)row * rg.ncol[p]);
-      splits = rg.nseg[rg.tile0[p] + (row >> 8) * rg.tiles_n[p] + (col >> 8)];
-    }
-    splitk_sum4(rg.part[p], splits, rg.n[p], rg.out[p], rg.vec[p], i);
+    splitk_sum4(rg.part[p], rg.splits, rg.n[p], rg.out[p], rg.vec[p], ((int64_t)b * 256 + threadIdx.x) * 4);
   } else {
     const int64_t i = ((int64_t)(b - rg.blocks_main[p]) * 256 + threadIdx.x) * 4;
-    if (i < rg.n2[p]) {
-      // column sums come from the first tile row
-      const int splits = rg.use_nseg ? rg.nseg[rg.tile0[p] + (int)(i >> 8)] : rg.splits;
-      splitk_sum4(rg.part2[p], splits, rg.n2[p], rg.out2[p], rg.vec2[p], i);
-    }
+    if (i < rg.n2[p]) splitk_sum4(rg.part2[p], rg.splits, rg.n2[p], rg.out2[p], rg.vec2[p], i);
   }
 }
 void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,
-                              const float* const* part2, const int64_t* n2, float* const* out2, const uint8_t* nseg,
-                              int ntiles, const int* tile0, const int* tiles_n, const int* ncol, hipStream_t st) {
+                              const float* const* part2, const int64_t* n2, float* const* out2, hipStream_t st) {
   ReduceGroup rg{};
   rg.nprob = nprob;
   rg.splits = splits;
-  rg.use_nseg = nseg ? 1 : 0;
   int b0 = 0;
   for (int i = 0; i < nprob; ++i) {
     rg.part[i] = part[i]; rg.out[i] = out[i]; rg.n[i] = n[i]; rg.vec[i] = vec_ok4(part[i], n[i], out[i]);
@@ -362,12 +347,7 @@ void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, c
     rg.block0[i] = b0;
     rg.blocks_main[i] = (int)cdiv64(n[i], 1024);
     b0 += rg.blocks_main[i] + (part2[i] ? (int)cdiv64(n2[i], 1024) : 0);
-    if (nseg) { rg.tile0[i] = tile0[i]; rg.tiles_n[i] = tiles_n[i]; rg.ncol[i] = ncol[i]; }
   }
-  // (the caller only passes per-tile counts when every product takes the 16-byte path: a thread's four values
-  // then lie in one row and one tile)
-  if (nseg)
-    for (int t = 0; t < ntiles && t < kMaxReduceTiles; ++t) rg.nseg[t] = nseg[t];
   rg.block0[nprob] = b0;
   hipLaunchKernelGGL(splitk_reduce_group_kernel, dim3((unsigned)b0), dim3(256), 0, st, rg);
 }
@@ -546,8 +526,6 @@ void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t m
 }
 
 size_t gemm_wgrad_batch_ws_floats(int D, int F) {
-  // slabs for the cut that a block's four products get at any token count (a balanced cut takes more slabs than a
-  // uniform split: the larger of the two needs)
   const int64_t shapes[4][2] = {{D, 3 * D}, {D, D}, {D, F}, {F, D}};
   int64_t tiles = 0, per_split = 0;
   for (auto& sh : shapes) {
@@ -555,7 +533,7 @@ size_t gemm_wgrad_batch_ws_floats(int D, int F) {
     per_split += sh[0] * sh[1] + sh[1];
   }
   const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 256 / std::max<int64_t>(tiles, 1)));
-  return (size_t)(std::max<int64_t>(splits, tiles >= 64 && tiles < 256 ? 4 : 1) * per_split);
+  return (size_t)(splits * per_split);
 }
 
 }  // namespace pt

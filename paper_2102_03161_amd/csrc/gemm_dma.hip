@@ -522,51 +522,17 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
 // 7- to 16-way split over K to occupy the chip and then writes and re-reads that many fp32 slabs.  Together
 // they fill the CUs with a two-way split.
 constexpr int kMaxGroup = 4;
-// Two ways of cutting the launch's work (tiles x k tiles) into workgroups:
-//  - uniform split: every tile's contraction is cut into `splits` equal ranges, one workgroup each;
-//  - balanced (items > 0): the k tiles of all tiles, laid end to end in tile order, are cut into `items`
-//    equal runs of `run` k tiles, one workgroup each, whatever tile boundaries fall inside a run.  A tile
-//    is then covered by up to kMaxSeg segments, each with a slab of its own (segment s of a tile goes to
-//    slab s); which workgroup computes which segment is fixed by the shapes alone, so the sums stay
-//    reproducible.  With 108 tiles of 197 k tiles on 256 CUs the uniform two-way split gives 216
-//    workgroups of 98-99 k tiles; the balanced cut gives 256 of 83-84.
-constexpr int kMaxSeg = 4;
 struct GroupArgs {
-  GemmDev<bf16> g[kMaxGroup];   // C = this problem's slab area (or the destination when there is one slab)
+  GemmDev<bf16> g[kMaxGroup];   // C = this problem's slab area (or the destination when splits == 1)
   float* colsum[kMaxGroup];
   int64_t slab[kMaxGroup];
   int tile0[kMaxGroup + 1];     // first tile of each problem in the launch's tile order
   int tiles_n[kMaxGroup];
   int vec_ok[kMaxGroup];
   int nprob, splits, tiles_per_split;
-  int items, run, nk;           // balanced cut: workgroups, k tiles per workgroup, k tiles per tile
 };
 __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
-  const int total_tiles = ga.tile0[ga.nprob];
-  if (ga.items > 0) {
-    const int per = (ga.items + 7) >> 3;
-    const int w = (blockIdx.x & 7) * per + (blockIdx.x >> 3);   // one XCD takes a contiguous range of runs
-    if (w >= ga.items) return;
-    const int64_t total = (int64_t)total_tiles * ga.nk;
-    int64_t it = (int64_t)w * ga.run;
-    const int64_t end = it + ga.run < total ? it + ga.run : total;
-    while (it < end) {
-      const int tt = (int)(it / ga.nk);
-      const int k0 = (int)(it - (int64_t)tt * ga.nk);
-      const int len = (int)((int64_t)(ga.nk - k0) < end - it ? (int64_t)(ga.nk - k0) : end - it);
-      const int seg = w - (int)(((int64_t)tt * ga.nk) / ga.run);   // runs that began inside or before this tile and reach it
-      int p = 0;
-      while (p + 1 < ga.nprob && tt >= ga.tile0[p + 1]) ++p;
-      const int local = tt - ga.tile0[p];
-      const SplitArgs sp{kMaxSeg, 0, ga.slab[p], ga.colsum[p]};
-      pp_run<256, true, false, EPI_STORE, float>(ga.g[p], sp, seg, k0, len, (local / ga.tiles_n[p]) * 256,
-                                                 (local % ga.tiles_n[p]) * 256, ga.vec_ok[p]);
-      it += len;
-      __syncthreads();   // the epilogue's staging reads are over before the next segment's loads land in LDS
-    }
-    return;
-  }
-  const int total_work = total_tiles * ga.splits;
+  const int total_tiles = ga.tile0[ga.nprob], total_work = total_tiles * ga.splits;
   const int per = (total_work + 7) >> 3;
   const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
   if (work >= total_work) return;
@@ -876,28 +842,6 @@ static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
   }
 }
 
-// How gemm_wgrad_group cuts `tiles` output tiles of `nk` k tiles each into workgroups (see GroupArgs).
-struct GroupCut { int splits, tiles_per_split, items, run; };
-static GroupCut group_cut(int64_t tiles, int nk) {
-  GroupCut c{1, nk, 0, 0};
-  constexpr int kCus = 256;
-  // balanced cut: one run per CU, if every run is long enough to amortise a prologue and an epilogue and no
-  // tile is cut into more than kMaxSeg segments
-  const int64_t total = tiles * nk;
-  const int run = (int)((total + kCus - 1) / kCus);
-  if (tiles >= 64 && tiles < kCus && run >= 32 && (nk + run - 1) / run + 1 <= kMaxSeg) {
-    c.items = (int)((total + run - 1) / run);
-    c.run = run;
-    return c;
-  }
-  int splits = (int)(kCus / tiles);
-  if (splits > nk / 4) splits = nk / 4;
-  if (splits > 16) splits = 16;
-  if (splits < 1) splits = 1;
-  c.splits = splits;
-  c.tiles_per_split = cdiv(nk, splits);
-  return c;
-}
 bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid) {
   if (n < 1 || n > kMaxGroup) return false;
   int64_t total = 0, per_split = 0;
@@ -909,24 +853,15 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid) {
     per_split += (int64_t)m.M * m.N + m.N;
   }
   const int nk = a[0].K / 64;
-  GroupCut cut = group_cut(total, nk);
-  bool balanced_ok = total <= kMaxReduceTiles && aligned16(a[0].ws) && (size_t)(kMaxSeg * per_split) <= a[0].ws_floats;
-  for (int i = 0; i < n; ++i) balanced_ok = balanced_ok && a[i].N % 4 == 0 && aligned16(a[i].C);
-  if (cut.items > 0 && !balanced_ok) {   // no room for the segment slabs, or no 16-byte reduction: uniform split
-    cut.items = 0;
-    cut.splits = 2;
-    cut.tiles_per_split = cdiv(nk, 2);
-  }
-  int splits = cut.items > 0 ? kMaxSeg : cut.splits;   // slabs per problem
-  while (cut.items == 0 && splits > 1 && (size_t)(splits * per_split) > a[0].ws_floats) --splits;
-  if (cut.items == 0) { cut.splits = splits; cut.tiles_per_split = cdiv(nk, splits); }
+  int splits = (int)(256 / total);
+  if (splits > nk / 4) splits = nk / 4;
+  if (splits > 16) splits = 16;
+  if (splits < 1) splits = 1;
+  while (splits > 1 && (size_t)(splits * per_split) > a[0].ws_floats) --splits;
   GroupArgs ga{};
   ga.nprob = n;
-  ga.splits = cut.splits;
-  ga.tiles_per_split = cut.tiles_per_split;
-  ga.items = cut.items;
-  ga.run = cut.run;
-  ga.nk = nk;
+  ga.splits = splits;
+  ga.tiles_per_split = cdiv(nk, splits);
   float* ws = a[0].ws;
   const float* part[kMaxGroup];
   const float* cpart[kMaxGroup];
@@ -949,32 +884,20 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid) {
     if (splits > 1) ws += splits * (mn + m.N);
   }
   ga.tile0[n] = t0;
-  const int wgs = cut.items > 0 ? cut.items : t0 * cut.splits;
-  hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(8 * cdiv(wgs, 8)), dim3(512), 0, st, ga);
+  hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(8 * cdiv(t0 * splits, 8)), dim3(512), 0, st, ga);
   if (mid) (void)hipEventRecord(mid, st);
   if (splits > 1) {
     int64_t mn[kMaxGroup], nn[kMaxGroup];
     float* out[kMaxGroup];
     float* out2[kMaxGroup];
-    int tiles_n[kMaxGroup], ncol[kMaxGroup];
     for (int i = 0; i < n; ++i) {
       mn[i] = (int64_t)a[i].M * a[i].N;
       nn[i] = a[i].N;
       out[i] = (float*)a[i].C;
       out2[i] = a[i].colsum_out;
-      tiles_n[i] = ga.tiles_n[i];
-      ncol[i] = a[i].N;
       if (!a[i].colsum_out) cpart[i] = nullptr;
     }
-    // balanced cut: tile t has the segments of the runs floor(t nk / run) .. floor(((t + 1) nk - 1) / run)
-    uint8_t nseg[kMaxReduceTiles];
-    const uint8_t* segs = nullptr;
-    if (cut.items > 0) {
-      for (int t = 0; t < t0; ++t)
-        nseg[t] = (uint8_t)((((int64_t)(t + 1) * nk - 1) / cut.run) - (((int64_t)t * nk) / cut.run) + 1);
-      segs = nseg;
-    }
-    gemm_splitk_reduce_group(n, splits, part, mn, out, cpart, nn, out2, segs, t0, ga.tile0, tiles_n, ncol, st);
+    gemm_splitk_reduce_group(n, splits, part, mn, out, cpart, nn, out2, st);
   }
   return true;
 }

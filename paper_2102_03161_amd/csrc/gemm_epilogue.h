@@ -227,11 +227,7 @@ void gemm_dma(const Gemm& a, int variant, hipStream_t st);
 bool gemm_dma_skinny(const Gemm& a, hipStream_t st);
 bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid);
 // the split-K reductions of up to four products (part2 entries may be null) in one launch
-// nseg (may be null): slabs that hold a partial result, per 256x256 output tile in the launch's tile order
-// (problem i's tiles start at tile0[i], tiles_n[i] per tile row); null = every tile has all `splits` slabs.
-constexpr int kMaxReduceTiles = 256;
 void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,
-                              const float* const* part2, const int64_t* n2, float* const* out2, const uint8_t* nseg,
-                              int ntiles, const int* tile0, const int* tiles_n, const int* ncol, hipStream_t st);
+                              const float* const* part2, const int64_t* n2, float* const* out2, hipStream_t st);
 
 }  // namespace pt
