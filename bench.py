@@ -36,11 +36,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of gemm_wgrad_group_kernel (one encoder block's four weight gradients, ViT-B/16 at
-# micro-batch 64) from the two rocprofv3 --pmc runs in profiles/vit_b16_b64_k0_hbm_traffic.md (FETCH_SIZE, then
-# WRITE_SIZE), each scaled by what the same counter reads for the plain copy of --calibrate-copy.
+# HBM bytes per launch of gemm_wgrad_group_kernel over one encoder block (its four weight gradients), from the
+# two rocprofv3 --pmc runs in profiles/*_hbm_traffic.md (FETCH_SIZE, then WRITE_SIZE), each scaled by what the
+# same counter reads for the plain copy of --calibrate-copy: fetched + written.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0): None,
+    ("vit_b16", 0): 496_800_000 + 56_768_374,        # profiles/vit_b16_b64_k0_hbm_traffic.md
+    ("bert_base_qa", 0): 540_524_738,                # profiles/bert_base_b32_s384_k0_hbm_traffic.md
 }
 
 

@@ -85,6 +85,11 @@ typedef struct {
   int32_t optimizer;   /* PT_SGDM | PT_ADAMW                                         */
   int32_t head;        /* PT_HEAD_DEFAULT | PT_HEAD_CLS                              */
   int32_t grad_accum;  /* 1: the state arena also holds a gradient accumulator, see pt_accumulate_grads */
+  int32_t k_min;       /* the boundary this context starts at and can never be below (0 = everything may train).
+                          Blocks 0..k_min-1 (and the front end when k_min >= 1) are frozen for good, so nothing a
+                          frozen layer does not need (Sec. 3.2.1 item 2) is planned for them: the state arena holds
+                          gradients and moments of the tensors from block k_min on only, and the work arena no
+                          saved activations of theirs                                                */
   int64_t cache_slots; /* 0 = no cache; slot i belongs to sample id i                */
   int64_t host_slots;  /* rows of the host tier: sample ids cache_slots .. cache_slots+host_slots-1 (0 = none) */
   int64_t window_slots;/* device rows the host tier is staged through, >= 2 B when host_slots > 0; they are
@@ -98,15 +103,18 @@ typedef struct {
 /* Bytes of the four caller-owned DEVICE arenas for this configuration:
  * params (fp32 masters + bf16 shadows), state (fp32 gradients + optimizer
  * moments, + one gradient accumulator when grad_accum is set), work (activations, saved tensors, scratch), cache (cache_slots rows
- * of S*D activations).  Each must be 256-byte aligned.  PT_EINVAL on a bad
- * configuration. */
+ * of S*D activations).  state and work shrink with cfg->k_min: a context that
+ * resumes training at a boundary k_min >= 1 is sized for F_pipe = blocks
+ * k_min..L-1 plus a forward-only F_frozen.  Each must be 256-byte aligned.
+ * PT_EINVAL on a bad configuration. */
 PT_API pt_status pt_query_arena_bytes(const pt_config* cfg /*HOST*/, size_t* params, size_t* state,
                                size_t* work, size_t* cache /*HOST out*/);
 
 /* Creates a context over the arenas (DEVICE pointers, sizes as queried).  The
  * params and state arenas are cleared (enqueued); parameters are then set with
  * pt_write_tensor.  hip_stream is a hipStream_t (NULL = default stream).  The
- * boundary starts at k = 0 and the step counter at 0 (Eq. 1: L_frozen^(0)=0). */
+ * boundary starts at k = k_min (0 unless the configuration says otherwise) and
+ * the step counter at 0 (Eq. 1: L_frozen^(0)=0). */
 PT_API pt_status pt_create(const pt_config* cfg /*HOST*/, void* d_params, void* d_state, void* d_work,
                     void* d_cache /*DEVICE, may be NULL iff cache_slots==0*/, void* hip_stream,
                     pt_ctx** out /*HOST out*/);
@@ -240,7 +248,9 @@ PT_API pt_status pt_num_tensors(const pt_ctx* ctx, int32_t* n /*HOST out*/);
 PT_API pt_status pt_tensor_info(const pt_ctx* ctx, int32_t id, char* name, size_t name_cap, int64_t* numel,
                          int32_t* rows, int32_t* cols, int32_t* group, int32_t* decayed);
 /* fp32 HOST buffers of numel elements.  pt_write_tensor(PT_KIND_PARAM) also
- * refreshes the bf16 shadow.  PT_KIND_SHADOW is read-only. */
+ * refreshes the bf16 shadow.  PT_KIND_SHADOW is read-only.  A tensor below
+ * k_min has no gradient or moments: reading them gives zeros, writing them is
+ * PT_EINVAL. */
 PT_API pt_status pt_write_tensor(pt_ctx* ctx, int32_t id, int32_t kind, const float* src);
 PT_API pt_status pt_read_tensor(pt_ctx* ctx, int32_t id, int32_t kind, float* dst);
 PT_API pt_status pt_get_step_count(const pt_ctx* ctx, int64_t* t);

@@ -31,7 +31,7 @@ class PtConfig(C.Structure):
                 ("F", C.c_int32), ("S", C.c_int32), ("B", C.c_int32), ("n_out", C.c_int32), ("img", C.c_int32),
                 ("patch", C.c_int32), ("chans", C.c_int32), ("vocab", C.c_int32), ("max_pos", C.c_int32),
                 ("ln_eps", C.c_float), ("optimizer", C.c_int32), ("head", C.c_int32), ("grad_accum", C.c_int32),
-                ("cache_slots", C.c_int64), ("host_slots", C.c_int64), ("window_slots", C.c_int64)]
+                ("k_min", C.c_int32), ("cache_slots", C.c_int64), ("host_slots", C.c_int64), ("window_slots", C.c_int64)]
 
 
 class PtOptHparams(C.Structure):
@@ -103,7 +103,7 @@ def load_library():
 
 
 def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum: bool = False,
-                host_slots: int = 0, window_slots: int = 0) -> PtConfig:
+                host_slots: int = 0, window_slots: int = 0, k_min: int = 0) -> PtConfig:
     """pt_config from a workload dict (see synth.WORKLOADS)."""
     return PtConfig(
         arch=PT_VIT_PRELN if w["arch"] == "vit" else PT_BERT_POSTLN,
@@ -112,7 +112,7 @@ def make_config(w: dict, B: int | None = None, cache_slots: int = 0, grad_accum:
         img=w["img"], patch=w["patch"], chans=w["chans"], vocab=w["vocab"], max_pos=w["max_pos"],
         ln_eps=w["ln_eps"], optimizer=PT_ADAMW if w["optimizer"] == "adamw" else PT_SGDM,
         head=PT_HEAD_CLS if w.get("head", "default") == "cls" else PT_HEAD_DEFAULT, grad_accum=1 if grad_accum else 0,
-        cache_slots=cache_slots, host_slots=host_slots, window_slots=window_slots)
+        k_min=k_min, cache_slots=cache_slots, host_slots=host_slots, window_slots=window_slots)
 
 
 def query_arena_bytes(cfg: PtConfig):

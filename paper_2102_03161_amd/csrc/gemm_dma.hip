@@ -324,28 +324,29 @@ void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
 }
 
 
-// ---- 256x256x64 tiles, two wave groups in alternating roles ----
+// ---- 256x256x64 (or 192x256x64) tiles, two wave groups in alternating roles ----
 // The eight waves form two groups of four, one wave of each group per SIMD.  Time is cut into phases that
 // end in a workgroup barrier.  In a phase one group only issues matrix instructions, on fragments it
-// already holds in registers (16 MFMAs, half a k tile), while the other group reads its next half tile's
-// fragments from LDS; at the barrier they swap.  The matrix cores therefore always have a wave whose
-// operands are complete, and LDS reads are spread evenly over time instead of arriving from all eight
-// waves right after a tile barrier.  Measured on the single-role pipeline above (12608 x 768 x 3072,
-// cycles per k tile and CU; 2048 are MFMA issue): MFMAs alone 2380, with LDS reads 2710, with the
-// global->LDS loads 2720-3250, all three 3500-3700.
+// already holds in registers, while the other group reads its next fragments from LDS; at the barrier they
+// swap.  The matrix cores therefore always have a wave whose operands are complete, and LDS reads are
+// spread evenly over time instead of arriving from all eight waves right after a tile barrier.  Measured on
+// the single-role pipeline above (12608 x 768 x 3072, cycles per k tile and CU; 2048 are MFMA issue): MFMAs
+// alone 2380, with LDS reads 2710, with the global->LDS loads 2720-3250, all three 3500-3700.
 //
-// Tile t is consumed in four phases (group 0: read half 0, compute, read half 1, compute; group 1 one
-// phase behind).  A tiles live in a ring of three 32 KB stages and B tiles in a ring of two, 160 KB in
-// all: A (the activations, streamed from HBM) is requested two tiles ahead, B (weights, mostly L2 hits)
-// one tile ahead.  Loads are issued a few per phase, behind MFMAs where the issuing wave computes.  Per
-// wave and iteration the order is B(t+1) in phase 0, then A(t+2) over phases 1-3, so that "at most
-// LA::LOADS loads outstanding" at the end of phase 3 means A(t+1) and B(t+1) have landed.
+// A group holds the fragments of half a k tile at a time (WHOLE = false: 16 MFMAs per phase, four phases and
+// barriers per tile) or, where the registers allow it (192-row tiles), of a whole k tile (WHOLE = true: two
+// phases per tile, 4-5 % faster).  Group 1 runs one phase behind group 0.  A tiles live in a ring of three
+// stages and B tiles in a ring of two, 160 KB (136 KB) in all: A (the activations, streamed from HBM) is
+// requested two tiles ahead, B (weights, mostly L2 hits) one tile ahead.  Loads are issued a few per phase:
+// B(t+1) in the first phase of tile t and A(t+2) in equal parts over the other phases, between MFMAs where
+// the issuing wave computes and in one go where it fetches, so that "at most LA::LOADS loads outstanding" at
+// the end of a tile's last phase means A(t+1) and B(t+1) have landed.
 //
-// pp_run computes one output tile (rows m0.., columns n0..) over the k tiles of `split`; all 512 threads of
-// the workgroup take part.
-template <int BM, bool TA, bool TB, int EPI, typename TC>
+// pp_run computes one output tile (rows m0.., columns n0..) over the k tiles kt0 .. kt0 + n - 1 and stores it
+// to slab `split`; all 512 threads of the workgroup take part.
+template <int BM, bool WHOLE, bool TA, bool TB, int EPI, typename TC>
 __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int kt0, int n, int m0, int n0,
-                                        int vec_ok) {
+                                       int vec_ok) {
   constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
   constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
   static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
@@ -354,7 +355,10 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
   constexpr int STAGE_LD = WTN + 4;
   constexpr int LDS_BYTES = NSA * LA::BYTES + NSB * LB::BYTES;
   static_assert(NW * 32 * STAGE_LD * 4 <= LDS_BYTES && LDS_BYTES <= 160 * 1024, "LDS budget");
-  static_assert(LA::LOADS >= 3, "A loads are spread over three phases");
+  constexpr int NH = WHOLE ? 1 : 2;        // halves of a k tile whose fragments a group holds at a time
+  constexpr int KSF = 4 / NH;              // k-steps (MFMA depth 16) per half
+  constexpr int NPART = 2 * NH - 1;        // A(t+2) goes out in this many parts, one per phase after the first
+  static_assert(LA::LOADS >= NPART, "A loads are spread over the phases");
   __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
   unsigned char* const ldsB = lds + NSA * LA::BYTES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -369,7 +373,6 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // k tiles kt0 .. kt0 + n - 1; `split` names the fp32 slab (and column-sum row) the result goes to
   const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
   float cs = 0.f;
 
@@ -378,33 +381,54 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
   ta.setup(g.A, g.lda, g.M, m0, kt0 * BK, wm * WTM, wave, lane);
   tb.setup(g.B, g.ldb, g.N, n0, kt0 * BK, wn * WTN, wave, lane);
 
-  bf16x8 fa[2][TM], fb[2][TN];
-  // fragment reads of one half tile (k-steps 2*half and 2*half + 1), complete on return
+  bf16x8 fa[KSF][TM], fb[KSF][TN];
+  // fragment reads of one half (k-steps KSF*half ..), complete once fetched() returns
   auto fetch = [&](const unsigned char* sa, const unsigned char* sb, int half) {
-    ta.read(sa, 2 * half, fa[0]);
-    tb.read(sb, 2 * half, fb[0]);
-    ta.read(sa, 2 * half + 1, fa[1]);
-    tb.read(sb, 2 * half + 1, fb[1]);
+#pragma unroll
+    for (int ks = 0; ks < KSF; ++ks) {
+      ta.read(sa, KSF * half + ks, fa[ks]);
+      tb.read(sb, KSF * half + ks, fb[ks]);
+    }
   };
   auto fetched = [&]() {
-    wait_lds<0>(fa[0], fb[0]);
-    wait_lds<0>(fa[1], fb[1]);
+#pragma unroll
+    for (int ks = 0; ks < KSF; ++ks) wait_lds<0>(fa[ks], fb[ks]);
   };
-  // 16 MFMAs on the fragments held; `load(q)` for q in [0, nq) goes out between them
+  // the MFMAs on the fragments held; `load(q)` for q in [0, nq) goes out between them
   auto compute = [&](bool on, int nq, auto load) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int ks = 0; ks < KSF; ++ks)
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
-        const int slot = ks * TM + i;   // 0..7
+        const int slot = ks * TM + i;
         if (slot < nq) {
           if (on) load(slot);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
+  };
+  // part q of A(t+2)'s loads: [part_lo(q), part_lo(q + 1))
+  auto part_lo = [](int q) constexpr { return q * LA::LOADS / NPART; };
+  // End of a phase.  Nothing may be scheduled across it: MFMAs have no side effects, and left to itself the
+  // compiler sinks most of a compute phase's MFMAs below the barrier into the wave's next fetch phase (to hide
+  // its LDS latency), which leaves compute phases with one or two MFMAs and puts both groups' MFMAs into
+  // the same phase: the alternation of the two groups exists only if the phases stay as written.
+  auto phase_end = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto tile_done = [&](bool moreA) {   // A(t+1) and B(t+1) have landed; everybody is past tile t
+    __builtin_amdgcn_sched_barrier(0);
+    if (moreA) wait_vm<LA::LOADS>();
+    else wait_vm<0>();
+    compiler_fence();
+    __builtin_amdgcn_s_barrier();
+    compiler_fence();
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   if (n > 0) {
@@ -422,8 +446,7 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
   compiler_fence();
 
   // The two groups run separate loops (straight-line code each, which the register allocator handles far
-  // better than one loop with a branch per phase); both execute four barriers per tile.
-  constexpr int A1 = LA::LOADS / 3, A2 = 2 * LA::LOADS / 3;
+  // better than one loop with a branch per phase); both execute 2 * NH barriers per tile.
   if (grp == 0) {
     int ia = 0, ib = 0;   // stages of tile t
     for (int t = 0; t < n; ++t) {
@@ -432,73 +455,60 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
       const unsigned char* sb = ldsB + ib * LB::BYTES;
       unsigned char* const dstB = ldsB + (ib ^ 1) * LB::BYTES;
       unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;   // stage (t + 2) % 3
-      // phase 0
-      fetch(sa, sb, 0);
-      if (moreB) tb.issue(dstB, wave);
-      fetched();
-      __builtin_amdgcn_s_barrier();
-      // phase 1
-      compute(moreA, A1, [&](int q) { ta.issue_one(dstA, wave, q); });
-      if constexpr (!TB) {
-        if (do_colsum) cs += LB::colsum(sb, tid);   // threads 0..255 are this group
-      }
-      __builtin_amdgcn_s_barrier();
-      // phase 2
-      fetch(sa, sb, 1);
-      if (moreA) {
 #pragma unroll
-        for (int q = A1; q < A2; ++q) ta.issue_one(dstA, wave, q);
+      for (int h = 0; h < NH; ++h) {
+        // fetch phase: B(t+1) with the first half, a part of A(t+2) with the others
+        fetch(sa, sb, h);
+        if (h == 0) {
+          if (moreB) tb.issue(dstB, wave);
+        } else if (moreA) {
+#pragma unroll
+          for (int q = part_lo(2 * h - 1); q < part_lo(2 * h); ++q) ta.issue_one(dstA, wave, q);
+        }
+        fetched();
+        phase_end();
+        // compute phase
+        compute(moreA, part_lo(2 * h + 1) - part_lo(2 * h), [&](int q) { ta.issue_one(dstA, wave, part_lo(2 * h) + q); });
+        if constexpr (!TB) {
+          if (h == 0 && do_colsum) cs += LB::colsum(sb, tid);   // threads 0..255 are this group
+        }
+        if (h == NH - 1) tile_done(moreA);
+        else phase_end();
       }
-      fetched();
-      __builtin_amdgcn_s_barrier();
-      // phase 3
-      compute(moreA, LA::LOADS - A2, [&](int q) { ta.issue_one(dstA, wave, A2 + q); });
-      if (moreA) wait_vm<LA::LOADS>();
-      else wait_vm<0>();
-      compiler_fence();
-      __builtin_amdgcn_s_barrier();
-      compiler_fence();
       ia = ia + 1 == NSA ? 0 : ia + 1;
       ib ^= 1;
     }
   } else {
     int ia = 0, ib = 0;
-    // phase 0 of tile 0: nothing to compute yet
+    // first phase of tile 0: nothing to compute yet
     if (n > 1) tb.issue(ldsB + LB::BYTES, wave);
-    if (n > 0) __builtin_amdgcn_s_barrier();
+    if (n > 0) phase_end();
     for (int t = 0; t < n; ++t) {
       const bool moreA = t + 2 < n;
       const unsigned char* sa = lds + ia * LA::BYTES;
       const unsigned char* sb = ldsB + ib * LB::BYTES;
       unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;
-      // phase 1
-      fetch(sa, sb, 0);
-      if (moreA) {
 #pragma unroll
-        for (int q = 0; q < A1; ++q) ta.issue_one(dstA, wave, q);
-      }
-      fetched();
-      __builtin_amdgcn_s_barrier();
-      // phase 2
-      compute(moreA, A2 - A1, [&](int q) { ta.issue_one(dstA, wave, A1 + q); });
-      __builtin_amdgcn_s_barrier();
-      // phase 3
-      fetch(sa, sb, 1);
-      if (moreA) {
+      for (int h = 0; h < NH; ++h) {
+        // fetch phase, with a part of A(t+2)
+        fetch(sa, sb, h);
+        if (moreA) {
 #pragma unroll
-        for (int q = A2; q < LA::LOADS; ++q) ta.issue_one(dstA, wave, q);
-      }
-      fetched();
-      if (moreA) wait_vm<LA::LOADS>();
-      else wait_vm<0>();
-      compiler_fence();
-      __builtin_amdgcn_s_barrier();
-      compiler_fence();
-      // phase 0 of tile t + 1: second half of tile t, and B(t + 2) into the stage tile t's B has just left
-      if (t + 1 < n) {
-        unsigned char* const dstB = ldsB + ib * LB::BYTES;
-        compute(moreA, LB::LOADS, [&](int q) { tb.issue_one(dstB, wave, q); });
-        __builtin_amdgcn_s_barrier();
+          for (int q = part_lo(2 * h); q < part_lo(2 * h + 1); ++q) ta.issue_one(dstA, wave, q);
+        }
+        fetched();
+        if (h == NH - 1) tile_done(moreA);
+        else phase_end();
+        // compute phase: the next part of A(t+2), or, in the first phase of tile t + 1, B(t+2) into the stage
+        // tile t's B has just left
+        if (h < NH - 1) {
+          compute(moreA, part_lo(2 * h + 2) - part_lo(2 * h + 1), [&](int q) { ta.issue_one(dstA, wave, part_lo(2 * h + 1) + q); });
+          phase_end();
+        } else if (t + 1 < n) {
+          unsigned char* const dstB = ldsB + ib * LB::BYTES;
+          compute(moreA, LB::LOADS, [&](int q) { tb.issue_one(dstB, wave, q); });
+          phase_end();
+        }
       }
       ia = ia + 1 == NSA ? 0 : ia + 1;
       ib ^= 1;
@@ -545,155 +555,8 @@ __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
   const int nk_all = ga.g[p].K / 64;
   const int kt0 = split * ga.tiles_per_split;
   const int kt1 = (kt0 + ga.tiles_per_split < nk_all) ? kt0 + ga.tiles_per_split : nk_all;
-  pp_run<256, true, false, EPI_STORE, float>(ga.g[p], sp, split, kt0, kt1 > kt0 ? kt1 - kt0 : 0, (local / ga.tiles_n[p]) * 256,
+  pp_run<256, false, true, false, EPI_STORE, float>(ga.g[p], sp, split, kt0, kt1 > kt0 ? kt1 - kt0 : 0, (local / ga.tiles_n[p]) * 256,
                                              (local % ga.tiles_n[p]) * 256, ga.vec_ok[p]);
-}
-
-// The same tile with whole-tile phases (see below); needs the fragments of a whole k tile in registers, which
-// only 192-row tiles leave room for.
-template <int BM, bool TA, bool TB, int EPI, typename TC>
-__device__ __forceinline__ void pp2_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int kt0, int n, int m0, int n0,
-                                        int vec_ok) {
-  constexpr int BN = 256, WGN = 4, BK = 64, NW = 8, NSA = 3, NSB = 2;
-  constexpr int WTM = BM / 2, WTN = 64, TM = WTM / 32, TN = 2;
-  static_assert(BM == 256 || BM == 192, "two rows of waves, 32-row fragments");
-  typedef typename TileSel<TA, BM, NW, TM, BK>::type LA;
-  typedef typename TileSel<!TB, BN, NW, TN, BK>::type LB;
-  constexpr int STAGE_LD = WTN + 4;
-  constexpr int LDS_BYTES = NSA * LA::BYTES + NSB * LB::BYTES;
-  static_assert(NW * 32 * STAGE_LD * 4 <= LDS_BYTES && LDS_BYTES <= 160 * 1024, "LDS budget");
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
-  unsigned char* const ldsB = lds + NSA * LA::BYTES;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int grp = __builtin_amdgcn_readfirstlane(wave >> 2);
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const bool do_colsum = !TB && sp.colsum != nullptr && m0 == 0;
-  float cs = 0.f;
-
-  LA ta;
-  LB tb;
-  ta.setup(g.A, g.lda, g.M, m0, kt0 * BK, wm * WTM, wave, lane);
-  tb.setup(g.B, g.ldb, g.N, n0, kt0 * BK, wn * WTN, wave, lane);
-
-  // Whole-tile phases: a group reads all four k-steps of a tile, then issues its 8*TM MFMAs; two barriers per
-  // tile instead of four.  B(t+1) is requested in the even phase of tile t, A(t+2) in the odd one.
-  bf16x8 fa[4][TM], fb[4][TN];
-  auto fetch = [&](const unsigned char* sa, const unsigned char* sb) {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      ta.read(sa, ks, fa[ks]);
-      tb.read(sb, ks, fb[ks]);
-    }
-  };
-  auto fetched = [&]() {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) wait_lds<0>(fa[ks], fb[ks]);
-  };
-  auto compute = [&](bool on, int nq, auto load) {
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
-        const int slot = ks * TM + i;
-        if (slot < nq) {
-          if (on) load(slot);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-  };
-
-  if (n > 0) {
-    ta.issue(lds, wave);
-    tb.issue(ldsB, wave);
-  }
-  if (n > 1) {
-    ta.issue(lds + LA::BYTES, wave);
-    wait_vm<LA::LOADS>();
-  } else {
-    wait_vm<0>();
-  }
-  compiler_fence();
-  __builtin_amdgcn_s_barrier();
-  compiler_fence();
-
-  if (grp == 0) {
-    int ia = 0, ib = 0;   // stages of tile t
-    for (int t = 0; t < n; ++t) {
-      const bool moreB = t + 1 < n, moreA = t + 2 < n;
-      const unsigned char* sa = lds + ia * LA::BYTES;
-      const unsigned char* sb = ldsB + ib * LB::BYTES;
-      unsigned char* const dstB = ldsB + (ib ^ 1) * LB::BYTES;
-      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;   // stage (t + 2) % 3
-      // even phase
-      fetch(sa, sb);
-      if (moreB) tb.issue(dstB, wave);
-      fetched();
-      __builtin_amdgcn_s_barrier();
-      // odd phase
-      compute(moreA, LA::LOADS, [&](int q) { ta.issue_one(dstA, wave, q); });
-      if constexpr (!TB) {
-        if (do_colsum) cs += LB::colsum(sb, tid);   // threads 0..255 are this group
-      }
-      if (moreA) wait_vm<LA::LOADS>();
-      else wait_vm<0>();
-      compiler_fence();
-      __builtin_amdgcn_s_barrier();
-      compiler_fence();
-      ia = ia + 1 == NSA ? 0 : ia + 1;
-      ib ^= 1;
-    }
-  } else {
-    int ia = 0, ib = 0;
-    // even phase of tile 0: nothing to compute yet
-    if (n > 1) tb.issue(ldsB + LB::BYTES, wave);
-    if (n > 0) __builtin_amdgcn_s_barrier();
-    for (int t = 0; t < n; ++t) {
-      const bool moreA = t + 2 < n;
-      const unsigned char* sa = lds + ia * LA::BYTES;
-      const unsigned char* sb = ldsB + ib * LB::BYTES;
-      unsigned char* const dstA = lds + (ia == 0 ? NSA - 1 : ia - 1) * LA::BYTES;
-      // odd phase
-      fetch(sa, sb);
-      if (moreA) ta.issue(dstA, wave);
-      fetched();
-      if (moreA) wait_vm<LA::LOADS>();
-      else wait_vm<0>();
-      compiler_fence();
-      __builtin_amdgcn_s_barrier();
-      compiler_fence();
-      // even phase of tile t + 1: tile t's MFMAs, and B(t + 2) into the stage tile t's B has just left
-      if (t + 1 < n) {
-        unsigned char* const dstB = ldsB + ib * LB::BYTES;
-        compute(moreA, LB::LOADS, [&](int q) { tb.issue_one(dstB, wave, q); });
-        __builtin_amdgcn_s_barrier();
-      }
-      ia = ia + 1 == NSA ? 0 : ia + 1;
-      ib ^= 1;
-    }
-    if (n > 0) compute(false, 0, [](int) {});
-  }
-  compiler_fence();
-  __builtin_amdgcn_s_barrier();   // all fragment reads done: the LDS can be reused for the epilogue
-  compiler_fence();
-  if constexpr (!TB) {
-    if (do_colsum && tid < BN && n0 + tid < g.N) sp.colsum[(int64_t)split * g.N + n0 + tid] = cs;
-  }
-  void* Cbase = sizeof(TC) == 4 ? (void*)(reinterpret_cast<float*>(g.C) + split * sp.slab)
-                                : (void*)(reinterpret_cast<bf16*>(g.C) + split * sp.slab);
-  staged_epilogue<TM, TN, WTM, WTN, EPI, TC>(g, Cbase, acc, reinterpret_cast<float*>(lds) + wave * 32 * STAGE_LD, m0 + wm * WTM,
-                                             n0 + wn * WTN, lane, vec_ok);
 }
 
 // Workgroups are dealt to the 8 XCDs round-robin by their index; the index is remapped so that one XCD works
@@ -715,8 +578,7 @@ __global__ __launch_bounds__(512) void gemm_pp_kernel(GemmDev<bf16> g, SplitArgs
   const int kt0 = split * sp.tiles_per_split;
   const int kt1 = (kt0 + sp.tiles_per_split < nk_all) ? kt0 + sp.tiles_per_split : nk_all;
   const int n = kt1 > kt0 ? kt1 - kt0 : 0;
-  if constexpr (WHOLE) pp2_run<BM, TA, TB, EPI, TC>(g, sp, split, kt0, n, m0, n0, vec_ok);
-  else pp_run<BM, TA, TB, EPI, TC>(g, sp, split, kt0, n, m0, n0, vec_ok);
+  pp_run<BM, WHOLE, TA, TB, EPI, TC>(g, sp, split, kt0, n, m0, n0, vec_ok);
 }
 
 #ifdef PT_TUNING_HOOKS   // stand-alone experiments only; the library is built without it

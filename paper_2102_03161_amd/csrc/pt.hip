@@ -47,6 +47,8 @@ struct Slot {
 struct Plan {
   std::vector<TensorDesc> tensors;
   int64_t arena_floats = 0;
+  int64_t state_lo = 0;     // floats of the parameter arena in front of the first tensor that can ever be trained
+                            // (k_min > 0): the gradient / moment arenas hold the tensors from there on only
   std::vector<int64_t> group_first_chunk;  // G+1
   size_t params_bytes = 0, state_bytes = 0, work_bytes = 0, cache_bytes = 0;
   // work arena
@@ -84,6 +86,7 @@ bool validate(const pt_config& c, std::string* why) {
   if (c.host_slots > 0 && c.window_slots < 2 * (int64_t)c.B) return bad("a host tier needs window_slots >= 2 B");
   if (c.host_slots == 0 && c.window_slots != 0) return bad("window_slots without host_slots");
   if (!(c.ln_eps >= 0.f)) return bad("ln_eps");
+  if (c.k_min < 0 || c.k_min > c.L) return bad("k_min outside 0..L");
   if ((int64_t)c.B * c.S > (1 << 24)) return bad("B*S too large");
   // attention kernels that keep a score row (or strip) of the whole sequence in LDS
   constexpr size_t kLdsPerCu = 160 * 1024;
@@ -135,17 +138,28 @@ void make_plan(const pt_config& c, Plan* p) {
 
   const size_t P = (size_t)p->arena_floats;
   p->params_bytes = align_up(P * 4) + (c.dtype == PT_BF16 ? align_up(P * 2) : 0);
-  p->state_bytes = align_up(P * 4) * ((c.optimizer == PT_ADAMW ? 3 : 2) + (c.grad_accum ? 1 : 0));
+  // A layer that is frozen for good keeps no gradient and no optimizer state (Sec. 3.2.1 item 2): with k_min > 0
+  // the state arenas start at block k_min's first tensor.
+  p->state_lo = c.k_min == 0 ? 0 : p->group_first_chunk[c.k_min + 1] * kChunk;
+  const size_t Ps = P - (size_t)p->state_lo;
+  p->state_bytes = align_up(Ps * 4) * ((c.optimizer == PT_ADAMW ? 3 : 2) + (c.grad_accum ? 1 : 0));
   p->cache_bytes = (size_t)(c.cache_slots + c.window_slots) * S * D * e;
 
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t o = off; off += align_up(bytes); return o; };
   const size_t T = (size_t)B * S;
   const size_t TD = T * D * e, TF = T * F * e, BHS = (size_t)B * c.H * S * 4;
+  // Blocks below k_min only ever run forward-only: their inputs ping-pong between two buffers and they keep
+  // no saved tensors (Sec. 3.2.1 item 2); every block from k_min on has an input buffer and a slot of its own.
   p->X.resize(L + 1);
-  for (int l = 0; l <= L; ++l) p->X[l] = take(TD);
+  {
+    size_t ping[2] = {0, 0};
+    if (c.k_min > 0) ping[0] = take(TD);
+    if (c.k_min > 1) ping[1] = take(TD);
+    for (int l = 0; l <= L; ++l) p->X[l] = l < c.k_min ? ping[l & 1] : take(TD);
+  }
   p->slot.resize(L + 1);
-  for (int l = 0; l <= L; ++l) {
+  for (int l = c.k_min < L ? c.k_min : L; l <= L; ++l) {
     Slot& s = p->slot[l];
     // post-LN keeps the two pre-LayerNorm sums (U, WN) in fp32
     const size_t TDsum = c.arch == PT_BERT_POSTLN ? T * D * 4 : TD;
@@ -153,6 +167,7 @@ void make_plan(const pt_config& c, Plan* p) {
     s.HP = take(TF); s.G = take(TF); s.LSE = take(BHS);
     s.MU1 = take(T * 4); s.RS1 = take(T * 4); s.MU2 = take(T * 4); s.RS2 = take(T * 4);
   }
+  for (int l = 0; l < c.k_min && l < L; ++l) p->slot[l] = p->slot[L];   // never used: these blocks take the prefix's scratch slot
   p->HKOUT = take(TD);
   const size_t TD4 = T * D * 4;
   p->sA = take(TD4); p->sB = take(TD4); p->sC = take(TD4); p->sD = take(TD4);
@@ -763,12 +778,15 @@ pt_status pt_create(const pt_config* cfg, void* d_params, void* d_state, void* d
   const size_t P = (size_t)c->plan.arena_floats;
   c->master = reinterpret_cast<float*>(d_params);
   c->shadow = c->dt ? reinterpret_cast<char*>(d_params) + align_up(P * 4) : nullptr;
-  c->grads = reinterpret_cast<float*>(d_state);
-  c->mom1 = reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + align_up(P * 4));
-  c->mom2 = cfg->optimizer == PT_ADAMW ? reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + 2 * align_up(P * 4)) : nullptr;
-  c->gacc = cfg->grad_accum ? reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) +
-                                                       (cfg->optimizer == PT_ADAMW ? 3 : 2) * align_up(P * 4))
-                            : nullptr;
+  // The state arenas hold the tensors from offset state_lo on; the pointers are those of a (virtual) full-size
+  // arena, so that a tensor's offset addresses all arenas alike.  Nothing below state_lo is ever touched.
+  const size_t Ps = P - (size_t)c->plan.state_lo, Sb = align_up(Ps * 4);
+  auto state_arena = [&](int i) { return reinterpret_cast<float*>(reinterpret_cast<char*>(d_state) + (size_t)i * Sb) - c->plan.state_lo; };
+  c->grads = state_arena(0);
+  c->mom1 = state_arena(1);
+  c->mom2 = cfg->optimizer == PT_ADAMW ? state_arena(2) : nullptr;
+  c->gacc = cfg->grad_accum ? state_arena(cfg->optimizer == PT_ADAMW ? 3 : 2) : nullptr;
+  c->k = cfg->k_min;
   c->work = reinterpret_cast<char*>(d_work);
   c->cache = reinterpret_cast<char*>(d_cache);
   c->slot_k.assign((size_t)(cfg->cache_slots + cfg->host_slots), -1);
@@ -1453,6 +1471,7 @@ pt_status pt_write_tensor(pt_ctx* c, int32_t id, int32_t kind, const float* src)
   float* base = kind_base(c, kind);
   if (!base) return fail(c, PT_EINVAL, "tensor kind not writable in this configuration");
   const TensorDesc& t = c->plan.tensors[id];
+  if (kind != PT_KIND_PARAM && t.offset < c->plan.state_lo) return fail(c, PT_EINVAL, "the tensor lies below k_min: it has no gradient or optimizer state");
   if (kind == PT_KIND_GRAD) { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }
   HIP_TRY(c, hipMemcpyAsync(base + t.offset, src, (size_t)t.numel * 4, hipMemcpyHostToDevice, c->st));
   if (kind == PT_KIND_PARAM && c->shadow) f32_to_bf16(c->master + t.offset, c->shadow + t.offset * 2, (size_t)t.numel, c->st);
@@ -1470,6 +1489,10 @@ pt_status pt_read_tensor(pt_ctx* c, int32_t id, int32_t kind, float* dst) {
   } else {
     float* base = kind_base(c, kind);
     if (!base) return fail(c, PT_EINVAL, "tensor kind not present in this configuration");
+    if (kind != PT_KIND_PARAM && t.offset < c->plan.state_lo) {   // below k_min: no storage, the value is zero by definition
+      std::memset(dst, 0, (size_t)t.numel * 4);
+      return PT_OK;
+    }
     HIP_TRY(c, hipMemcpyAsync(dst, base + t.offset, (size_t)t.numel * 4, hipMemcpyDeviceToHost, c->st));
   }
   HIP_TRY(c, hipStreamSynchronize(c->st));

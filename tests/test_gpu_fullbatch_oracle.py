@@ -1,5 +1,6 @@
 """The full batch of the benchmarked configurations against the oracle, element by element on every gradient
-tensor: ViT-B/16 micro-batch 64 at k = 0 and 6, BERT-base span QA batch 32 (S = 384) at k = 0, 4 and 8 -- the
+tensor: ViT-B/16 micro-batch 64 at k = 0 and 6 and micro-batch 128 at k = 9, BERT-base span QA batch 32 (S = 384) at
+k = 0, 4 and 8 -- the
 launch configurations bench.py times (192x256 and 256x256 two-group tiles, the grouped weight-gradient launch
 with its split over the tokens, fused attention backward at full occupancy).  The oracle computes the same
 batch in sub-batches (oracle.accumulated_fwd_bwd, fp64) to bound host memory; the loss and the gradient of the
@@ -73,3 +74,9 @@ def test_vit_b16_full_batch_against_the_oracle(torch_mod):
 
 def test_bert_base_full_batch_against_the_oracle(torch_mod):
     full_batch_case(torch_mod, "bert_base_qa", 4, (0, 4, 8), 4)
+
+
+def test_vit_b16_b128_full_batch_against_the_oracle(torch_mod):
+    """Micro-batch 128 (the freeze-schedule configuration: 25216 tokens, other tile counts and split depths than
+    at 64), at the last boundary of the schedule."""
+    full_batch_case(torch_mod, "vit_b16_b128", 5, (9,), 8)

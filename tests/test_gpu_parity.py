@@ -645,3 +645,39 @@ def test_attention_sequence_length_edges_bf16(torch_mod, S):
     w = dict(arch="bert", L=1, D=128, H=2, F=128, S=S, n_out=2, img=0, patch=0, chans=0, vocab=40, max_pos=S,
              ln_eps=1e-12, B=2, dtype="bf16", optimizer="adamw")
     run_case(torch_mod, w, 0, 2, seed=19 + S, tol=TOL["bf16"])
+
+
+@pytest.mark.parametrize("w", [MID_VIT, MID_BERT], ids=["vit", "bert"])
+def test_context_sized_for_a_minimum_boundary(torch_mod, w):
+    """A context created with k_min = 2 (no gradients, moments or saved tensors planned for the front end and
+    blocks 0, 1) trains blocks 2.. exactly as a full-size context does at boundary 2: same bits in the loss, the
+    norms, every gradient and every updated parameter.  Frozen tensors read back zero gradients, cannot be
+    given any, and the boundary cannot go below k_min."""
+    torch = torch_mod
+    k = 2
+    outs = []
+    for k_min in (0, k):
+        ctx = binding.Context(binding.make_config(w, cache_slots=w["B"], k_min=k_min))
+        vals = H.init_values(w, ctx, 21)
+        H.load_params(ctx, vals)
+        x, y = H.batch_for(w, 21, w["B"])
+        assert ctx.get_freeze_boundary() == k_min
+        outs.append(H.gpu_step(torch, ctx, w, x, y, k, sample_ids=np.arange(w["B"])))
+        if k_min:
+            tid = {n: t for t, n, *_ in ctx.tensors()}
+            with pytest.raises(binding.PtError) as e:
+                ctx.write_tensor(tid["blk0.Wqkv"], binding.KIND_GRAD, np.zeros_like(vals["blk0.Wqkv"]))
+            assert e.value.status == binding.PT_EINVAL
+            with pytest.raises(binding.PtError):
+                ctx.set_freeze_boundary(1)
+            assert not np.any(ctx.read_tensor(tid["blk1.W2"], binding.KIND_MOMENT1))
+            # a second step from the cache: the rows written by the first are hits
+            before = ctx.cache_stats()
+            g2 = H.gpu_step(torch, ctx, w, x, y, k, sample_ids=np.arange(w["B"]))
+            assert ctx.cache_stats()["hits"] - before["hits"] == w["B"] and np.isfinite(g2["loss"])
+        ctx.close()
+    a, b = outs
+    assert a["loss"] == b["loss"] and np.array_equal(a["norms"], b["norms"]) and np.array_equal(a["hk"], b["hk"])
+    for n in a["grads"]:
+        assert np.array_equal(a["grads"][n], b["grads"][n]), n
+        assert np.array_equal(a["params"][n], b["params"][n]), n

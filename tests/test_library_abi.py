@@ -141,3 +141,26 @@ def test_host_tier_accumulator_and_head_configuration():
     cfg.head = 9
     with pytest.raises(binding.PtError):
         binding.query_arena_bytes(cfg)
+
+
+def test_a_frozen_block_costs_a_fraction_of_an_active_one():
+    """Sec. 3.2.1 item 2: a frozen layer keeps no backward activation maps, gradients or optimizer state.  A context
+    created with k_min frozen blocks plans none of them: per block the state arena shrinks by the gradient and
+    the two moments (12 bytes per parameter) and the work arena by the block's saved tensors, so that what a
+    frozen block still occupies (its fp32 master and bf16 shadow) is well under a sixth of an active block."""
+    w = synth.workload("vit_b16")
+    block_params = 7_087_872
+    sizes = {k: binding.query_arena_bytes(binding.make_config(w, k_min=k)) for k in range(w["L"] + 1)}
+    for k in range(1, w["L"] + 1):
+        assert sizes[k][0] == sizes[0][0]                                   # parameters stay
+        assert sizes[k][1] < sizes[k - 1][1] and sizes[k][2] <= sizes[k - 1][2]
+    for k in range(2, w["L"]):                                              # (k = 1 also drops the front end's state)
+        d_state = sizes[k - 1][1] - sizes[k][1]
+        d_work = sizes[k - 1][2] - sizes[k][2]
+        assert abs(d_state - 12 * block_params) <= 12 * 12 * 1024           # padding of 12 tensors to 1024 values
+        assert d_work >= 14 * w["B"] * w["S"] * w["D"] * 2                  # the saved activations of a block
+        frozen = 6 * block_params
+        active = frozen + d_state + d_work
+        assert frozen / active < 1 / 6
+    with pytest.raises(binding.PtError):
+        binding.query_arena_bytes(binding.make_config(w, k_min=w["L"] + 1))
