@@ -364,7 +364,8 @@ def main():
     # ---- samples/s versus k (the boundary only moves up): uncached and cached ----
     if not a.no_sweep and not moved and a.k == 0:
         sweep = {"k0": round(sps, 1)}
-        ks = [int(v) for v in a.sweep.split(",")] if a.sweep else [1, w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4]
+        ks = [int(v) for v in a.sweep.split(",")] if a.sweep else [1, w["L"] // 4, w["L"] // 3, w["L"] // 2, 2 * w["L"] // 3, 3 * w["L"] // 4] \
+            if w["arch"] == "bert" else [1, w["L"] // 4, w["L"] // 2, 3 * w["L"] // 4]
         for k in sorted(set(ks)):
             r.ctx.set_freeze_boundary(k)
             s_unc = r.timed(2, 8, use_cache=False)

@@ -164,3 +164,20 @@ def test_a_frozen_block_costs_a_fraction_of_an_active_one():
         assert frozen / active < 1 / 6
     with pytest.raises(binding.PtError):
         binding.query_arena_bytes(binding.make_config(w, k_min=w["L"] + 1))
+
+
+def test_sequences_too_long_for_the_lds_resident_attention_kernels_are_rejected_up_front():
+    """Without matrix-core attention (fp32 mode, or a head size other than 64) a strip of score rows over the
+    whole sequence lives in LDS, and the first-token kernels keep one score row: configurations that would not
+    fit the 160 KB of a CU are refused by pt_query_arena_bytes / pt_create, before anything is enqueued."""
+    base = dict(synth.workload("bert_base_qa"), max_pos=1 << 20, vocab=100)
+    ok = binding.make_config(dict(base, dtype="f32", S=1024, B=1))
+    binding.query_arena_bytes(ok)
+    for bad in (dict(base, dtype="f32", S=1536, B=1),                    # fp32: generic kernels
+                dict(base, dtype="bf16", S=1536, B=1, H=24),             # bf16 with head size 32
+                dict(base, dtype="bf16", S=60000, B=1, head="cls", n_out=2)):   # first-token kernels
+        with pytest.raises(binding.PtError) as e:
+            binding.query_arena_bytes(binding.make_config(bad))
+        assert e.value.status == binding.PT_EINVAL
+    # the matrix-core path streams keys through LDS: long sequences are fine there
+    binding.query_arena_bytes(binding.make_config(dict(base, dtype="bf16", S=4096, B=1)))
