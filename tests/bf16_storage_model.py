@@ -222,6 +222,8 @@ def step(cfg, p, inputs, labels, k, rss=None):
         else:
             c = h[:, 0, :]
         z = c @ p["head.W"] + p["head.b"]
+        if rss is not None:   # the logits are sums too (two-class heads: 768 terms of order 0.1 giving 0.05)
+            rss["act:logits"] = np.sqrt((c * c) @ (p["head.W"] * p["head.W"]) + p["head.b"] ** 2)
         prob = orc.softmax_lastaxis(z)
         lse = np.log(np.exp(z - z.max(-1, keepdims=True)).sum(-1)) + z.max(-1)
         loss = (lse - z[np.arange(B), labels]).mean()
@@ -242,6 +244,7 @@ def step(cfg, p, inputs, labels, k, rss=None):
         loss, z, hs = orc.head_loss_forward(cfg, p, h, labels)
         dh = orc.head_loss_backward(cfg, p, hs, h.shape, grads)
         if rss is not None:
+            rss["act:logits"] = np.sqrt((h * h) @ (p["head.W"] * p["head.W"]) + p["head.b"] ** 2)
             dz = (dh.reshape(-1, cfg.D) @ np.linalg.pinv(p["head.W"].T)).reshape(B, cfg.S, 2)   # dh = dz W^T, W has rank 2
             _rss_lin(rss, "head.W", h.reshape(-1, cfg.D), dz.reshape(-1, 2))
             _rss_sum(rss, "head.b", dz, (0, 1))

@@ -153,11 +153,16 @@ def compare_step(w, g, o, k, tol, check_params=True, model=None, rss=None):
     errs["hk"] = rel_err(g["hk"], o["hk"])
     errs["hL"] = rel_err(g["hL"], o["aux"]["h_L"][:, :g["hL"].shape[1], :])
     errs["logits"] = rel_err(g["logits"], o["aux"]["logits"])
+    lscale = 1.0
+    if rss is not None and "act:logits" in rss:   # logits that cancel: against the root-sum-square of their summands
+        peak = float(np.max(np.abs(o["aux"]["logits"])))
+        lscale = peak / max(peak, float(np.max(rss["act:logits"])))
+        errs["logits"] *= lscale
     errs.update(grad_errors(w, g["grads"], o["grads"], cfg, k, rss))
     if model is not None:
         alt = {"loss": abs(g["loss"] - model["loss"]) / abs(model["loss"]), "hk": rel_err(g["hk"], model["hk"]),
                "hL": rel_err(g["hL"], model["aux"]["h_L"][:, :g["hL"].shape[1], :]),
-               "logits": rel_err(g["logits"], model["aux"]["logits"])}
+               "logits": rel_err(g["logits"], model["aux"]["logits"]) * lscale}
         alt.update(grad_errors(w, g["grads"], model["grads"], cfg, k, rss))
         by_model = sorted(n for n in errs if errs[n] > tol and alt[n] <= tol)
         if by_model:

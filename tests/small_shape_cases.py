@@ -22,6 +22,18 @@ CASES = [
           ln_eps=1e-6, B=8, optimizer="adamw", dtype="bf16"), 1, 8, 140),
     (dict(arch="bert", L=3, D=2048, H=16, F=1040, S=31, n_out=2, img=0, patch=0, chans=0, vocab=11, max_pos=34,
           ln_eps=1e-12, B=5, optimizer="adamw", dtype="bf16"), 0, 5, 108),
+    # two-class logits that nearly cancel (measured against the root-sum-square of their summands)
+    (dict(arch="vit", L=2, D=64, H=2, F=100, S=10, n_out=2, img=12, patch=4, chans=1, vocab=0, max_pos=0,
+          ln_eps=1e-6, B=130, optimizer="sgdm", dtype="bf16"), 1, 130, 123),
+]
+
+# Found by the same search and still outside the bar, by a hair: 52 tokens, one LayerNorm shift gradient whose
+# sums cancel to 46 % of their root-sum-square; the storage model is 1.5e-2 from the exact value, the library
+# 2.07e-2 from the exact value and 2.09e-2 from the model.  Tracked, not hidden: the GPU test runs it as an
+# expected (non-strict) failure.
+MARGINAL = [
+    (dict(arch="vit", L=3, D=160, H=4, F=32, S=26, n_out=2, img=20, patch=4, chans=1, vocab=0, max_pos=0,
+          ln_eps=1e-6, B=2, optimizer="adamw", dtype="bf16"), 0, 2, 102),
 ]
 
 
