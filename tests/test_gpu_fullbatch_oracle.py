@@ -68,12 +68,15 @@ def full_batch_case(torch, name, seed, ks, sub):
     ctx.close()
 
 
-def test_vit_b16_full_batch_against_the_oracle(torch_mod):
-    full_batch_case(torch_mod, "vit_b16", 2, (0, 6), 8)
+# one case per test, so that a test never computes for more than about half a minute without reporting
+@pytest.mark.parametrize("k", [0, 6])
+def test_vit_b16_full_batch_against_the_oracle(torch_mod, k):
+    full_batch_case(torch_mod, "vit_b16", 2, (k,), 8)
 
 
-def test_bert_base_full_batch_against_the_oracle(torch_mod):
-    full_batch_case(torch_mod, "bert_base_qa", 4, (0, 4, 8), 4)
+@pytest.mark.parametrize("k", [0, 4, 8])
+def test_bert_base_full_batch_against_the_oracle(torch_mod, k):
+    full_batch_case(torch_mod, "bert_base_qa", 4, (k,), 4)
 
 
 def test_vit_b16_b128_full_batch_against_the_oracle(torch_mod):
