@@ -81,10 +81,16 @@ size_t ln_partial_floats(int D);
 // rows, colsum[d] (may be null) += sum_i r[i * D + d]: adds a gradient that only every row_stride / D-th row has
 void add_rows(int dt, const float* r, float* x_s, void* x_o, int64_t row_stride, float* colsum, int n, int D,
               hipStream_t st);
+// With `deferred` non-null the pass leaves dgamma, dbeta and dxsum unwritten and describes in *deferred the
+// sum over its partial rows that produces them (np = 0: nothing to sum); layernorm_bwd_reduce then does that
+// for any number of passes in one launch per kLnReduceBatch of them.  Each such pass needs a `partial` of its own.
+constexpr int kLnReduceBatch = 64;
+struct LnReduceJob { const float* partial; int np; float* dgamma; float* dbeta; float* dxsum; };
 void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                    const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
                    float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
-                   int rows, int D, hipStream_t st);
+                   int rows, int D, hipStream_t st, LnReduceJob* deferred = nullptr);
+void layernorm_bwd_reduce(const LnReduceJob* jobs, int n, int D, hipStream_t st);
 
 // out[n] = sum_m X[m,n] (fp32), X is T [M,N] with leading dimension ld.
 size_t colsum_partial_floats(int N);

@@ -59,6 +59,7 @@ struct Plan {
   size_t rG, rHP, rDF, rXa, rXb, rCTX, rDO, rOC, rOD, rDCTX, rS0, rS1, rS2, rST;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS, IDS;  // front ends (EMB: ViT patch embeddings / BERT embedding sum; IDS: the batch's token ids)
   size_t CFEAT, MUF, RSF, LOGITS, DZ, DC, LOSSROWS;  // heads
+  int ln_slots = 1;
   size_t LOSS, LOSSACC, NORMS, LNPART, GEMMWS, QAPART, CHUNKDECAY, GROUPFIRST, CHUNKSQ, IDX, STAGE;
   size_t idx_capacity = 0, stage_floats = 0, gemmws_floats = 0;
 };
@@ -201,7 +202,10 @@ void make_plan(const pt_config& c, Plan* p) {
   p->LOSS = take(4);
   p->LOSSACC = take(4);
   p->NORMS = take((size_t)(L + 2) * 4);
-  p->LNPART = take(ln_partial_floats(D) * 4);
+  // one slot of partial sums per LayerNorm backward pass of a sweep: two per block that can be active, the
+  // final LayerNorm (ViT) or the embedding LayerNorm (BERT), and one to spare
+  p->ln_slots = 2 * (L - std::min(c.k_min, L)) + 2;
+  p->LNPART = take(ln_partial_floats(D) * 4 * p->ln_slots);
   // scratch of the weight-gradient products: split-K slabs (up to 16 splits, about 768 workgroups in
   // flight) plus their column-sum partials; also serves the separate column-sum pass of the FMA path
   {
@@ -246,6 +250,7 @@ struct pt_ctx {
   float* mom1 = nullptr;
   float* mom2 = nullptr;
   float* gacc = nullptr;      // gradient accumulator over micro-batches (grad_accum configurations)
+  std::vector<LnReduceJob> ln_jobs;   // LayerNorm backward passes whose partial sums are not summed yet
   int64_t acc_samples = 0;    // samples accumulated so far; 0 = no accumulation in progress
   char* work = nullptr;
   char* cache = nullptr;
@@ -328,6 +333,14 @@ struct ProfScope {
   }
 };
 
+// sums the partial rows of every LayerNorm backward pass enqueued since the last call (one launch)
+void flush_ln_reductions(pt_ctx* c) {
+  if (c->ln_jobs.empty()) return;
+  ProfScope ps_(c, PT_PROF_LN_BWD, 0.0);
+  layernorm_bwd_reduce(c->ln_jobs.data(), (int)c->ln_jobs.size(), c->cfg.D, c->st);
+  c->ln_jobs.clear();
+}
+
 // memory-bound launches timed with their algorithmic bytes (what must be read and written once)
 void prof_ln_fwd(pt_ctx* c, int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
                  int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
@@ -336,12 +349,21 @@ void prof_ln_fwd(pt_ctx* c, int dt, bool x_f32, const void* x, int64_t ldx, cons
 }
 void prof_ln_bwd(pt_ctx* c, int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                  const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres, float* dx_s,
-                 void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial, int rows, int D,
-                 hipStream_t st) {
+                 void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, int rows, int D, hipStream_t st,
+                 bool reduce_now = false) {
   const double per = (dy_f32 ? 4 : c->esz) + (x_f32 ? 4 : c->esz) + (dres ? 4 : 0) + (dx_s ? 4 : 0) + (dx_o ? c->esz : 0);
-  ProfScope ps_(c, PT_PROF_LN_BWD, (double)rows * D * per);
-  layernorm_bwd(dt, dy_f32, x_f32, dy, lddy, x, ldx, mean, rstd, gamma, dres, lddres, dx_s, dx_o, lddx, dgamma, dbeta, dxsum,
-                partial, rows, D, st);
+  // Each pass of a backward sweep writes its workgroups' partial sums of d(gamma), d(beta) and the column sums
+  // to a slot of its own; nothing reads those three results before the sweep ends, so they are summed for
+  // all passes in one launch there (flush_ln_reductions) unless the caller needs them at once.
+  if (c->ln_jobs.size() == (size_t)c->plan.ln_slots) flush_ln_reductions(c);
+  float* partial = c->wf(c->plan.LNPART) + c->ln_jobs.size() * ln_partial_floats(D);
+  LnReduceJob job;
+  {
+    ProfScope ps_(c, PT_PROF_LN_BWD, (double)rows * D * per);
+    layernorm_bwd(dt, dy_f32, x_f32, dy, lddy, x, ldx, mean, rstd, gamma, dres, lddres, dx_s, dx_o, lddx, dgamma, dbeta, dxsum,
+                  partial, rows, D, st, reduce_now ? nullptr : &job);
+  }
+  if (!reduce_now && job.np > 0) c->ln_jobs.push_back(job);
 }
 void prof_copy_rows(pt_ctx* c, void* dst, const int64_t* dst_idx, const void* src, const int64_t* src_idx, int nrows,
                     size_t row_bytes, hipStream_t st) {
@@ -447,7 +469,6 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
   const int D = g.D, F = g.F, Tn = ns * g.S, dt = c->dt;
   hipStream_t st = c->st;
   const Plan& p = c->plan;
-  float* lnp = c->wf(p.LNPART);
   float* sC = c->wf(p.sC); float* sD = c->wf(p.sD);
   void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* oE = c->w(p.oE); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
   // dW[K_in, N_out] = X^T dY ; db = colsum over tokens of dY (bias_dt 0: fp32 source, else T)
@@ -486,7 +507,7 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     wgrad(c->w(s.WN), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dLN2out
     { prof_ln_bwd(c, dt, false, false, oC, D, c->w(s.Y), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), dout.s, D, sC, oD,
-                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oD = dL/dY
+                  D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), Tn, D, st); }  // sC / oD = dL/dY
     wgrad(c->w(s.CTX), D, oD, D, c->blk(l, WO), -1);
     dgrad(oD, D, c->blk(l, WO), oC, D, EPI_STORE, nullptr, false);                      // oC = dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
@@ -494,16 +515,16 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
-                  c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
+                  c->gp(c->blk(l, LN1_B)), lower_b2, Tn, D, st); }
   } else {
     { prof_ln_bwd(c, dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
-                  oE, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, Tn, D, st); }  // sC / oE = dL/d(Y+MLP)
+                  oE, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), Tn, D, st); }  // sC / oE = dL/d(Y+MLP)
     wgrad(c->w(s.G), F, oE, D, c->blk(l, W2), -1);
     dgrad(oE, D, c->blk(l, W2), dF, F, EPI_MUL_DGELU, c->w(s.HP), false);
     wgrad(c->w(s.Y), D, dF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(dF, F, c->blk(l, W1), sD, D, EPI_RES, sC, true);                              // sD = dL/dY
     { prof_ln_bwd(c, dt, true, true, sD, D, c->w(s.U), D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0, sC, oC,
-                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, Tn, D, st); }  // sC / oC = dL/d(x+Attn)
+                  D, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), Tn, D, st); }  // sC / oC = dL/d(x+Attn)
     wgrad(c->w(s.CTX), D, oC, D, c->blk(l, WO), -1);
     dgrad(oC, D, c->blk(l, WO), oD, D, EPI_STORE, nullptr, false);                      // oD = dL/dCTX
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
@@ -582,7 +603,6 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
   const int64_t SD = (int64_t)S * D;
   hipStream_t st = c->st;
   const Plan& p = c->plan;
-  float* lnp = c->wf(p.LNPART);
   void* oC = c->w(p.oC); void* dQKV = c->w(p.dQKV);
   void* rG = c->w(p.rG); void* rHP = c->w(p.rHP); void* rDF = c->w(p.rDF); void* rXa = c->w(p.rXa); void* rXb = c->w(p.rXb);
   void* rCTX = c->w(p.rCTX); void* rDO = c->w(p.rDO); void* rOC = c->w(p.rOC); void* rOD = c->w(p.rOD);
@@ -635,7 +655,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     wgrad_rows(rXa, D, rDF, F, c->blk(l, W1), c->blk(l, B1));
     dgrad(rDF, F, c->blk(l, W1), rOC, D, EPI_STORE, nullptr, false, ns);                 // dL/dLN2out
     { prof_ln_bwd(c, dt, false, false, rOC, D, rXb, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), rS0, D, rS1, rOD, D,
-                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOD = dL/dY
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, BO)), ns, D, st); }  // rS1 / rOD = dL/dY
     wgrad_rows(rCTX, D, rOD, D, c->blk(l, WO), -1);
     wgrad_rows_launch();
     dgrad(rOD, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
@@ -646,7 +666,7 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     // those rows (and to the column sums) after the LayerNorm backward instead of being read as a full tensor
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), nullptr, 0,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
-                  c->gp(c->blk(l, LN1_B)), lower_b2, lnp, Tn, D, st); }
+                  c->gp(c->blk(l, LN1_B)), lower_b2, Tn, D, st, /*reduce_now=*/true); }   // add_rows adds to lower_b2
     if (need_dx) add_rows(dt, rS1, dx.s, dx.o, SD, lower_b2, ns, D, st);
   } else {
     // post-LN: U = x + Attn(x) and WN = Y + MLP(Y) are the fp32 sums in front of the two LayerNorms
@@ -654,13 +674,13 @@ void block_backward_first_rows(pt_ctx* c, int l, const void* xin, const Slot& s,
     const RowCopy in[] = {row(dout.s, SD, 4, rS0, D)};
     strided_rows_copy(in, 1, ns, st);
     { prof_ln_bwd(c, dt, true, true, rS0, D, rXa, D, rmu2, rrs2, c->cp(c->blk(l, LN2_G)), nullptr, 0, rS1, rOD, D,
-                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), lnp, ns, D, st); }  // rS1 / rOD = dL/d(Y+MLP)
+                  c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), ns, D, st); }  // rS1 / rOD = dL/d(Y+MLP)
     wgrad_rows(rG, F, rOD, D, c->blk(l, W2), -1);
     dgrad(rOD, D, c->blk(l, W2), rDF, F, EPI_MUL_DGELU, rHP, false, ns);
     wgrad_rows(rDO, D, rDF, F, c->blk(l, W1), c->blk(l, B1));                              // rDO holds the rows of Y here
     dgrad(rDF, F, c->blk(l, W1), rS2, D, EPI_RES, rS1, true, ns);                          // rS2 = dL/dY
     { prof_ln_bwd(c, dt, true, true, rS2, D, rXb, D, rmu1, rrs1, c->cp(c->blk(l, LN1_G)), nullptr, 0, rS1, rOC, D,
-                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), lnp, ns, D, st); }  // rS1 / rOC = dL/d(x+Attn)
+                  c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), c->gp(c->blk(l, BO)), ns, D, st); }  // rS1 / rOC = dL/d(x+Attn)
     wgrad_rows(rCTX, D, rOC, D, c->blk(l, WO), -1);
     wgrad_rows_launch();
     dgrad(rOC, D, c->blk(l, WO), rDCTX, D, EPI_STORE, nullptr, false, ns);                // dL/dCTX
@@ -710,7 +730,7 @@ void front_backward(pt_ctx* c, const float* dx, int ns) {
     { ProfScope ps_(c, gemm_cat(dt, m), 2.0 * m.M * m.N * m.K); gemm(dt, m, st); }
   } else {
     { prof_ln_bwd(c, dt, true, true, dx, D, c->w(p.EMB), D, c->wf(p.MUE), c->wf(p.RSE), c->cp(2), nullptr, 0, c->wf(p.DEMB),
-                  nullptr, D, c->gp(2), c->gp(3), nullptr, c->wf(p.LNPART), ns * g.S, D, st); }
+                  nullptr, D, c->gp(2), c->gp(3), nullptr, ns * g.S, D, st); }
     fill_zero(c->gp(0), (size_t)c->plan.tensors[0].padded * 4, st);
     fill_zero(c->gp(1), (size_t)c->plan.tensors[1].padded * 4, st);
     bert_embed_bwd(reinterpret_cast<const int32_t*>(c->w(p.IDS)), c->wf(p.DEMB), c->gp(0), c->gp(1),
@@ -1169,6 +1189,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   if (c->phase < 1) return fail(c, PT_ESTATE, "pt_frozen_forward has not run for this step");
   if (reinterpret_cast<uintptr_t>(d_hk) % 16) return fail(c, PT_EINVAL, "d_hk must be 16-byte aligned");
   { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
+  c->ln_jobs.clear();
   const pt_config& g = c->cfg;
   const Plan& p = c->plan;
   const int L = g.L, D = g.D, S = g.S, k = c->k, nb = c->nb, dt = c->dt;
@@ -1208,13 +1229,13 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     // go, dense, straight into its row buffers; otherwise into a zero-filled full-size gradient
     if (top_first_rows && k < L) {
       { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0,
-                    c->wf(p.rS0), c->w(p.rDO), D, c->gp(hg), c->gp(hb), c->gp(c->blk(L - 1, B2)), c->wf(p.LNPART), nb, D, st); }
+                    c->wf(p.rS0), c->w(p.rDO), D, c->gp(hg), c->gp(hb), c->gp(c->blk(L - 1, B2)), nb, D, st); }
     } else {
       fill_zero(dcur.s, (size_t)nb * S * D * 4, st);
       fill_zero(dcur.o, (size_t)nb * S * D * c->esz, st);
       { prof_ln_bwd(c, dt, false, false, c->w(p.DC), D, x, (int64_t)S * D, c->wf(p.MUF), c->wf(p.RSF), c->cp(hg), nullptr, 0, dcur.s,
                     dcur.o, (int64_t)S * D, c->gp(hg), c->gp(hb), k < L ? c->gp(c->blk(L - 1, B2)) : nullptr,
-                    c->wf(p.LNPART), nb, D, st); }
+                    nb, D, st); }
     }
   } else if (g.head == PT_HEAD_CLS) {
     // sequence classification: the first token's final activation -> linear classifier -> cross-entropy
@@ -1257,6 +1278,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     std::swap(dcur, dnext);
   }
   if (k == 0) front_backward(c, dcur.s, nb);
+  flush_ln_reductions(c);
   c->last_dhk = dcur.s;
   HIP_TRY(c, hipGetLastError());
   c->phase = 2;

@@ -264,10 +264,9 @@ __global__ __launch_bounds__(64 * kLnBwdWaves) void ln_bwd_kernel(const TDY* __r
 // in flight (the kernel is latency-bound: 9 MB over 72 workgroups); the sums are combined in a fixed order.
 // Column i goes to out0[i] for i < n0, to out1[i - n0] for i < 2 n0, else to out2[i - 2 n0]; a null
 // destination drops the column.
-__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
-                                                               float* __restrict__ out0, int n0,
-                                                               float* __restrict__ out1, float* __restrict__ out2) {
-  __shared__ float red[32][33];
+__device__ __forceinline__ void reduce_partials_body(const float* __restrict__ partial, int np, int n,
+                                                     float* __restrict__ out0, int n0, float* __restrict__ out1,
+                                                     float* __restrict__ out2, float (&red)[32][33]) {
   const int c = threadIdx.x & 31, rg = threadIdx.x >> 5;
   const int i = blockIdx.x * 32 + c;
   float s[8];
@@ -291,11 +290,44 @@ __global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __re
     if (dst) dst[i % n0] = t;
   }
 }
+__global__ __launch_bounds__(1024) void reduce_partials_kernel(const float* __restrict__ partial, int np, int n,
+                                                               float* __restrict__ out0, int n0,
+                                                               float* __restrict__ out1, float* __restrict__ out2) {
+  __shared__ float red[32][33];
+  reduce_partials_body(partial, np, n, out0, n0, out1, out2, red);
+}
+// the same for several LayerNorm backward passes at once (blockIdx.y = pass): their parameter gradients are
+// read by nothing before the end of the backward pass, so one launch there replaces one launch per pass
+struct LnReduceBatch {
+  const float* partial[kLnReduceBatch];
+  float* dgamma[kLnReduceBatch];
+  float* dbeta[kLnReduceBatch];
+  float* dxsum[kLnReduceBatch];
+  int np[kLnReduceBatch];
+};
+__global__ __launch_bounds__(1024) void reduce_partials_batch_kernel(LnReduceBatch b, int D) {
+  __shared__ float red[32][33];
+  const int j = blockIdx.y;
+  reduce_partials_body(b.partial[j], b.np[j], 3 * D, b.dgamma[j], D, b.dbeta[j], b.dxsum[j], red);
+}
+
+void layernorm_bwd_reduce(const LnReduceJob* jobs, int n, int D, hipStream_t st) {
+  for (int j0 = 0; j0 < n; j0 += kLnReduceBatch) {
+    LnReduceBatch b;
+    const int m = n - j0 < kLnReduceBatch ? n - j0 : kLnReduceBatch;
+    for (int j = 0; j < m; ++j) {
+      b.partial[j] = jobs[j0 + j].partial; b.np[j] = jobs[j0 + j].np;
+      b.dgamma[j] = jobs[j0 + j].dgamma; b.dbeta[j] = jobs[j0 + j].dbeta; b.dxsum[j] = jobs[j0 + j].dxsum;
+    }
+    hipLaunchKernelGGL(reduce_partials_batch_kernel, dim3(cdiv(3 * D, 32), m), dim3(1024), 0, st, b, D);
+  }
+}
 
 void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy, const void* x, int64_t ldx,
                    const float* mean, const float* rstd, const void* gamma, const float* dres, int64_t lddres,
                    float* dx_s, void* dx_o, int64_t lddx, float* dgamma, float* dbeta, float* dxsum, float* partial,
-                   int rows, int D, hipStream_t st) {
+                   int rows, int D, hipStream_t st, LnReduceJob* deferred) {
+  if (deferred) *deferred = LnReduceJob{partial, 0, dgamma, dbeta, dxsum};
   if (rows <= 0) return;
   const int cap = g_ln_bwd_blocks > 0 && g_ln_bwd_blocks < kLnBwdBlocks ? g_ln_bwd_blocks : kLnBwdBlocks;
   const int nb = cdiv(rows, kLnBwdWaves) < cap ? cdiv(rows, kLnBwdWaves) : cap;
@@ -318,8 +350,10 @@ void layernorm_bwd(int dt, bool dy_f32, bool x_f32, const void* dy, int64_t lddy
   else LN_BWD_V(bf16, bf16, bf16);
 #undef LN_BWD_V
 #undef LN_BWD
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(1024), 0, st, partial, nb, 3 * D, dgamma, D,
-                     dbeta, dxsum);
+  // the sums over the workgroups' partial rows: now, or later in one launch with those of other passes
+  if (deferred) deferred->np = nb;
+  else hipLaunchKernelGGL(reduce_partials_kernel, dim3(cdiv(3 * D, 32)), dim3(1024), 0, st, partial, nb, 3 * D, dgamma, D,
+                          dbeta, dxsum);
 }
 
 // ---------------------------------------------------------------------------
