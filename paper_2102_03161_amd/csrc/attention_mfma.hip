@@ -369,6 +369,7 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
   return (unsigned)(size_t)((__attribute__((address_space(3))) const void*)(p));
 }
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4v;
 
 // rows [0, rows_pad) of two [*, 64] matrices into row-major LDS images (rows >= nrows read as 0).  Eight
 // 16-byte global loads per thread are issued before the first LDS store, so a workgroup pays the global
@@ -916,12 +917,397 @@ __global__ __launch_bounds__(512) void attn_bwd_fused_res_kernel(const bf16* __r
   }
 }
 
+// ---------------------------------------------------------------------------
+// Pipelined fused backward (S <= 208): the fused kernel above spends half of a head's time waiting for the
+// head's four [S,64] matrices, with every CU of the chip loading at the same moment and computing at the same
+// moment.  Here a workgroup stays on its CU and walks over its heads, and the matrices of the next head arrive
+// while the current one is computed: they travel straight from global memory into LDS (global_load_lds, no
+// staging registers) into image slots that the current head no longer reads.
+//
+// LDS holds six images of rows_pad = ceil16(S) rows of 128 bytes, in three pairs that rotate per head:
+//   pair (n mod 3)      Q and dO of head n   (read by pass 2, and for the lanes' own rows at the head's start)
+//   pair (n + 1 mod 3)  K and V of head n    (read by pass 1, and for the lanes' own rows when pass 2 starts)
+//   pair (n + 2 mod 3)  free: K and V of head n + 1 are requested into it when head n starts;
+//                       Q and dO of head n + 1 go into head n's K/V pair once pass 1 is over.
+// An image has no padding (a wave-wide load writes 64 consecutive 16-byte slots = eight rows); slot (row, p)
+// holds the row's 16-byte chunk p ^ img_swz(row), the permutation being applied to the global address a lane
+// fetches.  img_swz makes both kinds of fragment reads conflict-free: the 16 rows a quarter-wave reads with
+// ds_read_b128 fall into 16 different 16-byte bank groups, and so do the 4 rows x 32 bytes that a half-wave's
+// two 16-lane groups address in a transpose read.  XOR-ing a chunk index is XOR-ing bits 4-6 of the byte
+// address, so a lane keeps two offsets and derives the others with one XOR.
+// Tiles are 32 rows and the last one may reach up to 16 rows past an image: those reads land in the next
+// image or in a zeroed pad behind the last one.  Everything there is finite (the whole LDS is zeroed first,
+// and rows past S of an image are copies of row S - 1), and it only meets probabilities that are exactly 0.
+// ---------------------------------------------------------------------------
+#define PT_LDS(p) ((__attribute__((address_space(3))) void*)(p))
+#define PT_GLB(p) ((const __attribute__((address_space(1))) void*)(p))
+constexpr int kImgRowBytes = 2 * DH;   // 128
+constexpr int kImgPadBytes = 16 * kImgRowBytes;
+__device__ __forceinline__ constexpr int img_swz(int row) {
+  const int t = (row >> 1) & 7;
+  return ((t & 1) << 2) | (t >> 1);
+}
+// requests rows [0, rows_pad) of a [nrows, 64] matrix (row stride ld elements) into the image at `img`; the
+// wave-wide loads are dealt to the nw waves round-robin
+__device__ __forceinline__ void img_request(unsigned char* img, const bf16* __restrict__ src, int64_t ld, int nrows, int rows_pad,
+                                            int wave, int nw, int lane) {
+  for (int i = wave; i < (rows_pad >> 3); i += nw) {
+    const int row = 8 * i + (lane >> 3);
+    const int c = (lane & 7) ^ img_swz(row);
+    const int rc = row < nrows ? row : nrows - 1;
+    __builtin_amdgcn_global_load_lds(PT_GLB(src + (int64_t)rc * ld + 8 * c), PT_LDS(img + i * 1024), 16, 0, 0);
+  }
+}
+// the four 16-byte fragments (features 16 ks + 8 half .. + 7, ks = 0..3) of the lane's row: rb is the lane's
+// offset of chunk `half` in a 32-row tile, base the tile's LDS address
+__device__ __forceinline__ void img_rows_issue(unsigned base, unsigned rb, bf16x8 (&f)[4]) {
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f[0]) : "v"(base + rb));
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f[1]) : "v"(base + (rb ^ 32u)));
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f[2]) : "v"(base + (rb ^ 64u)));
+  asm volatile("ds_read_b128 %0, %1" : "=v"(f[3]) : "v"(base + (rb ^ 96u)));
+}
+// the same reads from address registers that the caller advances by one tile per iteration: a[ks] is the
+// address of the lane's chunk (2 ks + half) in the current tile, t[] the four transposed-read addresses
+// {dt = 0, dt = 1} x {rows 0..7, rows 8..15}; delta moves to the neighbouring image of a pair
+__device__ __forceinline__ void img_rows_issue_at(const unsigned (&a)[4], unsigned delta, bf16x8 (&f)[4]) {
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) asm volatile("ds_read_b128 %0, %1" : "=v"(f[ks]) : "v"(a[ks] + delta));
+}
+template <int KS2>
+__device__ __forceinline__ void img_cols_tr_at(unsigned a0, unsigned a1, bf16x8& f) {
+  union { u32x2 h[2]; bf16x8 v; } t;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[0]) : "v"(a0), "n"(KS2 * 16 * kImgRowBytes));
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(t.h[1]) : "v"(a1), "n"(KS2 * 16 * kImgRowBytes + 8 * kImgRowBytes));
+  f = t.v;
+}
+__device__ __forceinline__ f32x4v lds_read_f4(unsigned addr) {
+  f32x4v r;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(r) : "v"(addr));
+  return r;
+}
+
+// A wave's [32 rows x 64] result (accumulator pair: feature rows, owned column) goes out through the wave's
+// own 32 rows of an image that nobody reads any more: written as 8-byte pieces in the image layout, read back
+// eight rows per instruction and stored as whole 128-byte lines (the direct form, 8 bytes per lane and
+// instruction, touches every line sixteen times).  Only the wave itself touches these LDS rows, and LDS
+// operations of a wave complete in order, so no barrier is involved.  tile_a = LDS address of the wave's row 0.
+__device__ __forceinline__ void store_rows_staged(unsigned tile_a, const f32x16 (&acc)[2], float mul, bf16* __restrict__ gbase,
+                                                  int64_t ld, int row0, int S, int lane) {
+  asm volatile("" : "+v"(lane));   // recompute the addresses here: hoisted, they would occupy registers over the passes
+  const int r = lane & 31, half = lane >> 5;
+  if (row0 + r < S) {   // rows past the end may lie outside the image
+    const unsigned wa = tile_a + r * kImgRowBytes + 8 * half;
+    const unsigned f = img_swz(r);
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        union { bf16 h[4]; u32x2 u; } t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t.h[e] = from_f32<bf16>(acc[dt][4 * g4 + e] * mul);
+        asm volatile("ds_write_b64 %0, %1" ::"v"(wa + (((4 * dt + g4) ^ f) << 4)), "v"(t.u) : "memory");
+      }
+  }
+  typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+  u32x4v d[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d[j]) : "v"(tile_a + lane * 16), "n"(j * 1024) : "memory");
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    asm volatile("" : "+v"(d[j]));
+    const int row = row0 + 8 * j + (lane >> 3);
+    const int ch = (lane & 7) ^ img_swz(row);
+    if (row < S) *reinterpret_cast<u32x4v*>(gbase + (int64_t)row * ld + 8 * ch) = d[j];
+  }
+}
+
+__global__ __launch_bounds__(512) void attn_bwd_pipe_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
+                                                            const bf16* __restrict__ dctx, const float* __restrict__ lse,
+                                                            bf16* __restrict__ dqkv, int S, int H, int ntile, int rows_pad,
+                                                            int nheads) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int img_bytes = rows_pad * kImgRowBytes;
+  float* ls = reinterpret_cast<float*>(smem + 6 * img_bytes + kImgPadBytes);   // row log-sum-exp in the log2 domain
+  float* dls = ls + ntile * 32;                                                // row delta
+  const int D = H * DH;
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // one wave per 32 rows
+  const int own = wave * 32 + (lane & 31);                     // the row this lane owns, as a query and as a key
+  const bool ok = own < S;
+  const int ownc = ok ? own : S - 1;
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+  // per-lane offsets inside a 32-row tile of an image
+  const unsigned rb = (unsigned)((lane & 31) * kImgRowBytes + ((half ^ img_swz(lane & 31)) << 4));
+  unsigned tr;
+  {
+    const int l16 = lane & 15, grp = lane >> 4;
+    const int row = 4 * (grp >> 1) + (l16 >> 2), ch = 2 * (grp & 1) + ((l16 & 3) >> 1);
+    tr = (unsigned)(row * kImgRowBytes + ((ch ^ img_swz(row)) << 4) + (l16 & 1) * 8);
+  }
+  const unsigned smem_a = lds_addr(smem);
+  const unsigned ls_a = lds_addr(ls), dls_a = lds_addr(dls);
+  const unsigned own_tile = wave * (32 * kImgRowBytes);   // the wave's own rows inside an image
+  // A wave requests its own 32 rows of an image (four wave-wide loads of eight rows): rows [0, rows_pad) of
+  // a [S, 64] matrix at src with row stride ld; rows past the end are copies of row S - 1.
+  auto request_own = [&](int slot, const bf16* __restrict__ src, int ld) {
+    int lane = tid & 63;
+    asm volatile("" : "+v"(lane));   // recompute the addresses here: hoisted, they would occupy registers over the passes
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int row0 = 32 * wave + 8 * j;
+      if (row0 < rows_pad) {
+        const int row = row0 + (lane >> 3);
+        const int ch = (lane & 7) ^ img_swz(row);
+        const int rc = row < S ? row : S - 1;
+        __builtin_amdgcn_global_load_lds(PT_GLB(src + (int64_t)rc * ld + 8 * ch),
+                                         PT_LDS(smem + slot * img_bytes + (4 * wave + j) * 1024), 16, 0, 0);
+      }
+    }
+  };
+
+  // zero the images and the pad once (see above); no load is in flight yet
+  for (int i = tid; i < (6 * img_bytes + kImgPadBytes) / 16; i += blockDim.x)
+    reinterpret_cast<uint4*>(smem)[i] = make_uint4(0, 0, 0, 0);
+  __syncthreads();
+
+  int head = blockIdx.x;
+  if (head >= nheads) return;
+  int pq = 0;   // pair of the current head's Q and dO images; K and V are in pair pq + 1, pair pq + 2 is free
+  union Frag { uint4 u; bf16x8 v; };
+  Frag of_[4];
+  float lse_own;
+  {
+    const int b = head / H, h = head - b * H;
+    const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
+    request_own(0, base, 3 * D);
+    request_own(1, dctx + (int64_t)b * S * D + h * DH, D);
+    request_own(2, base + D, 3 * D);
+    request_own(3, base + 2 * D, 3 * D);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      of_[ks].u = *reinterpret_cast<const uint4*>(ctx + ((int64_t)b * S + ownc) * D + h * DH + ks * 16 + half * 8);
+    lse_own = lse[((int64_t)b * H + h) * S + ownc];
+  }
+  f32x16 dk[2], dv[2];       // the previous head's dK and dV wait here until its Q and dO images are free
+  bf16* obase_prev = nullptr;
+
+  for (;;) {
+    const int b = head / H, h = head - b * H;
+    bf16* obase = dqkv + (int64_t)b * S * 3 * D + h * DH;
+    const int pk = pq == 2 ? 0 : pq + 1, pf = pk == 2 ? 0 : pk + 1;
+    const unsigned q_a = smem_a + 2 * pq * img_bytes, do_a = q_a + img_bytes;
+    const unsigned k_a = smem_a + 2 * pk * img_bytes, v_a = k_a + img_bytes;
+    const unsigned f_a = smem_a + 2 * pf * img_bytes;
+    const int next = head + gridDim.x;
+    const bool has_next = next < nheads;
+    const int nb_ = next / H, nh_ = next - nb_ * H;
+    const bf16* nbase = qkv + (int64_t)nb_ * S * 3 * D + nh_ * DH;
+
+    // ---- head start: the four images (and the lane's O row) have arrived ----
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();   // and nobody reads the previous head's Q and dO images (the free pair) any more
+    asm volatile("" ::: "memory");
+    if (obase_prev) {
+      store_rows_staged(f_a + own_tile, dk, scale, obase_prev + D, 3 * D, 32 * wave, S, lane);
+      store_rows_staged(f_a + img_bytes + own_tile, dv, 1.0f, obase_prev + 2 * D, 3 * D, 32 * wave, S, lane);
+    }
+    if (has_next) {
+      request_own(2 * pf, nbase + D, 3 * D);
+      request_own(2 * pf + 1, nbase + 2 * D, 3 * D);
+    }
+    bf16x8 qf[4], dof[4];
+    img_rows_issue(q_a + own_tile, rb, qf);
+    img_rows_issue(do_a + own_tile, rb, dof);
+    lds_wait<0>(qf);
+    lds_wait<0>(dof);
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of_[ks].v[i]);
+    const float dl = part + __shfl_xor(part, 32, 64);
+    // a row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
+    const float lq2 = ok ? lse_own * 1.44269504088896f : INFINITY;
+    if (half == 0) {
+      ls[own] = lq2;
+      dls[own] = ok ? dl : 0.f;
+    }
+
+    // ---- pass 1: the wave's rows as queries ----
+    f32x16 dq[2];
+    {
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dq[dt][v] = 0.f;
+      // addresses of the current tile's fragments in the K image, advanced once per tile (V = K + one image)
+      unsigned ka[4] = {k_a + rb, k_a + (rb ^ 32u), k_a + (rb ^ 64u), k_a + (rb ^ 96u)};
+      unsigned kta[4] = {k_a + tr, k_a + (tr ^ 64u), k_a + (tr ^ 32u), k_a + (tr ^ 96u)};
+      for (int kt = 0; kt < ntile; ++kt) {
+        bf16x8 kr[4], vr[4], kc[4];
+        img_rows_issue_at(ka, 0u, kr);
+        img_rows_issue_at(ka, (unsigned)img_bytes, vr);
+        f32x16 s, dp;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        lds_wait<4>(kr);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kr[ks], qf[ks], s, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dp[v] = 0.f;
+        lds_wait<0>(vr);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vr[ks], dof[ks], dp, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        img_cols_tr_at<0>(kta[0], kta[2], kc[0]);
+        img_cols_tr_at<0>(kta[1], kta[3], kc[1]);
+        img_cols_tr_at<1>(kta[0], kta[2], kc[2]);
+        img_cols_tr_at<1>(kta[1], kta[3], kc[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { ka[i] += 32 * kImgRowBytes; kta[i] += 32 * kImgRowBytes; }
+        if (kt == ntile - 1 && (S & 31)) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) s[v] = (kt * 32 + acc_row(v, half) < S) ? s[v] : -INFINITY;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float p = fast_exp2(fmaf(s[v], c, -lq2));
+          s[v] = p * (dp[v] - dl);  // dS^T
+        }
+        lds_wait<0>(kc);
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const bf16x8 dsb = pack8(s, 8 * ks2);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kc[2 * ks2 + dt], dsb, dq[dt], 0, 0, 0);
+        }
+      }
+    }
+
+    // ---- pass 2: the wave's rows as keys ----
+    bf16x8 kf[4], vf[4];
+    img_rows_issue(k_a + own_tile, rb, kf);
+    img_rows_issue(v_a + own_tile, rb, vf);
+    lds_wait<0>(kf);
+    lds_wait<0>(vf);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // ls / dls are written
+    __builtin_amdgcn_s_barrier();                          // nobody reads this head's K and V images any more
+    asm volatile("" ::: "memory");
+    store_rows_staged(k_a + own_tile, dq, scale, obase, 3 * D, 32 * wave, S, lane);
+    if (has_next) {
+      request_own(2 * pk, nbase, 3 * D);
+      request_own(2 * pk + 1, dctx + (int64_t)nb_ * S * D + nh_ * DH, D);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        of_[ks].u = *reinterpret_cast<const uint4*>(ctx + ((int64_t)nb_ * S + ownc) * D + nh_ * DH + ks * 16 + half * 8);
+      lse_own = lse[((int64_t)nb_ * H + nh_) * S + ownc];
+    }
+    {
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { dk[dt][v] = 0.f; dv[dt][v] = 0.f; }
+      unsigned qa[4] = {q_a + rb, q_a + (rb ^ 32u), q_a + (rb ^ 64u), q_a + (rb ^ 96u)};   // dO = Q + one image
+      unsigned qta[4] = {q_a + tr, q_a + (tr ^ 64u), q_a + (tr ^ 32u), q_a + (tr ^ 96u)};
+      for (int qt = 0; qt < ntile; ++qt) {
+        // The dO columns and the Q columns share four registers' worth of fragments each in turn, and the
+        // rows' log-sum-exp and delta come in two at a time: the pass keeps 64 accumulator registers and the
+        // wave's own K and V rows, and there must be room left for the next head's O row.
+        bf16x8 qr[4], dor[4], tc[4];
+        img_rows_issue_at(qa, 0u, qr);
+        img_rows_issue_at(qa, (unsigned)img_bytes, dor);
+        img_cols_tr_at<0>(qta[0] + img_bytes, qta[2] + img_bytes, tc[0]);
+        img_cols_tr_at<0>(qta[1] + img_bytes, qta[3] + img_bytes, tc[1]);
+        img_cols_tr_at<1>(qta[0] + img_bytes, qta[2] + img_bytes, tc[2]);
+        img_cols_tr_at<1>(qta[1] + img_bytes, qta[3] + img_bytes, tc[3]);
+        f32x16 s, dp;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+        lds_wait<8>(qr);
+        lds_wait<8>(dor);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qr[ks], kf[ks], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dor[ks], vf[ks], dp, 0, 0, 0);
+        }
+        f32x16 pr;
+        const unsigned l_a = ls_a + (qt * 32 + 4 * half) * 4, d_a = dls_a + (qt * 32 + 4 * half) * 4;
+        f32x4v lc = lds_read_f4(l_a), dc = lds_read_f4(d_a);
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          f32x4v ln = lc, dn = dc;
+          if (g4 + 1 < 4) {
+            ln = lds_read_f4(l_a + 32 * (g4 + 1));
+            dn = lds_read_f4(d_a + 32 * (g4 + 1));
+            asm volatile("s_waitcnt lgkmcnt(2)" ::: "memory");
+          } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          }
+          asm volatile("" : "+v"(lc), "+v"(dc));
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int v = 4 * g4 + e;
+            const float p = fast_exp2(fmaf(s[v], c, -lc[e]));
+            pr[v] = p;
+            s[v] = p * (dp[v] - dc[e]);  // dS
+          }
+          lc = ln;
+          dc = dn;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) asm volatile("" : "+v"(tc[i]));   // everything issued so far has arrived
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const bf16x8 pb = pack8(pr, 8 * ks2);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[2 * ks2 + dt], pb, dv[dt], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        img_cols_tr_at<0>(qta[0], qta[2], tc[0]);
+        img_cols_tr_at<0>(qta[1], qta[3], tc[1]);
+        img_cols_tr_at<1>(qta[0], qta[2], tc[2]);
+        img_cols_tr_at<1>(qta[1], qta[3], tc[3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { qa[i] += 32 * kImgRowBytes; qta[i] += 32 * kImgRowBytes; }
+        lds_wait<0>(tc);
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2) {
+          const bf16x8 dsb = pack8(s, 8 * ks2);
+#pragma unroll
+          for (int dt = 0; dt < 2; ++dt) dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tc[2 * ks2 + dt], dsb, dk[dt], 0, 0, 0);
+        }
+      }
+    }
+    obase_prev = obase;
+    if (!has_next) break;
+    head = next;
+    pq = pk;
+  }
+  // the last head's dK and dV: through its Q and dO images once every wave is done with them
+  {
+    const unsigned q_a = smem_a + 2 * pq * img_bytes;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    store_rows_staged(q_a + own_tile, dk, scale, obase_prev + D, 3 * D, 32 * wave, S, lane);
+    store_rows_staged(q_a + img_bytes + own_tile, dv, 1.0f, obase_prev + 2 * D, 3 * D, 32 * wave, S, lane);
+  }
+}
+
 // Sequence lengths the resident kernels take (the LDS image of two [S,64] matrices and two float rows must
 // fit in 160 KB, i.e. S <= 512).  Measured: forward wins at S = 197 (25 vs 33 us per layer at ViT-B, batch
 // 64) but loses at S = 384, where only one workgroup fits a CU (44 vs 39 us); backward wins at both.
 constexpr int g_attn_resident_max_s = 224;
 constexpr int g_attn_resident_max_s_bwd = 512;
 constexpr int g_attn_fused_max_s_bwd = 256;   // four [S,64] images and two float rows in 160 KB, eight waves
+#ifdef PT_TUNING_HOOKS   // stand-alone experiments only; the library is built without it
+int g_attn_bwd_pipe = 1;
+#else
+constexpr int g_attn_bwd_pipe = 1;            // the pipelined fused backward where its six images fit (S <= 208)
+#endif
 struct ResPlan { int ntile, nw, nblk; size_t lds; };
 ResPlan resident_plan(int S, bool with_rows) {
   ResPlan r;
@@ -931,6 +1317,18 @@ ResPlan resident_plan(int S, bool with_rows) {
   r.lds = (size_t)2 * r.ntile * 32 * LDR * sizeof(bf16) + (with_rows ? (size_t)2 * r.ntile * 32 * sizeof(float) : 0);
   return r;
 }
+// compute units of the current device (0 if the query fails); asked once per device
+int device_cu_count() {
+  static int count[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (count[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+    count[dev] = n > 0 ? n : -1;
+  }
+  return count[dev] > 0 ? count[dev] : 0;
+}
 template <typename K>
 hipError_t allow_lds(K kernel, size_t bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
@@ -938,6 +1336,9 @@ hipError_t allow_lds(K kernel, size_t bytes) {
 
 }  // namespace
 
+#ifdef PT_TUNING_HOOKS
+void attention_set_bwd_pipe(int v) { g_attn_bwd_pipe = v; }
+#endif
 void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, int H, hipStream_t st) {
   if (S <= g_attn_resident_max_s) {
     const ResPlan r = resident_plan(S, false);
@@ -953,6 +1354,24 @@ void attention_fwd_mfma(const void* qkv, void* ctx, float* lse, int nb, int S, i
 }
 void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, const float* lse, void* dqkv, float* delta,
                         int nb, int S, int H, hipStream_t st) {
+  {
+    // The pipelined kernel where it pays: its six unpadded images, the pad and the two float rows must fit in
+    // 160 KB (S <= 208); the fused kernel below must be down to one workgroup per CU (from 129 rows on: with
+    // shorter sequences several of its workgroups share a CU and overlap each other's loads anyway; measured
+    // 10.5 against 11.1 us at S = 128); and there must be more heads than CUs, or no workgroup has a next head.
+    const int ntile = cdiv(S, 32), rows_pad = 16 * cdiv(S, 16);
+    const size_t lds = (size_t)6 * rows_pad * kImgRowBytes + kImgPadBytes + (size_t)2 * ntile * 32 * sizeof(float);
+    const int cus = device_cu_count();
+    const int nheads = nb * H;
+    if (g_attn_bwd_pipe && ntile >= 5 && ntile <= 8 && lds <= 160 * 1024 && cus > 0 && nheads > cus &&
+        allow_lds(attn_bwd_pipe_kernel, lds) == hipSuccess) {
+      hipLaunchKernelGGL(attn_bwd_pipe_kernel, dim3(nheads < cus ? nheads : cus), dim3(64 * ntile), lds, st,
+                         (const bf16*)qkv, (const bf16*)ctx, (const bf16*)dctx, lse, (bf16*)dqkv, S, H, ntile, rows_pad,
+                         nheads);
+      return;
+    }
+    (void)hipGetLastError();
+  }
   if (S <= g_attn_fused_max_s_bwd) {
     const int ntile = cdiv(S, 32);
     const size_t lds = (size_t)4 * ntile * 32 * LDR * sizeof(bf16) + (size_t)2 * ntile * 32 * sizeof(float);
