@@ -1146,6 +1146,10 @@ __global__ __launch_bounds__(512) void attn_bwd_pipe_kernel(const bf16* __restri
       unsigned ka[4] = {k_a + rb, k_a + (rb ^ 32u), k_a + (rb ^ 64u), k_a + (rb ^ 96u)};
       unsigned kta[4] = {k_a + tr, k_a + (tr ^ 64u), k_a + (tr ^ 32u), k_a + (tr ^ 96u)};
       for (int kt = 0; kt < ntile; ++kt) {
+        // The two waves of a SIMD take turns at the higher priority, tile by tile: with equal priorities the
+        // older wave is served first throughout, finishes its pass early and leaves the younger one to run
+        // the rest alone, one dependent instruction after the other.
+        if ((kt ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         bf16x8 kr[4], vr[4], kc[4];
         img_rows_issue_at(ka, 0u, kr);
         img_rows_issue_at(ka, (unsigned)img_bytes, vr);
@@ -1213,6 +1217,7 @@ __global__ __launch_bounds__(512) void attn_bwd_pipe_kernel(const bf16* __restri
       unsigned qa[4] = {q_a + rb, q_a + (rb ^ 32u), q_a + (rb ^ 64u), q_a + (rb ^ 96u)};   // dO = Q + one image
       unsigned qta[4] = {q_a + tr, q_a + (tr ^ 64u), q_a + (tr ^ 32u), q_a + (tr ^ 96u)};
       for (int qt = 0; qt < ntile; ++qt) {
+        if ((qt ^ (wave >> 2)) & 1) __builtin_amdgcn_s_setprio(1); else __builtin_amdgcn_s_setprio(0);
         // The dO columns and the Q columns share four registers' worth of fragments each in turn, and the
         // rows' log-sum-exp and delta come in two at a time: the pass keeps 64 accumulator registers and the
         // wave's own K and V rows, and there must be room left for the next head's O row.
