@@ -120,9 +120,93 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const TX* __restrict__ x, i
   }
 }
 
+// bf16 rows whose length is a multiple of 256: half a wave per row, so that a lane moves 16 bytes per access
+// (8-byte accesses, which the one-wave-per-row kernel makes on bf16 rows, reach 4.4 TB/s on this pass)
+template <int VPL>
+__global__ __launch_bounds__(256) void ln_fwd_half_kernel(const bf16* __restrict__ x, int64_t ldx, const bf16* __restrict__ gamma,
+                                                          const bf16* __restrict__ beta, bf16* __restrict__ y, int64_t ldy,
+                                                          float* __restrict__ mean, float* __restrict__ rstd, int rows, int D,
+                                                          float eps) {
+  const int lane = threadIdx.x & 31;
+  auto cvt = [](const uint4& r, float (&v)[8]) {
+    v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+    v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+    v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+    v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+  };
+  auto half_sum = [](float v) {
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+  };
+  uint4 gr[VPL], br[VPL];
+#pragma unroll
+  for (int j = 0; j < VPL; ++j) {
+    gr[j] = *reinterpret_cast<const uint4*>(gamma + 8 * (lane + 32 * j));
+    br[j] = *reinterpret_cast<const uint4*>(beta + 8 * (lane + 32 * j));
+  }
+  const int stride = gridDim.x * 16;   // eight half-waves per workgroup, two rows per half-wave in flight
+  int row = blockIdx.x * 8 + (threadIdx.x >> 5);
+  const int step = gridDim.x * 8;
+  uint4 cur[VPL], nxt[VPL];
+  (void)stride;
+  auto fetch = [&](int r, uint4 (&in)[VPL]) {
+    const int rc = r < rows ? r : rows - 1;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) in[j] = *reinterpret_cast<const uint4*>(x + (int64_t)rc * ldx + 8 * (lane + 32 * j));
+  };
+  fetch(row, cur);
+  // both half-waves of a wave run the same number of iterations (the shuffles need all lanes present)
+  const int base_row = blockIdx.x * 8 + ((threadIdx.x >> 6) << 1);
+  for (int r0 = base_row; r0 < rows; r0 += step, row += step) {
+    fetch(row + step, nxt);
+    float v[VPL][8];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) {
+      cvt(cur[j], v[j]);
+      s += ((v[j][0] + v[j][1]) + (v[j][2] + v[j][3])) + ((v[j][4] + v[j][5]) + (v[j][6] + v[j][7]));
+    }
+    const float mu = half_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < VPL; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { const float d = v[j][e] - mu; q += d * d; }
+    const float rs = rsqrtf(half_sum(q) / (float)D + eps);
+    if (row < rows) {
+      if (lane == 0 && mean) { mean[row] = mu; rstd[row] = rs; }
+      bf16* yr = y + (int64_t)row * ldy;
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) {
+        float g[8], b[8];
+        cvt(gr[j], g);
+        cvt(br[j], b);
+        union { bf16 h[8]; uint4 u; } t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t.h[e] = from_f32<bf16>((v[j][e] - mu) * rs * g[e] + b[e]);
+        *reinterpret_cast<uint4*>(yr + 8 * (lane + 32 * j)) = t.u;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < VPL; ++j) cur[j] = nxt[j];
+  }
+}
+
 void layernorm_fwd(int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
                    int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
   if (rows <= 0) return;
+  if (dt != 0 && !x_f32 && (D == 768 || D == 1024) && ldx % 8 == 0 && ldy % 8 == 0 &&
+      ((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma | (uintptr_t)beta) % 16 == 0) {
+    const dim3 g(cdiv(rows, 8) < kLnFwdBlocks ? cdiv(rows, 8) : kLnFwdBlocks), b(256);
+    if (D == 768)
+      hipLaunchKernelGGL((ln_fwd_half_kernel<3>), g, b, 0, st, (const bf16*)x, ldx, (const bf16*)gamma, (const bf16*)beta,
+                         (bf16*)y, ldy, mean, rstd, rows, D, eps);
+    else
+      hipLaunchKernelGGL((ln_fwd_half_kernel<4>), g, b, 0, st, (const bf16*)x, ldx, (const bf16*)gamma, (const bf16*)beta,
+                         (bf16*)y, ldy, mean, rstd, rows, D, eps);
+    return;
+  }
   dim3 grid(cdiv(rows, 4) < kLnFwdBlocks ? cdiv(rows, 4) : kLnFwdBlocks), blk(256);
 #define LN_FWD(T, TX, V)                                                                                  \
   hipLaunchKernelGGL((ln_fwd_kernel<T, TX, V>), grid, blk, 0, st, (const TX*)x, ldx, (const T*)gamma, \
