@@ -269,29 +269,7 @@ __global__ __launch_bounds__(C::NT, 4) void gemm_mfma_kernel(GemmDev<bf16> g, Sp
                                                             m0 + wm * C::WTM, n0 + wn * C::WTN, lane, vec_ok);
 }
 
-typedef float f32x4_nt __attribute__((ext_vector_type(4)));
-// out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread).  A second, short
-// vector (the column-sum partials of the same product) may ride along in the last workgroups.
-__device__ __forceinline__ void splitk_sum4(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
-                                            int vec, int64_t i) {
-  if (vec && i + 3 < n) {
-    float4 s = *reinterpret_cast<const float4*>(part + i);
-    for (int z = 1; z < splits; ++z) {
-      const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)z * n + i);
-      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-    }
-    // a weight gradient is next read by the norm and update passes, after the rest of the backward pass
-    // has gone through the caches: stored past them
-    f32x4_nt o; o.x = s.x; o.y = s.y; o.z = s.z; o.w = s.w;
-    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_nt*>(out + i));
-  } else {
-    for (int64_t j = i; j < n && j < i + 4; ++j) {
-      float s = part[j];
-      for (int z = 1; z < splits; ++z) s += part[(int64_t)z * n + j];
-      out[j] = s;
-    }
-  }
-}
+// A second, short vector (the column-sum partials of the same product) may ride along in the last workgroups.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
                                                             float* __restrict__ out, int vec, int blocks_main,
                                                             const float* __restrict__ part2, int64_t n2,
@@ -304,9 +282,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
   }
 }
 
-static int vec_ok4(const float* part, int64_t n, const float* out) {
+int splitk_vec_ok4(const float* part, int64_t n, const float* out) {
   return (n % 4 == 0 && (reinterpret_cast<uintptr_t>(part) % 16) == 0 && (reinterpret_cast<uintptr_t>(out) % 16) == 0) ? 1 : 0;
 }
+static int vec_ok4(const float* part, int64_t n, const float* out) { return splitk_vec_ok4(part, n, out); }
 void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, const float* part2, int64_t n2, float* out2,
                         hipStream_t st) {
   const int blocks_main = (int)cdiv64(n, 1024);
@@ -515,12 +494,20 @@ void gemm(int dt, const Gemm& a, hipStream_t st) {
   if (a.colsum_out && a.ta && !a.tb && a.ws) colsum(dt, a.B, a.ldb, a.K, a.N, a.colsum_out, a.ws, st);
 }
 
-void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid) {
+void gemm_wgrad_flush(WgradCarry* carry, hipStream_t st) {
+  if (!carry || carry->nprob <= 0) return;
+  gemm_splitk_reduce_group(carry->nprob, carry->splits, carry->part, carry->n, carry->out, carry->part2, carry->n2,
+                           carry->out2, st);
+  carry->nprob = 0;
+}
+
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry) {
   if (n <= 0) return;
   bool mfma = dt != 0 && g_cfg_override != 0;
   for (int i = 0; i < n && mfma; ++i) mfma = gemm_uses_mfma(dt, g[i]);
   // one product alone goes to the grouped kernel too when its contraction is long (the tokens of a batch)
-  if (mfma && (n > 1 || g[0].K >= 2048) && gemm_wgrad_group(g, n, st, mid)) return;
+  if (mfma && (n > 1 || g[0].K >= 2048) && gemm_wgrad_group(g, n, st, mid, carry)) return;
+  gemm_wgrad_flush(carry, st);
   for (int i = 0; i < n; ++i) gemm(dt, g[i], st);
   if (mid) (void)hipEventRecord(mid, st);
 }

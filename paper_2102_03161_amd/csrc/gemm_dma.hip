@@ -540,10 +540,29 @@ struct GroupArgs {
   int tiles_n[kMaxGroup];
   int vec_ok[kMaxGroup];
   int nprob, splits, tiles_per_split;
+  // the slab reduction of an earlier launch, done by the workgroups behind this launch's own
+  const float* c_part[kMaxGroup]; float* c_out[kMaxGroup]; int64_t c_n[kMaxGroup];
+  const float* c_part2[kMaxGroup]; float* c_out2[kMaxGroup]; int64_t c_n2[kMaxGroup];
+  int c_vec[kMaxGroup], c_vec2[kMaxGroup];
+  int c_nprob, c_splits;
 };
 __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
   const int total_tiles = ga.tile0[ga.nprob], total_work = total_tiles * ga.splits;
   const int per = (total_work + 7) >> 3;
+  if ((int)blockIdx.x >= 8 * per) {
+    // One encoder block's tiles leave 40 of the 256 CUs without a workgroup.  The workgroups placed there sum
+    // the split-K slabs that the previous launch left behind (85 MB of streaming beside a launch that is bound
+    // by its matrix work), which therefore needs no launch of its own.
+    const int64_t first = ((int64_t)((int)blockIdx.x - 8 * per) * 512 + threadIdx.x) * 4;
+    const int64_t step = (int64_t)((int)gridDim.x - 8 * per) * 512 * 4;
+    for (int p = 0; p < ga.c_nprob; ++p) {
+      for (int64_t i = first; i < ga.c_n[p]; i += step) splitk_sum4(ga.c_part[p], ga.c_splits, ga.c_n[p], ga.c_out[p], ga.c_vec[p], i);
+      if (ga.c_part2[p])
+        for (int64_t i = first; i < ga.c_n2[p]; i += step)
+          splitk_sum4(ga.c_part2[p], ga.c_splits, ga.c_n2[p], ga.c_out2[p], ga.c_vec2[p], i);
+    }
+    return;
+  }
   const int work = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
   if (work >= total_work) return;
   const int split = work / total_tiles;
@@ -704,7 +723,7 @@ static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
   }
 }
 
-bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid) {
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry) {
   if (n < 1 || n > kMaxGroup) return false;
   int64_t total = 0, per_split = 0;
   for (int i = 0; i < n; ++i) {
@@ -746,20 +765,39 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid) {
     if (splits > 1) ws += splits * (mn + m.N);
   }
   ga.tile0[n] = t0;
-  hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(8 * cdiv(t0 * splits, 8)), dim3(512), 0, st, ga);
+  const int own = 8 * cdiv(t0 * splits, 8);
+  // a carried reduction rides on the workgroups that fit beside this launch's own (one per CU, 256 CUs), in
+  // multiples of eight (one per XCD); with fewer than eight to spare it runs on its own first
+  int extra = 0;
+  if (carry && carry->nprob > 0) {
+    extra = ((256 - own) / 8) * 8;
+    if (extra < 8) {
+      gemm_wgrad_flush(carry, st);
+      extra = 0;
+    } else {
+      ga.c_nprob = carry->nprob;
+      ga.c_splits = carry->splits;
+      for (int i = 0; i < carry->nprob; ++i) {
+        ga.c_part[i] = carry->part[i]; ga.c_out[i] = carry->out[i]; ga.c_n[i] = carry->n[i];
+        ga.c_vec[i] = splitk_vec_ok4(carry->part[i], carry->n[i], carry->out[i]);
+        ga.c_part2[i] = carry->part2[i]; ga.c_out2[i] = carry->out2[i]; ga.c_n2[i] = carry->part2[i] ? carry->n2[i] : 0;
+        ga.c_vec2[i] = carry->part2[i] ? splitk_vec_ok4(carry->part2[i], carry->n2[i], carry->out2[i]) : 0;
+      }
+      carry->nprob = 0;
+    }
+  }
+  hipLaunchKernelGGL(gemm_wgrad_group_kernel, dim3(own + extra), dim3(512), 0, st, ga);
   if (mid) (void)hipEventRecord(mid, st);
   if (splits > 1) {
-    int64_t mn[kMaxGroup], nn[kMaxGroup];
-    float* out[kMaxGroup];
-    float* out2[kMaxGroup];
+    WgradCarry now;
+    now.nprob = n;
+    now.splits = splits;
     for (int i = 0; i < n; ++i) {
-      mn[i] = (int64_t)a[i].M * a[i].N;
-      nn[i] = a[i].N;
-      out[i] = (float*)a[i].C;
-      out2[i] = a[i].colsum_out;
-      if (!a[i].colsum_out) cpart[i] = nullptr;
+      now.part[i] = part[i]; now.out[i] = (float*)a[i].C; now.n[i] = (int64_t)a[i].M * a[i].N;
+      now.part2[i] = a[i].colsum_out ? cpart[i] : nullptr; now.out2[i] = a[i].colsum_out; now.n2[i] = a[i].N;
     }
-    gemm_splitk_reduce_group(n, splits, part, mn, out, cpart, nn, out2, st);
+    if (carry) *carry = now;               // summed by the next launch or by gemm_wgrad_flush
+    else gemm_wgrad_flush(&now, st);
   }
   return true;
 }

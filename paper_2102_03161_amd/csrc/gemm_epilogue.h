@@ -217,6 +217,29 @@ __device__ __forceinline__ void staged_epilogue(const GemmDev<bf16>& g, void* Cb
   }
 }
 
+typedef float f32x4_st __attribute__((ext_vector_type(4)));   // operand type of the nontemporal store builtin
+// out[i] = sum over splits of part[z][i], z in increasing order (4 floats per thread).
+__device__ __forceinline__ void splitk_sum4(const float* __restrict__ part, int splits, int64_t n, float* __restrict__ out,
+                                            int vec, int64_t i) {
+  if (vec && i + 3 < n) {
+    float4 s = *reinterpret_cast<const float4*>(part + i);
+    for (int z = 1; z < splits; ++z) {
+      const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)z * n + i);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    // a weight gradient is next read by the norm and update passes, after the rest of the backward pass
+    // has gone through the caches: stored past them
+    f32x4_st o; o.x = s.x; o.y = s.y; o.z = s.z; o.w = s.w;
+    __builtin_nontemporal_store(o, reinterpret_cast<f32x4_st*>(out + i));
+  } else {
+    for (int64_t j = i; j < n && j < i + 4; ++j) {
+      float s = part[j];
+      for (int z = 1; z < splits; ++z) s += part[(int64_t)z * n + j];
+      out[j] = s;
+    }
+  }
+}
+
 // host side
 bool gemm_epilogue_vec_ok(const Gemm& a);
 void gemm_splitk_reduce(const float* part, int splits, int64_t n, float* out, const float* part2, int64_t n2, float* out2,
@@ -225,7 +248,8 @@ bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
 // few rows, long K, workspace given: split-K with a summing epilogue pass; false if the shape is not taken
 bool gemm_dma_skinny(const Gemm& a, hipStream_t st);
-bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid);
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry);
+int splitk_vec_ok4(const float* part, int64_t n, const float* out);
 // the split-K reductions of up to four products (part2 entries may be null) in one launch
 void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,
                               const float* const* part2, const int64_t* n2, float* const* out2, hipStream_t st);

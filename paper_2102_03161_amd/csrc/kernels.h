@@ -42,7 +42,18 @@ void gemm(int dt, const Gemm& g, hipStream_t st);
 // to fill the chip without a deep split over K); otherwise they run one after the other.
 // `mid` (may be null): an event recorded behind the product kernels and in front of the reduction of the
 // split-K slabs, so that a caller can time the two parts separately.
-void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid = nullptr);
+// `carry` (may be null): with it the reduction of this launch's split-K slabs is not launched but described
+// in *carry, and a reduction that *carry describes on entry is done by this launch, on workgroups added for
+// the CUs that its own tiles leave idle (or on its own first, if this launch cannot host it).  The weight
+// gradients of a launch are therefore final only after the next call with the same carry or after
+// gemm_wgrad_flush; successive calls must use different workspaces (the carried slabs stay where they are).
+struct WgradCarry {
+  int nprob = 0, splits = 0;
+  const float* part[4] = {}; float* out[4] = {}; int64_t n[4] = {};      // slabs -> weight gradient
+  const float* part2[4] = {}; float* out2[4] = {}; int64_t n2[4] = {};   // column-sum partials -> bias gradient (or null)
+};
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid = nullptr, WgradCarry* carry = nullptr);
+void gemm_wgrad_flush(WgradCarry* carry, hipStream_t st);
 // workspace floats gemm_wgrad_batch may use for a block's four matrices (D x 3D, D x D, D x F, F x D)
 size_t gemm_wgrad_batch_ws_floats(int D, int F);
 // true when gemm() will run the matrix-core kernel for this problem

@@ -218,7 +218,7 @@ void make_plan(const pt_config& c, Plan* p) {
       const int64_t splits = std::min<int64_t>(16, std::max<int64_t>(1, 1024 / tiles));
       need = std::max(need, (size_t)(splits * (sh[0] * sh[1] + sh[1])));
     }
-    need = std::max(need, gemm_wgrad_batch_ws_floats(D, F));
+    need = std::max(need, 2 * (gemm_wgrad_batch_ws_floats(D, F) + 64));   // two blocks' slabs (see run_wgrads)
     p->gemmws_floats = need;
     p->GEMMWS = take(need * 4);
   }
@@ -251,6 +251,8 @@ struct pt_ctx {
   float* mom2 = nullptr;
   float* gacc = nullptr;      // gradient accumulator over micro-batches (grad_accum configurations)
   std::vector<LnReduceJob> ln_jobs;   // LayerNorm backward passes whose partial sums are not summed yet
+  WgradCarry wgrad_carry;             // split-K slabs of the last block's weight gradients, not summed yet
+  int wgrad_parity = 0;               // which half of the GEMM workspace the next block's slabs go to
   int64_t acc_samples = 0;    // samples accumulated so far; 0 = no accumulation in progress
   char* work = nullptr;
   char* cache = nullptr;
@@ -332,6 +334,13 @@ struct ProfScope {
     if (r) (void)hipEventRecord(r->b, c->st);
   }
 };
+
+// the slab reduction that the last block's weight-gradient launch left for a successor
+void flush_wgrad_carry(pt_ctx* c) {
+  if (c->wgrad_carry.nprob <= 0) return;
+  ProfScope ps_(c, PT_PROF_SPLITK_REDUCE, 0.0);
+  gemm_wgrad_flush(&c->wgrad_carry, c->st);
+}
 
 // sums the partial rows of every LayerNorm backward pass enqueued since the last call (one launch)
 void flush_ln_reductions(pt_ctx* c) {
@@ -490,8 +499,15 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     // the four products of a whole block in the matrix-core path: the grouped kernel is timed on its own, the
     // reduction of its split-K slabs separately
     const bool grouped = nwg == 4 && gemm_cat(dt, wg[0]) == PT_PROF_GEMM_TN;
+    // Successive blocks alternate between the two halves of the workspace: the slabs of a split launch are
+    // summed by the next block's launch, on the CUs its tiles leave idle, or at the end of the sweep
+    // (flush_wgrad_carry), so they must survive that launch.
+    const size_t half = (p.gemmws_floats / 2) & ~(size_t)63;
+    float* ws = c->wf(p.GEMMWS) + (c->wgrad_parity ? half : 0);
+    c->wgrad_parity ^= 1;
+    for (int i = 0; i < nwg; ++i) { wg[i].ws = ws; wg[i].ws_floats = half; }
     ProfScope ps_(c, grouped ? PT_PROF_WGRAD_BLOCK : gemm_cat(dt, wg[0]), fl);
-    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr);
+    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr, &c->wgrad_carry);
   };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
@@ -1190,6 +1206,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   if (reinterpret_cast<uintptr_t>(d_hk) % 16) return fail(c, PT_EINVAL, "d_hk must be 16-byte aligned");
   { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
   c->ln_jobs.clear();
+  c->wgrad_carry.nprob = 0;
   const pt_config& g = c->cfg;
   const Plan& p = c->plan;
   const int L = g.L, D = g.D, S = g.S, k = c->k, nb = c->nb, dt = c->dt;
@@ -1277,6 +1294,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     else block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     std::swap(dcur, dnext);
   }
+  flush_wgrad_carry(c);   // in front of the front end's products, which use the same workspace
   if (k == 0) front_backward(c, dcur.s, nb);
   flush_ln_reductions(c);
   c->last_dhk = dcur.s;
