@@ -44,7 +44,7 @@ def build(force: bool = True, jobs: int = 4) -> str:
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h", "gemm_epilogue.h", "libpt.map")] + [os.path.join(HERE, "..", "include", "pt.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in ("common.h", "kernels.h", "gemm_epilogue.h", "ln_bwd_rows.h", "libpt.map")] + [os.path.join(HERE, "..", "include", "pt.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
     objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]

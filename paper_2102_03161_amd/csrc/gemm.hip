@@ -501,12 +501,13 @@ void gemm_wgrad_flush(WgradCarry* carry, hipStream_t st) {
   carry->nprob = 0;
 }
 
-void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry) {
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry, LnBwdRide* ln) {
+  if (ln) ln->taken_np = 0;
   if (n <= 0) return;
   bool mfma = dt != 0 && g_cfg_override != 0;
   for (int i = 0; i < n && mfma; ++i) mfma = gemm_uses_mfma(dt, g[i]);
   // one product alone goes to the grouped kernel too when its contraction is long (the tokens of a batch)
-  if (mfma && (n > 1 || g[0].K >= 2048) && gemm_wgrad_group(g, n, st, mid, carry)) return;
+  if (mfma && (n > 1 || g[0].K >= 2048) && gemm_wgrad_group(g, n, st, mid, carry, ln)) return;
   gemm_wgrad_flush(carry, st);
   for (int i = 0; i < n; ++i) gemm(dt, g[i], st);
   if (mid) (void)hipEventRecord(mid, st);

@@ -22,6 +22,7 @@
 #include "common.h"
 #include "kernels.h"
 #include "gemm_epilogue.h"
+#include "ln_bwd_rows.h"
 
 namespace pt {
 
@@ -344,6 +345,13 @@ void gemm_dma_kernel(GemmDev<bf16> g, SplitArgs sp, int tiles_m, int tiles_n,
 //
 // pp_run computes one output tile (rows m0.., columns n0..) over the k tiles kt0 .. kt0 + n - 1 and stores it
 // to slab `split`; all 512 threads of the workgroup take part.
+// the LDS of the two-group kernels: one array per size, so that a kernel's other roles can use the same bytes
+template <int BYTES>
+__device__ __forceinline__ unsigned char* pp_lds() {
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[BYTES];
+  return lds;
+}
+constexpr int kPpLdsBytes256 = 160 * 1024;   // 256-row tiles: three A stages and two B stages of 32 KB
 template <int BM, bool WHOLE, bool TA, bool TB, int EPI, typename TC>
 __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& sp, int split, int kt0, int n, int m0, int n0,
                                        int vec_ok) {
@@ -359,7 +367,8 @@ __device__ __forceinline__ void pp_run(const GemmDev<bf16>& g, const SplitArgs& 
   constexpr int KSF = 4 / NH;              // k-steps (MFMA depth 16) per half
   constexpr int NPART = 2 * NH - 1;        // A(t+2) goes out in this many parts, one per phase after the first
   static_assert(LA::LOADS >= NPART, "A loads are spread over the phases");
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
+  static_assert(BM != 256 || LDS_BYTES == kPpLdsBytes256, "kPpLdsBytes256 names the 256-row kernels' array");
+  unsigned char* const lds = pp_lds<LDS_BYTES>();
   unsigned char* const ldsB = lds + NSA * LA::BYTES;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -545,6 +554,9 @@ struct GroupArgs {
   const float* c_part2[kMaxGroup]; float* c_out2[kMaxGroup]; int64_t c_n2[kMaxGroup];
   int c_vec[kMaxGroup], c_vec2[kMaxGroup];
   int c_nprob, c_splits;
+  // a LayerNorm backward pass that is independent of the products, run by the same workgroups first
+  LnBwdArgs<bf16, bf16, bf16> ln;
+  int ln_on;
 };
 __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
   const int total_tiles = ga.tile0[ga.nprob], total_work = total_tiles * ga.splits;
@@ -553,6 +565,12 @@ __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
     // One encoder block's tiles leave 40 of the 256 CUs without a workgroup.  The workgroups placed there sum
     // the split-K slabs that the previous launch left behind (85 MB of streaming beside a launch that is bound
     // by its matrix work), which therefore needs no launch of its own.
+    // The same workgroups first run a LayerNorm backward pass that does not depend on these products (the
+    // block's last one, whose result only the next block reads): 135 MB more, still well inside what 40 CUs
+    // stream while the others work through their 98 k tiles.
+    if (ga.ln_on)
+      ln_bwd_rows<bf16, bf16, bf16, 3, 8>(ga.ln, reinterpret_cast<float*>(pp_lds<kPpLdsBytes256>()), (int)blockIdx.x - 8 * per,
+                                          (int)gridDim.x - 8 * per);
     const int64_t first = ((int64_t)((int)blockIdx.x - 8 * per) * 512 + threadIdx.x) * 4;
     const int64_t step = (int64_t)((int)gridDim.x - 8 * per) * 512 * 4;
     for (int p = 0; p < ga.c_nprob; ++p) {
@@ -723,7 +741,7 @@ static void dispatch_wgrad(const Gemm& a, hipStream_t st) {
   }
 }
 
-bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry) {
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry, LnBwdRide* ln) {
   if (n < 1 || n > kMaxGroup) return false;
   int64_t total = 0, per_split = 0;
   for (int i = 0; i < n; ++i) {
@@ -768,12 +786,21 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, Wgra
   const int own = 8 * cdiv(t0 * splits, 8);
   // a carried reduction rides on the workgroups that fit beside this launch's own (one per CU, 256 CUs), in
   // multiples of eight (one per XCD); with fewer than eight to spare it runs on its own first
-  int extra = 0;
-  if (carry && carry->nprob > 0) {
-    extra = ((256 - own) / 8) * 8;
-    if (extra < 8) {
+  int extra = ((256 - own) / 8) * 8;
+  if (extra < 8) extra = 0;
+  const bool host_ln = ln && extra > 0 && ln->D <= 768 && ln->D % 4 == 0 && ln->rows > 0 && ln->partial;
+  if (host_ln) {
+    ga.ln = LnBwdArgs<bf16, bf16, bf16>{(const bf16*)ln->dy, ln->lddy, (const bf16*)ln->x, ln->ldx, ln->mean, ln->rstd,
+                                        (const bf16*)ln->gamma, ln->dres, ln->lddres, ln->dx_s, (bf16*)ln->dx_o, ln->lddx,
+                                        ln->partial, ln->rows, ln->D};
+    ga.ln_on = 1;
+    ln->taken_np = extra;
+  }
+  if (!(carry && carry->nprob > 0)) {
+    if (!host_ln) extra = 0;
+  } else {
+    if (extra == 0) {
       gemm_wgrad_flush(carry, st);
-      extra = 0;
     } else {
       ga.c_nprob = carry->nprob;
       ga.c_splits = carry->splits;

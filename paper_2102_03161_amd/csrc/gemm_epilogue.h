@@ -248,7 +248,7 @@ bool gemm_dma_ok(const Gemm& a);
 void gemm_dma(const Gemm& a, int variant, hipStream_t st);
 // few rows, long K, workspace given: split-K with a summing epilogue pass; false if the shape is not taken
 bool gemm_dma_skinny(const Gemm& a, hipStream_t st);
-bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry);
+bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, WgradCarry* carry, LnBwdRide* ln);
 int splitk_vec_ok4(const float* part, int64_t n, const float* out);
 // the split-K reductions of up to four products (part2 entries may be null) in one launch
 void gemm_splitk_reduce_group(int nprob, int splits, const float* const* part, const int64_t* n, float* const* out,

@@ -52,7 +52,18 @@ struct WgradCarry {
   const float* part[4] = {}; float* out[4] = {}; int64_t n[4] = {};      // slabs -> weight gradient
   const float* part2[4] = {}; float* out2[4] = {}; int64_t n2[4] = {};   // column-sum partials -> bias gradient (or null)
 };
-void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid = nullptr, WgradCarry* carry = nullptr);
+// `ln` (may be null): a LayerNorm backward pass over bf16 tensors with D <= 768 (the arguments of
+// layernorm_bwd) that is independent of these products.  A grouped launch that has workgroups to spare runs
+// it beside the matrix work, leaves one partial row per such workgroup in ln->partial and sets ln->taken_np
+// to their number; the caller then owes the sum over those rows (layernorm_bwd_reduce).  taken_np == 0: the
+// pass was not taken and is still to be run.
+struct LnBwdRide {
+  const void* dy; int64_t lddy; const void* x; int64_t ldx; const float* mean; const float* rstd; const void* gamma;
+  const float* dres; int64_t lddres; float* dx_s; void* dx_o; int64_t lddx; float* partial; int rows, D;
+  int taken_np = 0;
+};
+void gemm_wgrad_batch(int dt, const Gemm* g, int n, hipStream_t st, hipEvent_t mid = nullptr, WgradCarry* carry = nullptr,
+                      LnBwdRide* ln = nullptr);
 void gemm_wgrad_flush(WgradCarry* carry, hipStream_t st);
 // workspace floats gemm_wgrad_batch may use for a block's four matrices (D x 3D, D x D, D x F, F x D)
 size_t gemm_wgrad_batch_ws_floats(int D, int F);

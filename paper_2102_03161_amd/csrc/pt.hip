@@ -350,6 +350,12 @@ void flush_ln_reductions(pt_ctx* c) {
   c->ln_jobs.clear();
 }
 
+// where the next LayerNorm backward pass of the sweep puts its workgroups' partial sums
+float* ln_partial_slot(pt_ctx* c) {
+  if (c->ln_jobs.size() == (size_t)c->plan.ln_slots) flush_ln_reductions(c);
+  return c->wf(c->plan.LNPART) + c->ln_jobs.size() * ln_partial_floats(c->cfg.D);
+}
+
 // memory-bound launches timed with their algorithmic bytes (what must be read and written once)
 void prof_ln_fwd(pt_ctx* c, int dt, bool x_f32, const void* x, int64_t ldx, const void* gamma, const void* beta, void* y,
                  int64_t ldy, float* mean, float* rstd, int rows, int D, float eps, hipStream_t st) {
@@ -364,8 +370,7 @@ void prof_ln_bwd(pt_ctx* c, int dt, bool dy_f32, bool x_f32, const void* dy, int
   // Each pass of a backward sweep writes its workgroups' partial sums of d(gamma), d(beta) and the column sums
   // to a slot of its own; nothing reads those three results before the sweep ends, so they are summed for
   // all passes in one launch there (flush_ln_reductions) unless the caller needs them at once.
-  if (c->ln_jobs.size() == (size_t)c->plan.ln_slots) flush_ln_reductions(c);
-  float* partial = c->wf(c->plan.LNPART) + c->ln_jobs.size() * ln_partial_floats(D);
+  float* partial = ln_partial_slot(c);
   LnReduceJob job;
   {
     ProfScope ps_(c, PT_PROF_LN_BWD, (double)rows * D * per);
@@ -493,7 +498,7 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
     m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
   };
-  auto run_wgrads = [&]() {
+  auto run_wgrads = [&](LnBwdRide* ln = nullptr) {
     double fl = 0;
     for (int i = 0; i < nwg; ++i) fl += 2.0 * wg[i].M * wg[i].N * wg[i].K;
     // the four products of a whole block in the matrix-core path: the grouped kernel is timed on its own, the
@@ -507,7 +512,7 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     c->wgrad_parity ^= 1;
     for (int i = 0; i < nwg; ++i) { wg[i].ws = ws; wg[i].ws_floats = half; }
     ProfScope ps_(c, grouped ? PT_PROF_WGRAD_BLOCK : gemm_cat(dt, wg[0]), fl);
-    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr, &c->wgrad_carry);
+    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr, &c->wgrad_carry, ln);
   };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
@@ -529,9 +534,23 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oC, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
     wgrad(c->w(s.U), D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     dgrad(dQKV, 3 * D, c->blk(l, WQKV), oC, D, EPI_STORE, nullptr, false);              // oC = dL/dU
+    // The block's last LayerNorm backward pass (-> dx) and its weight gradients do not depend on each other:
+    // the pass is offered to the weight-gradient launch, which runs it on its spare workgroups where it has
+    // them (gemm_wgrad_batch); otherwise it runs here as a launch of its own.
+    if (dt != 0) {
+      LnBwdRide ride{oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
+                     need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, ln_partial_slot(c), Tn, D};
+      run_wgrads(&ride);
+      if (ride.taken_np > 0) {
+        c->ln_jobs.push_back(LnReduceJob{ride.partial, ride.taken_np, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lower_b2});
+        return;
+      }
+      nwg = 0;   // the products are done
+    }
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
                   c->gp(c->blk(l, LN1_B)), lower_b2, Tn, D, st); }
+    if (dt != 0) return;
   } else {
     { prof_ln_bwd(c, dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
                   oE, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), Tn, D, st); }  // sC / oE = dL/d(Y+MLP)
