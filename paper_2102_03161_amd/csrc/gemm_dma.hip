@@ -555,7 +555,7 @@ struct GroupArgs {
   int c_vec[kMaxGroup], c_vec2[kMaxGroup];
   int c_nprob, c_splits;
   // a LayerNorm backward pass that is independent of the products, run by the same workgroups first
-  LnBwdArgs<bf16, bf16, bf16> ln;
+  LnBwdArgs<bf16, bf16, bf16> ln;   // dy and x are fp32 when ln_on == 2 (the pointers are cast back)
   int ln_on;
 };
 __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
@@ -568,9 +568,16 @@ __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
     // The same workgroups first run a LayerNorm backward pass that does not depend on these products (the
     // block's last one, whose result only the next block reads): 135 MB more, still well inside what 40 CUs
     // stream while the others work through their 98 k tiles.
-    if (ga.ln_on)
-      ln_bwd_rows<bf16, bf16, bf16, 3, 8>(ga.ln, reinterpret_cast<float*>(pp_lds<kPpLdsBytes256>()), (int)blockIdx.x - 8 * per,
-                                          (int)gridDim.x - 8 * per);
+    float* red = reinterpret_cast<float*>(pp_lds<kPpLdsBytes256>());
+    if (ga.ln_on == 1) {
+      ln_bwd_rows<bf16, bf16, bf16, 3, 8>(ga.ln, red, (int)blockIdx.x - 8 * per, (int)gridDim.x - 8 * per);
+    } else if (ga.ln_on == 2) {
+      const LnBwdArgs<bf16, float, float> a{reinterpret_cast<const float*>(ga.ln.dy), ga.ln.lddy,
+                                            reinterpret_cast<const float*>(ga.ln.x), ga.ln.ldx, ga.ln.mean, ga.ln.rstd,
+                                            ga.ln.gamma, ga.ln.dres, ga.ln.lddres, ga.ln.dx_s, ga.ln.dx_o, ga.ln.lddx,
+                                            ga.ln.partial, ga.ln.rows, ga.ln.D};
+      ln_bwd_rows<bf16, float, float, 3, 8>(a, red, (int)blockIdx.x - 8 * per, (int)gridDim.x - 8 * per);
+    }
     const int64_t first = ((int64_t)((int)blockIdx.x - 8 * per) * 512 + threadIdx.x) * 4;
     const int64_t step = (int64_t)((int)gridDim.x - 8 * per) * 512 * 4;
     for (int p = 0; p < ga.c_nprob; ++p) {
@@ -793,7 +800,7 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, Wgra
     ga.ln = LnBwdArgs<bf16, bf16, bf16>{(const bf16*)ln->dy, ln->lddy, (const bf16*)ln->x, ln->ldx, ln->mean, ln->rstd,
                                         (const bf16*)ln->gamma, ln->dres, ln->lddres, ln->dx_s, (bf16*)ln->dx_o, ln->lddx,
                                         ln->partial, ln->rows, ln->D};
-    ga.ln_on = 1;
+    ga.ln_on = ln->f32_in ? 2 : 1;
     ln->taken_np = extra;
   }
   if (!(carry && carry->nprob > 0)) {

@@ -54,7 +54,7 @@ struct Plan {
   // work arena
   std::vector<size_t> X;   // L+1 block inputs / outputs
   std::vector<Slot> slot;  // L+1 (slot L: scratch of the forward-only prefix)
-  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, dF, dQKV, DELTA;
+  size_t HKOUT, sA, sB, sC, sD, oA, oB, oC, oD, oE, oE2, dF, dQKV, DELTA;
   // dense copies of the first token's rows (top block's backward under a first-token head)
   size_t rG, rHP, rDF, rXa, rXb, rCTX, rDO, rOC, rOD, rDCTX, rS0, rS1, rS2, rST;  // s*: fp32 gradient stream, o*: T operand copies
   size_t PATCH, EMB, DEMB, MUE, RSE, CHAINWS, IDS;  // front ends (EMB: ViT patch embeddings / BERT embedding sum; IDS: the batch's token ids)
@@ -173,6 +173,7 @@ void make_plan(const pt_config& c, Plan* p) {
   const size_t TD4 = T * D * 4;
   p->sA = take(TD4); p->sB = take(TD4); p->sC = take(TD4); p->sD = take(TD4);
   p->oA = take(TD); p->oB = take(TD); p->oC = take(TD); p->oD = take(TD); p->oE = take(TD); p->dF = take(TF);
+  p->oE2 = c.arch == PT_BERT_POSTLN ? take(TD) : p->oE;   // post-LN: successive blocks alternate (see block_backward)
   p->dQKV = take(3 * TD); p->DELTA = take(BHS);
   {
     const size_t BD = (size_t)B * D, BF = (size_t)B * F;
@@ -251,6 +252,8 @@ struct pt_ctx {
   float* mom2 = nullptr;
   float* gacc = nullptr;      // gradient accumulator over micro-batches (grad_accum configurations)
   std::vector<LnReduceJob> ln_jobs;   // LayerNorm backward passes whose partial sums are not summed yet
+  Gemm pending_wg[4];                 // post-LN: a block's weight gradients, held back until the next block starts
+  int pending_nwg = 0;
   WgradCarry wgrad_carry;             // split-K slabs of the last block's weight gradients, not summed yet
   int wgrad_parity = 0;               // which half of the GEMM workspace the next block's slabs go to
   int64_t acc_samples = 0;    // samples accumulated so far; 0 = no accumulation in progress
@@ -472,6 +475,33 @@ void block_forward(pt_ctx* c, int l, const void* xin, void* xout, const Slot& s,
 // lower_b2 (pre-LN, may be null): where the column sums of dx go, i.e. the gradient of the second MLP
 // bias of the block below, whose output gradient dx is.
 // ---------------------------------------------------------------------------
+// The weight gradients of one block (all its products, one grouped launch in the matrix-core path).  `ln`: a
+// LayerNorm backward pass that does not depend on them and may ride on the launch (see gemm_wgrad_batch).
+void launch_wgrads(pt_ctx* c, Gemm* wg, int nwg, LnBwdRide* ln) {
+  if (nwg <= 0) return;
+  const Plan& p = c->plan;
+  const int dt = c->dt;
+  double fl = 0;
+  for (int i = 0; i < nwg; ++i) fl += 2.0 * wg[i].M * wg[i].N * wg[i].K;
+  // the four products of a whole block in the matrix-core path: the grouped kernel is timed on its own, the
+  // reduction of its split-K slabs separately
+  const bool grouped = nwg == 4 && gemm_cat(dt, wg[0]) == PT_PROF_GEMM_TN;
+  // Successive blocks alternate between the two halves of the workspace: the slabs of a split launch are
+  // summed by the next block's launch, on the CUs its tiles leave idle, or at the end of the sweep
+  // (flush_wgrad_carry), so they must survive that launch.
+  const size_t half = (p.gemmws_floats / 2) & ~(size_t)63;
+  float* ws = c->wf(p.GEMMWS) + (c->wgrad_parity ? half : 0);
+  c->wgrad_parity ^= 1;
+  for (int i = 0; i < nwg; ++i) { wg[i].ws = ws; wg[i].ws_floats = half; }
+  ProfScope ps_(c, grouped ? PT_PROF_WGRAD_BLOCK : gemm_cat(dt, wg[0]), fl);
+  gemm_wgrad_batch(dt, wg, nwg, c->st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr, &c->wgrad_carry, ln);
+}
+// post-LN: the weight gradients of the block above, held back for the next block's first LayerNorm pass
+void launch_pending_wgrads(pt_ctx* c, LnBwdRide* ln) {
+  if (c->pending_nwg > 0) launch_wgrads(c, c->pending_wg, c->pending_nwg, ln);
+  c->pending_nwg = 0;
+}
+
 struct GradBufs {
   float* s;  // fp32 stream
   void* o;   // T copy (pre-LN only)
@@ -484,7 +514,10 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
   hipStream_t st = c->st;
   const Plan& p = c->plan;
   float* sC = c->wf(p.sC); float* sD = c->wf(p.sD);
-  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* oE = c->w(p.oE); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
+  void* oC = c->w(p.oC); void* oD = c->w(p.oD); void* dF = c->w(p.dF); void* dQKV = c->w(p.dQKV);
+  // post-LN: the block above may still be reading its oE (its weight gradients are launched with this block's
+  // first LayerNorm pass on board, which writes this block's oE), so successive blocks alternate
+  void* oE = c->w((l & 1) ? p.oE2 : p.oE);
   // dW[K_in, N_out] = X^T dY ; db = colsum over tokens of dY (bias_dt 0: fp32 source, else T)
   // bid >= 0: also db = column sums of dY over the tokens, riding on the same product
   // The four weight gradients of the block are collected and run together at its end: every dY they read
@@ -498,22 +531,7 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     m.M = Kin; m.N = Nout; m.K = Tn; m.c_f32 = true;
     m.ws = c->wf(p.GEMMWS); m.ws_floats = p.gemmws_floats; m.colsum_out = bid >= 0 ? c->gp(bid) : nullptr;
   };
-  auto run_wgrads = [&](LnBwdRide* ln = nullptr) {
-    double fl = 0;
-    for (int i = 0; i < nwg; ++i) fl += 2.0 * wg[i].M * wg[i].N * wg[i].K;
-    // the four products of a whole block in the matrix-core path: the grouped kernel is timed on its own, the
-    // reduction of its split-K slabs separately
-    const bool grouped = nwg == 4 && gemm_cat(dt, wg[0]) == PT_PROF_GEMM_TN;
-    // Successive blocks alternate between the two halves of the workspace: the slabs of a split launch are
-    // summed by the next block's launch, on the CUs its tiles leave idle, or at the end of the sweep
-    // (flush_wgrad_carry), so they must survive that launch.
-    const size_t half = (p.gemmws_floats / 2) & ~(size_t)63;
-    float* ws = c->wf(p.GEMMWS) + (c->wgrad_parity ? half : 0);
-    c->wgrad_parity ^= 1;
-    for (int i = 0; i < nwg; ++i) { wg[i].ws = ws; wg[i].ws_floats = half; }
-    ProfScope ps_(c, grouped ? PT_PROF_WGRAD_BLOCK : gemm_cat(dt, wg[0]), fl);
-    gemm_wgrad_batch(dt, wg, nwg, st, grouped ? ps_.split(PT_PROF_SPLITK_REDUCE) : nullptr, &c->wgrad_carry, ln);
-  };
+  auto run_wgrads = [&](LnBwdRide* ln = nullptr) { launch_wgrads(c, wg, nwg, ln); };
   // dX[Tn, K_in] = dY W^T (+ epilogue)
   auto dgrad = [&](const void* dY, int Nout, int wid, void* dX, int Kin, Epi epi, const void* aux, bool out_f32) {
     Gemm m;
@@ -552,6 +570,21 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
                   c->gp(c->blk(l, LN1_B)), lower_b2, Tn, D, st); }
     if (dt != 0) return;
   } else {
+    // The block's first LayerNorm backward pass does not depend on the weight gradients of the block above,
+    // which were held back for it: it is offered to their launch, which runs it on its spare workgroups
+    // where it has them; otherwise it runs as a launch of its own behind them.
+    bool ln2_done = false;
+    if (dt != 0 && c->pending_nwg > 0) {
+      LnBwdRide ride{dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC, oE, D,
+                     ln_partial_slot(c), Tn, D};
+      ride.f32_in = true;
+      launch_pending_wgrads(c, &ride);
+      if (ride.taken_np > 0) {
+        c->ln_jobs.push_back(LnReduceJob{ride.partial, ride.taken_np, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2))});
+        ln2_done = true;
+      }
+    }
+    if (!ln2_done)
     { prof_ln_bwd(c, dt, true, true, dout.s, D, c->w(s.WN), D, c->wf(s.MU2), c->wf(s.RS2), c->cp(c->blk(l, LN2_G)), nullptr, 0, sC,
                   oE, D, c->gp(c->blk(l, LN2_G)), c->gp(c->blk(l, LN2_B)), c->gp(c->blk(l, B2)), Tn, D, st); }  // sC / oE = dL/d(Y+MLP)
     wgrad(c->w(s.G), F, oE, D, c->blk(l, W2), -1);
@@ -565,6 +598,11 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     { ProfScope ps_(c, PT_PROF_ATTN_BWD, 8.0 * ns * g.H * (double)g.S * g.S * (D / g.H)); attention_bwd(dt, c->w(s.QKV), c->w(s.CTX), oD, c->wf(s.LSE), dQKV, c->wf(p.DELTA), ns, g.S, g.H, D / g.H, st); }
     wgrad(xin, D, dQKV, 3 * D, c->blk(l, WQKV), c->blk(l, BQKV));
     if (need_dx) dgrad(dQKV, 3 * D, c->blk(l, WQKV), dx.s, D, EPI_RES, sC, true);
+    if (dt != 0) {   // held back for the next block's first LayerNorm pass (or the end of the sweep)
+      for (int i = 0; i < nwg; ++i) c->pending_wg[i] = wg[i];
+      c->pending_nwg = nwg;
+      return;
+    }
   }
   run_wgrads();
 }
@@ -1226,6 +1264,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
   { const pt_status fs = flush_deferred_norms(c); if (fs != PT_OK) return fs; }   // pending norms are of the gradients and boundary as they are now
   c->ln_jobs.clear();
   c->wgrad_carry.nprob = 0;
+  c->pending_nwg = 0;
   const pt_config& g = c->cfg;
   const Plan& p = c->plan;
   const int L = g.L, D = g.D, S = g.S, k = c->k, nb = c->nb, dt = c->dt;
@@ -1313,6 +1352,7 @@ pt_status pt_active_fwd_bwd(pt_ctx* c, const void* d_hk, const int32_t* d_labels
     else block_backward(c, l, xin, p.slot[l], dcur, dnext, nb, need_dx, lower_b2);
     std::swap(dcur, dnext);
   }
+  launch_pending_wgrads(c, nullptr);
   flush_wgrad_carry(c);   // in front of the front end's products, which use the same workspace
   if (k == 0) front_backward(c, dcur.s, nb);
   flush_ln_reductions(c);
