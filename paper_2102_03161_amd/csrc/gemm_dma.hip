@@ -569,14 +569,17 @@ __global__ __launch_bounds__(512) void gemm_wgrad_group_kernel(GroupArgs ga) {
     // block's last one, whose result only the next block reads): 135 MB more, still well inside what 40 CUs
     // stream while the others work through their 98 k tiles.
     float* red = reinterpret_cast<float*>(pp_lds<kPpLdsBytes256>());
+    const int rid = (int)blockIdx.x - 8 * per, nred = (int)gridDim.x - 8 * per;
     if (ga.ln_on == 1) {
-      ln_bwd_rows<bf16, bf16, bf16, 3, 8>(ga.ln, red, (int)blockIdx.x - 8 * per, (int)gridDim.x - 8 * per);
+      if (ga.ln.D <= 768) ln_bwd_rows<bf16, bf16, bf16, 3, 8>(ga.ln, red, rid, nred);
+      else ln_bwd_rows<bf16, bf16, bf16, 4, 8>(ga.ln, red, rid, nred);
     } else if (ga.ln_on == 2) {
       const LnBwdArgs<bf16, float, float> a{reinterpret_cast<const float*>(ga.ln.dy), ga.ln.lddy,
                                             reinterpret_cast<const float*>(ga.ln.x), ga.ln.ldx, ga.ln.mean, ga.ln.rstd,
                                             ga.ln.gamma, ga.ln.dres, ga.ln.lddres, ga.ln.dx_s, ga.ln.dx_o, ga.ln.lddx,
                                             ga.ln.partial, ga.ln.rows, ga.ln.D};
-      ln_bwd_rows<bf16, float, float, 3, 8>(a, red, (int)blockIdx.x - 8 * per, (int)gridDim.x - 8 * per);
+      if (ga.ln.D <= 768) ln_bwd_rows<bf16, float, float, 3, 8>(a, red, rid, nred);
+      else ln_bwd_rows<bf16, float, float, 4, 8>(a, red, rid, nred);
     }
     const int64_t first = ((int64_t)((int)blockIdx.x - 8 * per) * 512 + threadIdx.x) * 4;
     const int64_t step = (int64_t)((int)gridDim.x - 8 * per) * 512 * 4;
@@ -795,7 +798,7 @@ bool gemm_wgrad_group(const Gemm* a, int n, hipStream_t st, hipEvent_t mid, Wgra
   // multiples of eight (one per XCD); with fewer than eight to spare it runs on its own first
   int extra = ((256 - own) / 8) * 8;
   if (extra < 8) extra = 0;
-  const bool host_ln = ln && extra > 0 && ln->D <= 768 && ln->D % 4 == 0 && ln->rows > 0 && ln->partial;
+  const bool host_ln = ln && extra > 0 && ln->D <= 1024 && ln->D % 4 == 0 && ln->rows > 0 && ln->partial;
   if (host_ln) {
     ga.ln = LnBwdArgs<bf16, bf16, bf16>{(const bf16*)ln->dy, ln->lddy, (const bf16*)ln->x, ln->ldx, ln->mean, ln->rstd,
                                         (const bf16*)ln->gamma, ln->dres, ln->lddres, ln->dx_s, (bf16*)ln->dx_o, ln->lddx,

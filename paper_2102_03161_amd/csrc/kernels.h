@@ -52,7 +52,7 @@ struct WgradCarry {
   const float* part[4] = {}; float* out[4] = {}; int64_t n[4] = {};      // slabs -> weight gradient
   const float* part2[4] = {}; float* out2[4] = {}; int64_t n2[4] = {};   // column-sum partials -> bias gradient (or null)
 };
-// `ln` (may be null): a LayerNorm backward pass in bf16 mode with D <= 768 (the arguments of
+// `ln` (may be null): a LayerNorm backward pass in bf16 mode with D <= 1024 (the arguments of
 // layernorm_bwd) that is independent of these products.  A grouped launch that has workgroups to spare runs
 // it beside the matrix work, leaves one partial row per such workgroup in ln->partial and sets ln->taken_np
 // to their number; the caller then owes the sum over those rows (layernorm_bwd_reduce).  taken_np == 0: the
