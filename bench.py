@@ -39,11 +39,12 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of gemm_wgrad_group_kernel over one encoder block (its four weight gradients), from the
 # two rocprofv3 --pmc runs in profiles/*_hbm_traffic.md (FETCH_SIZE, then WRITE_SIZE), each scaled by what the
 # same counter reads for the plain copy of --calibrate-copy: fetched + written.
-# A launch also sums the previous block's split-K slabs (56.6 MB read, 28.3 MB written) on the workgroups it
-# adds for otherwise idle CUs; those bytes are in the figures.
+# A launch also carries, on the workgroups it adds for otherwise idle CUs, the summation of the previous block's
+# split-K slabs (56.6 MB read, 28.3 MB written) and one LayerNorm backward pass over the tokens (136 MB at
+# 12608 tokens); those bytes are in the figures.
 MEASURED_TRAFFIC = {
-    ("vit_b16", 0): 639_005_652,                     # profiles/vit_b16_b64_k0_hbm_traffic.md
-    ("bert_base_qa", 0): 626_007_040,                # profiles/bert_base_b32_s384_k0_hbm_traffic.md
+    ("vit_b16", 0): 769_487_200,                     # profiles/vit_b16_b64_k0_hbm_traffic.md
+    ("bert_base_qa", 0): 741_764_665,                # profiles/bert_base_b32_s384_k0_hbm_traffic.md
 }
 
 
@@ -336,8 +337,9 @@ def main():
         ach = wk / (ms * 1e-3) / 1e12
         traffic = MEASURED_TRAFFIC.get((a.workload, a.k))
         result["roofline"] = {"kernel": "gemm_wgrad_group_kernel (the four weight gradients dW = x^T dy of one encoder block, "
-                                        "one launch, two-way split over the tokens; the launch also sums the previous block's slabs on "
-                                        "workgroups of its own, the last block's reduction is breakdown.splitk_reduce)",
+                                        "one launch, two-way split over the tokens; on 40 workgroups added for idle CUs the launch also sums "
+                                        "the previous block's slabs and runs one LayerNorm backward pass, whose bytes are in "
+                                        "traffic and whose time is in avg_launch_us; flops_per_launch counts the weight gradients only)",
                               "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                               "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                               "avg_launch_us": round(1e3 * ms / n, 2), "launches_per_step": round(n / a.profile_steps, 2),
