@@ -511,21 +511,29 @@ __global__ __launch_bounds__(512) void attn_fwd_res_kernel(const bf16* __restric
   }
 }
 
+// A workgroup takes `upw` consecutive units (unit = nblk * (b * H + h) + block of queries): when only one
+// workgroup fits a CU and there are more units than CUs, a workgroup walks over several, and the K and V images
+// stay in LDS from one unit to the next of the same head (a head's two query blocks at S = 384 or 512).
 __global__ __launch_bounds__(512, 4) void attn_bwd_dq_res_kernel(const bf16* __restrict__ qkv, const bf16* __restrict__ ctx,
                                                               const bf16* __restrict__ dctx,
                                                               const float* __restrict__ lse, bf16* __restrict__ dqkv,
-                                                              float* __restrict__ delta, int S, int H, int ntile) {
+                                                              float* __restrict__ delta, int S, int H, int ntile, int nblk,
+                                                              int upw, int nunits) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Ks = reinterpret_cast<bf16*>(smem);
   bf16* Vs = Ks + ntile * 32 * LDR;
   const int D = H * DH;
-  const int b = blockIdx.z, h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const int nw = blockDim.x >> 6;
-  const int q = (blockIdx.x * nw + wave) * 32 + (lane & 31);
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+  int loaded = -1;   // the head whose K and V are in LDS
+  const int u_end = ((int)blockIdx.x + 1) * upw < nunits ? ((int)blockIdx.x + 1) * upw : nunits;
+  for (int u = (int)blockIdx.x * upw; u < u_end; ++u) {
+  const int bh = u / nblk, blk = u - bh * nblk;
+  const int b = bh / H, h = bh - b * H;
+  const int q = (blk * nw + wave) * 32 + (lane & 31);
   const bool qok = q < S;
   const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
-  const float scale = 0.125f, c = scale * 1.44269504088896f;
   bf16x8 qf[4], dof[4];
   float part = 0.f;
 #pragma unroll
@@ -536,9 +544,13 @@ __global__ __launch_bounds__(512, 4) void attn_bwd_dq_res_kernel(const bf16* __r
 #pragma unroll
     for (int i = 0; i < 8; ++i) part += to_f32(dof[ks][i]) * to_f32(of[i]);
   }
-  load_resident2(Ks, base + D, 3 * D, Vs, base + 2 * D, 3 * D, S, ntile * 32, tid, blockDim.x);
-  __syncthreads();
-  if ((blockIdx.x * nw + wave) * 32 >= S) return;
+  if (loaded != bh) {
+    if (loaded >= 0) __syncthreads();   // everybody is done with the previous head's images
+    load_resident2(Ks, base + D, 3 * D, Vs, base + 2 * D, 3 * D, S, ntile * 32, tid, blockDim.x);
+    loaded = bh;
+    __syncthreads();
+  }
+  if ((blk * nw + wave) * 32 >= S) continue;   // a wave without queries (it still meets the barriers above)
   const float dl = part + __shfl_xor(part, 32, 64);
   const float lq2 = (qok ? lse[((int64_t)b * H + h) * S + q] : 0.f) * 1.44269504088896f;
   if (qok && half == 0) delta[((int64_t)b * H + h) * S + q] = dl;
@@ -592,41 +604,52 @@ __global__ __launch_bounds__(512, 4) void attn_bwd_dq_res_kernel(const bf16* __r
     }
   }
   if (qok) store_owned_row(dqkv + ((int64_t)b * S + q) * 3 * D + h * DH, dq, scale, half);
+  }
 }
 
+// units as in attn_bwd_dq_res_kernel (here a unit's block is a block of keys, and Q, dO and the two float rows stay)
 __global__ __launch_bounds__(512) void attn_bwd_dkv_res_kernel(const bf16* __restrict__ qkv,
                                                                const bf16* __restrict__ dctx,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ delta,
-                                                               bf16* __restrict__ dqkv, int S, int H, int ntile) {
+                                                               bf16* __restrict__ dqkv, int S, int H, int ntile, int nblk,
+                                                               int upw, int nunits) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Qs = reinterpret_cast<bf16*>(smem);
   bf16* dOs = Qs + ntile * 32 * LDR;
   float* ls = reinterpret_cast<float*>(dOs + ntile * 32 * LDR);   // row log-sum-exp in the log2 domain
   float* dls = ls + ntile * 32;
   const int D = H * DH;
-  const int b = blockIdx.z, h = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
   const int nw = blockDim.x >> 6;
-  const int key = (blockIdx.x * nw + wave) * 32 + (lane & 31);
+  const float scale = 0.125f, c = scale * 1.44269504088896f;
+  int loaded = -1;
+  const int u_end = ((int)blockIdx.x + 1) * upw < nunits ? ((int)blockIdx.x + 1) * upw : nunits;
+  for (int u = (int)blockIdx.x * upw; u < u_end; ++u) {
+  const int bh = u / nblk, blk = u - bh * nblk;
+  const int b = bh / H, h = bh - b * H;
+  const int key = (blk * nw + wave) * 32 + (lane & 31);
   const bool kok = key < S;
   const bf16* base = qkv + (int64_t)b * S * 3 * D + h * DH;
   const bf16* dobase = dctx + (int64_t)b * S * D + h * DH;
-  const float scale = 0.125f, c = scale * 1.44269504088896f;
   bf16x8 kf[4], vf[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
     kf[ks] = own_row_frag(base + (int64_t)key * 3 * D + D, kok, lane, ks);
     vf[ks] = own_row_frag(base + (int64_t)key * 3 * D + 2 * D, kok, lane, ks);
   }
-  load_resident2(Qs, base, 3 * D, dOs, dobase, D, S, ntile * 32, tid, blockDim.x);
-  // a query row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
-  for (int r = tid; r < ntile * 32; r += blockDim.x) {
-    ls[r] = r < S ? lse[((int64_t)b * H + h) * S + r] * 1.44269504088896f : INFINITY;
-    dls[r] = r < S ? delta[((int64_t)b * H + h) * S + r] : 0.f;
+  if (loaded != bh) {
+    if (loaded >= 0) __syncthreads();
+    load_resident2(Qs, base, 3 * D, dOs, dobase, D, S, ntile * 32, tid, blockDim.x);
+    // a query row past the end gets log-sum-exp +inf, hence probability exp2(-inf) = 0, and delta 0
+    for (int r = tid; r < ntile * 32; r += blockDim.x) {
+      ls[r] = r < S ? lse[((int64_t)b * H + h) * S + r] * 1.44269504088896f : INFINITY;
+      dls[r] = r < S ? delta[((int64_t)b * H + h) * S + r] : 0.f;
+    }
+    loaded = bh;
+    __syncthreads();
   }
-  __syncthreads();
-  if ((blockIdx.x * nw + wave) * 32 >= S) return;
+  if ((blk * nw + wave) * 32 >= S) continue;
   f32x16 dk[2], dv[2];
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
@@ -687,6 +710,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_res_kernel(const bf16* __res
     bf16* row = dqkv + ((int64_t)b * S + key) * 3 * D + h * DH;
     store_owned_row(row + D, dk, scale, half);
     store_owned_row(row + 2 * D, dv, 1.0f, half);
+  }
   }
 }
 
@@ -1390,10 +1414,13 @@ void attention_bwd_mfma(const void* qkv, const void* ctx, const void* dctx, cons
   if (S <= g_attn_resident_max_s_bwd) {
     const ResPlan r = resident_plan(S, false), r2 = resident_plan(S, true);
     if (allow_lds(attn_bwd_dq_res_kernel, r.lds) == hipSuccess && allow_lds(attn_bwd_dkv_res_kernel, r2.lds) == hipSuccess) {
-      hipLaunchKernelGGL(attn_bwd_dq_res_kernel, dim3(r.nblk, H, nb), dim3(64 * r.nw), r.lds, st, (const bf16*)qkv,
-                         (const bf16*)ctx, (const bf16*)dctx, lse, (bf16*)dqkv, delta, S, H, r.ntile);
-      hipLaunchKernelGGL(attn_bwd_dkv_res_kernel, dim3(r2.nblk, H, nb), dim3(64 * r2.nw), r2.lds, st, (const bf16*)qkv,
-                         (const bf16*)dctx, lse, delta, (bf16*)dqkv, S, H, r2.ntile);
+      // one workgroup per CU (more than 80 KB of LDS) and more units than CUs: workgroups walk over units
+      const int nunits = r.nblk * H * nb, cus = device_cu_count();
+      const int upw = (r.lds > 80 * 1024 && cus > 0 && nunits > cus) ? cdiv(nunits, cus) : 1;
+      hipLaunchKernelGGL(attn_bwd_dq_res_kernel, dim3(cdiv(nunits, upw)), dim3(64 * r.nw), r.lds, st, (const bf16*)qkv,
+                         (const bf16*)ctx, (const bf16*)dctx, lse, (bf16*)dqkv, delta, S, H, r.ntile, r.nblk, upw, nunits);
+      hipLaunchKernelGGL(attn_bwd_dkv_res_kernel, dim3(cdiv(nunits, upw)), dim3(64 * r2.nw), r2.lds, st, (const bf16*)qkv,
+                         (const bf16*)dctx, lse, delta, (bf16*)dqkv, S, H, r2.ntile, r2.nblk, upw, nunits);
       return;
     }
     (void)hipGetLastError();
