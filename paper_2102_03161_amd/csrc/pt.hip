@@ -555,20 +555,21 @@ void block_backward(pt_ctx* c, int l, const void* xin, const Slot& s, GradBufs d
     // The block's last LayerNorm backward pass (-> dx) and its weight gradients do not depend on each other:
     // the pass is offered to the weight-gradient launch, which runs it on its spare workgroups where it has
     // them (gemm_wgrad_batch); otherwise it runs here as a launch of its own.
+    bool ln1_done = false;
     if (dt != 0) {
       LnBwdRide ride{oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                      need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, ln_partial_slot(c), Tn, D};
       run_wgrads(&ride);
       if (ride.taken_np > 0) {
         c->ln_jobs.push_back(LnReduceJob{ride.partial, ride.taken_np, c->gp(c->blk(l, LN1_G)), c->gp(c->blk(l, LN1_B)), lower_b2});
-        return;
+        ln1_done = true;
       }
-      nwg = 0;   // the products are done
     }
+    if (!ln1_done)
     { prof_ln_bwd(c, dt, false, false, oC, D, xin, D, c->wf(s.MU1), c->wf(s.RS1), c->cp(c->blk(l, LN1_G)), sC, D,
                   need_dx ? dx.s : nullptr, need_dx ? dx.o : nullptr, D, c->gp(c->blk(l, LN1_G)),
                   c->gp(c->blk(l, LN1_B)), lower_b2, Tn, D, st); }
-    if (dt != 0) return;
+    if (dt != 0) return;   // the products went out with the offer above
   } else {
     // The block's first LayerNorm backward pass does not depend on the weight gradients of the block above,
     // which were held back for it: it is offered to their launch, which runs it on its spare workgroups
